@@ -1,0 +1,139 @@
+"""ctypes front-end of the SAGE CPU oracle (oracle/sage_oracle.c).
+
+TEST INFRASTRUCTURE, NOT PRODUCT CODE: only tests, the smoke check and the
+benchmark's cpu_baseline leg may import this package.  It shares nothing with
+the HIP library; it takes numpy arrays (bf16 as uint16 bit patterns) and
+returns numpy arrays, fp64 for every real-valued result of O1/O3.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sage_oracle.c")
+_LIB = os.path.join(_HERE, "libsage_oracle.so")
+MAX_NODES = 64
+F32, BF16 = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with the host C compiler (no HIP, no contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(
+            ["gcc", "-O2", "-std=c99", "-fopenmp", "-ffp-contract=off", "-fno-fast-math", "-shared", "-fPIC",
+             "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.oracle_num_threads.restype = ctypes.c_int
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _dtype_code(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.uint16:
+        return BF16
+    raise TypeError("oracle inputs are float32 or bf16 bit patterns held as uint16")
+
+
+class TreeParams(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in ("d_min", "d_max", "w_min", "w_max", "k", "n_max")]
+
+
+def entropy_topk(logits: np.ndarray, k: int, n_valid: np.ndarray | None = None, rows_per_group: int = 1):
+    """O1 (Sec. 3.1, Eq. 7-9).  logits [rows, V] float32 or uint16(bf16)."""
+    assert logits.ndim == 2 and logits.strides[1] == logits.itemsize
+    rows, vocab = logits.shape
+    stride = logits.strides[0] // logits.itemsize
+    out = dict(
+        entropy=np.full(rows, np.nan), topk_idx=np.full((rows, k), -1, np.int32),
+        topk_prob=np.full((rows, k), np.nan), topk_renorm=np.full((rows, k), np.nan),
+        topk_entropy=np.full(rows, np.nan), alpha=np.full(rows, np.nan))
+    if n_valid is not None:
+        n_valid = np.ascontiguousarray(n_valid, np.int32)
+    rc = lib().oracle_entropy_topk(
+        _p(logits), _dtype_code(logits), rows, vocab, ctypes.c_long(stride), k, _p(n_valid), rows_per_group,
+        _p(out["entropy"]), _p(out["topk_idx"]), _p(out["topk_prob"]), _p(out["topk_renorm"]),
+        _p(out["topk_entropy"]), _p(out["alpha"]))
+    if rc:
+        raise ValueError(f"oracle_entropy_topk status {rc}")
+    return out
+
+
+def build_tree(topk_renorm: np.ndarray, alpha: np.ndarray, params: dict):
+    """O2 (Sec. 3.2, Eq. 10-12 and the membership rule).  fp32 inputs, bit-for-bit."""
+    pr = np.ascontiguousarray(topk_renorm, np.float32)
+    al = np.ascontiguousarray(alpha, np.float32)
+    B, k = pr.shape
+    tp = TreeParams(**{f: int(params[f]) for f, _ in TreeParams._fields_})
+    out = dict(
+        n_nodes=np.zeros(B, np.int32), parent=np.full((B, MAX_NODES), -2, np.int32),
+        depth=np.full((B, MAX_NODES), -2, np.int32), rank=np.full((B, MAX_NODES), -2, np.int32),
+        anc_mask=np.zeros((B, MAX_NODES), np.uint64), cum_prob=np.full((B, MAX_NODES), np.nan, np.float32))
+    rc = lib().oracle_build_tree(_p(pr), _p(al), B, k, ctypes.byref(tp), _p(out["n_nodes"]), _p(out["parent"]),
+                                 _p(out["depth"]), _p(out["rank"]), _p(out["anc_mask"]), _p(out["cum_prob"]))
+    if rc:
+        raise ValueError(f"oracle_build_tree status {rc}")
+    return out
+
+
+def tree_attention(Q, Kc, Vc, Kt, Vt, kv_start, kv_len, kv_token_stride, kv_head_stride, anc_mask, n_nodes,
+                   Hq: int, Hkv: int, d: int, scale: float | None = None):
+    """O3.  Q [B,64,Hq,d]; Kt,Vt [B,64,Hkv,d]; Kc,Vc flat caches addressed by strides. Returns fp64 O."""
+    B = Q.shape[0]
+    code = _dtype_code(Q)
+    for a in (Kc, Vc, Kt, Vt):
+        assert _dtype_code(a) == code and a.flags["C_CONTIGUOUS"]
+    assert Q.shape == (B, MAX_NODES, Hq, d) and Kt.shape == (B, MAX_NODES, Hkv, d) and Vt.shape == Kt.shape
+    kv_start = np.ascontiguousarray(kv_start, np.int64)
+    kv_len = np.ascontiguousarray(kv_len, np.int32)
+    anc_mask = np.ascontiguousarray(anc_mask, np.uint64)
+    n_nodes = np.ascontiguousarray(n_nodes, np.int32)
+    O = np.full((B, MAX_NODES, Hq, d), np.nan)
+    if scale is None:
+        scale = 1.0 / np.sqrt(float(d))
+    rc = lib().oracle_tree_attention(
+        _p(Q), _p(Kc), _p(Vc), _p(Kt), _p(Vt), _p(O), code, B, Hq, Hkv, d, _p(kv_start), _p(kv_len),
+        ctypes.c_long(kv_token_stride), ctypes.c_long(kv_head_stride), _p(anc_mask), _p(n_nodes),
+        ctypes.c_double(scale))
+    if rc:
+        raise ValueError(f"oracle_tree_attention status {rc}")
+    return O
+
+
+def verify_accept(token, target_argmax, parent, depth, n_nodes, path_cap: int):
+    """O4.  Integer arrays [B,64]; returns accept_len, best_node, path_nodes, out_tokens."""
+    token = np.ascontiguousarray(token, np.int32)
+    target_argmax = np.ascontiguousarray(target_argmax, np.int32)
+    parent = np.ascontiguousarray(parent, np.int32)
+    depth = np.ascontiguousarray(depth, np.int32)
+    n_nodes = np.ascontiguousarray(n_nodes, np.int32)
+    B = n_nodes.shape[0]
+    out = dict(accept_len=np.zeros(B, np.int32), best_node=np.zeros(B, np.int32),
+               path_nodes=np.full((B, path_cap), -1, np.int32), out_tokens=np.full((B, path_cap), -1, np.int32))
+    rc = lib().oracle_verify_accept(_p(token), _p(target_argmax), _p(parent), _p(depth), _p(n_nodes), B, path_cap,
+                                    _p(out["accept_len"]), _p(out["best_node"]), _p(out["path_nodes"]),
+                                    _p(out["out_tokens"]))
+    if rc:
+        raise ValueError(f"oracle_verify_accept status {rc}")
+    return out

@@ -1,0 +1,150 @@
+"""Pins for oracle O3 (tree-masked GQA attention of the verify pass; Sec. 2.2 tree mask, Alg. 1 Phase 2).
+
+The oracle is checked against a textbook causal attention from a library
+(torch SDPA in fp64) on chain trees, against a dense-mask matrix formulation
+written separately with numpy matmuls on random trees, and against special
+cases with closed-form answers.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from helpers import MAX_NODES, ancestor_sets, chain_parents, pad_tree, random_parents, star_parents
+from paper_2602_00523_amd import workloads as wl
+
+
+def widen(a):
+    return a.astype(np.float64) if a.dtype == np.float32 else wl.bf16_bits_to_f32(a).astype(np.float64)
+
+
+def run_oracle(inp, mask, n_nodes, Hq, Hkv, d, scale=None):
+    return oracle.tree_attention(inp["Q"], inp["Kc"], inp["Vc"], inp["Kt"], inp["Vt"], inp["kv_start"], inp["kv_len"],
+                                 inp["kv_token_stride"], inp["kv_head_stride"], mask, n_nodes, Hq, Hkv, d, scale)
+
+
+def dense_mask_attention(inp, par, b, Hq, Hkv, d):
+    """softmax(Q K^T / sqrt(d) + M) V with K = [cache; tree], M = 0 on cache and ancestors-or-self, -inf elsewhere."""
+    n, G = len(par), Hq // Hkv
+    L, s0 = int(inp["kv_len"][b]), int(inp["kv_start"][b])
+    Q = widen(inp["Q"])[b, :n]                                               # [n, Hq, d]
+    K = np.concatenate([widen(inp["Kc"])[s0:s0 + L], widen(inp["Kt"])[b, :n]], 0)   # [L+n, Hkv, d]
+    V = np.concatenate([widen(inp["Vc"])[s0:s0 + L], widen(inp["Vt"])[b, :n]], 0)
+    M = np.full((n, L + n), -np.inf)
+    M[:, :L] = 0
+    for i, s in enumerate(ancestor_sets(par)):
+        M[i, [L + j for j in s]] = 0
+    out = np.empty((n, Hq, d))
+    for h in range(Hq):
+        S = Q[:, h] @ K[:, h // G].T / np.sqrt(d) + M
+        P = np.exp(S - S.max(1, keepdims=True))
+        P /= P.sum(1, keepdims=True)
+        out[:, h] = P @ V[:, h // G]
+    return out
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,d,L,n", [("f32", 4, 1, 64, 256, 16), ("bf16", 8, 2, 128, 77, 9),
+                                                ("f32", 6, 3, 32, 0, 5)])
+def test_chain_tree_equals_causal_attention(dtype, Hq, Hkv, d, L, n):
+    inp = wl.attention_inputs(1, 1, Hq, Hkv, d, [L], dtype)
+    _, _, mask, nn = pad_tree(chain_parents(n))
+    O = run_oracle(inp, mask, nn, Hq, Hkv, d)
+    G = Hq // Hkv
+    # the chain's tokens are the last n positions of an ordinary causal sequence of length L+n
+    K = np.concatenate([widen(inp["Kc"])[:L], widen(inp["Kt"])[0, :n]], 0)
+    V = np.concatenate([widen(inp["Vc"])[:L], widen(inp["Vt"])[0, :n]], 0)
+    q = torch.zeros(1, Hq, L + n, d, dtype=torch.float64)
+    q[0, :, L:] = torch.from_numpy(widen(inp["Q"])[0, :n]).permute(1, 0, 2)
+    k = torch.from_numpy(K).permute(1, 0, 2).repeat_interleave(G, 0)[None]
+    v = torch.from_numpy(V).permute(1, 0, 2).repeat_interleave(G, 0)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True)[0, :, L:].permute(1, 0, 2).numpy()
+    np.testing.assert_allclose(O[0, :n], ref, rtol=1e-10, atol=1e-12)
+    assert np.isnan(O[0, n:]).all()                                          # rows beyond n_nodes untouched
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_trees_equal_dense_mask_formulation(seed):
+    g = np.random.default_rng(seed)
+    B, Hq, Hkv, d = 3, 8, 2, 16
+    dtype = "bf16" if seed % 2 else "f32"
+    lens = g.integers(0, 90, size=B)
+    inp = wl.attention_inputs(seed, B, Hq, Hkv, d, lens, dtype, pad_tokens=5)
+    pars = [random_parents(g, int(g.integers(1, 30)), chain_bias=0.4) for _ in range(B)]
+    mask = np.zeros((B, MAX_NODES), np.uint64)
+    nn = np.zeros(B, np.int32)
+    for b, par in enumerate(pars):
+        _, _, m, _ = pad_tree(par)
+        mask[b], nn[b] = m[0], len(par)
+    O = run_oracle(inp, mask, nn, Hq, Hkv, d)
+    for b, par in enumerate(pars):
+        np.testing.assert_allclose(O[b, :len(par)], dense_mask_attention(inp, par, b, Hq, Hkv, d), rtol=1e-10,
+                                   atol=1e-12)
+
+
+def test_star_tree_leaf_sees_cache_root_and_itself_only():
+    Hq, Hkv, d, L, n = 4, 2, 32, 40, 7
+    inp = wl.attention_inputs(3, 1, Hq, Hkv, d, [L], "f32")
+    _, _, mask, nn = pad_tree(star_parents(n))
+    O = run_oracle(inp, mask, nn, Hq, Hkv, d)
+    # perturbing a sibling's key/value must not change a leaf's output; perturbing the root's must
+    inp2 = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in inp.items()}
+    inp2["Kt"][0, 3] += 5
+    inp2["Vt"][0, 3] -= 5
+    O2 = run_oracle(inp2, mask, nn, Hq, Hkv, d)
+    others = [i for i in range(n) if i != 3]
+    np.testing.assert_array_equal(O2[0, others], O[0, others])
+    assert not np.allclose(O2[0, 3], O[0, 3])
+    inp3 = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in inp.items()}
+    inp3["Vt"][0, 0] += 1
+    O3 = run_oracle(inp3, mask, nn, Hq, Hkv, d)
+    assert all(not np.allclose(O3[0, i], O[0, i]) for i in range(n))
+
+
+def test_single_node_is_plain_decode_attention():
+    Hq, Hkv, d, L = 4, 4, 16, 50
+    inp = wl.attention_inputs(4, 1, Hq, Hkv, d, [L], "f32")
+    _, _, mask, nn = pad_tree(chain_parents(1))
+    O = run_oracle(inp, mask, nn, Hq, Hkv, d)
+    for h in range(Hq):
+        K = np.concatenate([widen(inp["Kc"])[:L, h], widen(inp["Kt"])[0, :1, h]], 0)
+        V = np.concatenate([widen(inp["Vc"])[:L, h], widen(inp["Vt"])[0, :1, h]], 0)
+        s = K @ widen(inp["Q"])[0, 0, h] / 4.0
+        p = np.exp(s - s.max())
+        np.testing.assert_allclose(O[0, 0, h], (p / p.sum()) @ V, rtol=1e-12)
+
+
+def test_identical_value_rows_are_returned_exactly_and_scale_is_used():
+    Hq, Hkv, d, L, n = 4, 1, 64, 33, 6
+    inp = wl.attention_inputs(5, 1, Hq, Hkv, d, [L], "f32")
+    row = np.linspace(-1, 1, d).astype(np.float32)
+    inp["Vc"][:] = row
+    inp["Vt"][:] = row
+    _, _, mask, nn = pad_tree(random_parents(np.random.default_rng(0), n))
+    O = run_oracle(inp, mask, nn, Hq, Hkv, d)
+    np.testing.assert_allclose(O[0, :n], np.broadcast_to(row.astype(np.float64), (n, Hq, d)), rtol=1e-13, atol=1e-15)
+    # scale = 0 makes every admitted key equally likely: the output is the plain mean of the admitted values
+    inp = wl.attention_inputs(6, 1, Hq, Hkv, d, [L], "f32")
+    par = chain_parents(n)
+    _, _, mask, nn = pad_tree(par)
+    O0 = run_oracle(inp, mask, nn, Hq, Hkv, d, scale=0.0)
+    for i in range(n):
+        V = np.concatenate([widen(inp["Vc"])[:L, 0], widen(inp["Vt"])[0, :i + 1, 0]], 0)
+        np.testing.assert_allclose(O0[0, i, 2], V.mean(0), rtol=1e-12, atol=1e-14)
+
+
+def test_cache_permutation_invariance_and_kv_start():
+    Hq, Hkv, d, L, n = 4, 2, 16, 61, 8
+    g = np.random.default_rng(9)
+    inp = wl.attention_inputs(7, 1, Hq, Hkv, d, [L], "bf16", pad_tokens=20)
+    _, _, mask, nn = pad_tree(random_parents(g, n))
+    O = run_oracle(inp, mask, nn, Hq, Hkv, d)
+    perm = g.permutation(L)
+    inp2 = dict(inp)
+    inp2["Kc"], inp2["Vc"] = inp["Kc"].copy(), inp["Vc"].copy()
+    inp2["Kc"][:L], inp2["Vc"][:L] = inp["Kc"][perm], inp["Vc"][perm]
+    np.testing.assert_allclose(run_oracle(inp2, mask, nn, Hq, Hkv, d)[0, :n], O[0, :n], rtol=1e-12, atol=1e-14)
+    # the same cache shifted by 13 tokens and addressed through kv_start gives the same bits
+    inp3 = dict(inp)
+    inp3["Kc"], inp3["Vc"] = np.roll(inp["Kc"], 13, 0), np.roll(inp["Vc"], 13, 0)
+    inp3["kv_start"] = np.array([13], np.int64)
+    np.testing.assert_array_equal(run_oracle(inp3, mask, nn, Hq, Hkv, d)[0, :n], O[0, :n])

@@ -1,0 +1,217 @@
+"""Pins for oracle O2 (adaptive tree construction; Sec. 3.2, Eq. 10-12 and the membership rule).
+
+The construction is a heuristic defined by its procedure, so it is pinned by
+(i) a brute-force enumeration of every rank path against the paper's formal
+"included iff" predicate, written without recursion and without sharing code
+with the oracle, (ii) the end-points the prose fixes (peaked -> deep chain,
+uniform -> shallow and wide), (iii) structural invariants recomputed by walking
+parent pointers.  The integerisation of D, W and W_l is this build's reading
+(parity unpinned by the paper); the tests state that reading explicitly.
+"""
+import itertools
+import json
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from helpers import ancestor_sets, depth_by_walk, mask_by_walk
+
+F = np.float32
+PAPER = dict(d_min=3, d_max=8, w_min=2, w_max=10, k=10, n_max=64)
+
+
+def renorm(p):
+    p = np.asarray(p, np.float64)
+    return (p / p.sum()).astype(np.float32)
+
+
+def rank_paths(t, b=0):
+    """Set of rank tuples (root excluded) of the oracle's tree."""
+    n = int(t["n_nodes"][b])
+    paths = set()
+    for v in range(1, n):
+        p, u = [], v
+        while u > 0:
+            p.append(int(t["rank"][b, u]))
+            u = int(t["parent"][b, u])
+        paths.add(tuple(reversed(p)))
+    return paths
+
+
+def brute_force_membership(ptilde, alpha, prm):
+    """Every rank path p with |p| <= D such that, for all l <= |p|: p_l < W_l and cumulative prob > theta_l."""
+    a = F(alpha)
+    D = int(np.floor(F(F(prm["d_min"]) + F(a * F(prm["d_max"] - prm["d_min"]))) + F(0.5)))
+    W = np.floor(F(F(prm["w_min"]) + F(F(F(1) - a) * F(prm["w_max"] - prm["w_min"]))) + F(0.5))
+    W = F(min(W, prm["k"]))
+    members = set()
+    for d in range(1, D + 1):
+        for p in itertools.product(range(prm["k"]), repeat=d):
+            cum, ok = F(1), True
+            for l, r in enumerate(p, start=1):
+                if l == 1:
+                    Wl = int(W)
+                else:
+                    Wl = max(1, int(np.floor(F(F(W / F(l)) * F(F(0.5) + cum)))))
+                Wl = min(Wl, prm["k"])
+                cum = F(cum * ptilde[r])
+                theta = F(F(F(0.1) * F(l)) / F(D))
+                if not (r < Wl and cum > theta):
+                    ok = False
+                    break
+            if ok:
+                members.add(p)
+    return members
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_node_set_equals_brute_force_membership(seed):
+    g = np.random.default_rng(seed)
+    k = int(g.integers(2, 5))
+    prm = dict(d_min=1, d_max=int(g.integers(2, 5)), w_min=1, w_max=k, k=k, n_max=64)
+    pt = np.sort(renorm(g.random(k) ** 2 + 1e-3))[::-1].copy()
+    alpha = F(g.random())
+    t = oracle.build_tree(pt[None, :], np.array([alpha], F), prm)
+    want = brute_force_membership(pt, alpha, prm)
+    if len(want) + 1 > prm["n_max"]:
+        pytest.skip("cap binds; membership rule alone does not define the result")
+    assert rank_paths(t) == want
+    assert int(t["n_nodes"][0]) == len(want) + 1
+
+
+def check_invariants(t, prm, b=0):
+    n = int(t["n_nodes"][b])
+    par, dep, rnk = t["parent"][b, :n], t["depth"][b, :n], t["rank"][b, :n]
+    assert 1 <= n <= prm["n_max"]
+    assert par[0] == -1 and dep[0] == 0 and rnk[0] == -1
+    assert all(0 <= par[v] < v for v in range(1, n))                     # creation order, DFS pre-order
+    np.testing.assert_array_equal(dep, depth_by_walk(par))
+    np.testing.assert_array_equal(t["anc_mask"][b, :n], mask_by_walk(par))
+    # pre-order: the parent of v is the nearest earlier node of depth dep[v]-1
+    for v in range(1, n):
+        u = v - 1
+        while dep[u] != dep[v] - 1:
+            u -= 1
+        assert par[v] == u
+    # siblings carry distinct ranks below k, in ascending order of creation
+    for u in range(n):
+        r = [int(rnk[v]) for v in range(1, n) if par[v] == u]
+        assert r == sorted(set(r)) and all(0 <= x < prm["k"] for x in r)
+    # the mask is exactly the ancestor-or-self relation
+    anc = ancestor_sets(par)
+    for v in range(n):
+        assert {j for j in range(64) if (int(t["anc_mask"][b, v]) >> j) & 1} == anc[v]
+    assert (t["parent"][b, n:] == -2).all()                              # entries beyond n untouched
+
+
+def test_invariants_over_random_inputs():
+    g = np.random.default_rng(100)
+    for _ in range(200):
+        k = int(g.integers(1, 17))
+        prm = dict(d_min=int(g.integers(1, 4)), d_max=int(g.integers(4, 11)), w_min=1, w_max=int(g.integers(1, k + 1)),
+                   k=k, n_max=int(g.integers(1, 65)))
+        pt = np.sort(renorm(g.random(k) ** int(g.integers(1, 6)) + 1e-6))[::-1].copy()
+        t = oracle.build_tree(pt[None, :], np.array([g.random()], F), prm)
+        check_invariants(t, prm)
+        # cumulative probability is the product of P~ along the path
+        n = int(t["n_nodes"][0])
+        for v in range(1, n):
+            u = int(t["parent"][0, v])
+            assert t["cum_prob"][0, v] == F(t["cum_prob"][0, u] * pt[t["rank"][0, v]])
+
+
+def test_peaked_distribution_gives_chain_of_d_max():
+    # alpha -> 1: "deeper but narrower": a one-hot P~ yields a single chain of D_max draft nodes
+    pt = np.zeros(10, F)
+    pt[0] = 1
+    t = oracle.build_tree(pt[None, :], np.array([1.0], F), PAPER)
+    n = int(t["n_nodes"][0])
+    assert n == PAPER["d_max"] + 1
+    np.testing.assert_array_equal(t["parent"][0, :n], np.arange(-1, n - 1))
+    np.testing.assert_array_equal(t["depth"][0, :n], np.arange(n))
+    assert (t["rank"][0, 1:n] == 0).all()
+
+
+def test_uniform_distribution_gives_root_plus_w_max_children():
+    # alpha -> 0: "shallower but wider": uniform P~ = 1/10 passes theta_1 = 0.1/3 but (1/10)^2 fails theta_2
+    pt = np.full(10, 0.1, F)
+    t = oracle.build_tree(pt[None, :], np.array([0.0], F), PAPER)
+    n = int(t["n_nodes"][0])
+    assert n == 1 + PAPER["w_max"]
+    assert (t["parent"][0, 1:n] == 0).all() and (t["depth"][0, 1:n] == 1).all()
+    np.testing.assert_array_equal(t["rank"][0, 1:n], np.arange(10))
+
+
+def test_depth_and_width_are_monotone_in_alpha_and_round_half_up():
+    alphas = np.linspace(0, 1, 101).astype(F)
+    hot = np.zeros(10, F)
+    hot[0] = 1
+    flat = np.full(10, 0.1, F)
+    depths, widths = [], []
+    for a in alphas:
+        t = oracle.build_tree(hot[None, :], np.array([a], F), PAPER)
+        depths.append(int(t["n_nodes"][0]) - 1)                  # chain length = D(alpha)
+        t = oracle.build_tree(flat[None, :], np.array([a], F), dict(PAPER, d_min=2, d_max=2))
+        widths.append(int(t["n_nodes"][0]) - 1)                  # level-1 children = W(alpha): 0.1 > theta_1 = 0.05, 0.01 < theta_2
+    assert depths == sorted(depths) and depths[0] == 3 and depths[-1] == 8
+    assert widths == sorted(widths, reverse=True) and widths[0] == 10 and widths[-1] == 2
+    # the initial confidence of Alg. 1 (alpha = 0.5) with the paper's ranges: D = 5.5 -> 6, W = 6
+    assert depths[50] == 6 and widths[50] == 6
+    for a, dd, ww in zip(alphas.astype(np.float64), depths, widths):
+        assert abs(dd - (3 + a * 5)) <= 0.5 + 1e-6 and abs(ww - (2 + (1 - a) * 8)) <= 0.5 + 1e-6
+
+
+def test_width_decay_follows_parent_probability():
+    # level 2 under a parent of cumulative probability c gets floor(W/2 * (0.5 + c)) candidates (at least 1)
+    prm = dict(d_min=2, d_max=2, w_min=8, w_max=8, k=8, n_max=64)
+    pt = renorm([0.55, 0.25, 0.08, 0.04, 0.03, 0.02, 0.02, 0.01])
+    t = oracle.build_tree(pt[None, :], np.array([0.3], F), prm)
+    n = int(t["n_nodes"][0])
+    theta2 = F(F(F(0.1) * F(2)) / F(2))
+    for u in range(1, n):
+        if t["depth"][0, u] != 1:
+            continue
+        c = t["cum_prob"][0, u]
+        wl = max(1, int(np.floor(F(F(F(8) / F(2)) * F(F(0.5) + c)))))
+        want = [r for r in range(wl) if F(c * pt[r]) > theta2]
+        got = [int(t["rank"][0, v]) for v in range(n) if t["parent"][0, v] == u]
+        assert got == want
+    # the most probable branch receives at least as many children as any other
+    kids = {u: sum(1 for v in range(n) if t["parent"][0, v] == u) for u in range(1, n) if t["depth"][0, u] == 1}
+    assert kids[1] == max(kids.values())
+
+
+def test_node_cap_binds_in_dfs_order():
+    prm = dict(d_min=4, d_max=4, w_min=4, w_max=4, k=4, n_max=64)
+    pt = np.full(4, 0.25, F)
+    full = oracle.build_tree(pt[None, :], np.array([0.5], F), dict(prm, n_max=64))
+    for cap in (1, 2, 7, 20):
+        t = oracle.build_tree(pt[None, :], np.array([0.5], F), dict(prm, n_max=cap))
+        n = int(t["n_nodes"][0])
+        assert n == min(cap, int(full["n_nodes"][0]))
+        for key in ("parent", "depth", "rank", "anc_mask"):          # a capped tree is a prefix of the uncapped one
+            np.testing.assert_array_equal(t[key][0, :n], full[key][0, :n])
+
+
+def test_batch_rows_are_independent():
+    g = np.random.default_rng(7)
+    pts = np.stack([np.sort(renorm(g.random(10) ** 3))[::-1] for _ in range(5)])
+    al = g.random(5).astype(F)
+    tb = oracle.build_tree(pts, al, PAPER)
+    for b in range(5):
+        t1 = oracle.build_tree(pts[b:b + 1], al[b:b + 1], PAPER)
+        n = int(t1["n_nodes"][0])
+        assert tb["n_nodes"][b] == n
+        for key in ("parent", "depth", "rank", "anc_mask"):
+            np.testing.assert_array_equal(tb[key][b, :n], t1[key][0, :n])
+
+
+def test_paper_hyperparameters_fixture():
+    with open(os.path.join(os.path.dirname(__file__), "golden", "paper_hyperparameters.json")) as f:
+        gold = json.load(f)
+    from paper_2602_00523_amd import workloads as wl
+    for name in ("c2", "c4", "c5"):
+        assert wl.CONFIGS[name]["tree"] == gold["tree"]
+    assert gold["alpha_init"] == 0.5
