@@ -1,0 +1,161 @@
+/*
+ * sage.h -- C ABI of the MI355X (gfx950) hot path of SAGE, entropy-guided adaptive
+ * speculative decoding: the per-step draft-tree machinery around the target model's
+ * parallel verification.
+ *
+ * Four operations, one call each, in the order a decoding step uses them
+ * (Alg. 1: Phase 3 prepares the tree that Phase 1/2 of the next iteration use):
+ *
+ *   sage_entropy_topk    Sec. 3.1, Eq. (7)-(9)   confidence from the draft distribution
+ *                        (also the target's greedy token per tree node, k = 1)
+ *   sage_build_tree      Sec. 3.2, Eq. (10)-(12) adaptive depth/width, recursive expansion
+ *   sage_tree_attention  Sec. 2.2 tree mask, Alg. 1 Phase 2: the attention operator of the
+ *                        target's single verification pass over all tree nodes
+ *   sage_verify_accept   Sec. 2.2 / Sec. 3.3 Phase 2: longest accepted root-to-leaf prefix
+ *
+ * Conventions common to all calls
+ *   - Every data pointer is caller-owned DEVICE memory unless marked (host).  The library
+ *     keeps no state, allocates nothing, never synchronises and never frees.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream).  Outputs are valid once the stream reaches that point.
+ *   - Sizes that change from step to step (n_nodes, kv_len, n_valid) are read on the
+ *     device, so the four calls chain without a host round trip.
+ *   - Per-sequence tree arrays have a fixed stride of SAGE_MAX_NODES entries; entries at or
+ *     beyond n_nodes[b] are neither read nor written.  Node 0 is the root (the last
+ *     committed token); nodes are in creation order (depth-first, pre-order), so
+ *     parent[v] < v.
+ *   - Return value: SAGE_OK, or an error code; on error nothing has been enqueued.
+ *   - Logits must be finite or -inf (NaN / +inf give unspecified values, never a fault).
+ */
+#ifndef SAGE_H
+#define SAGE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SAGE_MAX_NODES 64   /* tree nodes per sequence incl. the root: one 64-bit mask word, one wavefront */
+#define SAGE_MAX_TOPK 64    /* largest k of sage_entropy_topk */
+#define SAGE_MAX_DEPTH 31   /* largest d_max of sage_build_tree */
+
+enum sage_status {
+    SAGE_OK = 0,
+    SAGE_INVALID_ARG = 1,          /* null pointer, size or parameter out of range, bad stride/alignment */
+    SAGE_UNSUPPORTED = 2,          /* valid request outside the instantiated kernels (e.g. bf16 head_dim != 128) */
+    SAGE_WORKSPACE_TOO_SMALL = 3,
+    SAGE_LAUNCH_FAILED = 4         /* hipGetLastError() after a launch */
+};
+
+enum sage_dtype { SAGE_F32 = 0, SAGE_BF16 = 1 };
+
+/* Tree hyper-parameters of Alg. 1 (D_min, D_max, W_min, W_max, k, N_max).  The paper's
+ * experiments use 3, 8, 2, 10, 10, 64.  Constraints: 1 <= d_min <= d_max <= SAGE_MAX_DEPTH,
+ * 1 <= w_min <= w_max <= k <= SAGE_MAX_TOPK, 1 <= n_max <= SAGE_MAX_NODES (root included). */
+typedef struct sage_tree_params {
+    int d_min, d_max, w_min, w_max, k, n_max;
+} sage_tree_params;
+
+/* ------------------------------------------------------------------------------------------
+ * sage_entropy_topk -- Sec. 3.1.  For each row x[0..vocab) of logits:
+ *   P = softmax(x) (Eq. 1);  entropy = -sum P ln P (nats, full vocabulary, 0 ln 0 = 0);
+ *   Top_k = first k indices under the total order (logit descending, index ascending);
+ *   topk_prob = P on Top_k;  topk_renorm = topk_prob / sum(topk_prob)           (Eq. 7);
+ *   topk_entropy = -sum topk_renorm ln topk_renorm                              (Eq. 8);
+ *   alpha = clamp(1 - topk_entropy / ln k, 0, 1), alpha = 1 when k = 1          (Eq. 9).
+ * With k = 1, topk_idx is the greedy (argmax, ties to the lowest index) token of each row,
+ * which is how the target's choice at every tree node is obtained.
+ *
+ * logits       [rows, vocab], dtype f32 or bf16, row r starts at element r * row_stride;
+ *              rows must be 16-byte aligned (row_stride * elem size multiple of 16).
+ * n_valid      nullable.  Rows form groups of rows_per_group; only the first
+ *              n_valid[g] rows of group g are processed (e.g. rows_per_group = 64 and
+ *              n_valid = n_nodes for per-node target logits); other rows' outputs are untouched.
+ * entropy, topk_entropy, alpha   [rows] f32;  topk_idx [rows,k] i32;
+ * topk_prob, topk_renorm         [rows,k] f32.  Any output pointer except topk_idx may be NULL.
+ * workspace    sage_entropy_topk_workspace_bytes(rows, vocab, k) bytes, 16-byte aligned.
+ * Errors: INVALID_ARG for null logits/topk_idx/workspace, rows < 0, vocab < 1, k outside
+ * [1, min(vocab, SAGE_MAX_TOPK)], misaligned rows; WORKSPACE_TOO_SMALL.
+ */
+size_t sage_entropy_topk_workspace_bytes(int rows, int vocab, int k);
+int sage_entropy_topk(const void* logits, int dtype, int rows, int vocab, long row_stride, int k,
+                      const int* n_valid, int rows_per_group,
+                      float* entropy, int* topk_idx, float* topk_prob, float* topk_renorm,
+                      float* topk_entropy, float* alpha,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * sage_build_tree -- Sec. 3.2.  Per sequence b, from topk_renorm[b, 0..k) (descending) and
+ * alpha[b], in IEEE fp32 without fused multiply-add:
+ *   D = floor(d_min + alpha (d_max - d_min) + 0.5)                              (Eq. 10)
+ *   W = min(k, floor(w_min + (1 - alpha)(w_max - w_min) + 0.5))                 (Eq. 11)
+ *   expand(u) at level l = depth(u) + 1 <= D:  W_1 = W;  for l > 1
+ *       W_l = min(k, max(1, floor((W / l) (0.5 + cum(u)))))                     (Eq. 12)
+ *     for r = 0 .. W_l - 1:  c = cum(u) * topk_renorm[r];  if c > 0.1 l / D the candidate
+ *     becomes node v = n++ (parent u, depth l, rank r, cum c) and is expanded at once;
+ *     nothing is added once n == n_max.
+ * The same renormalised top-k vector is used at every node (the tree is planned for the
+ * next step from the current step's distribution).
+ *
+ * topk_renorm [B,k] f32, alpha [B] f32, params (host) copied at call time.
+ * n_nodes [B] i32; parent, depth, rank [B,64] i32 (root: -1, 0, -1); anc_mask [B,64] u64,
+ * bit j of anc_mask[b][v] set iff j is v or an ancestor of v; cum_prob [B,64] f32, nullable.
+ * Errors: INVALID_ARG for null pointers, B < 0, k != params->k, parameter constraints.
+ */
+int sage_build_tree(const float* topk_renorm, const float* alpha, int B, int k, const sage_tree_params* params,
+                    int* n_nodes, int* parent, int* depth, int* rank, uint64_t* anc_mask, float* cum_prob,
+                    void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * sage_tree_attention -- the attention operator of the verify pass (Alg. 1 Phase 2) under
+ * the tree mask of Sec. 2.2.  For sequence b, node i < n_nodes[b], query head h
+ * (kv head g = h / (Hq / Hkv)):
+ *   keys/values = all cache positions j < kv_len[b]  U  tree nodes t with bit t set in
+ *   anc_mask[b][i];   O[b,i,h,:] = softmax_j(scale * Q[b,i,h,:] . K_j) V_j.
+ *
+ * Q, O    [B,64,Hq,d];  Kt, Vt [B,64,Hkv,d] (keys/values of the tree nodes themselves);
+ * Kc, Vc  cache: element (b, j, g, c) at (kv_start[b] + j) * kv_token_stride
+ *         + g * kv_head_stride + c  (strides in elements; rows 16-byte aligned);
+ * kv_start [B] i64, kv_len [B] i32 (device); max_kv_len (host) >= every kv_len[b], used
+ * only to size the launch; dtype applies to Q, K, V and O alike.
+ * bf16: MFMA path, requires d == 128, Hq / Hkv in {1,2,4,8,16}; fp32: d <= 256, multiple of 4.
+ * Accumulation is fp32; bf16 outputs are rounded to nearest even.
+ * workspace: sage_tree_attention_workspace_bytes(...) bytes, 256-byte aligned.
+ * Errors: INVALID_ARG (null pointers, B < 0, Hq % Hkv != 0, strides, max_kv_len < 0),
+ * UNSUPPORTED (shape outside the above), WORKSPACE_TOO_SMALL.
+ */
+size_t sage_tree_attention_workspace_bytes(int dtype, int B, int Hq, int Hkv, int d, int max_kv_len);
+int sage_tree_attention(const void* Q, const void* Kc, const void* Vc, const void* Kt, const void* Vt, void* O,
+                        int dtype, int B, int Hq, int Hkv, int d,
+                        const int64_t* kv_start, const int* kv_len, int max_kv_len,
+                        long kv_token_stride, long kv_head_stride,
+                        const uint64_t* anc_mask, const int* n_nodes, float scale,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * sage_verify_accept -- acceptance under greedy decoding (Sec. 2.2, Sec. 3.3 Phase 2,
+ * Def. 4.1).  Node i > 0 matches iff token[i] == target_argmax[parent[i]]; it is accepted iff
+ * it and all its ancestors match.  best_node = deepest accepted node (ties: lowest index),
+ * accept_len = tau = its depth.  path_nodes = root .. best_node; out_tokens = the tau draft
+ * tokens on that path followed by target_argmax[best_node] (tau + 1 tokens advance).
+ *
+ * token, target_argmax, parent, depth [B,64] i32; anc_mask [B,64] u64 (as emitted by
+ * sage_build_tree; it must be the ancestor-or-self relation of parent[]); n_nodes [B].
+ * accept_len, best_node [B] i32; path_nodes, out_tokens [B,path_cap] i32, padded with -1.
+ * path_cap (host) must exceed the deepest node's depth (d_max + 1 suffices); deeper paths
+ * are truncated to path_cap entries, never written out of bounds.
+ * Errors: INVALID_ARG for null pointers, B < 0, path_cap < 1.
+ */
+int sage_verify_accept(const int* token, const int* target_argmax, const int* parent, const int* depth,
+                       const uint64_t* anc_mask, const int* n_nodes, int B, int path_cap,
+                       int* accept_len, int* best_node, int* path_nodes, int* out_tokens, void* stream);
+
+/* Library build identification (host): returns a static string naming the target architecture. */
+const char* sage_build_info(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAGE_H */

@@ -1,0 +1,133 @@
+"""Thin ctypes binding of libsage_hip.so (include/sage.h): same names, argument marshalling only.
+
+Tensors are torch CUDA(HIP) tensors used as device buffers; nothing here computes anything.  The library is
+loaded on first use and a missing library is an error (there is no fallback path of any kind).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsage_hip.so")
+MAX_NODES = 64
+F32, BF16 = 0, 1
+STATUS = {0: "OK", 1: "INVALID_ARG", 2: "UNSUPPORTED", 3: "WORKSPACE_TOO_SMALL", 4: "LAUNCH_FAILED"}
+
+
+class SageError(RuntimeError):
+    def __init__(self, call: str, code: int):
+        super().__init__(f"{call} -> {STATUS.get(code, code)}")
+        self.code = code
+
+
+class TreeParams(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in ("d_min", "d_max", "w_min", "w_max", "k", "n_max")]
+
+
+_lib = None
+_vp, _ci, _cl, _cf, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_float, ctypes.c_size_t
+
+
+def lib():
+    """Load the HIP library built in-tree by paper_2602_00523_amd.build; fail loudly when it is absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise SageError(f"{LIB_PATH} is missing: run `python -m paper_2602_00523_amd.build`", -1)
+        L = ctypes.CDLL(LIB_PATH)
+        L.sage_entropy_topk_workspace_bytes.restype = _sz
+        L.sage_entropy_topk_workspace_bytes.argtypes = [_ci, _ci, _ci]
+        L.sage_entropy_topk.restype = _ci
+        L.sage_entropy_topk.argtypes = [_vp, _ci, _ci, _ci, _cl, _ci, _vp, _ci, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+        L.sage_build_tree.restype = _ci
+        L.sage_build_tree.argtypes = [_vp, _vp, _ci, _ci, ctypes.POINTER(TreeParams), _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+        L.sage_tree_attention_workspace_bytes.restype = _sz
+        L.sage_tree_attention_workspace_bytes.argtypes = [_ci, _ci, _ci, _ci, _ci, _ci]
+        L.sage_tree_attention.restype = _ci
+        L.sage_tree_attention.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _cl, _cl,
+                                          _vp, _vp, _cf, _vp, _sz, _vp]
+        L.sage_verify_accept.restype = _ci
+        L.sage_verify_accept.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _ci, _ci, _vp, _vp, _vp, _vp, _vp]
+        L.sage_build_info.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError("float32 or bfloat16 expected")
+
+
+def _check(call: str, rc: int):
+    if rc != 0:
+        raise SageError(call, rc)
+
+
+def tree_params(d_min, d_max, w_min, w_max, k, n_max) -> TreeParams:
+    return TreeParams(d_min, d_max, w_min, w_max, k, n_max)
+
+
+def sage_entropy_topk_workspace_bytes(rows: int, vocab: int, k: int) -> int:
+    return int(lib().sage_entropy_topk_workspace_bytes(rows, vocab, k))
+
+
+def sage_entropy_topk(logits, k, entropy, topk_idx, topk_prob, topk_renorm, topk_entropy, alpha, workspace,
+                      n_valid=None, rows_per_group=1, stream=None):
+    rows, vocab = logits.shape
+    assert logits.stride(1) == 1
+    rc = lib().sage_entropy_topk(_ptr(logits), _dtype_code(logits), rows, vocab, logits.stride(0), k, _ptr(n_valid),
+                                 rows_per_group, _ptr(entropy), _ptr(topk_idx), _ptr(topk_prob), _ptr(topk_renorm),
+                                 _ptr(topk_entropy), _ptr(alpha), _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream(stream))
+    _check("sage_entropy_topk", rc)
+
+
+def sage_build_tree(topk_renorm, alpha, params: TreeParams, n_nodes, parent, depth, rank, anc_mask, cum_prob=None,
+                    stream=None):
+    B, k = topk_renorm.shape
+    rc = lib().sage_build_tree(_ptr(topk_renorm), _ptr(alpha), B, k, ctypes.byref(params), _ptr(n_nodes), _ptr(parent),
+                               _ptr(depth), _ptr(rank), _ptr(anc_mask), _ptr(cum_prob), _stream(stream))
+    _check("sage_build_tree", rc)
+
+
+def sage_tree_attention_workspace_bytes(dtype_code: int, B: int, Hq: int, Hkv: int, d: int, max_kv_len: int) -> int:
+    return int(lib().sage_tree_attention_workspace_bytes(dtype_code, B, Hq, Hkv, d, max_kv_len))
+
+
+def sage_tree_attention(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_token_stride, kv_head_stride, anc_mask,
+                        n_nodes, scale, workspace, stream=None):
+    B, _, Hq, d = Q.shape
+    Hkv = Kt.shape[2]
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib().sage_tree_attention(_ptr(Q), _ptr(Kc), _ptr(Vc), _ptr(Kt), _ptr(Vt), _ptr(O), _dtype_code(Q), B, Hq, Hkv,
+                                   d, _ptr(kv_start), _ptr(kv_len), max_kv_len, kv_token_stride, kv_head_stride,
+                                   _ptr(anc_mask), _ptr(n_nodes), scale, _ptr(workspace), ws_bytes, _stream(stream))
+    _check("sage_tree_attention", rc)
+
+
+def sage_verify_accept(token, target_argmax, parent, depth, anc_mask, n_nodes, path_cap, accept_len, best_node,
+                       path_nodes, out_tokens, stream=None):
+    B = n_nodes.shape[0]
+    rc = lib().sage_verify_accept(_ptr(token), _ptr(target_argmax), _ptr(parent), _ptr(depth), _ptr(anc_mask),
+                                  _ptr(n_nodes), B, path_cap, _ptr(accept_len), _ptr(best_node), _ptr(path_nodes),
+                                  _ptr(out_tokens), _stream(stream))
+    _check("sage_verify_accept", rc)
+
+
+def sage_build_info() -> str:
+    return lib().sage_build_info().decode()

@@ -1,0 +1,114 @@
+"""Helpers of the GPU parity tests: move seeded numpy inputs to the device, call the C-ABI binding, compare."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_2602_00523_amd import sage
+from paper_2602_00523_amd import workloads as wl
+
+MAX_NODES = 64
+DEV = "cuda:0"
+
+
+def to_dev(a: np.ndarray) -> torch.Tensor:
+    """numpy -> device tensor; uint16 arrays are bf16 bit patterns; uint64 travels as int64 bits."""
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).to(DEV).view(torch.bfloat16)
+    if a.dtype == np.uint64:
+        return torch.from_numpy(a.view(np.int64)).to(DEV)
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def widen(a: np.ndarray) -> np.ndarray:
+    return a.astype(np.float64) if a.dtype != np.uint16 else wl.bf16_bits_to_f32(a).astype(np.float64)
+
+
+def gpu_entropy_topk(logits_np, k, n_valid=None, rows_per_group=1):
+    if logits_np.flags["C_CONTIGUOUS"]:
+        x = to_dev(logits_np)
+    else:                                            # a column slice of a padded buffer: keep the row stride
+        full = logits_np.base
+        assert full is not None and full.shape[0] == logits_np.shape[0]
+        x = to_dev(full)[:, :logits_np.shape[1]]
+    rows, vocab = x.shape
+    f = lambda *s: torch.full(s, float("nan"), device=DEV, dtype=torch.float32)
+    out = dict(entropy=f(rows), topk_idx=torch.full((rows, k), -1, device=DEV, dtype=torch.int32), topk_prob=f(rows, k),
+               topk_renorm=f(rows, k), topk_entropy=f(rows), alpha=f(rows))
+    ws = torch.empty(sage.sage_entropy_topk_workspace_bytes(rows, vocab, k), device=DEV, dtype=torch.uint8)
+    nv = None if n_valid is None else to_dev(np.asarray(n_valid, np.int32))
+    sage.sage_entropy_topk(x, k, out["entropy"], out["topk_idx"], out["topk_prob"], out["topk_renorm"],
+                           out["topk_entropy"], out["alpha"], ws, nv, rows_per_group)
+    torch.cuda.synchronize()
+    return {key: v.cpu().numpy() for key, v in out.items()}
+
+
+def gpu_build_tree(topk_renorm_np, alpha_np, prm: dict):
+    pt, al = to_dev(np.ascontiguousarray(topk_renorm_np, np.float32)), to_dev(np.ascontiguousarray(alpha_np, np.float32))
+    B = pt.shape[0]
+    i32 = lambda fill: torch.full((B, MAX_NODES), fill, device=DEV, dtype=torch.int32)
+    out = dict(n_nodes=torch.zeros(B, device=DEV, dtype=torch.int32), parent=i32(-2), depth=i32(-2), rank=i32(-2),
+               anc_mask=torch.zeros((B, MAX_NODES), device=DEV, dtype=torch.int64),
+               cum_prob=torch.full((B, MAX_NODES), float("nan"), device=DEV, dtype=torch.float32))
+    sage.sage_build_tree(pt, al, sage.tree_params(**prm), out["n_nodes"], out["parent"], out["depth"], out["rank"],
+                         out["anc_mask"], out["cum_prob"])
+    torch.cuda.synchronize()
+    res = {key: v.cpu().numpy() for key, v in out.items()}
+    res["anc_mask"] = res["anc_mask"].view(np.uint64)
+    return res
+
+
+def gpu_tree_attention(inp: dict, anc_mask_np, n_nodes_np, Hq, Hkv, d, scale=None, fill=None):
+    """inp as produced by workloads.attention_inputs.  Returns O widened to fp64 ([B,64,Hq,d]) and the raw tensor."""
+    Q, Kc, Vc, Kt, Vt = (to_dev(inp[k]) for k in ("Q", "Kc", "Vc", "Kt", "Vt"))
+    B = Q.shape[0]
+    O = torch.zeros_like(Q)
+    if fill is not None:
+        O.fill_(fill)
+    kv_start, kv_len = to_dev(np.asarray(inp["kv_start"], np.int64)), to_dev(np.asarray(inp["kv_len"], np.int32))
+    mask, nn = to_dev(np.ascontiguousarray(anc_mask_np, np.uint64)), to_dev(np.asarray(n_nodes_np, np.int32))
+    max_len = int(np.max(inp["kv_len"])) if B else 0
+    code = sage.F32 if Q.dtype == torch.float32 else sage.BF16
+    ws = torch.empty(sage.sage_tree_attention_workspace_bytes(code, B, Hq, Hkv, d, max_len), device=DEV, dtype=torch.uint8)
+    if scale is None:
+        scale = 1.0 / float(np.sqrt(d))
+    sage.sage_tree_attention(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_len, inp["kv_token_stride"],
+                             inp["kv_head_stride"], mask, nn, scale, ws)
+    torch.cuda.synchronize()
+    return widen(to_host(O)), O
+
+
+def gpu_verify_accept(token, target_argmax, parent, depth, anc_mask, n_nodes, path_cap):
+    B = len(n_nodes)
+    args = [to_dev(np.ascontiguousarray(a, np.int32)) for a in (token, target_argmax, parent, depth)]
+    mask, nn = to_dev(np.ascontiguousarray(anc_mask, np.uint64)), to_dev(np.ascontiguousarray(n_nodes, np.int32))
+    out = dict(accept_len=torch.full((B,), -9, device=DEV, dtype=torch.int32),
+               best_node=torch.full((B,), -9, device=DEV, dtype=torch.int32),
+               path_nodes=torch.full((B, path_cap), -9, device=DEV, dtype=torch.int32),
+               out_tokens=torch.full((B, path_cap), -9, device=DEV, dtype=torch.int32))
+    sage.sage_verify_accept(*args, mask, nn, path_cap, out["accept_len"], out["best_node"], out["path_nodes"],
+                            out["out_tokens"])
+    torch.cuda.synchronize()
+    return {key: v.cpu().numpy() for key, v in out.items()}
+
+
+def assert_attention_close(gpu64, ref64, n_nodes, tol):
+    """Per (node, head) row: relative L2 error and max error relative to the row's largest magnitude, both <= tol."""
+    B = ref64.shape[0]
+    worst = 0.0
+    for b in range(B):
+        n = int(n_nodes[b])
+        g, r = gpu64[b, :n], ref64[b, :n]
+        assert np.isfinite(g).all(), f"non-finite output in sequence {b}"
+        l2 = np.linalg.norm(g - r, axis=-1) / np.maximum(np.linalg.norm(r, axis=-1), 1e-300)
+        mx = np.abs(g - r).max(-1) / np.maximum(np.abs(r).max(-1), 1e-300)
+        worst = max(worst, float(l2.max()), float(mx.max()))
+        assert l2.max() <= tol, f"seq {b}: rel L2 {l2.max():.3e} > {tol}"
+        assert mx.max() <= tol, f"seq {b}: rel max {mx.max():.3e} > {tol}"
+    return worst

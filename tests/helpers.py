@@ -45,7 +45,7 @@ def mask_by_walk(par: np.ndarray) -> np.ndarray:
     for v, s in enumerate(ancestor_sets(par)):
         bits = 0
         for u in s:
-            bits |= 1 << u
+            bits |= 1 << int(u)
         m[v] = np.uint64(bits)
     return m
 

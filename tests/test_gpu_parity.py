@@ -1,0 +1,267 @@
+"""GPU parity: every call of the C-ABI HIP library against the CPU oracle on the same seeded inputs.
+
+Integer outputs (top-k indices, trees, masks, acceptance) are bit-exact; entropies/probabilities agree to 1e-5
+(the kernels compute them in fp32 whatever the logits' storage type); attention outputs agree per (node, head)
+row to 1e-5 (fp32) / 2e-2 (bf16) in relative L2 norm and in max error relative to the row's largest magnitude.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import MAX_NODES, chain_parents, pad_tree, random_parents, star_parents
+from paper_2602_00523_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import gpu_utils
+    from paper_2602_00523_amd import sage
+    print("\n[lib]", sage.sage_build_info(), flush=True)
+    return gpu_utils
+
+
+def close(gpu, ref, tol=1e-5):
+    return np.abs(gpu.astype(np.float64) - ref) <= tol * np.maximum(np.abs(ref), 1.0)
+
+
+def check_entropy(gu, logits, k, n_valid=None, rpg=1, tol=1e-5):
+    o = oracle.entropy_topk(logits, k, n_valid, rpg)
+    g = gu.gpu_entropy_topk(logits, k, n_valid, rpg)
+    rows = logits.shape[0]
+    valid = np.ones(rows, bool) if n_valid is None else np.array([(r % rpg) < n_valid[r // rpg] for r in range(rows)])
+    np.testing.assert_array_equal(g["topk_idx"][valid], o["topk_idx"][valid])
+    for key in ("entropy", "topk_entropy", "alpha"):
+        assert close(g[key][valid], o[key][valid], tol).all(), key
+    for key in ("topk_prob", "topk_renorm"):
+        assert close(g[key][valid], o[key][valid], tol).all(), key
+        rel = np.abs(g[key][valid] - o[key][valid]) <= 1e-4 * o[key][valid] + 1e-30
+        assert rel.all(), key + " (relative)"
+    # skipped rows are untouched
+    assert (g["topk_idx"][~valid] == -1).all() and np.isnan(g["entropy"][~valid]).all()
+    return o, g
+
+
+# ------------------------------------------------------------------ a1 / a1'
+
+def test_entropy_topk_toy_rows(gu):
+    temps = wl.toy_temperatures(32)
+    z = wl.gaussian(wl.seed_for("toy", 0, 1), (32, 1024), "f32")
+    logits = (z / temps[:, None].astype(np.float32)).astype(np.float32)
+    o, _ = check_entropy(gu, logits, 8)
+    assert o["entropy"].min() < 4.0 and o["entropy"].max() > 6.5        # spans peaked to near-uniform rows
+
+
+@pytest.mark.parametrize("vocab,k,dtype", [(152064, 10, "bf16"), (152064, 16, "bf16"), (152064, 1, "bf16"),
+                                           (4099, 5, "f32"), (1000, 64, "f32"), (70001, 3, "bf16")])
+def test_entropy_topk_shapes(gu, vocab, k, dtype):
+    rows = 6
+    stride = (vocab + 15) // 16 * 16
+    scales = np.array([0.3, 1.0, 3.5, 5.0, 9.0, 40.0], np.float32)
+    z = wl.rng(vocab + k).standard_normal((rows, stride), dtype=np.float32) * scales[:, None]
+    buf = wl.to_storage(z, dtype)
+    check_entropy(gu, buf[:, :vocab], k)
+
+
+def test_entropy_topk_closed_forms_and_ties(gu):
+    V = 152064
+    x = np.zeros((4, V), np.float32)
+    x[1] = -np.inf
+    x[1, 777] = 2.0
+    x[2] = -np.inf
+    x[2, 5] = x[2, 150000] = 1.0
+    x[3, :] = 7.25                                   # uniform with a tie everywhere: top-k = lowest indices
+    o, g = check_entropy(gu, wl.to_storage(x, "bf16"), 10)
+    assert abs(g["entropy"][0] - np.log(V)) < 1e-4 and abs(g["alpha"][0]) < 1e-6
+    assert g["entropy"][1] == 0.0 and g["alpha"][1] == 1.0 and g["topk_idx"][1, 0] == 777
+    assert abs(g["entropy"][2] - np.log(2)) < 1e-6 and list(g["topk_idx"][2, :2]) == [5, 150000]
+    assert list(g["topk_idx"][3]) == list(range(10))
+
+
+def test_entropy_topk_row_groups_k1(gu):
+    V, rpg = 152064, 64
+    n_valid = np.array([9, 0, 64], np.int32)
+    z = wl.gaussian(77, (3 * rpg, V), "bf16", 4.0)
+    o, g = check_entropy(gu, z, 1, n_valid, rpg)
+    assert (g["alpha"][:9] == 1.0).all()
+
+
+# ------------------------------------------------------------------ a2
+
+def test_build_tree_bit_exact(gu):
+    g = wl.rng(2024)
+    cases = [("paper", wl.CONFIGS["c2"]["tree"]), ("c3", wl.CONFIGS["c3"]["tree"]), ("toy", wl.CONFIGS["toy"]["tree"]),
+             ("cap", dict(d_min=8, d_max=20, w_min=6, w_max=12, k=12, n_max=20)),
+             ("one", dict(d_min=1, d_max=1, w_min=1, w_max=1, k=1, n_max=1))]
+    for name, prm in cases:
+        B, k = 512, prm["k"]
+        pt = np.sort(g.random((B, k)) ** g.integers(1, 7, size=(B, 1)), axis=1)[:, ::-1]
+        pt = (pt / pt.sum(1, keepdims=True)).astype(np.float32)
+        alpha = g.random(B).astype(np.float32)
+        alpha[:4] = [0.0, 1.0, 0.5, 0.1]
+        pt[4] = 0
+        pt[4, 0] = 1                                 # one-hot
+        pt[5] = 1.0 / k                              # flat
+        o = oracle.build_tree(pt, alpha, prm)
+        t = gu.gpu_build_tree(pt, alpha, prm)
+        np.testing.assert_array_equal(t["n_nodes"], o["n_nodes"], err_msg=name)
+        for key in ("parent", "depth", "rank", "anc_mask", "cum_prob"):
+            for b in range(B):
+                n = int(o["n_nodes"][b])
+                np.testing.assert_array_equal(t[key][b, :n], o[key][b, :n], err_msg=f"{name} {key} seq {b}")
+            if key != "cum_prob":
+                assert (t[key][:, :][np.arange(MAX_NODES)[None, :] >= o["n_nodes"][:, None]] == (0 if key == "anc_mask" else -2)).all()
+        assert o["n_nodes"].max() == prm["n_max"] or name in ("paper", "toy", "c3")
+
+
+# ------------------------------------------------------------------ a4
+
+def test_verify_accept_bit_exact(gu):
+    g = wl.rng(99)
+    B = 600
+    parent = np.full((B, MAX_NODES), -7, np.int32)
+    depth = np.full((B, MAX_NODES), -7, np.int32)
+    mask = np.zeros((B, MAX_NODES), np.uint64)
+    nn = np.zeros(B, np.int32)
+    tok = g.integers(0, 3, (B, MAX_NODES)).astype(np.int32)
+    tgt = g.integers(0, 3, (B, MAX_NODES)).astype(np.int32)
+    for b in range(B):
+        n = int(g.integers(1, 65)) if b > 3 else (1, 64, 2, 33)[b]
+        par = random_parents(g, n, chain_bias=float(g.random()))
+        p, d, m, _ = pad_tree(par)
+        parent[b], depth[b], mask[b], nn[b] = p[0], d[0], m[0], n
+        if b % 5 == 0:                               # force long accepted paths
+            tok[b, 1:n] = tgt[b, par[1:]]
+            if n > 3 and b % 10 == 0:
+                tok[b, n // 2] = 9
+    cap = 65
+    o = oracle.verify_accept(tok, tgt, parent, depth, nn, cap)
+    r = gu.gpu_verify_accept(tok, tgt, parent, depth, mask, nn, cap)
+    for key in ("accept_len", "best_node", "path_nodes", "out_tokens"):
+        np.testing.assert_array_equal(r[key], o[key], err_msg=key)
+    assert o["accept_len"].max() >= 10 and o["accept_len"].min() == 0
+
+
+# ------------------------------------------------------------------ a3
+
+def tree_batch(g, B, sizes=None, kind="random"):
+    mask = np.zeros((B, MAX_NODES), np.uint64)
+    nn = np.zeros(B, np.int32)
+    for b in range(B):
+        n = int(sizes[b]) if sizes is not None else int(g.integers(1, 65))
+        par = {"random": lambda: random_parents(g, n, chain_bias=0.5), "chain": lambda: chain_parents(n),
+               "star": lambda: star_parents(n)}[kind]()
+        _, _, m, _ = pad_tree(par)
+        mask[b], nn[b] = m[0], n
+    return mask, nn
+
+
+def run_attention_case(gu, seed, dtype, B, Hq, Hkv, d, lens, sizes=None, kind="random", pad=3):
+    g = wl.rng(seed)
+    inp = wl.attention_inputs(seed, B, Hq, Hkv, d, lens, dtype, pad_tokens=pad)
+    mask, nn = tree_batch(g, B, sizes, kind)
+    ref = oracle.tree_attention(inp["Q"], inp["Kc"], inp["Vc"], inp["Kt"], inp["Vt"], inp["kv_start"], inp["kv_len"],
+                                inp["kv_token_stride"], inp["kv_head_stride"], mask, nn, Hq, Hkv, d)
+    got, raw = gu.gpu_tree_attention(inp, mask, nn, Hq, Hkv, d, fill=12345.0)
+    worst = gu.assert_attention_close(got, ref, nn, TOL[dtype])
+    for b in range(B):                               # rows at or beyond n_nodes are not written
+        assert (got[b, int(nn[b]):] == 12345.0).all() or dtype == "bf16" and np.allclose(got[b, int(nn[b]):], 12352.0)
+    return worst
+
+
+def test_attention_toy_f32(gu):
+    w = run_attention_case(gu, wl.seed_for("toy"), "f32", 1, 4, 1, 64, [256], sizes=[16])
+    print(f" worst rel err {w:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,d,lens", [(2, 4, 2, 64, [300, 0]), (1, 6, 3, 32, [1]), (3, 8, 1, 128, [511, 257, 64]),
+                                             (1, 2, 2, 256, [1000])])
+def test_attention_f32_shapes(gu, B, Hq, Hkv, d, lens):
+    run_attention_case(gu, 5 + B + d, "f32", B, Hq, Hkv, d, lens)
+
+
+@pytest.mark.parametrize("kind,sizes,lens", [
+    ("random", [64], [1000]),           # several tiles and a ragged tail, full tree
+    ("random", [1], [64]),              # single node, exactly one tile
+    ("chain", [9], [777]),              # deep-narrow tree of the confident regime
+    ("star", [17], [130]),              # shallow-wide tree
+    ("random", [33], [0]),              # empty cache: tree keys only
+    ("random", [5], [63]),
+    ("random", [20], [4096]),
+])
+def test_attention_bf16_72b_heads_single(gu, kind, sizes, lens):
+    w = run_attention_case(gu, 40 + sizes[0] + lens[0], "bf16", 1, 64, 8, 128, lens, sizes, kind)
+    print(f" worst rel err {w:.2e}", flush=True)
+
+
+def test_attention_bf16_ragged_batch(gu):
+    g = wl.rng(8)
+    B = 5
+    lens = g.integers(0, 700, size=B)
+    sizes = [8, 64, 1, 30, 47]
+    run_attention_case(gu, 81, "bf16", B, 64, 8, 128, lens, sizes)
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (16, 4), (32, 2)])
+def test_attention_bf16_other_group_sizes(gu, Hq, Hkv):
+    run_attention_case(gu, 90 + Hq, "bf16", 2, Hq, Hkv, 128, [333, 70], sizes=[64, 11])
+
+
+def test_attention_is_deterministic(gu):
+    inp = wl.attention_inputs(3, 1, 64, 8, 128, [2000], "bf16")
+    mask, nn = tree_batch(wl.rng(3), 1, [40])
+    a, _ = gu.gpu_tree_attention(inp, mask, nn, 64, 8, 128)
+    b, _ = gu.gpu_tree_attention(inp, mask, nn, 64, 8, 128)
+    np.testing.assert_array_equal(a, b)
+
+
+# ------------------------------------------------------------------ whole step, Toy configuration
+
+def test_toy_pipeline_32_steps(gu):
+    cfg = wl.CONFIGS["toy"]
+    prm, k, V = cfg["tree"], cfg["tree"]["k"], cfg["vocab"]
+    temps = wl.toy_temperatures(cfg["steps"])
+    taus = []
+    for step in range(cfg["steps"]):
+        seed = wl.seed_for("toy", step)
+        z = wl.gaussian(seed, (1, V), "f32")
+        draft = (z / np.float32(temps[step])).astype(np.float32)
+        # a1: confidence from the draft distribution
+        o1 = oracle.entropy_topk(draft, k)
+        g1 = gu.gpu_entropy_topk(draft, k)
+        np.testing.assert_array_equal(g1["topk_idx"], o1["topk_idx"])
+        assert close(g1["alpha"], o1["alpha"]).all() and close(g1["topk_renorm"], o1["topk_renorm"]).all()
+        # a2: the oracle consumes the GPU's fp32 bits so a 1-ulp difference upstream cannot pose as a tree mismatch
+        o2 = oracle.build_tree(g1["topk_renorm"], g1["alpha"], prm)
+        g2 = gu.gpu_build_tree(g1["topk_renorm"], g1["alpha"], prm)
+        n = int(o2["n_nodes"][0])
+        assert g2["n_nodes"][0] == n
+        for key in ("parent", "depth", "rank", "anc_mask"):
+            np.testing.assert_array_equal(g2[key][0, :n], o2[key][0, :n])
+        # a3
+        inp = wl.attention_inputs(seed + 50000, 1, cfg["Hq"], cfg["Hkv"], cfg["d"], [cfg["kv_len"]], "f32")
+        ref = oracle.tree_attention(inp["Q"], inp["Kc"], inp["Vc"], inp["Kt"], inp["Vt"], inp["kv_start"], inp["kv_len"],
+                                    inp["kv_token_stride"], inp["kv_head_stride"], o2["anc_mask"], o2["n_nodes"],
+                                    cfg["Hq"], cfg["Hkv"], cfg["d"])
+        got, _ = gu.gpu_tree_attention(inp, g2["anc_mask"], g2["n_nodes"], cfg["Hq"], cfg["Hkv"], cfg["d"])
+        gu.assert_attention_close(got, ref, o2["n_nodes"], 1e-5)
+        # a1': the target's greedy token per node; node tokens are the draft's top-k candidates by rank
+        tgt_logits = np.zeros((MAX_NODES, V), np.float32)
+        tgt_logits[:n] = wl.target_logits_from_draft(seed + 60000, draft[0], n, "f32", 0.35 / temps[step])
+        o1t = oracle.entropy_topk(tgt_logits, 1, o2["n_nodes"], MAX_NODES)
+        g1t = gu.gpu_entropy_topk(tgt_logits, 1, g2["n_nodes"], MAX_NODES)
+        np.testing.assert_array_equal(g1t["topk_idx"][:n], o1t["topk_idx"][:n])
+        token = np.zeros((1, MAX_NODES), np.int32)
+        token[0, 1:n] = g1["topk_idx"][0, g2["rank"][0, 1:n]]
+        tgt = g1t["topk_idx"][:, 0].reshape(1, MAX_NODES)
+        # a4
+        o4 = oracle.verify_accept(token, tgt, o2["parent"], o2["depth"], o2["n_nodes"], prm["d_max"] + 1)
+        g4 = gu.gpu_verify_accept(token, tgt, g2["parent"], g2["depth"], g2["anc_mask"], g2["n_nodes"], prm["d_max"] + 1)
+        for key in ("accept_len", "best_node", "path_nodes", "out_tokens"):
+            np.testing.assert_array_equal(g4[key], o4[key], err_msg=f"step {step} {key}")
+        taus.append(int(o4["accept_len"][0]))
+    print(f" accepted lengths over 32 steps: mean {np.mean(taus):.2f}, max {max(taus)}", flush=True)
+    assert max(taus) >= 2
