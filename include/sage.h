@@ -100,13 +100,19 @@ int sage_entropy_topk(const void* logits, int dtype, int rows, int vocab, long r
  * next step from the current step's distribution).
  *
  * topk_renorm [B,k] f32, alpha [B] f32, params (host) copied at call time.
+ * topk_idx [B,k] i32, nullable: the vocabulary ids of the k candidates (as written by
+ * sage_entropy_topk); with it, node_token[b][v] = topk_idx[b][rank(v)] is the draft token of
+ * node v (the candidate a node stands for), root -1.
  * n_nodes [B] i32; parent, depth, rank [B,64] i32 (root: -1, 0, -1); anc_mask [B,64] u64,
- * bit j of anc_mask[b][v] set iff j is v or an ancestor of v; cum_prob [B,64] f32, nullable.
- * Errors: INVALID_ARG for null pointers, B < 0, k != params->k, parameter constraints.
+ * bit j of anc_mask[b][v] set iff j is v or an ancestor of v; cum_prob [B,64] f32, nullable;
+ * node_token [B,64] i32, nullable (requires topk_idx).
+ * Errors: INVALID_ARG for null pointers, B < 0, k != params->k, parameter constraints,
+ * node_token without topk_idx.
  */
-int sage_build_tree(const float* topk_renorm, const float* alpha, int B, int k, const sage_tree_params* params,
+int sage_build_tree(const float* topk_renorm, const float* alpha, const int* topk_idx, int B, int k,
+                    const sage_tree_params* params,
                     int* n_nodes, int* parent, int* depth, int* rank, uint64_t* anc_mask, float* cum_prob,
-                    void* stream);
+                    int* node_token, void* stream);
 
 /* ------------------------------------------------------------------------------------------
  * sage_tree_attention -- the attention operator of the verify pass (Alg. 1 Phase 2) under

@@ -80,7 +80,7 @@ def entropy_topk(logits: np.ndarray, k: int, n_valid: np.ndarray | None = None, 
     return out
 
 
-def build_tree(topk_renorm: np.ndarray, alpha: np.ndarray, params: dict):
+def build_tree(topk_renorm: np.ndarray, alpha: np.ndarray, params: dict, topk_idx: np.ndarray | None = None):
     """O2 (Sec. 3.2, Eq. 10-12 and the membership rule).  fp32 inputs, bit-for-bit."""
     pr = np.ascontiguousarray(topk_renorm, np.float32)
     al = np.ascontiguousarray(alpha, np.float32)
@@ -89,9 +89,13 @@ def build_tree(topk_renorm: np.ndarray, alpha: np.ndarray, params: dict):
     out = dict(
         n_nodes=np.zeros(B, np.int32), parent=np.full((B, MAX_NODES), -2, np.int32),
         depth=np.full((B, MAX_NODES), -2, np.int32), rank=np.full((B, MAX_NODES), -2, np.int32),
-        anc_mask=np.zeros((B, MAX_NODES), np.uint64), cum_prob=np.full((B, MAX_NODES), np.nan, np.float32))
-    rc = lib().oracle_build_tree(_p(pr), _p(al), B, k, ctypes.byref(tp), _p(out["n_nodes"]), _p(out["parent"]),
-                                 _p(out["depth"]), _p(out["rank"]), _p(out["anc_mask"]), _p(out["cum_prob"]))
+        anc_mask=np.zeros((B, MAX_NODES), np.uint64), cum_prob=np.full((B, MAX_NODES), np.nan, np.float32),
+        node_token=np.full((B, MAX_NODES), -2, np.int32))
+    if topk_idx is not None:
+        topk_idx = np.ascontiguousarray(topk_idx, np.int32)
+    rc = lib().oracle_build_tree(_p(pr), _p(al), _p(topk_idx), B, k, ctypes.byref(tp), _p(out["n_nodes"]),
+                                 _p(out["parent"]), _p(out["depth"]), _p(out["rank"]), _p(out["anc_mask"]),
+                                 _p(out["cum_prob"]), _p(out["node_token"]))
     if rc:
         raise ValueError(f"oracle_build_tree status {rc}")
     return out

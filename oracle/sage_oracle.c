@@ -198,12 +198,14 @@ static void expand(tree_state* t, int u) {
  * Per sequence b: D = round-half-up of Eq. (10), W = round-half-up of Eq. (11)
  * capped at k; root = node 0 (parent -1, depth 0, rank -1, cum 1); nodes are
  * emitted in creation order (DFS pre-order), so parent[v] < v.  Arrays are
- * [B, 64]; entries at or beyond n_nodes[b] are left untouched.
+ * [B, 64]; entries at or beyond n_nodes[b] are left untouched.  When the
+ * candidates' vocabulary ids topk_idx [B,k] are given, node_token[v] is the
+ * id of the candidate node v stands for (root -1).
  */
-int oracle_build_tree(const float* topk_renorm, const float* alpha, int B, int k,
+int oracle_build_tree(const float* topk_renorm, const float* alpha, const int* topk_idx, int B, int k,
                       const oracle_tree_params* p,
                       int* n_nodes, int* parent, int* depth, int* rank, uint64_t* anc_mask,
-                      float* cum_prob) {
+                      float* cum_prob, int* node_token) {
     if (!topk_renorm || !alpha || !p || B < 0) return 1;
     if (p->k != k || k < 1 || p->n_max < 1 || p->n_max > ORACLE_MAX_NODES) return 1;
     if (p->d_min < 1 || p->d_min > p->d_max || p->w_min < 1 || p->w_min > p->w_max || p->w_max > k) return 1;
@@ -224,6 +226,12 @@ int oracle_build_tree(const float* topk_renorm, const float* alpha, int B, int k
         t.parent[0] = -1; t.depth[0] = 0; t.rank[0] = -1; t.cum[0] = 1.0f; t.mask[0] = 1;
         expand(&t, 0);
         n_nodes[b] = t.n;
+        /* a node stands for the candidate of its rank: its draft token is that candidate's vocabulary id */
+        if (node_token && topk_idx) {
+            node_token[(long)b * ORACLE_MAX_NODES] = -1;
+            for (int v = 1; v < t.n; ++v)
+                node_token[(long)b * ORACLE_MAX_NODES + v] = topk_idx[(long)b * k + t.rank[v]];
+        }
     }
     return 0;
 }

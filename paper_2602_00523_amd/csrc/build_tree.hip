@@ -18,9 +18,10 @@ struct Frame {
 };
 
 __global__ __launch_bounds__(64) void build_tree_kernel(
-    const float* __restrict__ topk_renorm, const float* __restrict__ alpha, int k, sage_tree_params prm,
-    int* __restrict__ n_nodes, int* __restrict__ parent, int* __restrict__ depth, int* __restrict__ rank,
-    uint64_t* __restrict__ anc_mask, float* __restrict__ cum_prob) {
+    const float* __restrict__ topk_renorm, const float* __restrict__ alpha, const int* __restrict__ topk_idx, int k,
+    sage_tree_params prm, int* __restrict__ n_nodes, int* __restrict__ parent, int* __restrict__ depth,
+    int* __restrict__ rank, uint64_t* __restrict__ anc_mask, float* __restrict__ cum_prob,
+    int* __restrict__ node_token) {
     __shared__ float s_pt[SAGE_MAX_TOPK];
     __shared__ int s_parent[SAGE_MAX_NODES], s_depth[SAGE_MAX_NODES], s_rank[SAGE_MAX_NODES];
     __shared__ float s_cum[SAGE_MAX_NODES];
@@ -86,23 +87,25 @@ __global__ __launch_bounds__(64) void build_tree_kernel(
         rank[base + lane] = s_rank[lane];
         anc_mask[base + lane] = s_mask[lane];
         if (cum_prob) cum_prob[base + lane] = s_cum[lane];
+        if (node_token) node_token[base + lane] = lane == 0 ? -1 : topk_idx[static_cast<long>(b) * k + s_rank[lane]];
     }
     if (lane == 0) n_nodes[b] = n;
 }
 
 }  // namespace
 
-extern "C" int sage_build_tree(const float* topk_renorm, const float* alpha, int B, int k,
+extern "C" int sage_build_tree(const float* topk_renorm, const float* alpha, const int* topk_idx, int B, int k,
                                const sage_tree_params* params, int* n_nodes, int* parent, int* depth, int* rank,
-                               uint64_t* anc_mask, float* cum_prob, void* stream) {
+                               uint64_t* anc_mask, float* cum_prob, int* node_token, void* stream) {
     if (!topk_renorm || !alpha || !params || !n_nodes || !parent || !depth || !rank || !anc_mask) return SAGE_INVALID_ARG;
+    if (node_token && !topk_idx) return SAGE_INVALID_ARG;
     const sage_tree_params p = *params;
     if (B < 0 || k != p.k || k < 1 || k > SAGE_MAX_TOPK) return SAGE_INVALID_ARG;
     if (p.n_max < 1 || p.n_max > SAGE_MAX_NODES) return SAGE_INVALID_ARG;
     if (p.d_min < 1 || p.d_min > p.d_max || p.d_max > SAGE_MAX_DEPTH) return SAGE_INVALID_ARG;
     if (p.w_min < 1 || p.w_min > p.w_max || p.w_max > k) return SAGE_INVALID_ARG;
     if (B == 0) return SAGE_OK;
-    hipLaunchKernelGGL(build_tree_kernel, dim3(B), dim3(64), 0, sage::as_stream(stream), topk_renorm, alpha, k, p,
-                       n_nodes, parent, depth, rank, anc_mask, cum_prob);
+    hipLaunchKernelGGL(build_tree_kernel, dim3(B), dim3(64), 0, sage::as_stream(stream), topk_renorm, alpha, topk_idx,
+                       k, p, n_nodes, parent, depth, rank, anc_mask, cum_prob, node_token);
     return sage::launch_status();
 }

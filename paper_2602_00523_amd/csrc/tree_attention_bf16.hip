@@ -3,41 +3,59 @@
 //
 // Formulation.  All query rows that share a KV head (node i, head-in-group hg -> row m = i*G + hg, up to 512
 // rows) are processed together so each K/V byte is fetched from HBM once.  Everything is computed transposed:
-//   S^T = K Q^T   (tokens x rows):  A operand = K rows straight from the cache layout (16-byte reads),
+//   S^T = K Q^T   (tokens x rows):  A operand = K rows as stored in the cache (16-byte LDS reads),
 //                                   B operand = Q rows held in registers for the whole kernel;
-//   O^T = V^T P^T (dims x rows):    A operand = V^T from LDS, B operand = P^T.
+//   O^T = V^T P^T (dims x rows):    A operand = V^T, read from row-major V in LDS with the transposing
+//                                   64-bit LDS read of gfx950, B operand = P^T.
 // In the 32x32 MFMA accumulator layout a lane owns ONE query row (column lane%32) and 16 tokens of it, so the
-// softmax max/sum are in-register reductions plus a single cross-half exchange, the rescale factor is a per-lane
+// softmax max/sum are in-register reductions plus one cross-half lane swap, the rescale factor is a per-lane
 // scalar, and the accumulator registers of S^T are, as they stand, the B operand of the PV product (the token
-// order inside a k-block is whatever the accumulator layout says; V^T is staged in LDS in that same order).
+// order inside a 16-token k-block is whatever the accumulator layout says; the V^T reads follow that order).
+// The running maximum is only raised when a score exceeds it by more than 2^8 in the exp2 domain, so the
+// accumulator is rescaled a handful of times per kernel instead of once per tile; the final normalisation
+// uses the same reference maximum for numerator and denominator, so the result is unchanged.
 //
-// Decomposition (decided on the device from n_nodes/kv_len, so no host round trip): a workgroup of 4 waves
-// owns (sequence, KV head, group of 4 column tiles = 128 query rows, KV split); wave w owns column tile w of
-// the group.  Workgroups of one KV head are congruent modulo the KV-head count, which with 8 KV heads pins a
-// head to one XCD and its L2: column groups of the same split re-read K/V from that L2, not from HBM.
-// K/V tiles of 64 tokens are double-buffered in LDS (register-staged loads one tile ahead; V is transposed in
-// registers on the way in).  Each workgroup writes an un-normalised partial (max, sum, O^T); a second kernel
-// merges the splits in a fixed order (deterministic, no float atomics) and writes bf16.
+// Data movement.  K/V tiles of 64 tokens go from global memory straight into LDS (16-byte LDS-direct loads, no
+// staging registers) through a 4-stage ring, three tiles ahead of the MFMAs.  A wave-level load writes 1 KB of
+// contiguous LDS (4 token rows); bank conflicts are avoided by permuting the 16-byte chunks inside a row
+// (chunk c of token t sits at slot c ^ f(t)), which only changes which global address a lane fetches.  Every
+// stage is its own LDS object so that loads in flight into one stage are known not to alias reads of another.
+//
+// Decomposition (decided on the device from n_nodes/kv_len, so no host round trip): a workgroup of 8 waves
+// owns (sequence, KV head, group of up to 8 column tiles = 256 query rows, KV split).  With more than 4 column
+// tiles in the group a wave owns one column tile; with 4 or fewer, two waves share a column tile and each
+// takes one 32-token half of every tile, and the halves are combined through LDS at the end.  Workgroups of
+// one KV head are congruent modulo the KV-head count, which with 8 KV heads pins a head to one XCD and its L2:
+// the two column groups of a large tree re-read K/V from that L2, not from HBM.  Each workgroup writes an
+// un-normalised partial (max, sum, O^T); a second kernel merges the splits in a fixed order (deterministic,
+// no float atomics) and writes bf16.
+#include <stdlib.h>
+
+#include <type_traits>
+
 #include "sage_internal.h"
 
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
+#define LDS_AS __attribute__((address_space(3)))
 
 constexpr int D = 128;                  // head_dim
 constexpr int TILE = 64;                // tokens per LDS stage
-constexpr int THREADS = 256;
-constexpr int CT_PER_WG = 4;            // column tiles (of 32 query rows) per workgroup
+constexpr int THREADS = 512;
+constexpr int CT_PER_WG = 8;            // column tiles (of 32 query rows) per workgroup
 constexpr int ROWS_PER_WG = CT_PER_WG * 32;
-constexpr int K_ROW_B = 272;            // LDS bytes per K token row (256 + 16 pad: 17 x 16 B, conflict-free b128 reads)
-constexpr int V_ROW_B = 144;            // LDS bytes per V^T dim row (128 + 16 pad: 9 x 16 B)
-constexpr int K_BYTES = TILE * K_ROW_B;
-constexpr int V_BYTES = D * V_ROW_B;
-constexpr int STAGE_BYTES = K_BYTES + V_BYTES;
-constexpr int PART_FLOATS = D + 2;      // per query row: O^T[128] in LDS-row order, then max, sum
+constexpr int ROW_B = 256;              // bytes of one token row (128 bf16), also its LDS footprint
+constexpr int TILE_B = TILE * ROW_B;    // 16 KB per K or V stage
+constexpr int STAGES = 4;
+constexpr int LOADS_PER_TILE = 2 * TILE_B / (THREADS * 16);   // LDS-direct loads per thread per tile (K and V)
+constexpr int PART_FLOATS = D + 2;      // per query row: O^T[128], then max, sum
+constexpr float RESCALE_THRESHOLD = 8.0f;   // raise the reference maximum only past 2^8
 
 struct Params {
     const uint16_t* Q; const uint16_t* Kc; const uint16_t* Vc; const uint16_t* Kt; const uint16_t* Vt;
@@ -45,7 +63,7 @@ struct Params {
     const int64_t* kv_start; const int* kv_len; const uint64_t* anc_mask; const int* n_nodes;
     float* part;                         // [B][Hkv][nslot][ROWS_PER_WG][PART_FLOATS]
     long kv_token_stride, kv_head_stride;
-    int B, Hq, Hkv, G, nslot;
+    int B, Hq, Hkv, G, nslot, debug;
     float scale_log2e;                   // softmax scale times log2(e): probabilities are exp2 of scaled differences
 };
 
@@ -67,12 +85,50 @@ __device__ __forceinline__ Split make_split(int n_nodes, int kv_len, int G, int 
     return s;
 }
 
-__device__ __forceinline__ bf16x8 lds_frag(const unsigned char* p) {
-    return __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(p));
+// LDS chunk permutations (see header): K is read 16 lanes = 16 consecutive tokens x one chunk at a time,
+// V is read 4 consecutive tokens x two adjacent chunks at a time.
+__device__ __forceinline__ int k_swz(int t) { return t & 15; }
+__device__ __forceinline__ int v_swz(int t) { return (t & 7) << 1; }
+
+// s_waitcnt on the vector-memory counter only (expcnt and lgkmcnt fields left at "no wait")
+template <int N> __device__ __forceinline__ void wait_vm() {
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
-__global__ __launch_bounds__(THREADS, 2) void tree_attention_bf16_kernel(const Params prm) {
-    __shared__ __align__(16) unsigned char smem[2 * STAGE_BYTES];
+// Workgroup barrier of the stage ring.  __syncthreads() would also fence, and a workgroup-scope release makes the
+// compiler wait for every LDS-direct load still in flight, which is exactly what the ring must not do: each
+// thread has already waited for its own share of the tile (wait_vm), LDS needs no cache maintenance, so the bare
+// barrier is enough; the wavefront-scope fences only pin the order of memory operations around it.
+__device__ __forceinline__ void stage_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// max / sum of a value with its partner in the other 32-lane half (both halves receive the result)
+__device__ __forceinline__ float cross_half_max(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float cross_half_sum(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+__global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Params prm) {
+    // one LDS object per stage and operand (see header)
+    __shared__ __align__(1024) unsigned char sK0[TILE_B];
+    __shared__ __align__(1024) unsigned char sK1[TILE_B];
+    __shared__ __align__(1024) unsigned char sK2[TILE_B];
+    __shared__ __align__(1024) unsigned char sK3[TILE_B];
+    __shared__ __align__(1024) unsigned char sV0[TILE_B];
+    __shared__ __align__(1024) unsigned char sV1[TILE_B];
+    __shared__ __align__(1024) unsigned char sV2[TILE_B];
+    __shared__ __align__(1024) unsigned char sV3[TILE_B];
+    __shared__ uint64_t s_mask[ROWS_PER_WG];
+    __shared__ float s_ml[4][2][32];                         // half-merge mailbox: per column tile, (max, sum) per row
+#define SK(i) ((i) == 0 ? sK0 : (i) == 1 ? sK1 : (i) == 2 ? sK2 : sK3)
+#define SV(i) ((i) == 0 ? sV0 : (i) == 1 ? sV1 : (i) == 2 ? sV2 : sV3)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -94,12 +150,25 @@ __global__ __launch_bounds__(THREADS, 2) void tree_attention_bf16_kernel(const P
     const int t_end = min(sp.tiles, t_begin + sp.tiles_per_split);
     const int tree_tile = sp.tiles - 1;
 
+    // ---- wave roles: column tile and the 32-token halves of each tile this wave takes
+    const int group_rows = min(ROWS_PER_WG, sp.rows - cg * ROWS_PER_WG);
+    const int group_ct = (group_rows + 31) / 32;             // 1..8 column tiles in this group
+    const bool shared_ct = group_ct <= 4;                    // two waves per column tile, one token half each
+    const int ct = shared_ct ? (wave & 3) : wave;
+    const int sub_lo = shared_ct ? (wave >> 2) : 0;
+    const bool wave_active = ct < group_ct && !(prm.debug & 1);
+
     // ---- this lane's query row
-    const int m = cg * ROWS_PER_WG + wave * 32 + r32;       // row within the KV head
+    const int m_local = ct * 32 + r32;                       // row within the group
+    const int m = cg * ROWS_PER_WG + m_local;                // row within the KV head
     const int node = m / prm.G;
-    const bool row_valid = m < sp.rows;
-    const bool wave_active = (cg * ROWS_PER_WG + wave * 32) < sp.rows;
-    const uint64_t tree_mask = row_valid ? prm.anc_mask[static_cast<long>(b) * SAGE_MAX_NODES + node] : 0ull;
+    const bool row_valid = ct < group_ct && m < sp.rows;
+    // the rows' ancestor-or-self masks wait in LDS until the tree tile comes
+    if (tid < ROWS_PER_WG) {
+        const int mm = cg * ROWS_PER_WG + tid;
+        s_mask[tid] = mm < sp.rows ? prm.anc_mask[static_cast<long>(b) * SAGE_MAX_NODES + mm / prm.G] : 0ull;
+    }
+    __syncthreads();                                         // masks visible before any LDS-direct load is in flight
 
     bf16x8 qf[8];
     {
@@ -112,169 +181,227 @@ __global__ __launch_bounds__(THREADS, 2) void tree_attention_bf16_kernel(const P
         }
     }
 
-    // ---- loader roles: waves 0,1 stage K (8 rows x 16 chunks per instruction), waves 2,3 stage V transposed
-    const bool k_loader = wave < 2;
-    const int lu = tid & 127;
-    const int chunk = lu & 15;                               // 16-byte chunk (8 dims) of a 256-byte row
-    const int lgrp = lu >> 4;                                // K: token row within each group of 8; V: position group
-    const uint16_t* cache_base = (k_loader ? prm.Kc : prm.Vc) + prm.kv_start[b] * prm.kv_token_stride +
-                                 static_cast<long>(g) * prm.kv_head_stride + chunk * 8;
-    const uint16_t* tree_base = (k_loader ? prm.Kt : prm.Vt) + (static_cast<long>(b) * SAGE_MAX_NODES * prm.Hkv + g) * D + chunk * 8;
-    const long tree_stride = static_cast<long>(prm.Hkv) * D;
+    // ---- loader: wave w copies token rows 8w..8w+7 of K and of V, four rows (1 KB of LDS) per instruction;
+    //      lane l fills slot l%16 of row l/16 with the chunk that the permutation assigns to that slot
+    const int ld_row = lane >> 4;                            // 0..3 within the instruction's 4 rows
+    const int ld_slot = lane & 15;
+    const unsigned char* k_cache = reinterpret_cast<const unsigned char*>(
+        prm.Kc + prm.kv_start[b] * prm.kv_token_stride + static_cast<long>(g) * prm.kv_head_stride);
+    const unsigned char* v_cache = reinterpret_cast<const unsigned char*>(
+        prm.Vc + prm.kv_start[b] * prm.kv_token_stride + static_cast<long>(g) * prm.kv_head_stride);
+    const unsigned char* k_tree = reinterpret_cast<const unsigned char*>(
+        prm.Kt + (static_cast<long>(b) * SAGE_MAX_NODES * prm.Hkv + g) * D);
+    const unsigned char* v_tree = reinterpret_cast<const unsigned char*>(
+        prm.Vt + (static_cast<long>(b) * SAGE_MAX_NODES * prm.Hkv + g) * D);
+    const long cache_row_b = prm.kv_token_stride * 2;
+    const long tree_row_b = static_cast<long>(prm.Hkv) * D * 2;
 
-    uint4 stage[8];
-    auto issue_loads = [&](int tile) {
+    auto issue_loads = [&](int tile, auto stc) __attribute__((always_inline)) {
+        constexpr int ST = decltype(stc)::value;
         const bool is_tree = (tile == tree_tile);
-        const int base = tile * TILE;
+        const unsigned char* kb = is_tree ? k_tree : k_cache;
+        const unsigned char* vb = is_tree ? v_tree : v_cache;
+        const long row_b = is_tree ? tree_row_b : cache_row_b;
+        const int first = is_tree ? 0 : tile * TILE;
+        const int last = is_tree ? sp.n - 1 : L - 1;         // rows past the end are masked later; keep reads in range
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            int t;                                          // token within the tile
-            if (k_loader) {
-                t = i * 8 + lgrp;
-            } else {                                        // position group lgrp = (sub, j, h); element i of the k-block
-                t = 32 * (lgrp >> 2) + 16 * ((lgrp >> 1) & 1) + 8 * (i >> 2) + 4 * (lgrp & 1) + (i & 3);
-            }
-            const uint16_t* src;
-            if (is_tree) {
-                src = tree_base + min(t, sp.n - 1) * tree_stride;           // rows past n are masked; keep the read in range
-            } else {
-                src = cache_base + static_cast<long>(min(base + t, L - 1)) * prm.kv_token_stride;
-            }
-            stage[i] = *reinterpret_cast<const uint4*>(src);
-        }
-    };
-    auto store_stage = [&](int buf) {
-        unsigned char* kb = smem + buf * STAGE_BYTES;
-        unsigned char* vb = kb + K_BYTES;
-        if (k_loader) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                *reinterpret_cast<uint4*>(kb + (i * 8 + lgrp) * K_ROW_B + chunk * 16) = stage[i];
-        } else {
-            // 8x8 transpose of 16-bit elements: stage[e] holds dims chunk*8..+7 of token e; row dd of the result
-            // holds tokens 0..7 of dim chunk*8+dd.  LDS row order is dd*16 + chunk (consecutive rows per store).
-            auto dw = [&](int e, int q) -> uint32_t {      // dims 2q, 2q+1 of token e
-                return q == 0 ? stage[e].x : q == 1 ? stage[e].y : q == 2 ? stage[e].z : stage[e].w;
-            };
-#pragma unroll
-            for (int dd = 0; dd < 8; ++dd) {
-                const uint32_t sel = (dd & 1) ? 0x07060302u : 0x05040100u;
-                uint4 o;
-                o.x = __builtin_amdgcn_perm(dw(1, dd / 2), dw(0, dd / 2), sel);
-                o.y = __builtin_amdgcn_perm(dw(3, dd / 2), dw(2, dd / 2), sel);
-                o.z = __builtin_amdgcn_perm(dw(5, dd / 2), dw(4, dd / 2), sel);
-                o.w = __builtin_amdgcn_perm(dw(7, dd / 2), dw(6, dd / 2), sel);
-                *reinterpret_cast<uint4*>(vb + (dd * 16 + chunk) * V_ROW_B + lgrp * 16) = o;
-            }
+        for (int i = 0; i < 2; ++i) {
+            const int t = (wave * 2 + i) * 4 + ld_row;       // token row within the tile
+            const long roff = static_cast<long>(min(first + t, last)) * row_b;
+            const int kc = ld_slot ^ k_swz(t);
+            const int vc = ld_slot ^ v_swz(t);
+            __builtin_amdgcn_global_load_lds(kb + roff + kc * 16, (LDS_AS unsigned char*)(&SK(ST)[(wave * 2 + i) * 1024]), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(vb + roff + vc * 16, (LDS_AS unsigned char*)(&SV(ST)[(wave * 2 + i) * 1024]), 16, 0, 0);
         }
     };
 
-    f32x16 acc[4];                                           // O^T: 4 tiles of 32 LDS rows x this lane's query row
+    // ---- per-lane LDS read offsets.  K fragment (sub, kk): token sub*32 + r32, chunk 2kk + half, whose slot is
+    // (2kk + half) ^ k_swz(r32); as byte offsets that is k_lane ^ (kk << 5).
+    const int k_lane = r32 * ROW_B + ((k_swz(r32) ^ half) << 4);
+    // V^T fragment (dt, kbk, u): the 16-lane group q = lane/16 reads tokens kbk*16 + 8u + 4(q/2) + s/4 and dims
+    // dt*32 + 16(q%2) + 4(s%4) .. +3  (s = lane%16); after the transposing read lane s holds dim dt*32+16(q%2)+s.
+    // Byte offset within the tile: (kbk*16 + 8u) rows, plus v_lane ^ (dt << 6).
+    int v_lane;
+    {
+        const int q = lane >> 4, s16 = lane & 15;
+        const int trow = 4 * (q >> 1) + (s16 >> 2);          // token row modulo 8
+        const int chunk_lo = 2 * (q & 1) + ((s16 & 3) >> 1); // chunk within the dt block of 4 chunks
+        v_lane = trow * ROW_B + ((chunk_lo ^ v_swz(trow)) << 4) + 8 * (s16 & 1);
+    }
+
+    f32x16 acc[4];                                           // O^T: 4 tiles of 32 dims x this lane's query row
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[dt][i] = 0.f;
-    float m_run = -INFINITY;                                 // running max of raw (unscaled) scores
+    float m_ref = -INFINITY;                                 // reference maximum of raw (unscaled) scores
     float l_run = 0.f;                                       // this lane's share of the running sum
     const float c = prm.scale_log2e;
 
-    issue_loads(t_begin);
-    store_stage(0);
-    __syncthreads();
-
-    for (int tile = t_begin; tile < t_end; ++tile) {
-        const int buf = (tile - t_begin) & 1;
-        const bool has_next = tile + 1 < t_end;
-        if (has_next) issue_loads(tile + 1);
-
-        if (wave_active) {
-            const unsigned char* kb = smem + buf * STAGE_BYTES;
-            const unsigned char* vb = kb + K_BYTES;
-            f32x16 s[2];
+    // One tile step for this wave's column tile over NSUB consecutive 32-token sub-tiles starting at kb/vb.
+    // With two sub-tiles the two score chains are independent, which lets MFMA, LDS and VALU work overlap.
+    auto compute = [&](auto nsubc, const lds_byte* kb, const lds_byte* vb, bool masked, uint64_t admit) __attribute__((always_inline)) {
+        constexpr int NSUB = decltype(nsubc)::value;
+        // ---- S^T = K Q^T, 32 tokens per sub-tile
+        f32x16 s[NSUB];
 #pragma unroll
-            for (int sub = 0; sub < 2; ++sub) {
+        for (int u = 0; u < NSUB; ++u)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) s[sub][i] = 0.f;
+            for (int i = 0; i < 16; ++i) s[u][i] = 0.f;
 #pragma unroll
-                for (int kk = 0; kk < 8; ++kk) {
-                    const bf16x8 a = lds_frag(kb + (sub * 32 + r32) * K_ROW_B + kk * 32 + half * 16);
-                    s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[kk], s[sub], 0, 0, 0);
-                }
+        for (int kh = 0; kh < 2; ++kh) {
+            bf16x8 a[NSUB][4];
+#pragma unroll
+            for (int u = 0; u < NSUB; ++u)
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk)
+                    a[u][kk] = __builtin_bit_cast(bf16x8, *(const LDS_AS uint4*)(kb + u * 32 * ROW_B + (k_lane ^ ((kh * 4 + kk) << 5))));
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+                for (int u = 0; u < NSUB; ++u)
+                    s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u][kk], qf[kh * 4 + kk], s[u], 0, 0, 0);
+        }
+        // ---- admit keys: cache positions below kv_len; tree nodes in this row's ancestor-or-self mask
+        if (masked) {
+#pragma unroll
+            for (int u = 0; u < NSUB; ++u) {
+                const uint32_t adm = static_cast<uint32_t>(admit >> (32 * u));
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    if (!((adm >> (8 * (i >> 2) + (i & 3))) & 1u)) s[u][i] = -INFINITY;
             }
-            // ---- admit keys: cache positions below kv_len; tree nodes in this row's ancestor-or-self mask
-            const bool is_tree = (tile == tree_tile);
-            if (is_tree || tile * TILE + TILE > L) {
-                uint64_t admit;
-                if (is_tree) {
-                    admit = tree_mask;
-                } else {
-                    const int left = L - tile * TILE;        // 1..63 valid tokens
-                    admit = (1ull << left) - 1ull;
-                }
+        }
+        // ---- online softmax for this lane's query row, lazily rescaled
+        float tmax = s[0][0];
 #pragma unroll
-                for (int sub = 0; sub < 2; ++sub)
+        for (int u = 0; u < NSUB; ++u)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int t = 32 * sub + 8 * (i >> 2) + 4 * half + (i & 3);
-                        if (!((admit >> t) & 1)) s[sub][i] = -INFINITY;
-                    }
-            }
-            // ---- online softmax for this lane's query row
-            float tmax = s[0][0];
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, s[sub][i]);
-            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-            const float m_new = fmaxf(m_run, tmax);
-            const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-            const float corr = __builtin_amdgcn_exp2f((m_run - m_safe) * c);   // 0 on the first admitted tile
-            const float neg_mc = -m_safe * c;
-            float psum = 0.f;
-            bf16x8 pf[4];
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    bf16x8 frag;
-#pragma unroll
-                    for (int e = 0; e < 8; e += 2) {
-                        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[sub][8 * j + e], c, neg_mc));
-                        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[sub][8 * j + e + 1], c, neg_mc));
-                        psum += p0 + p1;
-                        const f32x2 pp = {p0, p1};
-                        const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-                        frag[e] = pb[0];
-                        frag[e + 1] = pb[1];
-                    }
-                    pf[sub * 2 + j] = frag;
-                }
-            l_run = l_run * corr + psum;
-            m_run = m_new;
-            if (__any(corr != 1.0f)) {
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[dt][i] *= corr;
-            }
-            // ---- O^T += V^T P^T
+            for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, s[u][i]);
+        tmax = cross_half_max(tmax);
+        const bool raise = (tmax - m_ref) * c > RESCALE_THRESHOLD;     // also true for the first admitted key
+        if (__any(raise)) {
+            const float m_new = raise ? tmax : m_ref;
+            const float corr = (m_ref == -INFINITY) ? (raise ? 0.f : 1.f) : __builtin_amdgcn_exp2f((m_ref - m_new) * c);
+            m_ref = m_new;
+            l_run *= corr;
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-                for (int kbk = 0; kbk < 4; ++kbk) {
-                    const bf16x8 a = lds_frag(vb + (dt * 32 + r32) * V_ROW_B + kbk * 32 + half * 16);
-                    acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kbk], acc[dt], 0, 0, 0);
-                }
+                for (int i = 0; i < 16; ++i) acc[dt][i] *= corr;
         }
+        const float neg_mc = (m_ref == -INFINITY) ? 0.f : -m_ref * c;
+        float psum = 0.f;
+        bf16x8 pf[NSUB][2];
+#pragma unroll
+        for (int u = 0; u < NSUB; ++u)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                bf16x8 frag;
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    const float p0 = __builtin_amdgcn_exp2f(fmaf(s[u][8 * j + e], c, neg_mc));
+                    const float p1 = __builtin_amdgcn_exp2f(fmaf(s[u][8 * j + e + 1], c, neg_mc));
+                    psum += p0 + p1;
+                    const f32x2 pp = {p0, p1};
+                    const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+                    frag[e] = pb[0];
+                    frag[e + 1] = pb[1];
+                }
+                pf[u][j] = frag;
+            }
+        l_run += psum;
+        // ---- O^T += V^T P^T   (k-blocks of 16 tokens; two transposing reads of 4 tokens each per lane and block)
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) {
+            bf16x8 a[NSUB][2];
+#pragma unroll
+            for (int u = 0; u < NSUB; ++u)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const lds_byte* p0 = vb + (u * 32 + j * 16) * ROW_B + (v_lane ^ (dt << 6));
+                    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)p0);
+                    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)(p0 + 8 * ROW_B));
+                    a[u][j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                }
+#pragma unroll
+            for (int u = 0; u < NSUB; ++u)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u][j], pf[u][j], acc[dt], 0, 0, 0);
+        }
+    };
 
-        if (has_next) store_stage(buf ^ 1);
-        __syncthreads();
+    auto process = [&](int tile, auto stc) __attribute__((always_inline)) {
+        constexpr int ST = decltype(stc)::value;
+        const int ahead = t_end - 1 - tile;                  // later tiles whose loads may stay in flight (at most 2)
+        if (ahead >= 2) wait_vm<2 * LOADS_PER_TILE>();
+        else if (ahead == 1) wait_vm<LOADS_PER_TILE>();
+        else wait_vm<0>();                                   // this thread's part of `tile` has landed
+        stage_barrier();                                     // ... everyone's has, and the stage read last time is free
+        if (tile + 3 < t_end) issue_loads(tile + 3, std::integral_constant<int, (ST + 3) % STAGES>{});
+        if (!wave_active) return;
+
+        const bool is_tree = (tile == tree_tile);
+        const bool masked = is_tree || tile * TILE + TILE > L;
+        uint64_t admit = ~0ull;
+        if (masked) {
+            if (is_tree) {
+                admit = s_mask[m_local];
+            } else {
+                const int left = L - tile * TILE;            // 1..63 valid tokens
+                admit = (1ull << left) - 1ull;
+            }
+            admit >>= 4 * half;                              // token of accumulator register i: 32 sub + 8 (i/4) + 4 half + i%4
+        }
+        if (shared_ct) {
+            compute(std::integral_constant<int, 1>{}, (const lds_byte*)(SK(ST)) + sub_lo * 32 * ROW_B,
+                    (const lds_byte*)(SV(ST)) + sub_lo * 32 * ROW_B, masked, admit >> (32 * sub_lo));
+        } else {
+            compute(std::integral_constant<int, 2>{}, (const lds_byte*)(SK(ST)), (const lds_byte*)(SV(ST)), masked, admit);
+        }
+    };
+
+    if (t_begin < t_end) issue_loads(t_begin, std::integral_constant<int, 0>{});
+    if (t_begin + 1 < t_end) issue_loads(t_begin + 1, std::integral_constant<int, 1>{});
+    if (t_begin + 2 < t_end) issue_loads(t_begin + 2, std::integral_constant<int, 2>{});
+    for (int tile = t_begin; tile < t_end; tile += STAGES) {
+        process(tile, std::integral_constant<int, 0>{});
+        if (tile + 1 < t_end) process(tile + 1, std::integral_constant<int, 1>{});
+        if (tile + 2 < t_end) process(tile + 2, std::integral_constant<int, 2>{});
+        if (tile + 3 < t_end) process(tile + 3, std::integral_constant<int, 3>{});
     }
 
-    // ---- un-normalised partial for this (split, query row); LDS-row order of dims, merged by the second kernel
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
-    if (row_valid) {
-        float* out = prm.part + (((static_cast<long>(b) * prm.Hkv + g) * prm.nslot + slot) * ROWS_PER_WG + wave * 32 + r32) * PART_FLOATS;
+    float l_tot = cross_half_sum(l_run);
+
+    // ---- two waves shared a column tile: the wave of the upper token half hands its state to the other
+    if (shared_ct) {
+        __syncthreads();                                     // all stages are idle now: K stage `ct` becomes a mailbox
+        float* box = reinterpret_cast<float*>(SK(ct));       // [64 accumulator registers][64 lanes]
+        if (wave_active && sub_lo == 1) {
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) box[(dt * 16 + i) * 64 + lane] = acc[dt][i];
+            if (half == 0) { s_ml[ct][0][r32] = m_ref; s_ml[ct][1][r32] = l_tot; }
+        }
+        __syncthreads();
+        if (wave_active && sub_lo == 0) {
+            const float m_o = s_ml[ct][0][r32], l_o = s_ml[ct][1][r32];
+            const float m_new = fmaxf(m_ref, m_o);
+            const float w_s = (m_ref == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_ref - m_new) * c);
+            const float w_o = (m_o == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_o - m_new) * c);
+            m_ref = m_new;
+            l_tot = l_tot * w_s + l_o * w_o;
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[dt][i] = acc[dt][i] * w_s + box[(dt * 16 + i) * 64 + lane] * w_o;
+        }
+    }
+
+    // ---- un-normalised partial for this (split, query row), merged by the second kernel
+    if (row_valid && sub_lo == 0 && !(prm.debug & 1)) {
+        float* out = prm.part + (((static_cast<long>(b) * prm.Hkv + g) * prm.nslot + slot) * ROWS_PER_WG + m_local) * PART_FLOATS;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -283,60 +410,100 @@ __global__ __launch_bounds__(THREADS, 2) void tree_attention_bf16_kernel(const P
                 *reinterpret_cast<float4*>(out + dt * 32 + 8 * q + 4 * half) = v;
             }
         if (half == 0) {
-            out[D] = m_run;
+            out[D] = m_ref;
             out[D + 1] = l_tot;
         }
     }
+#undef SK
+#undef SV
 }
 
-// Merge the splits of one (sequence, node, query head) in split order and write bf16.
-__global__ __launch_bounds__(D) void tree_attention_merge_kernel(const Params prm) {
-    __shared__ uint16_t s_out[D];
-    const int node = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+// Merge the splits of one (sequence, node, query head) in split order and write bf16.  One wave per row:
+// lane = split for the (max, sum) pairs and their weights, lane = pair of output dims for the accumulation.
+// Every partial of the row is requested before the first one is used, so the merge costs one memory round trip.
+constexpr int MERGE_ROWS = 4;            // rows (waves) per workgroup
+__global__ __launch_bounds__(64 * MERGE_ROWS) void tree_attention_merge_kernel(const Params prm) {
+    const int lane = threadIdx.x & 63;
+    const int hh = blockIdx.y * MERGE_ROWS + (threadIdx.x >> 6);
+    const int node = blockIdx.x, b = blockIdx.z;
     const int L = prm.kv_len[b] > 0 ? prm.kv_len[b] : 0;
     const Split sp = make_split(prm.n_nodes[b], L, prm.G, prm.nslot);
-    if (node >= sp.n || sp.col_groups > prm.nslot) return;
-    const int g = h / prm.G;
-    const int m = node * prm.G + (h % prm.G);
+    if (node >= sp.n || hh >= prm.Hq || sp.col_groups > prm.nslot) return;
+    const int g = hh / prm.G;
+    const int m = node * prm.G + (hh % prm.G);
     const int cg = m / ROWS_PER_WG;
     const int row = m % ROWS_PER_WG;
-    const int p = threadIdx.x;                               // LDS-row index of the partial
     const float c = prm.scale_log2e;
     const float* base = prm.part + ((static_cast<long>(b) * prm.Hkv + g) * prm.nslot) * ROWS_PER_WG * PART_FLOATS;
+    const long split_stride = static_cast<long>(sp.col_groups) * ROWS_PER_WG * PART_FLOATS;
+    const float* first = base + (static_cast<long>(cg) * ROWS_PER_WG + row) * PART_FLOATS;
+    const int nsplit = sp.nsplit;
 
-    float m_all = -INFINITY;
-    for (int s = 0; s < sp.nsplit; ++s) {
-        const float* part = base + (static_cast<long>(s * sp.col_groups + cg) * ROWS_PER_WG + row) * PART_FLOATS;
-        m_all = fmaxf(m_all, part[D]);
+    float2 o = make_float2(0.f, 0.f);
+    float m_all = -INFINITY, l_all = 0.f;
+    for (int s0 = 0; s0 < nsplit; s0 += 64) {                 // 64 splits at a time (one per lane)
+        const int cnt = min(64, nsplit - s0);
+        float ms = -INFINITY, ls = 0.f;
+        if (lane < cnt) {
+            ms = first[(s0 + lane) * split_stride + D];
+            ls = first[(s0 + lane) * split_stride + D + 1];
+        }
+        float2 v[64];
+        if (cnt <= 32) {
+#pragma unroll
+            for (int s = 0; s < 32; ++s)
+                v[s] = s < cnt ? *reinterpret_cast<const float2*>(first + (s0 + s) * split_stride + 2 * lane) : make_float2(0.f, 0.f);
+        } else {
+#pragma unroll
+            for (int s = 0; s < 64; ++s)
+                v[s] = s < cnt ? *reinterpret_cast<const float2*>(first + (s0 + s) * split_stride + 2 * lane) : make_float2(0.f, 0.f);
+        }
+        float m_blk = ms;
+        for (int off = 32; off > 0; off >>= 1) m_blk = fmaxf(m_blk, __shfl_xor(m_blk, off));
+        const float m_new = fmaxf(m_all, m_blk);
+        const float keep = (m_all == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_all - m_new) * c);
+        const float w = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((ms - m_new) * c);
+        float l_blk = w * ls;
+        for (int off = 32; off > 0; off >>= 1) l_blk += __shfl_xor(l_blk, off);
+        l_all = l_all * keep + l_blk;
+        o.x *= keep; o.y *= keep;
+        m_all = m_new;
+        if (cnt <= 32) {
+#pragma unroll
+            for (int s = 0; s < 32; ++s) {
+                const float ws = __shfl(w, s);
+                o.x += ws * v[s].x; o.y += ws * v[s].y;
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 64; ++s) {
+                const float ws = __shfl(w, s);
+                o.x += ws * v[s].x; o.y += ws * v[s].y;
+            }
+        }
     }
-    float l_all = 0.f, o = 0.f;
-    for (int s = 0; s < sp.nsplit; ++s) {
-        const float* part = base + (static_cast<long>(s * sp.col_groups + cg) * ROWS_PER_WG + row) * PART_FLOATS;
-        const float ms = part[D];
-        if (ms == -INFINITY) continue;
-        const float w = __builtin_amdgcn_exp2f((ms - m_all) * c);
-        l_all += w * part[D + 1];
-        o += w * part[p];
-    }
-    const int dim = (p & 15) * 8 + (p >> 4);                 // LDS row dd*16 + chunk holds dim chunk*8 + dd
-    s_out[dim] = sage::float_to_bf16_bits(o / l_all);
-    __syncthreads();
-    prm.O[((static_cast<long>(b) * SAGE_MAX_NODES + node) * prm.Hq + h) * D + p] = s_out[p];
+    const float inv = 1.0f / l_all;
+    const uint32_t packed = static_cast<uint32_t>(sage::float_to_bf16_bits(o.x * inv)) |
+                            (static_cast<uint32_t>(sage::float_to_bf16_bits(o.y * inv)) << 16);
+    reinterpret_cast<uint32_t*>(prm.O + ((static_cast<long>(b) * SAGE_MAX_NODES + node) * prm.Hq + hh) * D)[lane] = packed;
 }
 
 }  // namespace
 
 namespace sage {
 
-// Number of workgroup slots per (sequence, KV head): enough to cover the device about twice, never more than
+// Number of workgroup slots per (sequence, KV head): about one 8-wave workgroup per CU, never more than
 // one slot per tile and column group, never fewer than the largest possible number of column groups.
 int attention_bf16_slots(int B, int Hkv, int G, int max_kv_len) {
     const int max_groups = (SAGE_MAX_NODES * G + ROWS_PER_WG - 1) / ROWS_PER_WG;
     const int tiles = (max_kv_len + TILE - 1) / TILE + 1;
-    long want = 512 / (static_cast<long>(B > 0 ? B : 1) * Hkv);
+    long want = 256 / (static_cast<long>(B > 0 ? B : 1) * Hkv);
+    if (const char* e = getenv("SAGE_ATTN_SLOTS")) want = atol(e);
     if (want < max_groups) want = max_groups;
     const long cap = static_cast<long>(tiles) * max_groups;
     if (want > cap) want = cap;
+    if (want > 256) want = 256;
+    if (want < max_groups) want = max_groups;
     return static_cast<int>(want);
 }
 
@@ -365,13 +532,16 @@ int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const voi
     p.kv_token_stride = kv_token_stride; p.kv_head_stride = kv_head_stride;
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.G = G;
     p.nslot = attention_bf16_slots(B, Hkv, G, max_kv_len);
+    if (static_cast<size_t>(B) * Hkv * p.nslot * ROWS_PER_WG * PART_FLOATS * sizeof(float) > workspace_bytes)
+        return SAGE_WORKSPACE_TOO_SMALL;
     p.scale_log2e = scale * 1.4426950408889634f;
+    p.debug = getenv("SAGE_ATTN_DEBUG") ? atoi(getenv("SAGE_ATTN_DEBUG")) : 0;
 
     const long blocks = static_cast<long>(B) * p.nslot * Hkv;
     if (blocks > 0x7FFFFFFFL) return SAGE_UNSUPPORTED;
     hipLaunchKernelGGL(tree_attention_bf16_kernel, dim3(static_cast<unsigned>(blocks)), dim3(THREADS), 0, stream, p);
     if (hipGetLastError() != hipSuccess) return SAGE_LAUNCH_FAILED;
-    hipLaunchKernelGGL(tree_attention_merge_kernel, dim3(SAGE_MAX_NODES, Hq, B), dim3(D), 0, stream, p);
+    hipLaunchKernelGGL(tree_attention_merge_kernel, dim3(SAGE_MAX_NODES, (Hq + MERGE_ROWS - 1) / MERGE_ROWS, B), dim3(64 * MERGE_ROWS), 0, stream, p);
     return launch_status();
 }
 

@@ -43,7 +43,8 @@ def lib():
         L.sage_entropy_topk.restype = _ci
         L.sage_entropy_topk.argtypes = [_vp, _ci, _ci, _ci, _cl, _ci, _vp, _ci, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
         L.sage_build_tree.restype = _ci
-        L.sage_build_tree.argtypes = [_vp, _vp, _ci, _ci, ctypes.POINTER(TreeParams), _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+        L.sage_build_tree.argtypes = [_vp, _vp, _vp, _ci, _ci, ctypes.POINTER(TreeParams), _vp, _vp, _vp, _vp, _vp, _vp, _vp,
+                                      _vp]
         L.sage_tree_attention_workspace_bytes.restype = _sz
         L.sage_tree_attention_workspace_bytes.argtypes = [_ci, _ci, _ci, _ci, _ci, _ci]
         L.sage_tree_attention.restype = _ci
@@ -98,10 +99,11 @@ def sage_entropy_topk(logits, k, entropy, topk_idx, topk_prob, topk_renorm, topk
 
 
 def sage_build_tree(topk_renorm, alpha, params: TreeParams, n_nodes, parent, depth, rank, anc_mask, cum_prob=None,
-                    stream=None):
+                    topk_idx=None, node_token=None, stream=None):
     B, k = topk_renorm.shape
-    rc = lib().sage_build_tree(_ptr(topk_renorm), _ptr(alpha), B, k, ctypes.byref(params), _ptr(n_nodes), _ptr(parent),
-                               _ptr(depth), _ptr(rank), _ptr(anc_mask), _ptr(cum_prob), _stream(stream))
+    rc = lib().sage_build_tree(_ptr(topk_renorm), _ptr(alpha), _ptr(topk_idx), B, k, ctypes.byref(params), _ptr(n_nodes),
+                               _ptr(parent), _ptr(depth), _ptr(rank), _ptr(anc_mask), _ptr(cum_prob), _ptr(node_token),
+                               _stream(stream))
     _check("sage_build_tree", rc)
 
 

@@ -49,15 +49,17 @@ def gpu_entropy_topk(logits_np, k, n_valid=None, rows_per_group=1):
     return {key: v.cpu().numpy() for key, v in out.items()}
 
 
-def gpu_build_tree(topk_renorm_np, alpha_np, prm: dict):
+def gpu_build_tree(topk_renorm_np, alpha_np, prm: dict, topk_idx_np=None):
     pt, al = to_dev(np.ascontiguousarray(topk_renorm_np, np.float32)), to_dev(np.ascontiguousarray(alpha_np, np.float32))
     B = pt.shape[0]
     i32 = lambda fill: torch.full((B, MAX_NODES), fill, device=DEV, dtype=torch.int32)
     out = dict(n_nodes=torch.zeros(B, device=DEV, dtype=torch.int32), parent=i32(-2), depth=i32(-2), rank=i32(-2),
                anc_mask=torch.zeros((B, MAX_NODES), device=DEV, dtype=torch.int64),
-               cum_prob=torch.full((B, MAX_NODES), float("nan"), device=DEV, dtype=torch.float32))
+               cum_prob=torch.full((B, MAX_NODES), float("nan"), device=DEV, dtype=torch.float32),
+               node_token=i32(-2))
+    ti = None if topk_idx_np is None else to_dev(np.ascontiguousarray(topk_idx_np, np.int32))
     sage.sage_build_tree(pt, al, sage.tree_params(**prm), out["n_nodes"], out["parent"], out["depth"], out["rank"],
-                         out["anc_mask"], out["cum_prob"])
+                         out["anc_mask"], out["cum_prob"], ti, out["node_token"] if ti is not None else None)
     torch.cuda.synchronize()
     res = {key: v.cpu().numpy() for key, v in out.items()}
     res["anc_mask"] = res["anc_mask"].view(np.uint64)

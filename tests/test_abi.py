@@ -1,0 +1,94 @@
+"""Host-side checks of the boundary: the built library loads without a GPU and exports every function that
+include/sage.h declares; argument validation returns status codes without touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2602_00523_amd", "libsage_hip.so")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2602_00523_amd import build
+        build.build()
+    return ctypes.CDLL(LIB)
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "sage.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sage_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_the_four_calls():
+    names = declared_functions()
+    for need in ("sage_entropy_topk", "sage_build_tree", "sage_tree_attention", "sage_verify_accept"):
+        assert need in names
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+    lib.sage_build_info.restype = ctypes.c_char_p
+    assert b"gfx950" in lib.sage_build_info()
+
+
+def test_workspace_sizes_are_pure_host_functions(lib):
+    lib.sage_entropy_topk_workspace_bytes.restype = ctypes.c_size_t
+    lib.sage_tree_attention_workspace_bytes.restype = ctypes.c_size_t
+    a = lib.sage_entropy_topk_workspace_bytes(64, 152064, 1)
+    b = lib.sage_entropy_topk_workspace_bytes(64, 152064, 10)
+    assert 0 < a < b < (1 << 24)
+    w1 = lib.sage_tree_attention_workspace_bytes(1, 1, 64, 8, 128, 4096)
+    w2 = lib.sage_tree_attention_workspace_bytes(1, 1, 64, 8, 128, 32768)
+    assert 0 < w1 <= w2 < (1 << 28)
+
+
+def test_invalid_arguments_are_rejected_on_the_host(lib):
+    INVALID = 1
+    null = ctypes.c_void_p(0)
+    one = ctypes.c_void_p(16)            # never dereferenced: validation fails first
+    assert lib.sage_verify_accept(null, one, one, one, one, one, 1, 9, one, one, one, one, null) == INVALID
+    assert lib.sage_verify_accept(one, one, one, one, one, one, 1, 0, one, one, one, one, null) == INVALID
+
+    class P(ctypes.Structure):
+        _fields_ = [(n, ctypes.c_int) for n in ("d_min", "d_max", "w_min", "w_max", "k", "n_max")]
+    bad = [P(3, 8, 2, 10, 10, 65), P(3, 8, 2, 11, 10, 64), P(9, 8, 2, 10, 10, 64), P(3, 40, 2, 10, 10, 64),
+           P(3, 8, 0, 10, 10, 64), P(3, 8, 2, 10, 9, 64)]
+    for p in bad:
+        assert lib.sage_build_tree(one, one, null, 1, 10, ctypes.byref(p), one, one, one, one, one, null, null, null) == INVALID
+    ok = P(3, 8, 2, 10, 10, 64)
+    assert lib.sage_build_tree(one, one, null, 1, 10, ctypes.byref(ok), one, one, one, one, one, null, one, null) == INVALID
+    assert lib.sage_build_tree(one, one, null, 0, 10, ctypes.byref(ok), one, one, one, one, one, null, null, null) == 0
+
+    lib.sage_entropy_topk.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_long,
+                                      ctypes.c_int, ctypes.c_void_p, ctypes.c_int] + [ctypes.c_void_p] * 7 + \
+                                     [ctypes.c_size_t, ctypes.c_void_p]
+    args = lambda **kw: [kw.get("logits", 256), kw.get("dtype", 1), kw.get("rows", 1), kw.get("vocab", 1024),
+                         kw.get("stride", 1024), kw.get("k", 10), None, 1, 256, kw.get("idx", 256), 256, 256, 256, 256,
+                         kw.get("ws", 256), kw.get("wsb", 1 << 20), None]
+    assert lib.sage_entropy_topk(*args(k=0)) == INVALID
+    assert lib.sage_entropy_topk(*args(k=65)) == INVALID
+    assert lib.sage_entropy_topk(*args(idx=None)) == INVALID
+    assert lib.sage_entropy_topk(*args(stride=1001)) == INVALID            # rows must stay 16-byte aligned
+    assert lib.sage_entropy_topk(*args(dtype=7)) == INVALID
+    assert lib.sage_entropy_topk(*args(wsb=8)) == 3                        # WORKSPACE_TOO_SMALL
+    assert lib.sage_entropy_topk(*args(rows=0)) == 0
+
+    lib.sage_tree_attention.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_int] * 5 + [ctypes.c_void_p, ctypes.c_void_p,
+                                       ctypes.c_int, ctypes.c_long, ctypes.c_long, ctypes.c_void_p, ctypes.c_void_p,
+                                       ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+    att = lambda **kw: [256] * 6 + [kw.get("dtype", 1), kw.get("B", 1), kw.get("Hq", 64), kw.get("Hkv", 8), kw.get("d", 128),
+                                    256, 256, kw.get("L", 4096), kw.get("ts", 1024), 128, 256, 256, kw.get("scale", 0.088),
+                                    kw.get("ws", 256), kw.get("wsb", 1 << 30), None]
+    assert lib.sage_tree_attention(*att(Hq=63)) == INVALID
+    assert lib.sage_tree_attention(*att(scale=0.0)) == INVALID
+    assert lib.sage_tree_attention(*att(d=96)) == 2                        # UNSUPPORTED head_dim on the bf16 path
+    assert lib.sage_tree_attention(*att(Hq=24, Hkv=8)) == 2                # group size 3
+    assert lib.sage_tree_attention(*att(ts=1004)) == INVALID               # token rows must stay 16-byte aligned
+    assert lib.sage_tree_attention(*att(wsb=1024)) == 3
+    assert lib.sage_tree_attention(*att(B=0)) == 0

@@ -105,10 +105,11 @@ def test_build_tree_bit_exact(gu):
         pt[4] = 0
         pt[4, 0] = 1                                 # one-hot
         pt[5] = 1.0 / k                              # flat
-        o = oracle.build_tree(pt, alpha, prm)
-        t = gu.gpu_build_tree(pt, alpha, prm)
+        ids = g.integers(0, 152064, size=(B, k)).astype(np.int32)
+        o = oracle.build_tree(pt, alpha, prm, ids)
+        t = gu.gpu_build_tree(pt, alpha, prm, ids)
         np.testing.assert_array_equal(t["n_nodes"], o["n_nodes"], err_msg=name)
-        for key in ("parent", "depth", "rank", "anc_mask", "cum_prob"):
+        for key in ("parent", "depth", "rank", "anc_mask", "cum_prob", "node_token"):
             for b in range(B):
                 n = int(o["n_nodes"][b])
                 np.testing.assert_array_equal(t[key][b, :n], o[key][b, :n], err_msg=f"{name} {key} seq {b}")
@@ -235,11 +236,11 @@ def test_toy_pipeline_32_steps(gu):
         np.testing.assert_array_equal(g1["topk_idx"], o1["topk_idx"])
         assert close(g1["alpha"], o1["alpha"]).all() and close(g1["topk_renorm"], o1["topk_renorm"]).all()
         # a2: the oracle consumes the GPU's fp32 bits so a 1-ulp difference upstream cannot pose as a tree mismatch
-        o2 = oracle.build_tree(g1["topk_renorm"], g1["alpha"], prm)
-        g2 = gu.gpu_build_tree(g1["topk_renorm"], g1["alpha"], prm)
+        o2 = oracle.build_tree(g1["topk_renorm"], g1["alpha"], prm, g1["topk_idx"])
+        g2 = gu.gpu_build_tree(g1["topk_renorm"], g1["alpha"], prm, g1["topk_idx"])
         n = int(o2["n_nodes"][0])
         assert g2["n_nodes"][0] == n
-        for key in ("parent", "depth", "rank", "anc_mask"):
+        for key in ("parent", "depth", "rank", "anc_mask", "node_token"):
             np.testing.assert_array_equal(g2[key][0, :n], o2[key][0, :n])
         # a3
         inp = wl.attention_inputs(seed + 50000, 1, cfg["Hq"], cfg["Hkv"], cfg["d"], [cfg["kv_len"]], "f32")
@@ -254,8 +255,8 @@ def test_toy_pipeline_32_steps(gu):
         o1t = oracle.entropy_topk(tgt_logits, 1, o2["n_nodes"], MAX_NODES)
         g1t = gu.gpu_entropy_topk(tgt_logits, 1, g2["n_nodes"], MAX_NODES)
         np.testing.assert_array_equal(g1t["topk_idx"][:n], o1t["topk_idx"][:n])
-        token = np.zeros((1, MAX_NODES), np.int32)
-        token[0, 1:n] = g1["topk_idx"][0, g2["rank"][0, 1:n]]
+        token = g2["node_token"]
+        assert (token[0, 1:n] == g1["topk_idx"][0, g2["rank"][0, 1:n]]).all() and token[0, 0] == -1
         tgt = g1t["topk_idx"][:, 0].reshape(1, MAX_NODES)
         # a4
         o4 = oracle.verify_accept(token, tgt, o2["parent"], o2["depth"], o2["n_nodes"], prm["d_max"] + 1)

@@ -215,3 +215,16 @@ def test_paper_hyperparameters_fixture():
     for name in ("c2", "c4", "c5"):
         assert wl.CONFIGS[name]["tree"] == gold["tree"]
     assert gold["alpha_init"] == 0.5
+
+
+def test_node_token_is_the_candidate_of_the_nodes_rank():
+    g = np.random.default_rng(5)
+    pts = np.stack([np.sort(renorm(g.random(10) ** 2))[::-1] for _ in range(4)])
+    ids = g.integers(0, 152064, size=(4, 10)).astype(np.int32)
+    t = oracle.build_tree(pts, g.random(4).astype(F), PAPER, ids)
+    for b in range(4):
+        n = int(t["n_nodes"][b])
+        assert t["node_token"][b, 0] == -1
+        for v in range(1, n):
+            assert t["node_token"][b, v] == ids[b, t["rank"][b, v]]
+        assert (t["node_token"][b, n:] == -2).all()
