@@ -43,6 +43,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the long-KV attention measurements")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--eager", action="store_true", help="time the steps eagerly instead of as HIP-graph replays")
     return ap.parse_args()
 
 
@@ -137,50 +138,60 @@ class Workload:
         self.scale = 1.0 / math.sqrt(d)
         self.cur = 0
         self.step_no = 0
+        self.ev_used = 0
+        self._prepare()
         torch.cuda.synchronize()
 
-    # -- the five calls of one step ------------------------------------------------------------------------
+    # -- the five calls of one step, marshalled once per (input set, layer, tree buffer) ------------------------
+    def _prepare(self, stream=None):
+        """Marshal every call of a step once for the given stream (None = the current stream)."""
+        sg = self.sage
+        self.c_a1 = [sg.prepare("sage_entropy_topk", self.draft[s], self.k, self.H, self.idx, self.prob, self.renorm,
+                                self.Hk, self.alpha, self.ws1, stream=stream) for s in range(self.slots)]
+        self.c_a2, self.c_a3, self.c_a1t, self.c_a4 = [], [], [], []
+        for cur in range(2):
+            t, nxt = self.tree[cur], self.tree[cur ^ 1]
+            self.c_a2.append(sg.prepare("sage_build_tree", self.renorm, self.alpha, self.prm, nxt["n_nodes"], nxt["parent"],
+                                        nxt["depth"], nxt["rank"], nxt["anc_mask"], None, self.idx, nxt["node_token"],
+                                        stream=stream))
+            self.c_a3.append([[sg.prepare("sage_tree_attention", self.Q[s], self.Kc[s % self.kv_slots][layer],
+                                          self.Vc[s % self.kv_slots][layer], self.Kt[s], self.Vt[s], self.O, self.kv_start,
+                                          self.kv_len, self.max_len, self.Hkv * self.d, self.d, t["anc_mask"], t["n_nodes"],
+                                          self.scale, self.ws3, stream=stream) for layer in range(self.layers)]
+                              for s in range(self.slots)])
+            self.c_a1t.append([sg.prepare("sage_entropy_topk", self.target[s], 1, self.tH, self.tgt_idx, None, None, self.tHk,
+                                          self.talpha, self.ws1t, t["n_nodes"], MAX_NODES, stream=stream)
+                               for s in range(self.slots)])
+            self.c_a4.append(sg.prepare("sage_verify_accept", t["node_token"], self.tgt_idx, t["parent"], t["depth"],
+                                        t["anc_mask"], t["n_nodes"], self.path_cap, self.acc_len, self.best, self.path,
+                                        self.out_tok, stream=stream))
+
     def draft_confidence(self, s):
-        self.sage.sage_entropy_topk(self.draft[s], self.k, self.H, self.idx, self.prob, self.renorm, self.Hk, self.alpha,
-                                    self.ws1)
+        self.c_a1[s]()
 
     def plan_next_tree(self):
-        t = self.tree[self.cur ^ 1]
-        self.sage.sage_build_tree(self.renorm, self.alpha, self.prm, t["n_nodes"], t["parent"], t["depth"], t["rank"],
-                                  t["anc_mask"], None, self.idx, t["node_token"])
+        self.c_a2[self.cur]()
 
     def attention(self, s, layer):
-        t = self.tree[self.cur]
-        ks = s % self.kv_slots
-        self.sage.sage_tree_attention(self.Q[s], self.Kc[ks][layer], self.Vc[ks][layer], self.Kt[s], self.Vt[s], self.O,
-                                      self.kv_start, self.kv_len, self.max_len, self.Hkv * self.d, self.d, t["anc_mask"],
-                                      t["n_nodes"], self.scale, self.ws3)
-
-    def target_greedy(self, s):
-        t = self.tree[self.cur]
-        self.sage.sage_entropy_topk(self.target[s], 1, self.tH, self.tgt_idx, None, None, self.tHk, self.talpha, self.ws1t,
-                                    t["n_nodes"], MAX_NODES)
-
-    def accept(self):
-        t = self.tree[self.cur]
-        self.sage.sage_verify_accept(t["node_token"], self.tgt_idx, t["parent"], t["depth"], t["anc_mask"], t["n_nodes"],
-                                     self.path_cap, self.acc_len, self.best, self.path, self.out_tok)
+        self.c_a3[self.cur][s][layer]()
 
     def step(self, events=None):
-        torch = self.torch
         s = self.step_no % self.slots
-        self.draft_confidence(s)
-        self.plan_next_tree()
-        for layer in range(self.layers):
-            if events is not None:
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        cur = self.cur
+        self.c_a1[s]()
+        self.c_a2[cur]()
+        if events is None:
+            for call in self.c_a3[cur][s]:
+                call()
+        else:
+            for call in self.c_a3[cur][s]:
+                e0, e1 = events[self.ev_used], events[self.ev_used + 1]
+                self.ev_used += 2
                 e0.record()
-            self.attention(s, layer)
-            if events is not None:
+                call()
                 e1.record()
-                events.append((e0, e1))
-        self.target_greedy(s)
-        self.accept()
+        self.c_a1t[cur][s]()
+        self.c_a4[cur]()
         self.cur ^= 1
         self.step_no += 1
 
@@ -195,22 +206,89 @@ class Workload:
         return float(sum(4.0 * n * self.Hq * self.d * (int(L) + n) for n, L in zip(n_nodes_per_seq, self.kv_lens)))
 
 
-def time_steps(w: Workload, steps: int, warmup: int):
+def snapshot(w: Workload):
+    t = w.tree[w.cur]
+    return [x.clone() for x in (w.O, w.acc_len, w.best, w.path, w.out_tok, w.tgt_idx, w.alpha, t["n_nodes"], t["parent"],
+                                t["anc_mask"], t["node_token"])]
+
+
+def capture_cycle(w: Workload):
+    """Record one full cycle over the input sets as a HIP graph and check its replays against eager execution.
+
+    A cycle returns the step state (tree buffers, input-set index) to where it started, so every replay computes
+    what an eager cycle computes; that is checked bit for bit on three replays with eager cycles in between.
+    Returns (graph, steps_per_replay) or (None, 0) when capture is unavailable or a replay disagrees.
+    """
+    torch = w.torch
+    cycle = w.slots if w.slots % 2 == 0 else 2 * w.slots
+    while w.step_no % cycle:                      # align to a cycle boundary
+        w.step()
+    torch.cuda.synchronize()
+    try:
+        side = torch.cuda.Stream()
+        w._prepare(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(cycle):
+                w.step()
+        w._prepare(None)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            for _ in range(cycle):
+                w.step()
+            torch.cuda.synchronize()
+            want = snapshot(w)
+            graph.replay()
+            torch.cuda.synchronize()
+            got = snapshot(w)
+            if not all(torch.equal(a, b) for a, b in zip(want, got)):
+                print("bench.py: graph replay differs from eager execution; timing eagerly", file=sys.stderr)
+                return None, 0
+        return graph, cycle
+    except Exception as ex:  # capture unsupported on this stack: time eagerly
+        print(f"bench.py: graph capture unavailable ({type(ex).__name__}); timing eagerly", file=sys.stderr)
+        w._prepare(None)
+        return None, 0
+
+
+def time_steps(w: Workload, steps: int, warmup: int, use_graph: bool):
+    """Timed region: exactly `steps` steps, as graph replays of whole cycles (plus an eager remainder) or eagerly."""
     torch = w.torch
     for _ in range(warmup):
         w.step()
     torch.cuda.synchronize()
+    graph, cycle = capture_cycle(w) if use_graph else (None, 0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    done = 0
+    if graph is not None:
+        while done + cycle <= steps:
+            graph.replay()
+            done += cycle
+            w.step_no += cycle
+    while done < steps:
+        w.step()
+        done += 1
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall, graph is not None
+
+
+def time_attention_launches(w: Workload, steps: int):
+    """Eager pass over `steps` steps with HIP events around every sage_tree_attention call."""
+    torch = w.torch
     first = w.step_no
-    events, n_log = [], []
+    events = [torch.cuda.Event(enable_timing=True) for _ in range(2 * steps * w.layers)]
+    w.ev_used = 0
     t0 = time.perf_counter()
     for _ in range(steps):
         w.step(events)
     torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    att_ms = [a.elapsed_time(b) for a, b in events]
-    # tree sizes seen by the timed attention launches: the tree verified at step t was planned at step t-1 from
-    # slot (t-1) % slots; replay that planning (untimed) to read the node counts back
-    sizes = {}
+    eager_wall = time.perf_counter() - t0
+    att_ms = [events[i].elapsed_time(events[i + 1]) for i in range(0, w.ev_used, 2)]
+    # tree sizes seen by those launches: the tree verified at step t was planned at step t-1 from input set
+    # (t-1) % slots; replay that planning (untimed) to read the node counts back
+    sizes, n_log = {}, []
     for s in range(w.slots):
         w.draft_confidence(s)
         w.plan_next_tree()
@@ -218,7 +296,7 @@ def time_steps(w: Workload, steps: int, warmup: int):
         sizes[s] = w.tree[w.cur ^ 1]["n_nodes"].cpu().numpy().copy()
     for t in range(first, first + steps):
         n_log.append(sizes[(t - 1) % w.slots])
-    return wall, att_ms, n_log
+    return att_ms, n_log, eager_wall
 
 
 def cpu_baseline(w: Workload, budget_s: float):
@@ -264,39 +342,35 @@ def cpu_baseline(w: Workload, budget_s: float):
     return dict(value=n_steps / spent, unit="steps/s", cores=oracle.num_threads(), kind="oracle", sample=sample)
 
 
-def long_kv_attention(names, launches=40):
-    """Attention kernel alone on the long-KV shapes: rotating layer buffers, HIP events around every launch."""
+def long_kv_attention(names, launches=48):
+    """Attention alone on the long-KV shapes: rotating input sets / layers, HIP events around every launch."""
     out = []
     for name in names:
         import torch
         w = Workload(name, None)
-        if name == "c5":
-            w.layers_avail = w.layers
-        # plan one tree per slot, then time attention launches cycling over slots/layers
-        per_slot = []
-        for s in range(w.slots):
-            w.draft_confidence(s)
-            w.plan_next_tree()
-            torch.cuda.synchronize()
-            per_slot.append({k: v.clone() for k, v in w.tree[w.cur ^ 1].items()})
         ms, nodes = [], []
+        events = [torch.cuda.Event(enable_timing=True) for _ in range(2 * (launches + 8))]
         for it in range(launches + 8):
             s = it % w.slots
-            w.tree[w.cur] = per_slot[s]
-            layer = it % w.layers
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            w.draft_confidence(s)                 # plan the tree of this input set into the other buffer, switch to it
+            w.plan_next_tree()
+            w.cur ^= 1
+            if it >= 8:
+                nodes.append(w.tree[w.cur]["n_nodes"].cpu().numpy().copy())
+            torch.cuda.synchronize()
+            e0, e1 = events[2 * it], events[2 * it + 1]
             e0.record()
-            w.attention(s, layer)
+            w.attention(s, it % w.layers)
             e1.record()
             if it >= 8:
                 ms.append((e0, e1))
-                nodes.append(per_slot[s]["n_nodes"].cpu().numpy())
         torch.cuda.synchronize()
         t = [a.elapsed_time(b) for a, b in ms]
         avg_ms = sum(t) / len(t)
         bytes_avg = sum(w.attention_algorithmic_bytes(n) for n in nodes) / len(nodes)
         flops_avg = sum(w.attention_flops(n) for n in nodes) / len(nodes)
-        out.append(dict(workload=name, kv_len=int(w.max_len), mean_nodes=float(sum(n.sum() for n in nodes) / len(nodes)),
+        out.append(dict(workload=name, kv_len=[int(x) for x in w.kv_lens] if w.B > 1 else int(w.max_len),
+                        mean_nodes=float(sum(n.sum() for n in nodes) / len(nodes)),
                         avg_us=avg_ms * 1e3, min_us=min(t) * 1e3, hbm_GBps=bytes_avg / (avg_ms * 1e-3) / 1e9,
                         hbm_frac=bytes_avg / (avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                         mfma_TFLOPs=flops_avg / (avg_ms * 1e-3) / 1e12,
@@ -322,7 +396,8 @@ def main():
     warmup = args.warmup if args.warmup is not None else defaults[args.workload][1]
 
     w = Workload(args.workload, args.slots)
-    wall, att_ms, n_log = time_steps(w, steps, warmup)
+    wall, graphed = time_steps(w, steps, warmup, not args.eager)
+    att_ms, n_log, eager_wall = time_attention_launches(w, min(steps, 2000))
     ms_per_step = wall * 1e3 / steps
     att_avg_ms = sum(att_ms) / len(att_ms)
     per_launch_bytes = sum(w.attention_algorithmic_bytes(n) for n in n_log) / len(n_log)
@@ -342,10 +417,13 @@ def main():
             "c4": "72B shape, batch 8, ragged KV 2048..12288, ragged trees, vocab 152064",
             "c5": "80-layer attention stack at the 72B shape, KV 32768 per layer, 64-node tree, vocab 152064"}[args.workload],
             "kv_len": [int(x) for x in w.kv_lens], "layers": w.layers, "batch": w.B, "input_sets": w.slots,
-            "mean_tree_nodes": mean_nodes, "tree_params": w.tree_prm},
+            "mean_tree_nodes": mean_nodes, "tree_params": w.tree_prm,
+            "launch_mode": "HIP graph replay of whole input-set cycles" if graphed else "eager launches",
+            "eager_ms_per_step": eager_wall * 1e3 / len(n_log) * w.layers / w.layers},
         "roofline": {"bound": "hbm", "kernel": "sage_tree_attention (bf16 MFMA kernel + split merge, per layer launch)",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": None, "avg_launch_us": att_avg_ms * 1e3, "algorithmic_bytes_per_launch": per_launch_bytes,
+                     "traffic": None, "avg_launch_us": att_avg_ms * 1e3,
+                     "timing": "HIP events around every sage_tree_attention call in an eager pass over the same steps", "algorithmic_bytes_per_launch": per_launch_bytes,
                      "mfma_TFLOPs": per_launch_flops / (att_avg_ms * 1e-3) / 1e12,
                      "mfma_frac": per_launch_flops / (att_avg_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
     }
@@ -354,7 +432,7 @@ def main():
     del w
     torch.cuda.empty_cache()
     if not args.no_extras and args.workload == "c2":
-        result["attention_long_kv"] = long_kv_attention(["c3", "c5"])
+        result["attention_long_kv"] = long_kv_attention(["c3", "c4", "c5"])
     print(json.dumps(result))
 
 

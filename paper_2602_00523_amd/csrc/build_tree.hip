@@ -2,92 +2,116 @@
 // Eq. 12 per-level width decay, recursive expansion with the depth-adaptive threshold, node cap).
 //
 // The result is defined by the order of the recursive expansion (depth-first, ranks ascending, global node
-// cap), which is inherently serial over at most 64 nodes, so one lane per sequence walks an explicit stack in
-// LDS while the rest of its wave only helps with the coalesced write-out.  All real arithmetic is IEEE fp32
-// with round-to-nearest add/mul/div and no fused multiply-add (this file is compiled with contraction off
-// and uses the explicit *_rn intrinsics), so the integer outcome is reproducible bit for bit.
+// cap), which is inherently serial over at most 64 nodes, so one wave64 per sequence walks it with wave-uniform
+// control flow and keeps everything in registers:
+//   lane r   holds candidate probability P~[r]; the candidates of an expansion are tested in one ballot;
+//   lane l   holds theta_l = 0.1 l / D and W / l of level l (the divisions are done once, in parallel);
+//   lane v   holds the fields of node v (parent, depth, rank, cumulative probability, ancestor mask);
+//   lane s   holds the parked frame of stack depth s (node being expanded, candidates not yet tried).
+// All real arithmetic is IEEE fp32 with round-to-nearest add/mul/div and no fused multiply-add (this file is
+// compiled with contraction off and uses the explicit *_rn intrinsics), so the integer outcome is reproducible
+// bit for bit.
 #include "sage_internal.h"
 
 namespace {
 
-struct Frame {
-    int node;     // node being expanded
-    int next_r;   // next candidate rank to try
-    int width;    // W_l of this expansion
-    float theta;  // theta_l of the level being created
-};
+__device__ __forceinline__ float lane_read(float v, int lane) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+__device__ __forceinline__ int lane_read(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
+__device__ __forceinline__ uint64_t lane_read(uint64_t v, int lane) {
+    const uint32_t lo = __builtin_amdgcn_readlane(static_cast<int>(v), lane);
+    const uint32_t hi = __builtin_amdgcn_readlane(static_cast<int>(v >> 32), lane);
+    return (static_cast<uint64_t>(hi) << 32) | lo;
+}
 
 __global__ __launch_bounds__(64) void build_tree_kernel(
     const float* __restrict__ topk_renorm, const float* __restrict__ alpha, const int* __restrict__ topk_idx, int k,
     sage_tree_params prm, int* __restrict__ n_nodes, int* __restrict__ parent, int* __restrict__ depth,
     int* __restrict__ rank, uint64_t* __restrict__ anc_mask, float* __restrict__ cum_prob,
     int* __restrict__ node_token) {
-    __shared__ float s_pt[SAGE_MAX_TOPK];
-    __shared__ int s_parent[SAGE_MAX_NODES], s_depth[SAGE_MAX_NODES], s_rank[SAGE_MAX_NODES];
-    __shared__ float s_cum[SAGE_MAX_NODES];
-    __shared__ uint64_t s_mask[SAGE_MAX_NODES];
-    __shared__ Frame s_stack[SAGE_MAX_DEPTH + 1];
-    __shared__ int s_n;
-
     const int b = blockIdx.x;
     const int lane = threadIdx.x;
-    if (lane < k) s_pt[lane] = topk_renorm[static_cast<long>(b) * k + lane];
-    __syncthreads();
+    const float pt = lane < k ? topk_renorm[static_cast<long>(b) * k + lane] : 0.0f;
+    const int tok = (topk_idx && lane < k) ? topk_idx[static_cast<long>(b) * k + lane] : -1;
+    const float a = alpha[b];
 
-    if (lane == 0) {
-        const float a = alpha[b];
-        // Eq. 10 / Eq. 11, rounded half up
-        const float Df = floorf(__fadd_rn(__fadd_rn((float)prm.d_min, __fmul_rn(a, (float)(prm.d_max - prm.d_min))), 0.5f));
-        float W = floorf(__fadd_rn(
-            __fadd_rn((float)prm.w_min, __fmul_rn(__fsub_rn(1.0f, a), (float)(prm.w_max - prm.w_min))), 0.5f));
-        if (W > (float)k) W = (float)k;
-        // alpha is a confidence in [0,1]; anything else is clamped to the stack's capacity rather than trusted
-        const int D = Df >= (float)SAGE_MAX_DEPTH ? SAGE_MAX_DEPTH : (Df >= 0.0f ? (int)Df : 0);
+    // Eq. 10 / Eq. 11, rounded half up
+    const float Df = floorf(__fadd_rn(__fadd_rn((float)prm.d_min, __fmul_rn(a, (float)(prm.d_max - prm.d_min))), 0.5f));
+    float W = floorf(__fadd_rn(__fadd_rn((float)prm.w_min, __fmul_rn(__fsub_rn(1.0f, a), (float)(prm.w_max - prm.w_min))), 0.5f));
+    if (W > (float)k) W = (float)k;
+    // alpha is a confidence in [0,1]; anything else is clamped to the stack's capacity rather than trusted
+    const int D = Df >= (float)SAGE_MAX_DEPTH ? SAGE_MAX_DEPTH : (Df >= 0.0f ? (int)Df : 0);
 
-        s_parent[0] = -1; s_depth[0] = 0; s_rank[0] = -1; s_cum[0] = 1.0f; s_mask[0] = 1ull;
-        int n = 1;
-        int sp = 0;
-        if (D >= 1) {
-            int w1 = (int)W;
-            if (w1 > k) w1 = k;
-            s_stack[0] = Frame{0, 0, w1, __fdiv_rn(__fmul_rn(0.1f, 1.0f), Df)};
-            sp = 1;
-        }
-        while (sp > 0 && n < prm.n_max) {
-            Frame& f = s_stack[sp - 1];
-            if (f.next_r >= f.width) { --sp; continue; }
-            const int r = f.next_r++;
-            const int u = f.node;
-            const float c = __fmul_rn(s_cum[u], s_pt[r]);
-            if (c > f.theta) {
-                const int v = n++;
-                const int l = s_depth[u] + 1;
-                s_parent[v] = u; s_depth[v] = l; s_rank[v] = r; s_cum[v] = c;
-                s_mask[v] = s_mask[u] | (1ull << v);
-                const int l2 = l + 1;                       // level that expanding v would create
-                if (l2 <= D) {
-                    // Eq. 12 with the parent's cumulative path probability, at least one candidate
-                    const float w = floorf(__fmul_rn(__fdiv_rn(W, (float)l2), __fadd_rn(0.5f, c)));
-                    int wl = (int)w;
-                    if (wl < 1) wl = 1;
-                    if (wl > k) wl = k;
-                    s_stack[sp++] = Frame{v, 0, wl, __fdiv_rn(__fmul_rn(0.1f, (float)l2), Df)};
-                }
-            }
-        }
-        s_n = n;
+    // per-level constants, lane l <-> level l
+    const float lvl = (float)(lane > 0 ? lane : 1);
+    const float theta_l = __fdiv_rn(__fmul_rn(0.1f, lvl), Df);     // depth-adaptive threshold
+    const float per_level_l = __fdiv_rn(W, lvl);                   // W / l of Eq. 12
+
+    // node fields, lane v <-> node v (the root is node 0)
+    int nd_parent = -1, nd_depth = 0, nd_rank = -1, nd_token = -1;
+    float nd_cum = 1.0f;
+    uint64_t nd_mask = 1ull;
+
+    // parked frames, lane s <-> stack depth s
+    int st_node = 0;
+    uint64_t st_rest = 0;
+
+    int n = 1;
+    int sp = 0;
+    int f_node = 0, f_depth = 0;                     // frame being expanded (uniform)
+    float f_cum = 1.0f;
+    uint64_t f_nmask = 1ull;
+    uint64_t f_rest = 0;                             // candidates of this expansion not yet tried (bit r = rank r)
+    if (D >= 1) {
+        int w1 = (int)W;
+        if (w1 > k) w1 = k;
+        f_rest = __ballot(lane < w1 && __fmul_rn(1.0f, pt) > lane_read(theta_l, 1));
     }
-    __syncthreads();
+    while (n < prm.n_max) {
+        if (f_rest == 0) {                           // this expansion is exhausted: resume the parent's
+            if (sp == 0) break;
+            --sp;
+            f_node = lane_read(st_node, sp);
+            f_rest = lane_read(st_rest, sp);
+            f_cum = lane_read(nd_cum, f_node);
+            f_depth = lane_read(nd_depth, f_node);
+            f_nmask = lane_read(nd_mask, f_node);
+            continue;
+        }
+        const int r = __builtin_ctzll(f_rest);       // lowest untried rank that passes the threshold
+        f_rest &= f_rest - 1;
+        const float c = __fmul_rn(f_cum, lane_read(pt, r));
+        const int v = n++;
+        const int l = f_depth + 1;
+        const uint64_t vm = f_nmask | (1ull << v);
+        if (lane == v) {
+            nd_parent = f_node; nd_depth = l; nd_rank = r; nd_cum = c; nd_mask = vm;
+        }
+        const int tok_r = lane_read(tok, r);
+        if (lane == v) nd_token = tok_r;
+        const int l2 = l + 1;                        // level that expanding v creates
+        if (l2 <= D) {
+            // Eq. 12 with the parent's cumulative path probability, at least one candidate
+            const float w = floorf(__fmul_rn(lane_read(per_level_l, l2), __fadd_rn(0.5f, c)));
+            int wl = (int)w;
+            if (wl < 1) wl = 1;
+            if (wl > k) wl = k;
+            const uint64_t pass = __ballot(lane < wl && __fmul_rn(c, pt) > lane_read(theta_l, l2));
+            if (lane == sp) { st_node = f_node; st_rest = f_rest; }
+            ++sp;
+            f_node = v; f_depth = l; f_cum = c; f_nmask = vm; f_rest = pass;
+        }
+    }
 
-    const int n = s_n;
     const long base = static_cast<long>(b) * SAGE_MAX_NODES;
     if (lane < n) {
-        parent[base + lane] = s_parent[lane];
-        depth[base + lane] = s_depth[lane];
-        rank[base + lane] = s_rank[lane];
-        anc_mask[base + lane] = s_mask[lane];
-        if (cum_prob) cum_prob[base + lane] = s_cum[lane];
-        if (node_token) node_token[base + lane] = lane == 0 ? -1 : topk_idx[static_cast<long>(b) * k + s_rank[lane]];
+        parent[base + lane] = nd_parent;
+        depth[base + lane] = nd_depth;
+        rank[base + lane] = nd_rank;
+        anc_mask[base + lane] = nd_mask;
+        if (cum_prob) cum_prob[base + lane] = nd_cum;
+        if (node_token) node_token[base + lane] = nd_token;
     }
     if (lane == 0) n_nodes[b] = n;
 }

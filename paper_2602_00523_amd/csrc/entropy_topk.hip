@@ -2,23 +2,25 @@
 // (Sec. 3.1: Eq. 7 renormalised top-k, Eq. 8 its entropy, Eq. 9 confidence; Eq. 1 softmax) and, with k = 1,
 // the target's greedy token per tree node (Sec. 2.2 / Def. 4.1).
 //
-// HBM-bound: every logit is read exactly once with 16-byte loads.  Pass 1 splits each row into chunks of
-// CHUNK logits, one workgroup per (chunk, row): the chunk lives in registers, the workgroup selects its k best
-// entries under the total order (value descending, index ascending) by k rounds of wave-shuffle argmax on a
-// 64-bit composite key, and reduces the softmax statistics (m, Z, T) of the chunk, where
+// HBM-bound: every logit is read exactly once with 16-byte loads.  Pass 1: each WAVE owns a slice of UNIT
+// logits of one row, held in registers; it extracts the slice's k best entries under the total order (value
+// descending, index ascending) by k rounds of a wave-wide maximum on a 64-bit composite key, done with DPP row
+// rotations and the 16/32-lane swaps (no LDS, no workgroup barrier), and reduces the slice's softmax statistics
 //   Z = sum exp(x - m),  T = sum exp(x - m) (m - x)   so that   H = ln Z + T / Z   (both terms >= 0).
-// Pass 2 (one wave per row) combines the chunk statistics by log-sum-exp, merges the sorted per-chunk lists
-// with a k-round tournament over the list heads, and evaluates Eq. 7-9 on the k winners.
+// Pass 2 (one wave per row) combines the slice statistics by log-sum-exp, merges the sorted per-slice lists with
+// a k-round tournament over the list heads (lists staged in LDS), and evaluates Eq. 7-9 on the k winners.
 #include "sage_internal.h"
 
 namespace {
 
 constexpr int THREADS = 256;
-constexpr int EPT = 16;                  // logits per thread
-constexpr int CHUNK = THREADS * EPT;     // logits per workgroup
+constexpr int EPT = 16;                  // logits per lane
+constexpr int UNIT = 64 * EPT;           // logits per wave
 constexpr int WAVES = THREADS / 64;
+constexpr int MERGE_LDS_KEYS = 6144;     // lists are staged in LDS when they fit (48 KB)
+constexpr int MAX_OWN = 16;              // lists per lane in pass 2: up to 1024 slices = 1M logits
 
-struct ChunkStats { float m, Z, T, pad; };
+struct UnitStats { float m, Z, T, pad; };
 
 // Order-preserving map float -> uint32 (larger float -> larger code); -0 is folded into +0 so that equal
 // values compare equal before the index tie-break.
@@ -32,27 +34,54 @@ __device__ __forceinline__ float unsortable(uint32_t s) {
     return __uint_as_float(u);
 }
 // key: high word = value code, low word = ~index, so a larger key is a better candidate; 0 = no candidate.
-__device__ __forceinline__ uint64_t make_key(float v, int idx) {
-    return (static_cast<uint64_t>(sortable(v)) << 32) | static_cast<uint32_t>(0xFFFFFFFFu - static_cast<uint32_t>(idx));
-}
-__device__ __forceinline__ int key_index(uint64_t key) { return static_cast<int>(0xFFFFFFFFu - static_cast<uint32_t>(key)); }
-__device__ __forceinline__ float key_value(uint64_t key) { return unsortable(static_cast<uint32_t>(key >> 32)); }
+struct Key { uint32_t hi, lo; };
+__device__ __forceinline__ Key make_key(float v, int idx) { return Key{sortable(v), 0xFFFFFFFFu - static_cast<uint32_t>(idx)}; }
+__device__ __forceinline__ bool key_less(Key a, Key b) { return a.hi < b.hi || (a.hi == b.hi && a.lo < b.lo); }
+__device__ __forceinline__ bool key_equal(Key a, Key b) { return a.hi == b.hi && a.lo == b.lo; }
+__device__ __forceinline__ bool key_none(Key a) { return (a.hi | a.lo) == 0; }
+__device__ __forceinline__ Key key_max(Key a, Key b) { return key_less(a, b) ? b : a; }
+__device__ __forceinline__ int key_index(Key k) { return static_cast<int>(0xFFFFFFFFu - k.lo); }
+__device__ __forceinline__ float key_value(Key k) { return unsortable(k.hi); }
+__device__ __forceinline__ uint64_t key_pack(Key k) { return (static_cast<uint64_t>(k.hi) << 32) | k.lo; }
+__device__ __forceinline__ Key key_unpack(uint64_t v) { return Key{static_cast<uint32_t>(v >> 32), static_cast<uint32_t>(v)}; }
 
-__device__ __forceinline__ uint64_t shfl_xor_u64(uint64_t v, int off) {
-    uint32_t lo = __shfl_xor(static_cast<uint32_t>(v), off);
-    uint32_t hi = __shfl_xor(static_cast<uint32_t>(v >> 32), off);
-    return (static_cast<uint64_t>(hi) << 32) | lo;
+// Wave-wide maximum, result in every lane: four rotations inside each row of 16 lanes, then the 16-lane and
+// 32-lane swaps combine the four rows.  A key is reduced in two passes: the value code first, then the index
+// code among the lanes that hold the winning value.
+template <int CTRL> __device__ __forceinline__ uint32_t u_dpp(uint32_t v) {
+    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, false));
 }
-__device__ __forceinline__ uint64_t wave_max_u64(uint64_t v) {
-    for (int off = 32; off > 0; off >>= 1) {
-        uint64_t o = shfl_xor_u64(v, off);
-        v = o > v ? o : v;
-    }
-    return v;
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+    v = max(v, u_dpp<0x128>(v));         // row_ror:8
+    v = max(v, u_dpp<0x124>(v));         // row_ror:4
+    v = max(v, u_dpp<0x122>(v));         // row_ror:2
+    v = max(v, u_dpp<0x121>(v));         // row_ror:1
+    auto a = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    v = max(a[0], a[1]);
+    a = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return max(a[0], a[1]);
+}
+__device__ __forceinline__ Key wave_max_key(Key k) {
+    const uint32_t hi = wave_max_u32(k.hi);
+    const uint32_t lo = wave_max_u32(k.hi == hi ? k.lo : 0u);
+    return Key{hi, lo};
+}
+template <int CTRL> __device__ __forceinline__ float f_dpp(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
 }
 __device__ __forceinline__ float wave_sum(float v) {
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-    return v;
+    v += f_dpp<0x128>(v); v += f_dpp<0x124>(v); v += f_dpp<0x122>(v); v += f_dpp<0x121>(v);
+    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(a[0]) + __uint_as_float(a[1]);
+}
+__device__ __forceinline__ float wave_max(float v) {
+    v = fmaxf(v, f_dpp<0x128>(v)); v = fmaxf(v, f_dpp<0x124>(v)); v = fmaxf(v, f_dpp<0x122>(v)); v = fmaxf(v, f_dpp<0x121>(v));
+    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
 }
 
 __device__ __forceinline__ bool row_is_valid(int row, const int* n_valid, int rows_per_group) {
@@ -83,28 +112,26 @@ template <> struct Loader<uint16_t> {
     __device__ static float one(const uint16_t* p) { return sage::bf16_bits_to_float(*p); }
 };
 
+// Pass 1: one wave per (slice, row).
 template <typename T>
-__global__ __launch_bounds__(THREADS) void chunk_kernel(const T* __restrict__ logits, int vocab, long row_stride, int k,
-                                                        const int* __restrict__ n_valid, int rows_per_group, int nchunks,
-                                                        ChunkStats* __restrict__ stats, uint64_t* __restrict__ keys) {
+__global__ __launch_bounds__(THREADS) void slice_kernel(const T* __restrict__ logits, int vocab, long row_stride, int k,
+                                                        const int* __restrict__ n_valid, int rows_per_group, int nunits,
+                                                        UnitStats* __restrict__ stats, uint64_t* __restrict__ keys) {
     using L = Loader<T>;
     constexpr int VEC = L::VEC;
     constexpr int NV = EPT / VEC;
-    __shared__ uint64_t s_key[WAVES];
-    __shared__ float s_sum[2][WAVES];
-
     const int row = blockIdx.y;
-    const int chunk = blockIdx.x;
-    if (!row_is_valid(row, n_valid, rows_per_group)) return;
-    const int tid = threadIdx.x;
+    const int unit = blockIdx.x * WAVES + (threadIdx.x >> 6);
+    if (unit >= nunits || !row_is_valid(row, n_valid, rows_per_group)) return;
+    const int lane = threadIdx.x & 63;
     const T* rowp = logits + static_cast<long>(row) * row_stride;
-    const int base = chunk * CHUNK;
+    const int base = unit * UNIT;
 
     float v[EPT];
     int first[NV];
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
-        const int e0 = base + (j * THREADS + tid) * VEC;
+        const int e0 = base + (j * 64 + lane) * VEC;
         first[j] = e0;
         if (e0 + VEC <= vocab) {
             L::load(rowp + e0, v + j * VEC);
@@ -114,37 +141,37 @@ __global__ __launch_bounds__(THREADS) void chunk_kernel(const T* __restrict__ lo
         }
     }
 
-    // ---- k rounds of workgroup-wide argmax on the composite key
-    uint32_t taken = 0;
-    float chunk_max = -INFINITY;
-    uint64_t* out_keys = keys + (static_cast<long>(row) * nchunks + chunk) * k;
-    for (int round = 0; round < k; ++round) {
-        uint64_t best = 0;
-        int best_slot = -1;
+    // ---- k rounds of wave-wide argmax on the composite key
+    Key cand[EPT];
 #pragma unroll
-        for (int s = 0; s < EPT; ++s) {
-            const int idx = first[s / VEC] + (s % VEC);
-            const uint64_t key = (idx < vocab && !((taken >> s) & 1)) ? make_key(v[s], idx) : 0;
-            if (key > best) { best = key; best_slot = s; }
-        }
-        uint64_t w = wave_max_u64(best);
-        if ((tid & 63) == 0) s_key[tid >> 6] = w;
-        __syncthreads();
-        uint64_t g = s_key[0];
-#pragma unroll
-        for (int i = 1; i < WAVES; ++i) g = s_key[i] > g ? s_key[i] : g;
-        __syncthreads();
-        if (g != 0 && best == g) taken |= 1u << best_slot;
-        if (round == 0) chunk_max = (g != 0) ? key_value(g) : -INFINITY;
-        if (tid == 0) out_keys[round] = g;
+    for (int s = 0; s < EPT; ++s) {
+        const int idx = first[s / VEC] + (s % VEC);
+        cand[s] = idx < vocab ? make_key(v[s], idx) : Key{0, 0};
     }
+    uint64_t* out_keys = keys + (static_cast<long>(row) * nunits + unit) * k;
+    float unit_max = -INFINITY;
+    Key mine = Key{0, 0};                            // lane j keeps the winner of round j (k <= 64)
+    for (int round = 0; round < k; ++round) {
+        Key best = cand[0];
+#pragma unroll
+        for (int s = 1; s < EPT; ++s) best = key_max(best, cand[s]);
+        const Key g = wave_max_key(best);
+        if (!key_none(g)) {
+#pragma unroll
+            for (int s = 0; s < EPT; ++s)
+                if (key_equal(cand[s], g)) cand[s] = Key{0, 0};      // keys are unique: exactly one lane, one slot
+        }
+        if (round == 0) unit_max = key_none(g) ? -INFINITY : key_value(g);
+        if (lane == round) mine = g;
+    }
+    if (lane < k) out_keys[lane] = key_pack(mine);
 
-    // ---- softmax statistics of the chunk relative to its own maximum
+    // ---- softmax statistics of the slice relative to its own maximum
     float Z = 0.f, Tm = 0.f;
-    if (chunk_max > -INFINITY) {
+    if (unit_max > -INFINITY) {
 #pragma unroll
         for (int s = 0; s < EPT; ++s) {
-            const float dlt = chunk_max - v[s];          // >= 0, +inf for padding and -inf logits
+            const float dlt = unit_max - v[s];               // >= 0, +inf for padding and -inf logits
             const float e = expf(-dlt);
             Z += e;
             Tm += (e > 0.f) ? e * dlt : 0.f;
@@ -152,69 +179,185 @@ __global__ __launch_bounds__(THREADS) void chunk_kernel(const T* __restrict__ lo
     }
     Z = wave_sum(Z);
     Tm = wave_sum(Tm);
-    if ((tid & 63) == 0) { s_sum[0][tid >> 6] = Z; s_sum[1][tid >> 6] = Tm; }
+    if (lane == 0) stats[static_cast<long>(row) * nunits + unit] = UnitStats{unit_max, Z, Tm, 0.f};
+}
+
+// Pass 1 for k > 1 (few rows, latency matters more than bandwidth): one WORKGROUP per slice, 4 logits per lane.
+// Each wave extracts the k best of its 256 logits; wave 0 then merges the four sorted lists.
+template <typename T>
+__global__ __launch_bounds__(THREADS) void slice_topk_kernel(const T* __restrict__ logits, int vocab, long row_stride, int k,
+                                                             const int* __restrict__ n_valid, int rows_per_group, int nunits,
+                                                             UnitStats* __restrict__ stats, uint64_t* __restrict__ keys) {
+    __shared__ uint64_t s_list[WAVES][SAGE_MAX_TOPK];
+    __shared__ float s_red[3][WAVES];
+    const int row = blockIdx.y;
+    const int unit = blockIdx.x;
+    if (!row_is_valid(row, n_valid, rows_per_group)) return;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const T* rowp = logits + static_cast<long>(row) * row_stride;
+    const int e0 = unit * UNIT + threadIdx.x * 4;
+
+    float v[4];
+    if (e0 + 4 <= vocab) {
+        if constexpr (sizeof(T) == 4) {
+            const float4 q = *reinterpret_cast<const float4*>(rowp + e0);
+            v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+        } else {
+            const uint2 q = *reinterpret_cast<const uint2*>(rowp + e0);
+            v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xFFFF0000u);
+            v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xFFFF0000u);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (e0 + e < vocab) ? Loader<T>::one(rowp + e0 + e) : -INFINITY;
+    }
+    Key cand[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) cand[e] = (e0 + e < vocab) ? make_key(v[e], e0 + e) : Key{0, 0};
+
+    Key mine = Key{0, 0};                            // lane j keeps the wave's winner of round j
+    Key top = Key{0, 0};
+    for (int round = 0; round < k; ++round) {
+        const Key best = key_max(key_max(cand[0], cand[1]), key_max(cand[2], cand[3]));
+        const Key g = wave_max_key(best);
+        if (round == 0) top = g;
+        if (!key_none(g)) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (key_equal(cand[e], g)) cand[e] = Key{0, 0};
+        }
+        if (lane == round) mine = g;
+    }
+    if (lane < k) s_list[wave][lane] = key_pack(mine);
+    // softmax statistics relative to the wave's maximum, combined across the four waves below
+    const float wmax = key_none(top) ? -INFINITY : key_value(top);
+    float Z = 0.f, Tm = 0.f;
+    if (wmax > -INFINITY) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float dlt = wmax - v[e];
+            const float ex = expf(-dlt);
+            Z += ex;
+            Tm += (ex > 0.f) ? ex * dlt : 0.f;
+        }
+    }
+    Z = wave_sum(Z);
+    Tm = wave_sum(Tm);
+    if (lane == 0) { s_red[0][wave] = wmax; s_red[1][wave] = Z; s_red[2][wave] = Tm; }
     __syncthreads();
-    if (tid == 0) {
+    if (wave != 0) return;
+
+    // ---- wave 0: merge the four sorted lists (lane w < 4 owns list w) and the four statistics
+    int cursor = 0;
+    Key head = lane < WAVES ? key_unpack(s_list[lane][0]) : Key{0, 0};
+    Key out = Key{0, 0};
+    for (int round = 0; round < k; ++round) {
+        const Key g = wave_max_key(head);
+        if (lane == round) out = g;
+        if (lane < WAVES && !key_none(g) && key_equal(head, g)) {
+            ++cursor;
+            head = cursor < k ? key_unpack(s_list[lane][cursor]) : Key{0, 0};
+        }
+    }
+    if (lane < k) keys[(static_cast<long>(row) * nunits + unit) * k + lane] = key_pack(out);
+    if (lane == 0) {
+        float m = fmaxf(fmaxf(s_red[0][0], s_red[0][1]), fmaxf(s_red[0][2], s_red[0][3]));
         float z = 0.f, t = 0.f;
 #pragma unroll
-        for (int i = 0; i < WAVES; ++i) { z += s_sum[0][i]; t += s_sum[1][i]; }
-        stats[static_cast<long>(row) * nchunks + chunk] = ChunkStats{chunk_max, z, t, 0.f};
+        for (int w = 0; w < WAVES; ++w) {
+            if (s_red[0][w] > -INFINITY) {
+                const float dlt = m - s_red[0][w];
+                const float sc = expf(-dlt);
+                z += sc * s_red[1][w];
+                t += sc * (s_red[2][w] + s_red[1][w] * dlt);
+            }
+        }
+        stats[static_cast<long>(row) * nunits + unit] = UnitStats{m, z, t, 0.f};
     }
 }
 
-// One wave per row: combine chunk statistics, k-way merge of the per-chunk sorted key lists, Eq. 7-9.
-__global__ __launch_bounds__(64) void merge_kernel(int k, const int* __restrict__ n_valid, int rows_per_group, int nchunks,
-                                                   const ChunkStats* __restrict__ stats, const uint64_t* __restrict__ keys,
-                                                   float* __restrict__ entropy, int* __restrict__ topk_idx,
-                                                   float* __restrict__ topk_prob, float* __restrict__ topk_renorm,
-                                                   float* __restrict__ topk_entropy, float* __restrict__ alpha) {
+// Pass 2: one wave per row: combine slice statistics, k-way merge of the per-slice sorted key lists, Eq. 7-9.
+// OWN = lists per lane (lane owns lists lane, lane+64, ...); the head of every owned list stays in registers and
+// only the lane whose list wins a round fetches its next entry.
+template <int OWN>
+__global__ __launch_bounds__(THREADS) void merge_kernel(int k, const int* __restrict__ n_valid, int rows_per_group, int nunits,
+                                                        const UnitStats* __restrict__ stats, const uint64_t* __restrict__ keys,
+                                                        float* __restrict__ entropy, int* __restrict__ topk_idx,
+                                                        float* __restrict__ topk_prob, float* __restrict__ topk_renorm,
+                                                        float* __restrict__ topk_entropy, float* __restrict__ alpha) {
+    __shared__ uint64_t s_keys[MERGE_LDS_KEYS];
+    __shared__ UnitStats s_stats[64 * OWN];
     const int row = blockIdx.x;
     if (!row_is_valid(row, n_valid, rows_per_group)) return;
-    const int lane = threadIdx.x;
-    const ChunkStats* st = stats + static_cast<long>(row) * nchunks;
-    const uint64_t* kk = keys + static_cast<long>(row) * nchunks * k;
+    const int tid = threadIdx.x;
+    const UnitStats* st = stats + static_cast<long>(row) * nunits;
+    const uint64_t* kk = keys + static_cast<long>(row) * nunits * k;
+    const int total = nunits * k;
+    const bool in_lds = total <= MERGE_LDS_KEYS;
+    // ---- the whole workgroup stages statistics and lists in LDS, eight independent loads per thread at a time
+    for (int c = tid; c < nunits; c += THREADS) s_stats[c] = st[c];
+    if (in_lds) {
+        for (int i0 = tid; i0 < total; i0 += THREADS * 8) {
+            uint64_t tmp[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) tmp[j] = (i0 + j * THREADS < total) ? kk[i0 + j * THREADS] : 0;
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (i0 + j * THREADS < total) s_keys[i0 + j * THREADS] = tmp[j];
+        }
+    }
+    __syncthreads();
+    if (tid >= 64) return;                           // wave 0 finishes the row
+    const int lane = tid;
 
+    Key head[OWN];
+    int cursor[OWN];
+#pragma unroll
+    for (int i = 0; i < OWN; ++i) {
+        const int c = lane + 64 * i;
+        head[i] = c < nunits ? key_unpack(in_lds ? s_keys[c * k] : kk[static_cast<long>(c) * k]) : Key{0, 0};
+        cursor[i] = 0;
+    }
     float m = -INFINITY;
-    for (int c = lane; c < nchunks; c += 64) m = fmaxf(m, st[c].m);
-    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
+#pragma unroll
+    for (int i = 0; i < OWN; ++i)
+        if (lane + 64 * i < nunits) m = fmaxf(m, s_stats[lane + 64 * i].m);
+    m = wave_max(m);
     float Z = 0.f, Tm = 0.f;
-    for (int c = lane; c < nchunks; c += 64) {
-        const ChunkStats s = st[c];
-        if (s.m > -INFINITY) {
-            const float dlt = m - s.m;
-            const float w = expf(-dlt);
-            Z += w * s.Z;
-            Tm += w * (s.T + s.Z * dlt);
+#pragma unroll
+    for (int i = 0; i < OWN; ++i) {
+        if (lane + 64 * i < nunits) {
+            const UnitStats u = s_stats[lane + 64 * i];
+            if (u.m > -INFINITY) {
+                const float dlt = m - u.m;
+                const float w = expf(-dlt);
+                Z += w * u.Z;
+                Tm += w * (u.T + u.Z * dlt);
+            }
         }
     }
     Z = wave_sum(Z);
     Tm = wave_sum(Tm);
     if (lane == 0 && entropy) entropy[row] = logf(Z) + Tm / Z;
 
-    // tournament over list heads; lane owns chunks lane, lane+64, ... and a cursor per owned chunk
-    constexpr int MAX_OWN = 16;                      // supports nchunks <= 1024
-    unsigned char cursor[MAX_OWN];
-#pragma unroll
-    for (int i = 0; i < MAX_OWN; ++i) cursor[i] = 0;
-    uint64_t mine = 0;                               // the winner this lane reports: lane j keeps winner j
+    Key mine = Key{0, 0};                            // lane j keeps winner j
     for (int round = 0; round < k; ++round) {
-        uint64_t best = 0;
-        int best_own = -1;
+        Key best = head[0];
 #pragma unroll
-        for (int i = 0; i < MAX_OWN; ++i) {
-            const int c = lane + 64 * i;
-            if (c < nchunks && cursor[i] < k) {
-                const uint64_t key = kk[static_cast<long>(c) * k + cursor[i]];
-                if (key > best) { best = key; best_own = i; }
+        for (int i = 1; i < OWN; ++i) best = key_max(best, head[i]);
+        const Key g = wave_max_key(best);
+        if (lane == round) mine = g;
+        if (!key_none(g) && key_equal(best, g) && round + 1 < k) {   // the owning lane advances the winning list
+#pragma unroll
+            for (int i = 0; i < OWN; ++i) {
+                if (key_equal(head[i], g)) {
+                    const int nxt = ++cursor[i];
+                    const long at = static_cast<long>(lane + 64 * i) * k + nxt;
+                    head[i] = nxt < k ? key_unpack(in_lds ? s_keys[at] : kk[at]) : Key{0, 0};
+                }
             }
         }
-        const uint64_t g = wave_max_u64(best);
-        if (g != 0 && best == g) {
-#pragma unroll
-            for (int i = 0; i < MAX_OWN; ++i)
-                if (i == best_own) cursor[i]++;
-        }
-        if (lane == round) mine = g;
     }
 
     const bool have = lane < k;
@@ -238,9 +381,9 @@ __global__ __launch_bounds__(64) void merge_kernel(int k, const int* __restrict_
     }
 }
 
-inline int num_chunks(int vocab) { return (vocab + CHUNK - 1) / CHUNK; }
+inline int num_units(int vocab) { return (vocab + UNIT - 1) / UNIT; }
 inline size_t stats_bytes(int rows, int vocab) {
-    size_t b = static_cast<size_t>(rows) * num_chunks(vocab) * sizeof(ChunkStats);
+    size_t b = static_cast<size_t>(rows) * num_units(vocab) * sizeof(UnitStats);
     return (b + 255) & ~static_cast<size_t>(255);
 }
 
@@ -248,7 +391,7 @@ inline size_t stats_bytes(int rows, int vocab) {
 
 extern "C" size_t sage_entropy_topk_workspace_bytes(int rows, int vocab, int k) {
     if (rows < 0 || vocab < 1 || k < 1) return 0;
-    return stats_bytes(rows, vocab) + static_cast<size_t>(rows) * num_chunks(vocab) * k * sizeof(uint64_t) + 256;
+    return stats_bytes(rows, vocab) + static_cast<size_t>(rows) * num_units(vocab) * k * sizeof(uint64_t) + 256;
 }
 
 extern "C" int sage_entropy_topk(const void* logits, int dtype, int rows, int vocab, long row_stride, int k,
@@ -262,24 +405,38 @@ extern "C" int sage_entropy_topk(const void* logits, int dtype, int rows, int vo
     const size_t esz = dtype == SAGE_F32 ? 4 : 2;
     if (!sage::aligned(logits, 16) || (static_cast<size_t>(row_stride) * esz) % 16 != 0 || !sage::aligned(workspace, 16))
         return SAGE_INVALID_ARG;
-    const int nchunks = num_chunks(vocab);
-    if (nchunks > 1024) return SAGE_UNSUPPORTED;
+    const int nunits = num_units(vocab);
+    if (nunits > 64 * MAX_OWN) return SAGE_UNSUPPORTED;
     if (rows > 65535) return SAGE_UNSUPPORTED;
     if (workspace_bytes < sage_entropy_topk_workspace_bytes(rows, vocab, k)) return SAGE_WORKSPACE_TOO_SMALL;
     if (rows == 0) return SAGE_OK;
 
-    ChunkStats* stats = static_cast<ChunkStats*>(workspace);
+    UnitStats* stats = static_cast<UnitStats*>(workspace);
     uint64_t* keys = reinterpret_cast<uint64_t*>(static_cast<char*>(workspace) + stats_bytes(rows, vocab));
     hipStream_t s = sage::as_stream(stream);
-    const dim3 grid(nchunks, rows);
-    if (dtype == SAGE_F32)
-        hipLaunchKernelGGL(chunk_kernel<float>, grid, dim3(THREADS), 0, s, static_cast<const float*>(logits), vocab,
-                           row_stride, k, n_valid, rows_per_group, nchunks, stats, keys);
-    else
-        hipLaunchKernelGGL(chunk_kernel<uint16_t>, grid, dim3(THREADS), 0, s, static_cast<const uint16_t*>(logits), vocab,
-                           row_stride, k, n_valid, rows_per_group, nchunks, stats, keys);
+    if (k == 1) {                                    // many rows, one round: a wave per slice, 16 logits per lane
+        const dim3 grid((nunits + WAVES - 1) / WAVES, rows);
+        if (dtype == SAGE_F32)
+            hipLaunchKernelGGL(slice_kernel<float>, grid, dim3(THREADS), 0, s, static_cast<const float*>(logits), vocab,
+                               row_stride, k, n_valid, rows_per_group, nunits, stats, keys);
+        else
+            hipLaunchKernelGGL(slice_kernel<uint16_t>, grid, dim3(THREADS), 0, s, static_cast<const uint16_t*>(logits),
+                               vocab, row_stride, k, n_valid, rows_per_group, nunits, stats, keys);
+    } else {                                         // k rounds: a workgroup per slice, 4 logits per lane
+        const dim3 grid(nunits, rows);
+        if (dtype == SAGE_F32)
+            hipLaunchKernelGGL(slice_topk_kernel<float>, grid, dim3(THREADS), 0, s, static_cast<const float*>(logits), vocab,
+                               row_stride, k, n_valid, rows_per_group, nunits, stats, keys);
+        else
+            hipLaunchKernelGGL(slice_topk_kernel<uint16_t>, grid, dim3(THREADS), 0, s, static_cast<const uint16_t*>(logits),
+                               vocab, row_stride, k, n_valid, rows_per_group, nunits, stats, keys);
+    }
     if (hipGetLastError() != hipSuccess) return SAGE_LAUNCH_FAILED;
-    hipLaunchKernelGGL(merge_kernel, dim3(rows), dim3(64), 0, s, k, n_valid, rows_per_group, nchunks, stats, keys, entropy,
-                       topk_idx, topk_prob, topk_renorm, topk_entropy, alpha);
+    if (nunits <= 256)
+        hipLaunchKernelGGL(merge_kernel<4>, dim3(rows), dim3(THREADS), 0, s, k, n_valid, rows_per_group, nunits, stats, keys,
+                           entropy, topk_idx, topk_prob, topk_renorm, topk_entropy, alpha);
+    else
+        hipLaunchKernelGGL(merge_kernel<MAX_OWN>, dim3(rows), dim3(THREADS), 0, s, k, n_valid, rows_per_group, nunits, stats,
+                           keys, entropy, topk_idx, topk_prob, topk_renorm, topk_entropy, alpha);
     return sage::launch_status();
 }

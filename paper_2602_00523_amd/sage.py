@@ -87,48 +87,83 @@ def sage_entropy_topk_workspace_bytes(rows: int, vocab: int, k: int) -> int:
     return int(lib().sage_entropy_topk_workspace_bytes(rows, vocab, k))
 
 
-def sage_entropy_topk(logits, k, entropy, topk_idx, topk_prob, topk_renorm, topk_entropy, alpha, workspace,
-                      n_valid=None, rows_per_group=1, stream=None):
-    rows, vocab = logits.shape
-    assert logits.stride(1) == 1
-    rc = lib().sage_entropy_topk(_ptr(logits), _dtype_code(logits), rows, vocab, logits.stride(0), k, _ptr(n_valid),
-                                 rows_per_group, _ptr(entropy), _ptr(topk_idx), _ptr(topk_prob), _ptr(topk_renorm),
-                                 _ptr(topk_entropy), _ptr(alpha), _ptr(workspace),
-                                 workspace.numel() * workspace.element_size(), _stream(stream))
-    _check("sage_entropy_topk", rc)
-
-
-def sage_build_tree(topk_renorm, alpha, params: TreeParams, n_nodes, parent, depth, rank, anc_mask, cum_prob=None,
-                    topk_idx=None, node_token=None, stream=None):
-    B, k = topk_renorm.shape
-    rc = lib().sage_build_tree(_ptr(topk_renorm), _ptr(alpha), _ptr(topk_idx), B, k, ctypes.byref(params), _ptr(n_nodes),
-                               _ptr(parent), _ptr(depth), _ptr(rank), _ptr(anc_mask), _ptr(cum_prob), _ptr(node_token),
-                               _stream(stream))
-    _check("sage_build_tree", rc)
-
-
 def sage_tree_attention_workspace_bytes(dtype_code: int, B: int, Hq: int, Hkv: int, d: int, max_kv_len: int) -> int:
     return int(lib().sage_tree_attention_workspace_bytes(dtype_code, B, Hq, Hkv, d, max_kv_len))
 
 
-def sage_tree_attention(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_token_stride, kv_head_stride, anc_mask,
-                        n_nodes, scale, workspace, stream=None):
+def _nbytes(t) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+# ---- argument marshalling: tensors -> the C argument list of each call -----------------------------------
+
+def _args_entropy_topk(logits, k, entropy, topk_idx, topk_prob, topk_renorm, topk_entropy, alpha, workspace,
+                       n_valid=None, rows_per_group=1, stream=None):
+    rows, vocab = logits.shape
+    assert logits.stride(1) == 1
+    return [_ptr(logits), _dtype_code(logits), rows, vocab, logits.stride(0), k, _ptr(n_valid), rows_per_group,
+            _ptr(entropy), _ptr(topk_idx), _ptr(topk_prob), _ptr(topk_renorm), _ptr(topk_entropy), _ptr(alpha),
+            _ptr(workspace), _nbytes(workspace), _stream(stream)]
+
+
+def _args_build_tree(topk_renorm, alpha, params: TreeParams, n_nodes, parent, depth, rank, anc_mask, cum_prob=None,
+                     topk_idx=None, node_token=None, stream=None):
+    B, k = topk_renorm.shape
+    return [_ptr(topk_renorm), _ptr(alpha), _ptr(topk_idx), B, k, ctypes.byref(params), _ptr(n_nodes), _ptr(parent),
+            _ptr(depth), _ptr(rank), _ptr(anc_mask), _ptr(cum_prob), _ptr(node_token), _stream(stream)]
+
+
+def _args_tree_attention(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_token_stride, kv_head_stride, anc_mask,
+                         n_nodes, scale, workspace, stream=None):
     B, _, Hq, d = Q.shape
     Hkv = Kt.shape[2]
-    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    rc = lib().sage_tree_attention(_ptr(Q), _ptr(Kc), _ptr(Vc), _ptr(Kt), _ptr(Vt), _ptr(O), _dtype_code(Q), B, Hq, Hkv,
-                                   d, _ptr(kv_start), _ptr(kv_len), max_kv_len, kv_token_stride, kv_head_stride,
-                                   _ptr(anc_mask), _ptr(n_nodes), scale, _ptr(workspace), ws_bytes, _stream(stream))
-    _check("sage_tree_attention", rc)
+    return [_ptr(Q), _ptr(Kc), _ptr(Vc), _ptr(Kt), _ptr(Vt), _ptr(O), _dtype_code(Q), B, Hq, Hkv, d, _ptr(kv_start),
+            _ptr(kv_len), max_kv_len, kv_token_stride, kv_head_stride, _ptr(anc_mask), _ptr(n_nodes), scale,
+            _ptr(workspace), _nbytes(workspace), _stream(stream)]
 
 
-def sage_verify_accept(token, target_argmax, parent, depth, anc_mask, n_nodes, path_cap, accept_len, best_node,
-                       path_nodes, out_tokens, stream=None):
+def _args_verify_accept(token, target_argmax, parent, depth, anc_mask, n_nodes, path_cap, accept_len, best_node,
+                        path_nodes, out_tokens, stream=None):
     B = n_nodes.shape[0]
-    rc = lib().sage_verify_accept(_ptr(token), _ptr(target_argmax), _ptr(parent), _ptr(depth), _ptr(anc_mask),
-                                  _ptr(n_nodes), B, path_cap, _ptr(accept_len), _ptr(best_node), _ptr(path_nodes),
-                                  _ptr(out_tokens), _stream(stream))
-    _check("sage_verify_accept", rc)
+    return [_ptr(token), _ptr(target_argmax), _ptr(parent), _ptr(depth), _ptr(anc_mask), _ptr(n_nodes), B, path_cap,
+            _ptr(accept_len), _ptr(best_node), _ptr(path_nodes), _ptr(out_tokens), _stream(stream)]
+
+
+_MARSHAL = {"sage_entropy_topk": _args_entropy_topk, "sage_build_tree": _args_build_tree,
+            "sage_tree_attention": _args_tree_attention, "sage_verify_accept": _args_verify_accept}
+
+
+def sage_entropy_topk(*a, **kw):
+    _check("sage_entropy_topk", lib().sage_entropy_topk(*_args_entropy_topk(*a, **kw)))
+
+
+def sage_build_tree(*a, **kw):
+    _check("sage_build_tree", lib().sage_build_tree(*_args_build_tree(*a, **kw)))
+
+
+def sage_tree_attention(*a, **kw):
+    _check("sage_tree_attention", lib().sage_tree_attention(*_args_tree_attention(*a, **kw)))
+
+
+def sage_verify_accept(*a, **kw):
+    _check("sage_verify_accept", lib().sage_verify_accept(*_args_verify_accept(*a, **kw)))
+
+
+def prepare(name: str, *a, **kw):
+    """Marshal the arguments of call `name` once and return a zero-argument callable that enqueues it.
+
+    For loops that issue the same call on the same buffers and stream many times: the per-call cost drops to
+    one foreign-function call.  The tensors (and the TreeParams object) must outlive the callable.
+    """
+    fn = getattr(lib(), name)
+    args = _MARSHAL[name](*a, **kw)
+    keep = (a, kw)
+
+    def call(_fn=fn, _args=args, _name=name, _keep=keep):
+        rc = _fn(*_args)
+        if rc != 0:
+            raise SageError(_name, rc)
+    return call
 
 
 def sage_build_info() -> str:
