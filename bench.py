@@ -26,6 +26,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
 MAX_NODES = 64
+# HBM bytes of one attention launch (main kernel + split merge) from rocprofv3 FETCH_SIZE/WRITE_SIZE runs, scaled by
+# the counters' readings for a 64 MiB copy (profiles/tree_attention_c2_hbm_traffic.md); workloads not profiled: null.
+MEASURED_TRAFFIC_BYTES = {"c2": 36.0e6}
 
 # Trees of the 80-layer configuration are asked to have 64 nodes every step.  With the paper's own parameters the
 # rule never grows a tree that large, so that workload plants a geometric top-64 distribution (ratio 1/2) in the
@@ -44,6 +47,8 @@ def parse():
     ap.add_argument("--no-extras", action="store_true", help="skip the long-KV attention measurements")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--eager", action="store_true", help="time the steps eagerly instead of as HIP-graph replays")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run plain 64 MiB device copies, the known-size reference for rocprofv3 FETCH_SIZE/WRITE_SIZE")
     return ap.parse_args()
 
 
@@ -187,6 +192,7 @@ class Workload:
             for call in self.c_a3[cur][s]:
                 e0, e1 = events[self.ev_used], events[self.ev_used + 1]
                 self.ev_used += 2
+                self.pad_dst.copy_(self.pad_src)      # keeps the queue busy so the start event is not reached early
                 e0.record()
                 call()
                 e1.record()
@@ -275,8 +281,15 @@ def time_steps(w: Workload, steps: int, warmup: int, use_graph: bool):
 
 
 def time_attention_launches(w: Workload, steps: int):
-    """Eager pass over `steps` steps with HIP events around every sage_tree_attention call."""
+    """Eager measurement pass over `steps` steps with HIP events around every sage_tree_attention call.
+
+    Launching from Python is slower than these kernels run, so an idle queue would let the start event fire before
+    the kernel is even submitted; a 64 MiB device copy is queued ahead of every start event, which keeps the GPU
+    busy while the host enqueues event, kernels and event (and leaves the caches cold for the attention launch).
+    """
     torch = w.torch
+    w.pad_src = torch.empty(64 << 20, device="cuda:0", dtype=torch.uint8)
+    w.pad_dst = torch.empty_like(w.pad_src)
     first = w.step_no
     events = [torch.cuda.Event(enable_timing=True) for _ in range(2 * steps * w.layers)]
     w.ev_used = 0
@@ -422,13 +435,20 @@ def main():
             "eager_ms_per_step": eager_wall * 1e3 / len(n_log) * w.layers / w.layers},
         "roofline": {"bound": "hbm", "kernel": "sage_tree_attention (bf16 MFMA kernel + split merge, per layer launch)",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": None, "avg_launch_us": att_avg_ms * 1e3,
-                     "timing": "HIP events around every sage_tree_attention call in an eager pass over the same steps", "algorithmic_bytes_per_launch": per_launch_bytes,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "avg_launch_us": att_avg_ms * 1e3,
+                     "timing": "HIP events around every sage_tree_attention call in an eager pass over the same steps, queue kept busy", "algorithmic_bytes_per_launch": per_launch_bytes,
                      "mfma_TFLOPs": per_launch_flops / (att_avg_ms * 1e-3) / 1e12,
                      "mfma_frac": per_launch_flops / (att_avg_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds)
+    if args.calibrate_copy:
+        src = torch.empty(64 << 20, device="cuda:0", dtype=torch.uint8).random_()
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     del w
     torch.cuda.empty_cache()
     if not args.no_extras and args.workload == "c2":

@@ -29,8 +29,6 @@
 // the two column groups of a large tree re-read K/V from that L2, not from HBM.  Each workgroup writes an
 // un-normalised partial (max, sum, O^T); a second kernel merges the splits in a fixed order (deterministic,
 // no float atomics) and writes bf16.
-#include <stdlib.h>
-
 #include <type_traits>
 
 #include "sage_internal.h"
@@ -63,7 +61,7 @@ struct Params {
     const int64_t* kv_start; const int* kv_len; const uint64_t* anc_mask; const int* n_nodes;
     float* part;                         // [B][Hkv][nslot][ROWS_PER_WG][PART_FLOATS]
     long kv_token_stride, kv_head_stride;
-    int B, Hq, Hkv, G, nslot, debug;
+    int B, Hq, Hkv, G, nslot, min_tiles_per_split;
     float scale_log2e;                   // softmax scale times log2(e): probabilities are exp2 of scaled differences
 };
 
@@ -71,7 +69,7 @@ struct Params {
 struct Split {
     int n, rows, col_groups, tiles, tiles_per_split, nsplit;
 };
-__device__ __forceinline__ Split make_split(int n_nodes, int kv_len, int G, int nslot) {
+__device__ __forceinline__ Split make_split(int n_nodes, int kv_len, int G, int nslot, int min_tps) {
     Split s;
     s.n = n_nodes < 1 ? 1 : (n_nodes > SAGE_MAX_NODES ? SAGE_MAX_NODES : n_nodes);
     s.rows = s.n * G;
@@ -80,7 +78,7 @@ __device__ __forceinline__ Split make_split(int n_nodes, int kv_len, int G, int 
     s.tiles = (L + TILE - 1) / TILE + 1;                    // cache tiles, then one tile holding the tree's keys
     int max_split = nslot / s.col_groups;
     if (max_split < 1) max_split = 1;
-    s.tiles_per_split = (s.tiles + max_split - 1) / max_split;
+    s.tiles_per_split = max(min_tps, (s.tiles + max_split - 1) / max_split);
     s.nsplit = (s.tiles + s.tiles_per_split - 1) / s.tiles_per_split;
     return s;
 }
@@ -141,7 +139,7 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
     const int slot = id % prm.nslot;
     const int b = id / prm.nslot;
     const int L = prm.kv_len[b] > 0 ? prm.kv_len[b] : 0;
-    const Split sp = make_split(prm.n_nodes[b], L, prm.G, prm.nslot);
+    const Split sp = make_split(prm.n_nodes[b], L, prm.G, prm.nslot, prm.min_tiles_per_split);
     if (sp.col_groups > prm.nslot) return;                  // host guarantees nslot >= the largest group count
     const int cg = slot % sp.col_groups;
     const int split = slot / sp.col_groups;
@@ -156,7 +154,7 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
     const bool shared_ct = group_ct <= 4;                    // two waves per column tile, one token half each
     const int ct = shared_ct ? (wave & 3) : wave;
     const int sub_lo = shared_ct ? (wave >> 2) : 0;
-    const bool wave_active = ct < group_ct && !(prm.debug & 1);
+    const bool wave_active = ct < group_ct;
 
     // ---- this lane's query row
     const int m_local = ct * 32 + r32;                       // row within the group
@@ -400,7 +398,7 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
     }
 
     // ---- un-normalised partial for this (split, query row), merged by the second kernel
-    if (row_valid && sub_lo == 0 && !(prm.debug & 1)) {
+    if (row_valid && sub_lo == 0) {
         float* out = prm.part + (((static_cast<long>(b) * prm.Hkv + g) * prm.nslot + slot) * ROWS_PER_WG + m_local) * PART_FLOATS;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
@@ -427,7 +425,7 @@ __global__ __launch_bounds__(64 * MERGE_ROWS) void tree_attention_merge_kernel(c
     const int hh = blockIdx.y * MERGE_ROWS + (threadIdx.x >> 6);
     const int node = blockIdx.x, b = blockIdx.z;
     const int L = prm.kv_len[b] > 0 ? prm.kv_len[b] : 0;
-    const Split sp = make_split(prm.n_nodes[b], L, prm.G, prm.nslot);
+    const Split sp = make_split(prm.n_nodes[b], L, prm.G, prm.nslot, prm.min_tiles_per_split);
     if (node >= sp.n || hh >= prm.Hq || sp.col_groups > prm.nslot) return;
     const int g = hh / prm.G;
     const int m = node * prm.G + (hh % prm.G);
@@ -492,23 +490,38 @@ __global__ __launch_bounds__(64 * MERGE_ROWS) void tree_attention_merge_kernel(c
 
 namespace sage {
 
-// Number of workgroup slots per (sequence, KV head): about one 8-wave workgroup per CU, never more than
-// one slot per tile and column group, never fewer than the largest possible number of column groups.
-int attention_bf16_slots(int B, int Hkv, int G, int max_kv_len) {
+// Launch shape.  Slots = workgroups per (sequence, KV head); a slot is (KV split, column group).  A single
+// sequence is cut into about one 8-wave workgroup per CU (one round, no tail).  A batch is cut into splits of a
+// fixed number of tiles instead (every workgroup pays a few microseconds of prologue and epilogue, so long splits
+// win), sized for about one workgroup per CU in total, so that ragged sequences get splits in proportion to
+// their length.
+struct LaunchShape { int nslot, min_tiles_per_split; };
+LaunchShape attention_bf16_shape(int B, int Hkv, int G, int max_kv_len) {
     const int max_groups = (SAGE_MAX_NODES * G + ROWS_PER_WG - 1) / ROWS_PER_WG;
     const int tiles = (max_kv_len + TILE - 1) / TILE + 1;
-    long want = 256 / (static_cast<long>(B > 0 ? B : 1) * Hkv);
-    if (const char* e = getenv("SAGE_ATTN_SLOTS")) want = atol(e);
-    if (want < max_groups) want = max_groups;
-    const long cap = static_cast<long>(tiles) * max_groups;
-    if (want > cap) want = cap;
-    if (want > 256) want = 256;
-    if (want < max_groups) want = max_groups;
-    return static_cast<int>(want);
+    LaunchShape sh;
+    if (B <= 1) {
+        long want = 256 / Hkv;
+        if (want < max_groups) want = max_groups;
+        const long cap = static_cast<long>(tiles) * max_groups;
+        if (want > cap) want = cap;
+        sh.nslot = static_cast<int>(want);
+        sh.min_tiles_per_split = 1;
+    } else {
+        const double est_tiles = 0.6 * B * Hkv * static_cast<double>(tiles);    // ragged batches average below the maximum
+        long tps = static_cast<long>(est_tiles / 256.0) + 1;       // about one workgroup per CU in total
+        if (tps < 4) tps = 4;
+        if (tps > tiles) tps = tiles;
+        sh.min_tiles_per_split = static_cast<int>(tps);
+        sh.nslot = static_cast<int>((tiles + tps - 1) / tps) * max_groups;
+    }
+    if (sh.nslot > 256) sh.nslot = 256;               // the merge handles any count; this bounds the workspace
+    if (sh.nslot < max_groups) sh.nslot = max_groups;
+    return sh;
 }
 
 size_t attention_bf16_workspace_bytes(int B, int Hkv, int G, int max_kv_len) {
-    const size_t slots = attention_bf16_slots(B, Hkv, G, max_kv_len);
+    const size_t slots = attention_bf16_shape(B, Hkv, G, max_kv_len).nslot;
     return static_cast<size_t>(B) * Hkv * slots * ROWS_PER_WG * PART_FLOATS * sizeof(float);
 }
 
@@ -531,11 +544,10 @@ int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const voi
     p.part = static_cast<float*>(workspace);
     p.kv_token_stride = kv_token_stride; p.kv_head_stride = kv_head_stride;
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.G = G;
-    p.nslot = attention_bf16_slots(B, Hkv, G, max_kv_len);
-    if (static_cast<size_t>(B) * Hkv * p.nslot * ROWS_PER_WG * PART_FLOATS * sizeof(float) > workspace_bytes)
-        return SAGE_WORKSPACE_TOO_SMALL;
+    const LaunchShape sh = attention_bf16_shape(B, Hkv, G, max_kv_len);
+    p.nslot = sh.nslot;
+    p.min_tiles_per_split = sh.min_tiles_per_split;
     p.scale_log2e = scale * 1.4426950408889634f;
-    p.debug = getenv("SAGE_ATTN_DEBUG") ? atoi(getenv("SAGE_ATTN_DEBUG")) : 0;
 
     const long blocks = static_cast<long>(B) * p.nslot * Hkv;
     if (blocks > 0x7FFFFFFFL) return SAGE_UNSUPPORTED;

@@ -1,0 +1,138 @@
+"""GPU parity at the full sizes of the benchmark configurations, through the same entry points and launch
+configuration bench.py uses (sage_tree_attention picks its own grid from B, head counts and max_kv_len).
+
+The oracle computes whole outputs where that takes seconds (c2, c3) and sampled KV-head groups / sequences where it
+would take minutes (c4, c5); attention tolerance 2e-2 (bf16), integers bit-exact.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import MAX_NODES
+from paper_2602_00523_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import gpu_utils
+    return gpu_utils
+
+
+def planned_tree(gu, name, step, prm=None, planted=False):
+    """Tree of one step of configuration `name`: draft row -> a1 -> a2 on the GPU, checked against the oracle."""
+    cfg = wl.CONFIGS[name]
+    prm = prm or cfg["tree"]
+    h = wl.entropy_targets(name, step + 1)[step]
+    draft = wl.draft_logits(wl.seed_for(name, step, 1), 1, cfg["vocab"], "bf16", wl.scale_for_entropy(h))
+    if planted:                                    # geometric top-64 so that the rule fills all 64 nodes
+        row = wl.bf16_bits_to_f32(draft) * 0.05 - 60.0
+        pos = wl.rng(step).permutation(cfg["vocab"])[:64]
+        row[0, pos] = -np.log(2.0) * np.arange(64, dtype=np.float32)
+        draft = wl.to_storage(row, "bf16")
+    g1 = gu.gpu_entropy_topk(draft, prm["k"])
+    o1 = oracle.entropy_topk(draft, prm["k"])
+    np.testing.assert_array_equal(g1["topk_idx"], o1["topk_idx"])
+    assert abs(g1["entropy"][0] - o1["entropy"][0]) <= 1e-5 * max(1.0, o1["entropy"][0])
+    g2 = gu.gpu_build_tree(g1["topk_renorm"], g1["alpha"], prm, g1["topk_idx"])
+    o2 = oracle.build_tree(g1["topk_renorm"], g1["alpha"], prm, g1["topk_idx"])
+    n = int(o2["n_nodes"][0])
+    assert int(g2["n_nodes"][0]) == n
+    for key in ("parent", "depth", "rank", "anc_mask", "node_token"):
+        np.testing.assert_array_equal(g2[key][0, :n], o2[key][0, :n])
+    return o2, n, float(o1["entropy"][0])
+
+
+def head_group(inp, g, G, d):
+    """Inputs restricted to KV head g and its G query heads (the oracle then costs 1/Hkv of the full problem)."""
+    sub = dict(inp)
+    sub["Q"] = np.ascontiguousarray(inp["Q"][:, :, g * G:(g + 1) * G])
+    for key in ("Kt", "Vt"):
+        sub[key] = np.ascontiguousarray(inp[key][:, :, g:g + 1])
+    for key in ("Kc", "Vc"):
+        sub[key] = np.ascontiguousarray(inp[key][:, g:g + 1])
+    sub["kv_token_stride"], sub["kv_head_stride"] = d, d
+    return sub
+
+
+def oracle_attention(inp, mask, nn, Hq, Hkv, d):
+    return oracle.tree_attention(inp["Q"], inp["Kc"], inp["Vc"], inp["Kt"], inp["Vt"], inp["kv_start"], inp["kv_len"],
+                                 inp["kv_token_stride"], inp["kv_head_stride"], mask, nn, Hq, Hkv, d)
+
+
+@pytest.mark.parametrize("name,steps", [("c2", (0, 5)), ("c3", (0, 3, 7))])
+def test_single_sequence_configs_whole_output(gu, name, steps):
+    cfg = wl.CONFIGS[name]
+    Hq, Hkv, d, L = cfg["Hq"], cfg["Hkv"], cfg["d"], cfg["kv_len"]
+    seen = []
+    for step in steps:
+        tree, n, ent = planned_tree(gu, name, step)
+        seen.append(n)
+        inp = wl.attention_inputs(wl.seed_for(name, step, 2), 1, Hq, Hkv, d, [L], "bf16")
+        got, _ = gu.gpu_tree_attention(inp, tree["anc_mask"], tree["n_nodes"], Hq, Hkv, d)
+        ref = oracle_attention(inp, tree["anc_mask"], tree["n_nodes"], Hq, Hkv, d)
+        worst = gu.assert_attention_close(got, ref, tree["n_nodes"], 2e-2)
+        print(f" {name} step {step}: entropy {ent:.2f} nats, {n} nodes, worst rel err {worst:.2e}", flush=True)
+    assert len(set(seen)) > 1                      # the trees really change from step to step
+
+
+def test_c4_ragged_batch_sampled_sequences(gu):
+    cfg = wl.CONFIGS["c4"]
+    B, Hq, Hkv, d = cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["d"]
+    lens = wl.ragged_kv_lens(wl.seed_for("c4", 0, 3), B, *cfg["kv_len"])
+    assert lens.min() >= 2048 and lens.max() <= 12288
+    masks = np.zeros((B, MAX_NODES), np.uint64)
+    nn = np.zeros(B, np.int32)
+    for b in range(B):                             # every sequence has its own entropy-driven tree
+        tree, n, _ = planned_tree(gu, "c4", b)
+        masks[b], nn[b] = tree["anc_mask"][0], n
+    inp = wl.attention_inputs(wl.seed_for("c4", 0, 2), B, Hq, Hkv, d, lens, "bf16")
+    got, _ = gu.gpu_tree_attention(inp, masks, nn, Hq, Hkv, d, fill=7.0)
+    order = np.argsort(lens)
+    for b in (int(order[0]), int(order[-1]), int(order[B // 2])):       # shortest, longest, a middle one
+        for g in (0, 5):
+            sub = head_group(inp, g, Hq // Hkv, d)
+            one = {k: (v[b:b + 1] if k in ("Q", "Kt", "Vt") else v) for k, v in sub.items()}
+            one["kv_start"], one["kv_len"] = sub["kv_start"][b:b + 1], sub["kv_len"][b:b + 1]
+            ref = oracle_attention(one, masks[b:b + 1], nn[b:b + 1], Hq // Hkv, 1, d)
+            gu.assert_attention_close(got[b:b + 1, :, g * 8:(g + 1) * 8], ref, nn[b:b + 1], 2e-2)
+    for b in range(B):
+        assert (got[b, int(nn[b]):] == 7.0).all()  # rows beyond each sequence's tree are untouched
+    print(f" c4: kv_len {lens.tolist()}, nodes {nn.tolist()}", flush=True)
+
+
+def test_c5_full_tree_long_cache_sampled_heads(gu):
+    import bench
+    cfg = wl.CONFIGS["c5"]
+    Hq, Hkv, d, L = cfg["Hq"], cfg["Hkv"], cfg["d"], cfg["kv_len"]
+    tree, n, _ = planned_tree(gu, "c5", 0, prm=bench.C5_TREE, planted=True)
+    assert n == 64
+    inp = wl.attention_inputs(wl.seed_for("c5", 0, 2), 1, Hq, Hkv, d, [L], "bf16")
+    got, _ = gu.gpu_tree_attention(inp, tree["anc_mask"], tree["n_nodes"], Hq, Hkv, d)
+    for g in (2, 7):
+        ref = oracle_attention(head_group(inp, g, Hq // Hkv, d), tree["anc_mask"], tree["n_nodes"], Hq // Hkv, 1, d)
+        worst = gu.assert_attention_close(got[:, :, g * 8:(g + 1) * 8], ref, tree["n_nodes"], 2e-2)
+        print(f" c5 kv head {g}: worst rel err {worst:.2e}", flush=True)
+
+
+def test_target_rows_and_acceptance_at_full_vocab(gu):
+    """a1' + a4 at the 72B vocabulary: 64 target rows, ragged validity, acceptance bit-exact."""
+    name = "c2"
+    cfg = wl.CONFIGS[name]
+    tree, n, _ = planned_tree(gu, name, 2)
+    draft = wl.draft_logits(wl.seed_for(name, 2, 1), 1, cfg["vocab"], "bf16", 4.0)
+    tgt_logits = np.zeros((MAX_NODES, cfg["vocab"]), np.uint16)
+    tgt_logits[:n] = wl.target_logits_from_draft(9, wl.bf16_bits_to_f32(draft[0]), n, "bf16", 1.5)
+    g = gu.gpu_entropy_topk(tgt_logits, 1, tree["n_nodes"], MAX_NODES)
+    o = oracle.entropy_topk(tgt_logits, 1, tree["n_nodes"], MAX_NODES)
+    np.testing.assert_array_equal(g["topk_idx"][:n], o["topk_idx"][:n])
+    assert (g["topk_idx"][n:] == -1).all()
+    tgt = g["topk_idx"][:, 0].reshape(1, MAX_NODES)
+    token = tree["node_token"].copy()
+    token[0, 1:n] = np.where(np.arange(1, n) % 3 == 0, -5, tgt[0, tree["parent"][0, 1:n]])   # every third node mismatches
+    cap = cfg["tree"]["d_max"] + 1
+    g4 = gu.gpu_verify_accept(token, tgt, tree["parent"], tree["depth"], tree["anc_mask"], tree["n_nodes"], cap)
+    o4 = oracle.verify_accept(token, tgt, tree["parent"], tree["depth"], tree["n_nodes"], cap)
+    for key in o4:
+        np.testing.assert_array_equal(g4[key], o4[key], err_msg=key)
