@@ -16,19 +16,21 @@
 // uses the same reference maximum for numerator and denominator, so the result is unchanged.
 //
 // Data movement.  K/V tiles of 64 tokens go from global memory straight into LDS (16-byte LDS-direct loads, no
-// staging registers) through a 4-stage ring, three tiles ahead of the MFMAs.  A wave-level load writes 1 KB of
+// staging registers) through a 4-stage ring, two tiles ahead of the MFMAs (the fourth stage keeps the previous tile's V alive for the
+// waves that run one phase behind, see below).  A wave-level load writes 1 KB of
 // contiguous LDS (4 token rows); bank conflicts are avoided by permuting the 16-byte chunks inside a row
 // (chunk c of token t sits at slot c ^ f(t)), which only changes which global address a lane fetches.  Every
 // stage is its own LDS object so that loads in flight into one stage are known not to alias reads of another.
 //
 // Decomposition (decided on the device from n_nodes/kv_len, so no host round trip): a workgroup of 8 waves
-// owns (sequence, KV head, group of up to 8 column tiles = 256 query rows, KV split).  With more than 4 column
-// tiles in the group a wave owns one column tile; with 4 or fewer, two waves share a column tile and each
-// takes one 32-token half of every tile, and the halves are combined through LDS at the end.  Workgroups of
-// one KV head are congruent modulo the KV-head count, which with 8 KV heads pins a head to one XCD and its L2:
-// the two column groups of a large tree re-read K/V from that L2, not from HBM.  Each workgroup writes an
-// un-normalised partial (max, sum, O^T); a second kernel merges the splits in a fixed order (deterministic,
-// no float atomics) and writes bf16.
+// owns (sequence, KV head, group of up to 4 column tiles = 128 query rows, KV split).  Waves w and w+4 share
+// column tile w and each takes one 32-token half of every tile; the halves are combined through LDS at the end.
+// Waves w and w+4 also share a SIMD, and waves 4-7 run one phase behind waves 0-3 (softmax + PV of the previous
+// tile, then the scores of the current one), so one wave's matrix work overlaps the other's vector work.
+// Workgroups of one KV head are congruent modulo the KV-head count, which with 8 KV heads pins a head to one
+// XCD and its L2: the column groups of a large tree re-read K/V from that L2, not from HBM.  Each workgroup
+// writes an un-normalised partial (max, sum, O^T); a second kernel merges the splits in a fixed order
+// (deterministic, no float atomics) and writes bf16.
 #include <type_traits>
 
 #include "sage_internal.h"
@@ -46,7 +48,7 @@ typedef __attribute__((address_space(3))) unsigned char lds_byte;
 constexpr int D = 128;                  // head_dim
 constexpr int TILE = 64;                // tokens per LDS stage
 constexpr int THREADS = 512;
-constexpr int CT_PER_WG = 8;            // column tiles (of 32 query rows) per workgroup
+constexpr int CT_PER_WG = 4;            // column tiles (of 32 query rows) per workgroup
 constexpr int ROWS_PER_WG = CT_PER_WG * 32;
 constexpr int ROW_B = 256;              // bytes of one token row (128 bf16), also its LDS footprint
 constexpr int TILE_B = TILE * ROW_B;    // 16 KB per K or V stage
@@ -148,12 +150,11 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
     const int t_end = min(sp.tiles, t_begin + sp.tiles_per_split);
     const int tree_tile = sp.tiles - 1;
 
-    // ---- wave roles: column tile and the 32-token halves of each tile this wave takes
+    // ---- wave roles: waves w and w+4 share column tile w; each takes one 32-token half of every tile
     const int group_rows = min(ROWS_PER_WG, sp.rows - cg * ROWS_PER_WG);
-    const int group_ct = (group_rows + 31) / 32;             // 1..8 column tiles in this group
-    const bool shared_ct = group_ct <= 4;                    // two waves per column tile, one token half each
-    const int ct = shared_ct ? (wave & 3) : wave;
-    const int sub_lo = shared_ct ? (wave >> 2) : 0;
+    const int group_ct = (group_rows + 31) / 32;             // 1..4 column tiles in this group
+    const int ct = wave & 3;
+    const int sub_lo = wave >> 2;
     const bool wave_active = ct < group_ct;
 
     // ---- this lane's query row
@@ -236,46 +237,39 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
     float l_run = 0.f;                                       // this lane's share of the running sum
     const float c = prm.scale_log2e;
 
-    // One tile step for this wave's column tile over NSUB consecutive 32-token sub-tiles starting at kb/vb.
-    // With two sub-tiles the two score chains are independent, which lets MFMA, LDS and VALU work overlap.
-    auto compute = [&](auto nsubc, const lds_byte* kb, const lds_byte* vb, bool masked, uint64_t admit) __attribute__((always_inline)) {
-        constexpr int NSUB = decltype(nsubc)::value;
-        // ---- S^T = K Q^T, 32 tokens per sub-tile
-        f32x16 s[NSUB];
+    // A tile step has two phases for this wave's column tile: scores (S^T = K Q^T, MFMA) and softmax + PV (VALU, then
+    // MFMA).  Waves 0-3 run them back to back on the current tile.  Waves 4-7, each of which shares a SIMD with one
+    // of waves 0-3, run one phase behind (softmax + PV of the previous tile, then the scores of the current one), so
+    // that on every SIMD one wave's matrix work overlaps the other wave's vector work instead of both waves hitting
+    // the same pipe after each barrier.
+    f32x16 sc;                                               // scores of this wave's 32-token half tile
+    const bool lag = wave >= 4;
+
+    auto score_phase = [&](const lds_byte* kb, bool masked, uint32_t adm) __attribute__((always_inline)) {
 #pragma unroll
-        for (int u = 0; u < NSUB; ++u)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) s[u][i] = 0.f;
+        for (int i = 0; i < 16; ++i) sc[i] = 0.f;
 #pragma unroll
         for (int kh = 0; kh < 2; ++kh) {
-            bf16x8 a[NSUB][4];
-#pragma unroll
-            for (int u = 0; u < NSUB; ++u)
-#pragma unroll
-                for (int kk = 0; kk < 4; ++kk)
-                    a[u][kk] = __builtin_bit_cast(bf16x8, *(const LDS_AS uint4*)(kb + u * 32 * ROW_B + (k_lane ^ ((kh * 4 + kk) << 5))));
+            bf16x8 a[4];
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)
+                a[kk] = __builtin_bit_cast(bf16x8, *(const LDS_AS uint4*)(kb + (k_lane ^ ((kh * 4 + kk) << 5))));
 #pragma unroll
-                for (int u = 0; u < NSUB; ++u)
-                    s[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u][kk], qf[kh * 4 + kk], s[u], 0, 0, 0);
+            for (int kk = 0; kk < 4; ++kk) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk], qf[kh * 4 + kk], sc, 0, 0, 0);
         }
-        // ---- admit keys: cache positions below kv_len; tree nodes in this row's ancestor-or-self mask
+        // admit keys: cache positions below kv_len; tree nodes in this row's ancestor-or-self mask
         if (masked) {
 #pragma unroll
-            for (int u = 0; u < NSUB; ++u) {
-                const uint32_t adm = static_cast<uint32_t>(admit >> (32 * u));
-#pragma unroll
-                for (int i = 0; i < 16; ++i)
-                    if (!((adm >> (8 * (i >> 2) + (i & 3))) & 1u)) s[u][i] = -INFINITY;
-            }
+            for (int i = 0; i < 16; ++i)
+                if (!((adm >> (8 * (i >> 2) + (i & 3))) & 1u)) sc[i] = -INFINITY;
         }
+    };
+
+    auto value_phase = [&](const lds_byte* vb) __attribute__((always_inline)) {
         // ---- online softmax for this lane's query row, lazily rescaled
-        float tmax = s[0][0];
+        float tmax = sc[0];
 #pragma unroll
-        for (int u = 0; u < NSUB; ++u)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) tmax = fmaxf(tmax, s[u][i]);
+        for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, sc[i]);
         tmax = cross_half_max(tmax);
         const bool raise = (tmax - m_ref) * c > RESCALE_THRESHOLD;     // also true for the first admitted key
         if (__any(raise)) {
@@ -290,53 +284,48 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
         }
         const float neg_mc = (m_ref == -INFINITY) ? 0.f : -m_ref * c;
         float psum = 0.f;
-        bf16x8 pf[NSUB][2];
+        bf16x8 pf[2];
 #pragma unroll
-        for (int u = 0; u < NSUB; ++u)
+        for (int j = 0; j < 2; ++j) {
+            bf16x8 frag;
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                bf16x8 frag;
-#pragma unroll
-                for (int e = 0; e < 8; e += 2) {
-                    const float p0 = __builtin_amdgcn_exp2f(fmaf(s[u][8 * j + e], c, neg_mc));
-                    const float p1 = __builtin_amdgcn_exp2f(fmaf(s[u][8 * j + e + 1], c, neg_mc));
-                    psum += p0 + p1;
-                    const f32x2 pp = {p0, p1};
-                    const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-                    frag[e] = pb[0];
-                    frag[e + 1] = pb[1];
-                }
-                pf[u][j] = frag;
+            for (int e = 0; e < 8; e += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[8 * j + e], c, neg_mc));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[8 * j + e + 1], c, neg_mc));
+                psum += p0 + p1;
+                const f32x2 pp = {p0, p1};
+                const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+                frag[e] = pb[0];
+                frag[e + 1] = pb[1];
             }
+            pf[j] = frag;
+        }
         l_run += psum;
-        // ---- O^T += V^T P^T   (k-blocks of 16 tokens; two transposing reads of 4 tokens each per lane and block)
+        // ---- O^T += V^T P^T   (two k-blocks of 16 tokens; two transposing reads of 4 tokens each per lane and block)
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) {
-            bf16x8 a[NSUB][2];
+            bf16x8 a[2];
 #pragma unroll
-            for (int u = 0; u < NSUB; ++u)
+            for (int j = 0; j < 2; ++j) {
+                const lds_byte* p0 = vb + (j * 16) * ROW_B + (v_lane ^ (dt << 6));
+                const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)p0);
+                const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)(p0 + 8 * ROW_B));
+                a[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const lds_byte* p0 = vb + (u * 32 + j * 16) * ROW_B + (v_lane ^ (dt << 6));
-                    const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)p0);
-                    const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)(p0 + 8 * ROW_B));
-                    a[u][j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                }
-#pragma unroll
-            for (int u = 0; u < NSUB; ++u)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u][j], pf[u][j], acc[dt], 0, 0, 0);
+            for (int j = 0; j < 2; ++j) acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], pf[j], acc[dt], 0, 0, 0);
         }
     };
 
+    const int sub_off = sub_lo * 32 * ROW_B;                 // this wave's half of the tile when a column tile is shared
+
     auto process = [&](int tile, auto stc) __attribute__((always_inline)) {
         constexpr int ST = decltype(stc)::value;
-        const int ahead = t_end - 1 - tile;                  // later tiles whose loads may stay in flight (at most 2)
-        if (ahead >= 2) wait_vm<2 * LOADS_PER_TILE>();
-        else if (ahead == 1) wait_vm<LOADS_PER_TILE>();
+        constexpr int PREV = (ST + STAGES - 1) % STAGES;
+        if (tile + 1 < t_end) wait_vm<LOADS_PER_TILE>();     // the next tile's loads may stay in flight
         else wait_vm<0>();                                   // this thread's part of `tile` has landed
-        stage_barrier();                                     // ... everyone's has, and the stage read last time is free
-        if (tile + 3 < t_end) issue_loads(tile + 3, std::integral_constant<int, (ST + 3) % STAGES>{});
+        stage_barrier();                                     // ... everyone's has, and the stage read two steps ago is free
+        if (tile + 2 < t_end) issue_loads(tile + 2, std::integral_constant<int, (ST + 2) % STAGES>{});
         if (!wave_active) return;
 
         const bool is_tree = (tile == tree_tile);
@@ -351,28 +340,33 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
             }
             admit >>= 4 * half;                              // token of accumulator register i: 32 sub + 8 (i/4) + 4 half + i%4
         }
-        if (shared_ct) {
-            compute(std::integral_constant<int, 1>{}, (const lds_byte*)(SK(ST)) + sub_lo * 32 * ROW_B,
-                    (const lds_byte*)(SV(ST)) + sub_lo * 32 * ROW_B, masked, admit >> (32 * sub_lo));
+        const uint32_t adm = static_cast<uint32_t>(admit >> (32 * sub_lo));
+        if (lag) {
+            if (tile > t_begin) value_phase((const lds_byte*)(SV(PREV)) + sub_off);
+            score_phase((const lds_byte*)(SK(ST)) + sub_off, masked, adm);
         } else {
-            compute(std::integral_constant<int, 2>{}, (const lds_byte*)(SK(ST)), (const lds_byte*)(SV(ST)), masked, admit);
+            score_phase((const lds_byte*)(SK(ST)) + sub_off, masked, adm);
+            value_phase((const lds_byte*)(SV(ST)) + sub_off);
         }
     };
 
     if (t_begin < t_end) issue_loads(t_begin, std::integral_constant<int, 0>{});
     if (t_begin + 1 < t_end) issue_loads(t_begin + 1, std::integral_constant<int, 1>{});
-    if (t_begin + 2 < t_end) issue_loads(t_begin + 2, std::integral_constant<int, 2>{});
     for (int tile = t_begin; tile < t_end; tile += STAGES) {
         process(tile, std::integral_constant<int, 0>{});
         if (tile + 1 < t_end) process(tile + 1, std::integral_constant<int, 1>{});
         if (tile + 2 < t_end) process(tile + 2, std::integral_constant<int, 2>{});
         if (tile + 3 < t_end) process(tile + 3, std::integral_constant<int, 3>{});
     }
+    if (wave_active && lag && t_begin < t_end) {             // the trailing waves still owe the last tile's softmax + PV
+        const int last_stage = (t_end - 1 - t_begin) % STAGES;
+        value_phase((const lds_byte*)(SV(last_stage)) + sub_off);
+    }
 
     float l_tot = cross_half_sum(l_run);
 
-    // ---- two waves shared a column tile: the wave of the upper token half hands its state to the other
-    if (shared_ct) {
+    // ---- the wave of the upper token half hands its state to the wave it shares the column tile with
+    {
         __syncthreads();                                     // all stages are idle now: K stage `ct` becomes a mailbox
         float* box = reinterpret_cast<float*>(SK(ct));       // [64 accumulator registers][64 lanes]
         if (wave_active && sub_lo == 1) {
