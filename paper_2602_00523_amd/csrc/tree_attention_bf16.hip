@@ -16,17 +16,14 @@
 // uses the same reference maximum for numerator and denominator, so the result is unchanged.
 //
 // Data movement.  K/V tiles of 64 tokens go from global memory straight into LDS (16-byte LDS-direct loads, no
-// staging registers) through a 4-stage ring, two tiles ahead of the MFMAs (the fourth stage keeps the previous tile's V alive for the
-// waves that run one phase behind, see below).  A wave-level load writes 1 KB of
-// contiguous LDS (4 token rows); bank conflicts are avoided by permuting the 16-byte chunks inside a row
-// (chunk c of token t sits at slot c ^ f(t)), which only changes which global address a lane fetches.  Every
-// stage is its own LDS object so that loads in flight into one stage are known not to alias reads of another.
+// staging registers) through a 4-stage ring, three tiles ahead of the MFMAs.  A wave-level load writes 1 KB of
+// contiguous LDS; it carries four tokens that are 16 apart, and the 1 KB groups are padded so that consecutive
+// tokens are staggered across the banks (conflict-free reads with compile-time offsets, see the layout constants).
+// Every stage is its own LDS object so that loads in flight into one stage are known not to alias reads of another.
 //
 // Decomposition (decided on the device from n_nodes/kv_len, so no host round trip): a workgroup of 8 waves
 // owns (sequence, KV head, group of up to 4 column tiles = 128 query rows, KV split).  Waves w and w+4 share
 // column tile w and each takes one 32-token half of every tile; the halves are combined through LDS at the end.
-// Waves w and w+4 also share a SIMD, and waves 4-7 run one phase behind waves 0-3 (softmax + PV of the previous
-// tile, then the scores of the current one), so one wave's matrix work overlaps the other's vector work.
 // Workgroups of one KV head are congruent modulo the KV-head count, which with 8 KV heads pins a head to one
 // XCD and its L2: the column groups of a large tree re-read K/V from that L2, not from HBM.  Each workgroup
 // writes an un-normalised partial (max, sum, O^T); a second kernel merges the splits in a fixed order
@@ -50,10 +47,17 @@ constexpr int TILE = 64;                // tokens per LDS stage
 constexpr int THREADS = 512;
 constexpr int CT_PER_WG = 4;            // column tiles (of 32 query rows) per workgroup
 constexpr int ROWS_PER_WG = CT_PER_WG * 32;
-constexpr int ROW_B = 256;              // bytes of one token row (128 bf16), also its LDS footprint
-constexpr int TILE_B = TILE * ROW_B;    // 16 KB per K or V stage
+constexpr int ROW_B = 256;              // bytes of one token row (128 bf16)
+// LDS stage layout: token t of a tile sits at (t % 16) * GROUP + (t / 16) * ROW_B, where a group is the 1 KB that
+// one wave-level LDS-direct load writes (tokens t, t+16, t+32, t+48) plus padding.  The padding staggers
+// consecutive tokens across the banks: 16 bytes for K (read 16 consecutive tokens x one 16-byte chunk at a time),
+// 64 bytes for V (read 4 consecutive tokens x 64 bytes at a time).  All per-fragment offsets are compile-time.
+constexpr int K_GROUP = 4 * ROW_B + 16;
+constexpr int V_GROUP = 4 * ROW_B + 64;
+constexpr int K_STAGE_B = 16 * K_GROUP;
+constexpr int V_STAGE_B = 16 * V_GROUP;
 constexpr int STAGES = 4;
-constexpr int LOADS_PER_TILE = 2 * TILE_B / (THREADS * 16);   // LDS-direct loads per thread per tile (K and V)
+constexpr int LOADS_PER_TILE = 2 * TILE * ROW_B / (THREADS * 16);   // LDS-direct loads per thread per tile (K and V)
 constexpr int PART_FLOATS = D + 2;      // per query row: O^T[128], then max, sum
 constexpr float RESCALE_THRESHOLD = 8.0f;   // raise the reference maximum only past 2^8
 
@@ -85,11 +89,6 @@ __device__ __forceinline__ Split make_split(int n_nodes, int kv_len, int G, int 
     return s;
 }
 
-// LDS chunk permutations (see header): K is read 16 lanes = 16 consecutive tokens x one chunk at a time,
-// V is read 4 consecutive tokens x two adjacent chunks at a time.
-__device__ __forceinline__ int k_swz(int t) { return t & 15; }
-__device__ __forceinline__ int v_swz(int t) { return (t & 7) << 1; }
-
 // s_waitcnt on the vector-memory counter only (expcnt and lgkmcnt fields left at "no wait")
 template <int N> __device__ __forceinline__ void wait_vm() {
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
@@ -117,14 +116,14 @@ __device__ __forceinline__ float cross_half_sum(float v) {
 
 __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Params prm) {
     // one LDS object per stage and operand (see header)
-    __shared__ __align__(1024) unsigned char sK0[TILE_B];
-    __shared__ __align__(1024) unsigned char sK1[TILE_B];
-    __shared__ __align__(1024) unsigned char sK2[TILE_B];
-    __shared__ __align__(1024) unsigned char sK3[TILE_B];
-    __shared__ __align__(1024) unsigned char sV0[TILE_B];
-    __shared__ __align__(1024) unsigned char sV1[TILE_B];
-    __shared__ __align__(1024) unsigned char sV2[TILE_B];
-    __shared__ __align__(1024) unsigned char sV3[TILE_B];
+    __shared__ __align__(1024) unsigned char sK0[K_STAGE_B];
+    __shared__ __align__(1024) unsigned char sK1[K_STAGE_B];
+    __shared__ __align__(1024) unsigned char sK2[K_STAGE_B];
+    __shared__ __align__(1024) unsigned char sK3[K_STAGE_B];
+    __shared__ __align__(1024) unsigned char sV0[V_STAGE_B];
+    __shared__ __align__(1024) unsigned char sV1[V_STAGE_B];
+    __shared__ __align__(1024) unsigned char sV2[V_STAGE_B];
+    __shared__ __align__(1024) unsigned char sV3[V_STAGE_B];
     __shared__ uint64_t s_mask[ROWS_PER_WG];
     __shared__ float s_ml[4][2][32];                         // half-merge mailbox: per column tile, (max, sum) per row
 #define SK(i) ((i) == 0 ? sK0 : (i) == 1 ? sK1 : (i) == 2 ? sK2 : sK3)
@@ -132,7 +131,7 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, so LDS stage addresses stay scalar
     const int r32 = lane & 31;           // MFMA row (A) / column (B, C) owned by this lane
     const int half = lane >> 5;
 
@@ -162,13 +161,56 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
     const int m = cg * ROWS_PER_WG + m_local;                // row within the KV head
     const int node = m / prm.G;
     const bool row_valid = ct < group_ct && m < sp.rows;
-    // the rows' ancestor-or-self masks wait in LDS until the tree tile comes
+    // ---- loader: instruction i of wave w copies tokens r, r+16, r+32, r+48 (r = 2w + i) of K and of V, 1 KB of
+    //      LDS each: lane l fills chunk l%16 of token r + 16 (l/16).  Addresses are a wave-uniform tile base plus a
+    //      32-bit per-lane offset that is the same for every full tile, so a tile costs no address arithmetic.
+    const int ld_tok = (lane >> 4) * 16 + wave * 2;          // token within the tile for i = 0 (i = 1: the next one)
+    const unsigned ld_chunk_b = (lane & 15) * 16;
+    const unsigned char* k_cache = reinterpret_cast<const unsigned char*>(
+        prm.Kc + prm.kv_start[b] * prm.kv_token_stride + static_cast<long>(g) * prm.kv_head_stride);
+    const unsigned char* v_cache = reinterpret_cast<const unsigned char*>(
+        prm.Vc + prm.kv_start[b] * prm.kv_token_stride + static_cast<long>(g) * prm.kv_head_stride);
+    const unsigned char* k_tree = reinterpret_cast<const unsigned char*>(
+        prm.Kt + (static_cast<long>(b) * SAGE_MAX_NODES * prm.Hkv + g) * D);
+    const unsigned char* v_tree = reinterpret_cast<const unsigned char*>(
+        prm.Vt + (static_cast<long>(b) * SAGE_MAX_NODES * prm.Hkv + g) * D);
+    const unsigned cache_row_b = static_cast<unsigned>(prm.kv_token_stride) * 2u;   // host: 64 rows fit 32 bits
+    const unsigned tree_row_b = static_cast<unsigned>(prm.Hkv) * D * 2u;
+    const unsigned ld_off0 = static_cast<unsigned>(ld_tok) * cache_row_b + ld_chunk_b;
+    const unsigned ld_off1 = ld_off0 + cache_row_b;
+
+    auto issue_loads = [&](int tile, auto stc) __attribute__((always_inline)) {
+        constexpr int ST = decltype(stc)::value;
+        LDS_AS unsigned char* k_dst = (LDS_AS unsigned char*)(&SK(ST)[wave * 2 * K_GROUP]);
+        LDS_AS unsigned char* v_dst = (LDS_AS unsigned char*)(&SV(ST)[wave * 2 * V_GROUP]);
+        const bool is_tree = (tile == tree_tile);
+        if (!is_tree && tile * TILE + TILE <= L) {           // full cache tile
+            const unsigned char* kb = k_cache + static_cast<long>(tile) * TILE * cache_row_b;
+            const unsigned char* vb = v_cache + static_cast<long>(tile) * TILE * cache_row_b;
+            __builtin_amdgcn_global_load_lds(kb + ld_off0, k_dst, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(vb + ld_off0, v_dst, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(kb + ld_off1, k_dst + K_GROUP, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(vb + ld_off1, v_dst + V_GROUP, 16, 0, 0);
+        } else {                                             // ragged tail or the tree's keys: rows past the end are
+            const unsigned char* kb = is_tree ? k_tree : k_cache + static_cast<long>(tile) * TILE * cache_row_b;   // masked later,
+            const unsigned char* vb = is_tree ? v_tree : v_cache + static_cast<long>(tile) * TILE * cache_row_b;   // reads stay in range
+            const unsigned row_b = is_tree ? tree_row_b : cache_row_b;
+            const int last = is_tree ? sp.n - 1 : L - 1 - tile * TILE;
+            const unsigned o0 = static_cast<unsigned>(min(ld_tok, last)) * row_b + ld_chunk_b;
+            const unsigned o1 = static_cast<unsigned>(min(ld_tok + 1, last)) * row_b + ld_chunk_b;
+            __builtin_amdgcn_global_load_lds(kb + o0, k_dst, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(vb + o0, v_dst, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(kb + o1, k_dst + K_GROUP, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(vb + o1, v_dst + V_GROUP, 16, 0, 0);
+        }
+    };
+    // Everything the prologue needs from memory is requested back to back (ancestor masks, Q rows, the first three
+    // K/V tiles) so that the workgroup pays one memory round trip before its first MFMA, not three.
+    uint64_t my_mask = 0ull;                                 // threads 0..127: mask of row `tid` of this group
     if (tid < ROWS_PER_WG) {
         const int mm = cg * ROWS_PER_WG + tid;
-        s_mask[tid] = mm < sp.rows ? prm.anc_mask[static_cast<long>(b) * SAGE_MAX_NODES + mm / prm.G] : 0ull;
+        if (mm < sp.rows) my_mask = prm.anc_mask[static_cast<long>(b) * SAGE_MAX_NODES + mm / prm.G];
     }
-    __syncthreads();                                         // masks visible before any LDS-direct load is in flight
-
     bf16x8 qf[8];
     {
         const uint16_t* qrow = prm.Q + ((static_cast<long>(b) * SAGE_MAX_NODES + node) * prm.Hq + g * prm.G + (m % prm.G)) * D;
@@ -179,53 +221,23 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
             qf[kk] = __builtin_bit_cast(bf16x8, v);
         }
     }
+    if (t_begin < t_end) issue_loads(t_begin, std::integral_constant<int, 0>{});
+    if (t_begin + 1 < t_end) issue_loads(t_begin + 1, std::integral_constant<int, 1>{});
+    if (t_begin + 2 < t_end) issue_loads(t_begin + 2, std::integral_constant<int, 2>{});
+    // the rows' masks wait in LDS until the tree tile comes; the store is complete before this wave's first barrier
+    if (tid < ROWS_PER_WG) s_mask[tid] = my_mask;
+    __builtin_amdgcn_s_waitcnt(0xc07f);                      // lgkmcnt(0)
 
-    // ---- loader: wave w copies token rows 8w..8w+7 of K and of V, four rows (1 KB of LDS) per instruction;
-    //      lane l fills slot l%16 of row l/16 with the chunk that the permutation assigns to that slot
-    const int ld_row = lane >> 4;                            // 0..3 within the instruction's 4 rows
-    const int ld_slot = lane & 15;
-    const unsigned char* k_cache = reinterpret_cast<const unsigned char*>(
-        prm.Kc + prm.kv_start[b] * prm.kv_token_stride + static_cast<long>(g) * prm.kv_head_stride);
-    const unsigned char* v_cache = reinterpret_cast<const unsigned char*>(
-        prm.Vc + prm.kv_start[b] * prm.kv_token_stride + static_cast<long>(g) * prm.kv_head_stride);
-    const unsigned char* k_tree = reinterpret_cast<const unsigned char*>(
-        prm.Kt + (static_cast<long>(b) * SAGE_MAX_NODES * prm.Hkv + g) * D);
-    const unsigned char* v_tree = reinterpret_cast<const unsigned char*>(
-        prm.Vt + (static_cast<long>(b) * SAGE_MAX_NODES * prm.Hkv + g) * D);
-    const long cache_row_b = prm.kv_token_stride * 2;
-    const long tree_row_b = static_cast<long>(prm.Hkv) * D * 2;
-
-    auto issue_loads = [&](int tile, auto stc) __attribute__((always_inline)) {
-        constexpr int ST = decltype(stc)::value;
-        const bool is_tree = (tile == tree_tile);
-        const unsigned char* kb = is_tree ? k_tree : k_cache;
-        const unsigned char* vb = is_tree ? v_tree : v_cache;
-        const long row_b = is_tree ? tree_row_b : cache_row_b;
-        const int first = is_tree ? 0 : tile * TILE;
-        const int last = is_tree ? sp.n - 1 : L - 1;         // rows past the end are masked later; keep reads in range
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int t = (wave * 2 + i) * 4 + ld_row;       // token row within the tile
-            const long roff = static_cast<long>(min(first + t, last)) * row_b;
-            const int kc = ld_slot ^ k_swz(t);
-            const int vc = ld_slot ^ v_swz(t);
-            __builtin_amdgcn_global_load_lds(kb + roff + kc * 16, (LDS_AS unsigned char*)(&SK(ST)[(wave * 2 + i) * 1024]), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(vb + roff + vc * 16, (LDS_AS unsigned char*)(&SV(ST)[(wave * 2 + i) * 1024]), 16, 0, 0);
-        }
-    };
-
-    // ---- per-lane LDS read offsets.  K fragment (sub, kk): token sub*32 + r32, chunk 2kk + half, whose slot is
-    // (2kk + half) ^ k_swz(r32); as byte offsets that is k_lane ^ (kk << 5).
-    const int k_lane = r32 * ROW_B + ((k_swz(r32) ^ half) << 4);
-    // V^T fragment (dt, kbk, u): the 16-lane group q = lane/16 reads tokens kbk*16 + 8u + 4(q/2) + s/4 and dims
+    // ---- per-lane LDS read offsets (this wave's 32-token half starts sub_lo * 2 * ROW_B into every group).
+    // K fragment kk: token r32 of the half, chunk 2kk + half -> k_lane + 32 kk.
+    const int k_lane = (r32 & 15) * K_GROUP + (r32 >> 4) * ROW_B + half * 16 + sub_lo * 2 * ROW_B;
+    // V^T fragment (dt, j, u): the 16-lane group q = lane/16 reads tokens 16j + 8u + 4(q/2) + s/4 of the half and dims
     // dt*32 + 16(q%2) + 4(s%4) .. +3  (s = lane%16); after the transposing read lane s holds dim dt*32+16(q%2)+s.
-    // Byte offset within the tile: (kbk*16 + 8u) rows, plus v_lane ^ (dt << 6).
+    // Offset: v_lane + j * ROW_B + u * 8 * V_GROUP + dt * 64.
     int v_lane;
     {
         const int q = lane >> 4, s16 = lane & 15;
-        const int trow = 4 * (q >> 1) + (s16 >> 2);          // token row modulo 8
-        const int chunk_lo = 2 * (q & 1) + ((s16 & 3) >> 1); // chunk within the dt block of 4 chunks
-        v_lane = trow * ROW_B + ((chunk_lo ^ v_swz(trow)) << 4) + 8 * (s16 & 1);
+        v_lane = (4 * (q >> 1) + (s16 >> 2)) * V_GROUP + (2 * (q & 1) + ((s16 & 3) >> 1)) * 16 + 8 * (s16 & 1) + sub_lo * 2 * ROW_B;
     }
 
     f32x16 acc[4];                                           // O^T: 4 tiles of 32 dims x this lane's query row
@@ -236,37 +248,46 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
     float m_ref = -INFINITY;                                 // reference maximum of raw (unscaled) scores
     float l_run = 0.f;                                       // this lane's share of the running sum
     const float c = prm.scale_log2e;
-
-    // A tile step has two phases for this wave's column tile: scores (S^T = K Q^T, MFMA) and softmax + PV (VALU, then
-    // MFMA).  Waves 0-3 run them back to back on the current tile.  Waves 4-7, each of which shares a SIMD with one
-    // of waves 0-3, run one phase behind (softmax + PV of the previous tile, then the scores of the current one), so
-    // that on every SIMD one wave's matrix work overlaps the other wave's vector work instead of both waves hitting
-    // the same pipe after each barrier.
     f32x16 sc;                                               // scores of this wave's 32-token half tile
-    const bool lag = wave >= 4;
+    bf16x8 pf[2];                                            // P^T of that half tile, the B operand of PV
 
-    auto score_phase = [&](const lds_byte* kb, bool masked, uint32_t adm) __attribute__((always_inline)) {
+    // A tile step of a wave: scores (S^T = K Q^T, MFMA), softmax (VALU), PV (MFMA).  The LDS reads of a phase are
+    // issued in batches ahead of the arithmetic that hides their latency; the scheduling fences keep the compiler
+    // from sinking them back next to their uses, where every MFMA group would wait out a full LDS round trip.
+    auto read_k = [&](const lds_byte* kb, bf16x8 (&a)[8], auto firstc) __attribute__((always_inline)) {
+        constexpr int FIRST = decltype(firstc)::value;        // dims FIRST*16 .. FIRST*16 + 63
 #pragma unroll
-        for (int i = 0; i < 16; ++i) sc[i] = 0.f;
-#pragma unroll
-        for (int kh = 0; kh < 2; ++kh) {
-            bf16x8 a[4];
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk)
-                a[kk] = __builtin_bit_cast(bf16x8, *(const LDS_AS uint4*)(kb + (k_lane ^ ((kh * 4 + kk) << 5))));
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk], qf[kh * 4 + kk], sc, 0, 0, 0);
-        }
-        // admit keys: cache positions below kv_len; tree nodes in this row's ancestor-or-self mask
-        if (masked) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-                if (!((adm >> (8 * (i >> 2) + (i & 3))) & 1u)) sc[i] = -INFINITY;
-        }
+        for (int kk = FIRST; kk < FIRST + 4; ++kk) a[kk] = __builtin_bit_cast(bf16x8, *(const LDS_AS uint4*)(kb + k_lane + kk * 32));
     };
-
-    auto value_phase = [&](const lds_byte* vb) __attribute__((always_inline)) {
-        // ---- online softmax for this lane's query row, lazily rescaled
+    auto read_v = [&](const lds_byte* vb, bf16x8 (&v)[4][2], auto dt0c) __attribute__((always_inline)) {
+        constexpr int DT0 = decltype(dt0c)::value;            // dims DT0*32 .. DT0*32 + 63
+#pragma unroll
+        for (int dt = DT0; dt < DT0 + 2; ++dt)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const lds_byte* p0 = vb + v_lane + j * ROW_B + dt * 64;
+                const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)p0);
+                const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)(p0 + 8 * V_GROUP));
+                v[dt][j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
+    };
+    auto score_mfma = [&](const bf16x8 (&a)[8], auto firstc) __attribute__((always_inline)) {
+        constexpr int FIRST = decltype(firstc)::value;
+        if (FIRST == 0) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sc[i] = 0.f;
+        }
+#pragma unroll
+        for (int kk = FIRST; kk < FIRST + 4; ++kk) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk], qf[kk], sc, 0, 0, 0);
+    };
+    // admit keys: cache positions below kv_len; tree nodes in this row's ancestor-or-self mask
+    auto score_mask = [&](uint32_t adm) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if (!((adm >> (8 * (i >> 2) + (i & 3))) & 1u)) sc[i] = -INFINITY;
+    };
+    // online softmax for this lane's query row, lazily rescaled: sc -> pf
+    auto softmax_phase = [&]() __attribute__((always_inline)) {
         float tmax = sc[0];
 #pragma unroll
         for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, sc[i]);
@@ -284,7 +305,6 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
         }
         const float neg_mc = (m_ref == -INFINITY) ? 0.f : -m_ref * c;
         float psum = 0.f;
-        bf16x8 pf[2];
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             bf16x8 frag;
@@ -301,67 +321,69 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
             pf[j] = frag;
         }
         l_run += psum;
-        // ---- O^T += V^T P^T   (two k-blocks of 16 tokens; two transposing reads of 4 tokens each per lane and block)
-#pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
-            bf16x8 a[2];
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const lds_byte* p0 = vb + (j * 16) * ROW_B + (v_lane ^ (dt << 6));
-                const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)p0);
-                const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)(p0 + 8 * ROW_B));
-                a[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            }
-#pragma unroll
-            for (int j = 0; j < 2; ++j) acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], pf[j], acc[dt], 0, 0, 0);
-        }
     };
-
-    const int sub_off = sub_lo * 32 * ROW_B;                 // this wave's half of the tile when a column tile is shared
+    // O^T += V^T P^T for 64 dims (two k-blocks of 16 tokens)
+    auto pv_mfma = [&](const bf16x8 (&v)[4][2], auto dt0c) __attribute__((always_inline)) {
+        constexpr int DT0 = decltype(dt0c)::value;
+#pragma unroll
+        for (int dt = DT0; dt < DT0 + 2; ++dt)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v[dt][j], pf[j], acc[dt], 0, 0, 0);
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I2 = std::integral_constant<int, 2>;
+    using I4 = std::integral_constant<int, 4>;
+#define FENCE() __builtin_amdgcn_sched_barrier(0)
 
     auto process = [&](int tile, auto stc) __attribute__((always_inline)) {
         constexpr int ST = decltype(stc)::value;
-        constexpr int PREV = (ST + STAGES - 1) % STAGES;
-        if (tile + 1 < t_end) wait_vm<LOADS_PER_TILE>();     // the next tile's loads may stay in flight
+        if (tile + 2 < t_end) wait_vm<2 * LOADS_PER_TILE>();     // the next two tiles' loads may stay in flight
+        else if (tile + 1 < t_end) wait_vm<LOADS_PER_TILE>();
         else wait_vm<0>();                                   // this thread's part of `tile` has landed
-        stage_barrier();                                     // ... everyone's has, and the stage read two steps ago is free
-        if (tile + 2 < t_end) issue_loads(tile + 2, std::integral_constant<int, (ST + 2) % STAGES>{});
+        stage_barrier();                                     // ... everyone's has, and the stage read last step is free
+        if (tile + 3 < t_end) issue_loads(tile + 3, std::integral_constant<int, (ST + 3) % STAGES>{});
         if (!wave_active) return;
 
         const bool is_tree = (tile == tree_tile);
         const bool masked = is_tree || tile * TILE + TILE > L;
-        uint64_t admit = ~0ull;
+        uint32_t adm = ~0u;
         if (masked) {
+            uint64_t admit;
             if (is_tree) {
                 admit = s_mask[m_local];
             } else {
                 const int left = L - tile * TILE;            // 1..63 valid tokens
                 admit = (1ull << left) - 1ull;
             }
-            admit >>= 4 * half;                              // token of accumulator register i: 32 sub + 8 (i/4) + 4 half + i%4
+            // token of accumulator register i: 32 sub + 8 (i/4) + 4 half + i%4
+            adm = static_cast<uint32_t>(admit >> (4 * half + 32 * sub_lo));
         }
-        const uint32_t adm = static_cast<uint32_t>(admit >> (32 * sub_lo));
-        if (lag) {
-            if (tile > t_begin) value_phase((const lds_byte*)(SV(PREV)) + sub_off);
-            score_phase((const lds_byte*)(SK(ST)) + sub_off, masked, adm);
-        } else {
-            score_phase((const lds_byte*)(SK(ST)) + sub_off, masked, adm);
-            value_phase((const lds_byte*)(SV(ST)) + sub_off);
-        }
+        const lds_byte* kst = (const lds_byte*)(SK(ST));
+        const lds_byte* vst = (const lds_byte*)(SV(ST));
+        bf16x8 ka[8], va[4][2];
+        read_k(kst, ka, I0{});
+        read_k(kst, ka, I4{});
+        FENCE();
+        score_mfma(ka, I0{});
+        FENCE();
+        read_v(vst, va, I0{});                               // V reads go out between the score MFMAs and land
+        FENCE();                                             // during the softmax
+        score_mfma(ka, I4{});
+        FENCE();
+        read_v(vst, va, I2{});
+        FENCE();
+        if (masked) score_mask(adm);
+        softmax_phase();
+        pv_mfma(va, I0{});
+        pv_mfma(va, I2{});
     };
-
-    if (t_begin < t_end) issue_loads(t_begin, std::integral_constant<int, 0>{});
-    if (t_begin + 1 < t_end) issue_loads(t_begin + 1, std::integral_constant<int, 1>{});
     for (int tile = t_begin; tile < t_end; tile += STAGES) {
         process(tile, std::integral_constant<int, 0>{});
         if (tile + 1 < t_end) process(tile + 1, std::integral_constant<int, 1>{});
         if (tile + 2 < t_end) process(tile + 2, std::integral_constant<int, 2>{});
         if (tile + 3 < t_end) process(tile + 3, std::integral_constant<int, 3>{});
     }
-    if (wave_active && lag && t_begin < t_end) {             // the trailing waves still owe the last tile's softmax + PV
-        const int last_stage = (t_end - 1 - t_begin) % STAGES;
-        value_phase((const lds_byte*)(SV(last_stage)) + sub_off);
-    }
+#undef FENCE
 
     float l_tot = cross_half_sum(l_run);
 
@@ -526,6 +548,7 @@ int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const voi
     const int G = Hq / Hkv;
     if (d != D || !(G == 1 || G == 2 || G == 4 || G == 8 || G == 16)) return SAGE_UNSUPPORTED;
     if ((kv_token_stride % 8) != 0 || (kv_head_stride % 8) != 0) return SAGE_INVALID_ARG;
+    if (kv_token_stride > (1L << 24)) return SAGE_UNSUPPORTED;   // the byte offsets inside a 64-token tile are 32-bit
     if (!aligned(Q, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(Kt, 16) || !aligned(Vt, 16) || !aligned(workspace, 16))
         return SAGE_INVALID_ARG;
     if (workspace_bytes < attention_bf16_workspace_bytes(B, Hkv, G, max_kv_len)) return SAGE_WORKSPACE_TOO_SMALL;
