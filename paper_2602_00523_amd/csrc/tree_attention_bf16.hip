@@ -54,8 +54,10 @@ constexpr int ROW_B = 256;              // bytes of one token row (128 bf16)
 // 64 bytes for V (read 4 consecutive tokens x 64 bytes at a time).  All per-fragment offsets are compile-time.
 constexpr int K_GROUP = 4 * ROW_B + 16;
 constexpr int V_GROUP = 4 * ROW_B + 64;
-constexpr int K_STAGE_B = 16 * K_GROUP;
+constexpr int EPI_ROW_F = 132;            // floats per parked row in the epilogue (130 used; 132 keeps 16-byte stores conflict-free)
+constexpr int K_STAGE_B = 32 * EPI_ROW_F * 4;   // 16 * K_GROUP for the ring, rounded up to hold an epilogue block
 constexpr int V_STAGE_B = 16 * V_GROUP;
+static_assert(K_STAGE_B >= 16 * K_GROUP && V_STAGE_B >= 32 * EPI_ROW_F * 4, "stage buffers double as epilogue blocks");
 constexpr int STAGES = 4;
 constexpr int LOADS_PER_TILE = 2 * TILE * ROW_B / (THREADS * 16);   // LDS-direct loads per thread per tile (K and V)
 constexpr int PART_FLOATS = D + 2;      // per query row: O^T[128], then max, sum
@@ -125,7 +127,6 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
     __shared__ __align__(1024) unsigned char sV2[V_STAGE_B];
     __shared__ __align__(1024) unsigned char sV3[V_STAGE_B];
     __shared__ uint64_t s_mask[ROWS_PER_WG];
-    __shared__ float s_ml[4][2][32];                         // half-merge mailbox: per column tile, (max, sum) per row
 #define SK(i) ((i) == 0 ? sK0 : (i) == 1 ? sK1 : (i) == 2 ? sK2 : sK3)
 #define SV(i) ((i) == 0 ? sV0 : (i) == 1 ? sV1 : (i) == 2 ? sV2 : sV3)
 
@@ -385,47 +386,40 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
     }
 #undef FENCE
 
-    float l_tot = cross_half_sum(l_run);
+    const float l_tot = cross_half_sum(l_run);
 
-    // ---- the wave of the upper token half hands its state to the wave it shares the column tile with
-    {
-        __syncthreads();                                     // all stages are idle now: K stage `ct` becomes a mailbox
-        float* box = reinterpret_cast<float*>(SK(ct));       // [64 accumulator registers][64 lanes]
-        if (wave_active && sub_lo == 1) {
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) box[(dt * 16 + i) * 64 + lane] = acc[dt][i];
-            if (half == 0) { s_ml[ct][0][r32] = m_ref; s_ml[ct][1][r32] = l_tot; }
-        }
-        __syncthreads();
-        if (wave_active && sub_lo == 0) {
-            const float m_o = s_ml[ct][0][r32], l_o = s_ml[ct][1][r32];
-            const float m_new = fmaxf(m_ref, m_o);
-            const float w_s = (m_ref == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_ref - m_new) * c);
-            const float w_o = (m_o == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_o - m_new) * c);
-            m_ref = m_new;
-            l_tot = l_tot * w_s + l_o * w_o;
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[dt][i] = acc[dt][i] * w_s + box[(dt * 16 + i) * 64 + lane] * w_o;
-        }
-    }
-
-    // ---- un-normalised partial for this (split, query row), merged by the second kernel
-    if (row_valid && sub_lo == 0) {
-        float* out = prm.part + (((static_cast<long>(b) * prm.Hkv + g) * prm.nslot + slot) * ROWS_PER_WG + m_local) * PART_FLOATS;
+    // ---- epilogue: every wave parks its block (O^T, max, sum) in the stage buffer of its (column tile, token half)
+    // as [32 rows][EPI_ROW_F floats]; then the whole workgroup combines the two halves of each row and writes the
+    // un-normalised partial of this split row by row (512 contiguous bytes per row), for the second kernel to merge.
+    __syncthreads();                                         // all stages are idle now
+    if (wave_active) {
+        float* blk = reinterpret_cast<float*>(sub_lo ? SV(ct) : SK(ct)) + r32 * EPI_ROW_F;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float4 v = make_float4(acc[dt][4 * q], acc[dt][4 * q + 1], acc[dt][4 * q + 2], acc[dt][4 * q + 3]);
-                *reinterpret_cast<float4*>(out + dt * 32 + 8 * q + 4 * half) = v;
-            }
-        if (half == 0) {
-            out[D] = m_ref;
-            out[D + 1] = l_tot;
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<float4*>(blk + dt * 32 + 8 * q + 4 * half) =
+                    make_float4(acc[dt][4 * q], acc[dt][4 * q + 1], acc[dt][4 * q + 2], acc[dt][4 * q + 3]);
+        if (half == 0) { blk[D] = m_ref; blk[D + 1] = l_tot; }
+    }
+    __syncthreads();
+    {
+        float* out_base = prm.part + ((static_cast<long>(b) * prm.Hkv + g) * prm.nslot + slot) * ROWS_PER_WG * PART_FLOATS;
+        for (int it = tid; it < group_rows * 32; it += THREADS) {
+            const int row = it >> 5, ch = it & 31;           // row of the group, 16-byte chunk of its 128 dims
+            const int rct = row >> 5;
+            const float* b0 = reinterpret_cast<const float*>(SK(rct)) + (row & 31) * EPI_ROW_F;
+            const float* b1 = reinterpret_cast<const float*>(SV(rct)) + (row & 31) * EPI_ROW_F;
+            const float m0 = b0[D], l0 = b0[D + 1], m1 = b1[D], l1 = b1[D + 1];
+            const float m_new = fmaxf(m0, m1);
+            const float w0 = (m0 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m0 - m_new) * c);
+            const float w1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m1 - m_new) * c);
+            const float4 x = *reinterpret_cast<const float4*>(b0 + ch * 4);
+            const float4 y = *reinterpret_cast<const float4*>(b1 + ch * 4);
+            float* out = out_base + row * PART_FLOATS;
+            *reinterpret_cast<float4*>(out + ch * 4) =
+                make_float4(x.x * w0 + y.x * w1, x.y * w0 + y.y * w1, x.z * w0 + y.z * w1, x.w * w0 + y.w * w1);
+            if (ch == 0) { out[D] = m_new; out[D + 1] = l0 * w0 + l1 * w1; }
         }
     }
 #undef SK
