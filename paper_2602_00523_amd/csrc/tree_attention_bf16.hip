@@ -431,14 +431,20 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
 // Every partial of the row is requested before the first one is used, so the merge costs one memory round trip.
 constexpr int MERGE_ROWS = 4;            // rows (waves) per workgroup
 __global__ __launch_bounds__(64 * MERGE_ROWS) void tree_attention_merge_kernel(const Params prm) {
+    // blockIdx = ((b * 64 + node) * (G / rows-per-block) + head group) * Hkv + KV head: like the main kernel, a KV
+    // head's blocks are congruent modulo the KV-head count, so with 8 KV heads they run on the XCD whose L2 still
+    // holds that head's partials.
     const int lane = threadIdx.x & 63;
-    const int hh = blockIdx.y * MERGE_ROWS + (threadIdx.x >> 6);
-    const int node = blockIdx.x, b = blockIdx.z;
+    int id = blockIdx.x;
+    const int g = id % prm.Hkv; id /= prm.Hkv;
+    const int per_node = (prm.G + MERGE_ROWS - 1) / MERGE_ROWS;
+    const int hg = (id % per_node) * MERGE_ROWS + (threadIdx.x >> 6); id /= per_node;
+    const int node = id % SAGE_MAX_NODES, b = id / SAGE_MAX_NODES;
     const int L = prm.kv_len[b] > 0 ? prm.kv_len[b] : 0;
     const Split sp = make_split(prm.n_nodes[b], L, prm.G, prm.nslot, prm.min_tiles_per_split);
-    if (node >= sp.n || hh >= prm.Hq || sp.col_groups > prm.nslot) return;
-    const int g = hh / prm.G;
-    const int m = node * prm.G + (hh % prm.G);
+    if (node >= sp.n || hg >= prm.G || sp.col_groups > prm.nslot) return;
+    const int hh = g * prm.G + hg;
+    const int m = node * prm.G + hg;
     const int cg = m / ROWS_PER_WG;
     const int row = m % ROWS_PER_WG;
     const float c = prm.scale_log2e;
@@ -564,7 +570,9 @@ int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const voi
     if (blocks > 0x7FFFFFFFL) return SAGE_UNSUPPORTED;
     hipLaunchKernelGGL(tree_attention_bf16_kernel, dim3(static_cast<unsigned>(blocks)), dim3(THREADS), 0, stream, p);
     if (hipGetLastError() != hipSuccess) return SAGE_LAUNCH_FAILED;
-    hipLaunchKernelGGL(tree_attention_merge_kernel, dim3(SAGE_MAX_NODES, (Hq + MERGE_ROWS - 1) / MERGE_ROWS, B), dim3(64 * MERGE_ROWS), 0, stream, p);
+    const long merge_blocks = static_cast<long>(B) * SAGE_MAX_NODES * ((G + MERGE_ROWS - 1) / MERGE_ROWS) * Hkv;
+    if (merge_blocks > 0x7FFFFFFFL) return SAGE_UNSUPPORTED;
+    hipLaunchKernelGGL(tree_attention_merge_kernel, dim3(static_cast<unsigned>(merge_blocks)), dim3(64 * MERGE_ROWS), 0, stream, p);
     return launch_status();
 }
 
