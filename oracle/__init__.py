@@ -80,7 +80,8 @@ def entropy_topk(logits: np.ndarray, k: int, n_valid: np.ndarray | None = None, 
     return out
 
 
-def build_tree(topk_renorm: np.ndarray, alpha: np.ndarray, params: dict, topk_idx: np.ndarray | None = None):
+def build_tree(topk_renorm: np.ndarray, alpha: np.ndarray, params: dict, topk_idx: np.ndarray | None = None,
+               d_max_seq: np.ndarray | None = None):
     """O2 (Sec. 3.2, Eq. 10-12 and the membership rule).  fp32 inputs, bit-for-bit."""
     pr = np.ascontiguousarray(topk_renorm, np.float32)
     al = np.ascontiguousarray(alpha, np.float32)
@@ -93,7 +94,10 @@ def build_tree(topk_renorm: np.ndarray, alpha: np.ndarray, params: dict, topk_id
         node_token=np.full((B, MAX_NODES), -2, np.int32))
     if topk_idx is not None:
         topk_idx = np.ascontiguousarray(topk_idx, np.int32)
-    rc = lib().oracle_build_tree(_p(pr), _p(al), _p(topk_idx), B, k, ctypes.byref(tp), _p(out["n_nodes"]),
+    if d_max_seq is not None:
+        d_max_seq = np.ascontiguousarray(d_max_seq, np.int32)
+        assert d_max_seq.shape == (B,)
+    rc = lib().oracle_build_tree(_p(pr), _p(al), _p(topk_idx), B, k, ctypes.byref(tp), _p(d_max_seq), _p(out["n_nodes"]),
                                  _p(out["parent"]), _p(out["depth"]), _p(out["rank"]), _p(out["anc_mask"]),
                                  _p(out["cum_prob"]), _p(out["node_token"]))
     if rc:
@@ -141,3 +145,49 @@ def verify_accept(token, target_argmax, parent, depth, n_nodes, path_cap: int):
     if rc:
         raise ValueError(f"oracle_verify_accept status {rc}")
     return out
+
+
+def commit_path(Kt, Vt, Kc, Vc, kv_start, kv_len, kv_capacity: int, kv_token_stride: int, kv_head_stride: int,
+                path_nodes, accept_len, Hkv: int, d: int):
+    """O5 (Alg. 1 Phase 3).  Appends the K/V rows of the accepted path to the caches IN PLACE (one layer)."""
+    code = _dtype_code(Kt)
+    for a in (Kt, Vt, Kc, Vc):
+        assert _dtype_code(a) == code and a.flags["C_CONTIGUOUS"]
+    assert Kc.flags["WRITEABLE"] and Vc.flags["WRITEABLE"]
+    B = Kt.shape[0]
+    assert Kt.shape == (B, MAX_NODES, Hkv, d) and Vt.shape == Kt.shape
+    kv_start = np.ascontiguousarray(kv_start, np.int64)
+    kv_len = np.ascontiguousarray(kv_len, np.int32)
+    path_nodes = np.ascontiguousarray(path_nodes, np.int32)
+    accept_len = np.ascontiguousarray(accept_len, np.int32)
+    rc = lib().oracle_commit_path(_p(Kt), _p(Vt), _p(Kc), _p(Vc), code, B, Hkv, d, _p(kv_start), _p(kv_len),
+                                  int(kv_capacity), ctypes.c_long(kv_token_stride), ctypes.c_long(kv_head_stride),
+                                  _p(path_nodes), _p(accept_len), path_nodes.shape[1])
+    if rc:
+        raise ValueError(f"oracle_commit_path status {rc}")
+
+
+def advance_kv_len(kv_len, accept_len, kv_capacity: int):
+    """O5: new sequence lengths after a commit (returns a new array)."""
+    out = np.array(kv_len, np.int32, copy=True)
+    accept_len = np.ascontiguousarray(accept_len, np.int32)
+    rc = lib().oracle_advance_kv_len(_p(out), _p(accept_len), out.shape[0], int(kv_capacity))
+    if rc:
+        raise ValueError(f"oracle_advance_kv_len status {rc}")
+    return out
+
+
+def update_history(accept_len, hist, count, d_max, window: int, lo: float, hi: float, d_floor: int, d_cap: int):
+    """O6 (Sec. 3.3 adaptive history tracking).  hist [B,window], count [B], d_max [B] are updated IN PLACE
+    (int32, C-contiguous); returns the moving averages."""
+    accept_len = np.ascontiguousarray(accept_len, np.int32)
+    B = accept_len.shape[0]
+    for a in (hist, count, d_max):
+        assert a.dtype == np.int32 and a.flags["C_CONTIGUOUS"] and a.flags["WRITEABLE"]
+    assert hist.shape == (B, window) and count.shape == (B,) and d_max.shape == (B,)
+    avg = np.zeros(B, np.float32)
+    rc = lib().oracle_update_history(_p(accept_len), B, window, ctypes.c_float(lo), ctypes.c_float(hi), d_floor, d_cap,
+                                     _p(hist), _p(count), _p(d_max), _p(avg))
+    if rc:
+        raise ValueError(f"oracle_update_history status {rc}")
+    return avg

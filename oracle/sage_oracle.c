@@ -20,6 +20,11 @@
  *                            Alg. 1 Phase 2.
  *   O4 oracle_verify_accept  Sec. 2.2 (longest matching prefix, advance
  *                            tau+1), Sec. 3.3 Phase 2, Def. 4.1 (greedy match).
+ *   O5 oracle_commit_path    Alg. 1 Phase 3 / Sec. 2.2: the accepted tokens join
+ *      oracle_advance_kv_len the context, i.e. their keys and values are appended
+ *                            to the KV cache and the sequence length advances.
+ *   O6 oracle_update_history Sec. 3.3 "Adaptive History Tracking" with the window
+ *                            and thresholds of Sec. 5 "Implementation details".
  *
  * Arithmetic: O1 and O3 are plain definitions and are evaluated in fp64 from
  * the exact input bits (bf16/fp32 widened exactly), two-pass softmax, no
@@ -27,12 +32,18 @@
  * outcome depends on rounding, so its real arithmetic is IEEE fp32 with the
  * four basic operations only, evaluated left to right, no fused multiply-add
  * (compile with -ffp-contract=off); that is the precision the decision is
- * defined in for both sides.  O4 is integer-only.
+ * defined in for both sides.  O4 and O5 are integer/byte-only.  O6 compares a
+ * sum of small integers with threshold * count in fp32 (both exact for the
+ * paper's thresholds).
  *
  * Pins (tests marked "not gpu"): closed forms for O1 (uniform -> ln V, one-hot
  * -> 0, shift invariance, library sort for the top-k order), brute-force
  * enumeration of the membership rule for O2, textbook causal attention for O3
- * on chain trees, brute-force path enumeration for O4.
+ * on chain trees, brute-force path enumeration for O4; for O5 the attention of
+ * a lone root over the extended cache must equal the tree attention of the
+ * deepest accepted node before the commit (O3 is the independent witness); for
+ * O6 hand-computed depth sequences for constant and step-change acceptance
+ * lengths and a full-history recomputation of the moving average.
  * parity unpinned: the integerisation of Eq. (10)/(11)/(12) in O2 (the paper
  * gives real-valued formulas only); pinned at the end-points and by
  * monotonicity only.
@@ -200,10 +211,12 @@ static void expand(tree_state* t, int u) {
  * emitted in creation order (DFS pre-order), so parent[v] < v.  Arrays are
  * [B, 64]; entries at or beyond n_nodes[b] are left untouched.  When the
  * candidates' vocabulary ids topk_idx [B,k] are given, node_token[v] is the
- * id of the candidate node v stands for (root -1).
+ * id of the candidate node v stands for (root -1).  When d_max_seq [B] is
+ * given, sequence b uses d_max_seq[b] (clamped to [d_min, 31]) as the D_max of
+ * Eq. (10): the maximum depth that adaptive history tracking maintains.
  */
 int oracle_build_tree(const float* topk_renorm, const float* alpha, const int* topk_idx, int B, int k,
-                      const oracle_tree_params* p,
+                      const oracle_tree_params* p, const int* d_max_seq,
                       int* n_nodes, int* parent, int* depth, int* rank, uint64_t* anc_mask,
                       float* cum_prob, int* node_token) {
     if (!topk_renorm || !alpha || !p || B < 0) return 1;
@@ -211,7 +224,13 @@ int oracle_build_tree(const float* topk_renorm, const float* alpha, const int* t
     if (p->d_min < 1 || p->d_min > p->d_max || p->w_min < 1 || p->w_min > p->w_max || p->w_max > k) return 1;
     for (int b = 0; b < B; ++b) {
         float a = alpha[b];
-        float D = floorf(((float)p->d_min + a * (float)(p->d_max - p->d_min)) + 0.5f);
+        int d_max = p->d_max;
+        if (d_max_seq) {
+            d_max = d_max_seq[b];
+            if (d_max < p->d_min) d_max = p->d_min;
+            if (d_max > 31) d_max = 31;
+        }
+        float D = floorf(((float)p->d_min + a * (float)(d_max - p->d_min)) + 0.5f);
         float W = floorf(((float)p->w_min + (1.0f - a) * (float)(p->w_max - p->w_min)) + 0.5f);
         if (W > (float)k) W = (float)k;
         float cum_local[ORACLE_MAX_NODES];
@@ -340,6 +359,90 @@ int oracle_verify_accept(const int* token, const int* target_argmax, const int* 
         for (int v = best; v >= 0; v = par[v]) path[dep[v]] = v;
         for (int j = 1; j <= tau; ++j) out[j - 1] = tok[path[j]];
         out[tau] = tgt[best];
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ O5 */
+
+static size_t elem_size(int dtype) { return dtype == ORACLE_F32 ? 4 : 2; }
+
+/*
+ * One layer's share of committing the accepted path.  For sequence b with
+ * tau = accept_len[b] and path = path_nodes[b][0..tau] (root first, as
+ * verify_accept emits it), the key and value rows of the tau + 1 path nodes
+ * (the root, whose K/V is not in the cache yet, and the tau accepted draft
+ * tokens) are copied, bytes unchanged, to cache positions kv_len[b] + j,
+ * j = 0..tau.  The bonus token has no K/V yet: it is the next step's root.
+ * Positions at or beyond kv_capacity are not written.  kv_len is not changed
+ * here (every layer commits against the same old length).
+ */
+int oracle_commit_path(const void* Kt, const void* Vt, void* Kc, void* Vc, int dtype, int B, int Hkv, int d,
+                       const int64_t* kv_start, const int* kv_len, int kv_capacity,
+                       long kv_token_stride, long kv_head_stride,
+                       const int* path_nodes, const int* accept_len, int path_cap) {
+    if (!Kt || !Vt || !Kc || !Vc || !kv_start || !kv_len || !path_nodes || !accept_len) return 1;
+    if (B < 0 || Hkv < 1 || d < 1 || path_cap < 1 || kv_capacity < 0) return 1;
+    const size_t es = elem_size(dtype);
+    for (int b = 0; b < B; ++b) {
+        const int tau = accept_len[b];
+        if (tau < 0 || tau + 1 > path_cap) return 1;
+        for (int j = 0; j <= tau; ++j) {
+            const int node = path_nodes[(long)b * path_cap + j];
+            const long pos = (long)kv_len[b] + j;
+            if (node < 0 || node >= ORACLE_MAX_NODES) return 1;
+            if (pos >= kv_capacity) break;
+            for (int g = 0; g < Hkv; ++g) {
+                const size_t src = ((((size_t)b * ORACLE_MAX_NODES + node) * Hkv + g) * d) * es;
+                const size_t dst = (size_t)((kv_start[b] + pos) * kv_token_stride + (long)g * kv_head_stride) * es;
+                memcpy((char*)Kc + dst, (const char*)Kt + src, (size_t)d * es);
+                memcpy((char*)Vc + dst, (const char*)Vt + src, (size_t)d * es);
+            }
+        }
+    }
+    return 0;
+}
+
+/* After every layer has committed: the sequence grows by the root and the tau accepted tokens. */
+int oracle_advance_kv_len(int* kv_len, const int* accept_len, int B, int kv_capacity) {
+    if (!kv_len || !accept_len || B < 0) return 1;
+    for (int b = 0; b < B; ++b) {
+        long n = (long)kv_len[b] + accept_len[b] + 1;
+        kv_len[b] = n > kv_capacity ? kv_capacity : (int)n;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ O6 */
+
+/*
+ * Adaptive history tracking.  Per sequence: the step's acceptance length is
+ * pushed into a sliding window of the last `window` values (a ring: slot =
+ * count mod window); the moving average runs over the values present (fewer
+ * than `window` during the first steps).  Average below `lo` (strictly): the
+ * maximum depth drops by one, not below d_floor; average above `hi`
+ * (strictly): it rises by one, not above d_cap; in between it stays.  The
+ * comparison is sum < lo * n, resp. sum > hi * n, in fp32.
+ */
+int oracle_update_history(const int* accept_len, int B, int window, float lo, float hi, int d_floor, int d_cap,
+                          int* hist, int* count, int* d_max, float* avg_out) {
+    if (!accept_len || !hist || !count || !d_max || B < 0 || window < 1 || window > 64) return 1;
+    if (d_floor < 1 || d_floor > d_cap || !(lo <= hi)) return 1;
+    for (int b = 0; b < B; ++b) {
+        int* h = hist + (long)b * window;
+        h[count[b] % window] = accept_len[b];
+        count[b] += 1;
+        const int n = count[b] < window ? count[b] : window;
+        int sum = 0;
+        for (int i = 0; i < n; ++i) sum += h[i];
+        const float fs = (float)sum, fn = (float)n;
+        if (avg_out) avg_out[b] = fs / fn;
+        int dm = d_max[b];
+        if (fs < lo * fn) dm -= 1;
+        else if (fs > hi * fn) dm += 1;
+        if (dm < d_floor) dm = d_floor;
+        if (dm > d_cap) dm = d_cap;
+        d_max[b] = dm;
     }
     return 0;
 }
