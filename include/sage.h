@@ -100,6 +100,9 @@ int sage_entropy_topk(const void* logits, int dtype, int rows, int vocab, long r
  * next step from the current step's distribution).
  *
  * topk_renorm [B,k] f32, alpha [B] f32, params (host) copied at call time.
+ * d_max_seq [B] i32 (device), nullable: when given, sequence b uses d_max_seq[b], clamped to
+ * [d_min, SAGE_MAX_DEPTH], in place of params->d_max (the maximum depth that
+ * sage_update_history maintains, Sec. 3.3).
  * topk_idx [B,k] i32, nullable: the vocabulary ids of the k candidates (as written by
  * sage_entropy_topk); with it, node_token[b][v] = topk_idx[b][rank(v)] is the draft token of
  * node v (the candidate a node stands for), root -1.
@@ -110,7 +113,7 @@ int sage_entropy_topk(const void* logits, int dtype, int rows, int vocab, long r
  * node_token without topk_idx.
  */
 int sage_build_tree(const float* topk_renorm, const float* alpha, const int* topk_idx, int B, int k,
-                    const sage_tree_params* params,
+                    const sage_tree_params* params, const int* d_max_seq,
                     int* n_nodes, int* parent, int* depth, int* rank, uint64_t* anc_mask, float* cum_prob,
                     int* node_token, void* stream);
 
@@ -158,6 +161,47 @@ int sage_tree_attention(const void* Q, const void* Kc, const void* Vc, const voi
 int sage_verify_accept(const int* token, const int* target_argmax, const int* parent, const int* depth,
                        const uint64_t* anc_mask, const int* n_nodes, int B, int path_cap,
                        int* accept_len, int* best_node, int* path_nodes, int* out_tokens, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * sage_commit_path -- the accepted tokens join the context (Alg. 1 Phase 3, Sec. 2.2): one
+ * layer's share.  For sequence b with tau = accept_len[b] and path = path_nodes[b][0..tau]
+ * (root first, as sage_verify_accept emits it), the K and V rows of the tau + 1 path nodes
+ * (the root, whose K/V is not in the cache yet, and the tau accepted draft tokens) are
+ * copied, bytes unchanged, to cache positions kv_len[b] + j, j = 0..tau.  The bonus token
+ * has no K/V yet; it is the next step's root.  kv_len is read, not changed: every layer
+ * commits against the same old length; call sage_advance_kv_len once afterwards.
+ *
+ * Kt, Vt [B,64,Hkv,d] (device); Kc, Vc cache addressed as in sage_tree_attention (rows
+ * 16-byte aligned, d * element size a multiple of 16); kv_capacity (host): positions per
+ * sequence that the cache holds, positions at or beyond it are not written;
+ * path_nodes [B,path_cap] i32, accept_len [B] i32 (device).  Entries of path_nodes outside
+ * [0,64) are skipped.  Errors: INVALID_ARG (null pointers, sizes, strides, alignment),
+ * UNSUPPORTED (B > 65535, path_cap > 64).
+ *
+ * sage_advance_kv_len -- kv_len[b] = min(kv_len[b] + accept_len[b] + 1, kv_capacity), in place.
+ */
+int sage_commit_path(const void* Kt, const void* Vt, void* Kc, void* Vc, int dtype, int B, int Hkv, int d,
+                     const int64_t* kv_start, const int* kv_len, int kv_capacity,
+                     long kv_token_stride, long kv_head_stride,
+                     const int* path_nodes, const int* accept_len, int path_cap, void* stream);
+int sage_advance_kv_len(int* kv_len, const int* accept_len, int B, int kv_capacity, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * sage_update_history -- adaptive history tracking (Sec. 3.3; Sec. 5 "Implementation details":
+ * window 10, thresholds 2 and 3).  Per sequence b the step's acceptance length accept_len[b]
+ * enters a sliding window of the last `window` values; the moving average runs over the
+ * values present (fewer than `window` during the first steps).  Average < lo: d_max[b]
+ * drops by one, not below d_floor; average > hi: it rises by one, not above d_cap; otherwise
+ * unchanged (both comparisons strict, evaluated as sum vs threshold * count in fp32).
+ * Feed d_max to sage_build_tree as d_max_seq.
+ *
+ * State, all device, updated in place: hist [B,window] i32 (ring, slot = count mod window),
+ * count [B] i32 (steps so far; start at 0), d_max [B] i32.  avg_out [B] f32, nullable.
+ * Errors: INVALID_ARG (null pointers, B < 0, window outside [1,64], d_floor < 1,
+ * d_floor > d_cap, d_cap > SAGE_MAX_DEPTH, lo > hi).
+ */
+int sage_update_history(const int* accept_len, int B, int window, float lo, float hi, int d_floor, int d_cap,
+                        int* hist, int* count, int* d_max, float* avg_out, void* stream);
 
 /* Library build identification (host): returns a static string naming the target architecture. */
 const char* sage_build_info(void);

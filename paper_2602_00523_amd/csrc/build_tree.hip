@@ -27,7 +27,7 @@ __device__ __forceinline__ uint64_t lane_read(uint64_t v, int lane) {
 
 __global__ __launch_bounds__(64) void build_tree_kernel(
     const float* __restrict__ topk_renorm, const float* __restrict__ alpha, const int* __restrict__ topk_idx, int k,
-    sage_tree_params prm, int* __restrict__ n_nodes, int* __restrict__ parent, int* __restrict__ depth,
+    sage_tree_params prm, const int* __restrict__ d_max_seq, int* __restrict__ n_nodes, int* __restrict__ parent, int* __restrict__ depth,
     int* __restrict__ rank, uint64_t* __restrict__ anc_mask, float* __restrict__ cum_prob,
     int* __restrict__ node_token) {
     const int b = blockIdx.x;
@@ -36,8 +36,11 @@ __global__ __launch_bounds__(64) void build_tree_kernel(
     const int tok = (topk_idx && lane < k) ? topk_idx[static_cast<long>(b) * k + lane] : -1;
     const float a = alpha[b];
 
+    // the maximum depth of Eq. 10 is per sequence when adaptive history tracking (Sec. 3.3) maintains one
+    int d_max = prm.d_max;
+    if (d_max_seq) d_max = min(max(d_max_seq[b], prm.d_min), SAGE_MAX_DEPTH);
     // Eq. 10 / Eq. 11, rounded half up
-    const float Df = floorf(__fadd_rn(__fadd_rn((float)prm.d_min, __fmul_rn(a, (float)(prm.d_max - prm.d_min))), 0.5f));
+    const float Df = floorf(__fadd_rn(__fadd_rn((float)prm.d_min, __fmul_rn(a, (float)(d_max - prm.d_min))), 0.5f));
     float W = floorf(__fadd_rn(__fadd_rn((float)prm.w_min, __fmul_rn(__fsub_rn(1.0f, a), (float)(prm.w_max - prm.w_min))), 0.5f));
     if (W > (float)k) W = (float)k;
     // alpha is a confidence in [0,1]; anything else is clamped to the stack's capacity rather than trusted
@@ -119,8 +122,8 @@ __global__ __launch_bounds__(64) void build_tree_kernel(
 }  // namespace
 
 extern "C" int sage_build_tree(const float* topk_renorm, const float* alpha, const int* topk_idx, int B, int k,
-                               const sage_tree_params* params, int* n_nodes, int* parent, int* depth, int* rank,
-                               uint64_t* anc_mask, float* cum_prob, int* node_token, void* stream) {
+                               const sage_tree_params* params, const int* d_max_seq, int* n_nodes, int* parent,
+                               int* depth, int* rank, uint64_t* anc_mask, float* cum_prob, int* node_token, void* stream) {
     if (!topk_renorm || !alpha || !params || !n_nodes || !parent || !depth || !rank || !anc_mask) return SAGE_INVALID_ARG;
     if (node_token && !topk_idx) return SAGE_INVALID_ARG;
     const sage_tree_params p = *params;
@@ -130,6 +133,6 @@ extern "C" int sage_build_tree(const float* topk_renorm, const float* alpha, con
     if (p.w_min < 1 || p.w_min > p.w_max || p.w_max > k) return SAGE_INVALID_ARG;
     if (B == 0) return SAGE_OK;
     hipLaunchKernelGGL(build_tree_kernel, dim3(B), dim3(64), 0, sage::as_stream(stream), topk_renorm, alpha, topk_idx,
-                       k, p, n_nodes, parent, depth, rank, anc_mask, cum_prob, node_token);
+                       k, p, d_max_seq, n_nodes, parent, depth, rank, anc_mask, cum_prob, node_token);
     return sage::launch_status();
 }

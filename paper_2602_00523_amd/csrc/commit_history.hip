@@ -1,0 +1,110 @@
+// sage_commit_path / sage_advance_kv_len: the accepted tokens join the context (Alg. 1 Phase 3, Sec. 2.2): their
+// keys and values are appended to the KV cache and the sequence length advances.
+// sage_update_history: adaptive history tracking (Sec. 3.3; window and thresholds of Sec. 5 "Implementation
+// details"): a sliding window of acceptance lengths steers the maximum tree depth of every sequence.
+// All three are byte/integer work of a few KB per step: one small kernel each, no workspace.
+#include "sage_internal.h"
+
+namespace {
+
+// One workgroup per (path slot j, sequence b): copies the K row and the V row of node path[j] (Hkv heads x d
+// elements each) to cache position kv_len[b] + j in 16-byte pieces.
+__global__ __launch_bounds__(256) void commit_path_kernel(
+    const unsigned char* __restrict__ Kt, const unsigned char* __restrict__ Vt, unsigned char* __restrict__ Kc,
+    unsigned char* __restrict__ Vc, int esz, int Hkv, int d, const int64_t* __restrict__ kv_start,
+    const int* __restrict__ kv_len, int kv_capacity, long kv_token_stride, long kv_head_stride,
+    const int* __restrict__ path_nodes, const int* __restrict__ accept_len, int path_cap) {
+    const int j = blockIdx.x, b = blockIdx.y;
+    const int tau = accept_len[b];
+    if (j > tau || j >= path_cap) return;
+    const int node = path_nodes[static_cast<long>(b) * path_cap + j];
+    const long pos = static_cast<long>(kv_len[b]) + j;
+    if (node < 0 || node >= SAGE_MAX_NODES || pos >= kv_capacity) return;      // never read or write out of range
+    const int pieces = d * esz / 16;                                           // 16-byte pieces of one head's row
+    const long src_row = (static_cast<long>(b) * SAGE_MAX_NODES + node) * Hkv * d * esz;
+    const long dst_tok = (kv_start[b] + pos) * kv_token_stride * esz;
+    for (int t = threadIdx.x; t < Hkv * pieces; t += blockDim.x) {
+        const int g = t / pieces, c = t % pieces;
+        const long src = src_row + (static_cast<long>(g) * d * esz) + c * 16;
+        const long dst = dst_tok + static_cast<long>(g) * kv_head_stride * esz + c * 16;
+        *reinterpret_cast<uint4*>(Kc + dst) = *reinterpret_cast<const uint4*>(Kt + src);
+        *reinterpret_cast<uint4*>(Vc + dst) = *reinterpret_cast<const uint4*>(Vt + src);
+    }
+}
+
+__global__ void advance_kv_len_kernel(int* __restrict__ kv_len, const int* __restrict__ accept_len, int B, int kv_capacity) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const long n = static_cast<long>(kv_len[b]) + accept_len[b] + 1;          // the root and the tau accepted tokens
+    kv_len[b] = n > kv_capacity ? kv_capacity : static_cast<int>(n);
+}
+
+// One wave per sequence: lane i holds window slot i.
+__global__ __launch_bounds__(64) void update_history_kernel(const int* __restrict__ accept_len, int window, float lo, float hi,
+                                                            int d_floor, int d_cap, int* __restrict__ hist,
+                                                            int* __restrict__ count, int* __restrict__ d_max,
+                                                            float* __restrict__ avg_out) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    int* h = hist + static_cast<long>(b) * window;
+    const int cnt = count[b];
+    const int slot = cnt % window;
+    const int tau = accept_len[b];
+    const int n = min(cnt + 1, window);
+    int v = 0;
+    if (lane < n) v = (lane == slot) ? tau : h[lane];
+    int sum = v;
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+    if (lane == 0) {
+        h[slot] = tau;
+        count[b] = cnt + 1;
+        const float fs = static_cast<float>(sum), fn = static_cast<float>(n);
+        if (avg_out) avg_out[b] = __fdiv_rn(fs, fn);
+        int dm = d_max[b];
+        if (fs < __fmul_rn(lo, fn)) dm -= 1;                                   // strictly below the lower threshold
+        else if (fs > __fmul_rn(hi, fn)) dm += 1;                              // strictly above the upper one
+        d_max[b] = min(max(dm, d_floor), d_cap);
+    }
+}
+
+}  // namespace
+
+extern "C" int sage_commit_path(const void* Kt, const void* Vt, void* Kc, void* Vc, int dtype, int B, int Hkv, int d,
+                                const int64_t* kv_start, const int* kv_len, int kv_capacity, long kv_token_stride,
+                                long kv_head_stride, const int* path_nodes, const int* accept_len, int path_cap,
+                                void* stream) {
+    if (!Kt || !Vt || !Kc || !Vc || !kv_start || !kv_len || !path_nodes || !accept_len) return SAGE_INVALID_ARG;
+    if (dtype != SAGE_F32 && dtype != SAGE_BF16) return SAGE_INVALID_ARG;
+    if (B < 0 || Hkv < 1 || d < 1 || path_cap < 1 || kv_capacity < 0) return SAGE_INVALID_ARG;
+    if (kv_head_stride < d || kv_token_stride < d) return SAGE_INVALID_ARG;
+    const int esz = dtype == SAGE_F32 ? 4 : 2;
+    if ((static_cast<long>(d) * esz) % 16 != 0 || (kv_token_stride * esz) % 16 != 0 || (kv_head_stride * esz) % 16 != 0)
+        return SAGE_INVALID_ARG;
+    if (!sage::aligned(Kt, 16) || !sage::aligned(Vt, 16) || !sage::aligned(Kc, 16) || !sage::aligned(Vc, 16))
+        return SAGE_INVALID_ARG;
+    if (B > 65535 || path_cap > SAGE_MAX_NODES) return SAGE_UNSUPPORTED;
+    if (B == 0) return SAGE_OK;
+    hipLaunchKernelGGL(commit_path_kernel, dim3(path_cap, B), dim3(256), 0, sage::as_stream(stream),
+                       static_cast<const unsigned char*>(Kt), static_cast<const unsigned char*>(Vt),
+                       static_cast<unsigned char*>(Kc), static_cast<unsigned char*>(Vc), esz, Hkv, d, kv_start, kv_len,
+                       kv_capacity, kv_token_stride, kv_head_stride, path_nodes, accept_len, path_cap);
+    return sage::launch_status();
+}
+
+extern "C" int sage_advance_kv_len(int* kv_len, const int* accept_len, int B, int kv_capacity, void* stream) {
+    if (!kv_len || !accept_len || B < 0 || kv_capacity < 0) return SAGE_INVALID_ARG;
+    if (B == 0) return SAGE_OK;
+    hipLaunchKernelGGL(advance_kv_len_kernel, dim3((B + 255) / 256), dim3(256), 0, sage::as_stream(stream), kv_len,
+                       accept_len, B, kv_capacity);
+    return sage::launch_status();
+}
+
+extern "C" int sage_update_history(const int* accept_len, int B, int window, float lo, float hi, int d_floor, int d_cap,
+                                   int* hist, int* count, int* d_max, float* avg_out, void* stream) {
+    if (!accept_len || !hist || !count || !d_max || B < 0) return SAGE_INVALID_ARG;
+    if (window < 1 || window > 64 || d_floor < 1 || d_floor > d_cap || d_cap > SAGE_MAX_DEPTH || !(lo <= hi))
+        return SAGE_INVALID_ARG;
+    if (B == 0) return SAGE_OK;
+    hipLaunchKernelGGL(update_history_kernel, dim3(B), dim3(64), 0, sage::as_stream(stream), accept_len, window, lo, hi,
+                       d_floor, d_cap, hist, count, d_max, avg_out);
+    return sage::launch_status();
+}

@@ -43,8 +43,8 @@ def lib():
         L.sage_entropy_topk.restype = _ci
         L.sage_entropy_topk.argtypes = [_vp, _ci, _ci, _ci, _cl, _ci, _vp, _ci, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
         L.sage_build_tree.restype = _ci
-        L.sage_build_tree.argtypes = [_vp, _vp, _vp, _ci, _ci, ctypes.POINTER(TreeParams), _vp, _vp, _vp, _vp, _vp, _vp, _vp,
-                                      _vp]
+        L.sage_build_tree.argtypes = [_vp, _vp, _vp, _ci, _ci, ctypes.POINTER(TreeParams), _vp, _vp, _vp, _vp, _vp, _vp,
+                                      _vp, _vp, _vp]
         L.sage_tree_attention_workspace_bytes.restype = _sz
         L.sage_tree_attention_workspace_bytes.argtypes = [_ci, _ci, _ci, _ci, _ci, _ci]
         L.sage_tree_attention.restype = _ci
@@ -52,6 +52,12 @@ def lib():
                                           _vp, _vp, _cf, _vp, _sz, _vp]
         L.sage_verify_accept.restype = _ci
         L.sage_verify_accept.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _ci, _ci, _vp, _vp, _vp, _vp, _vp]
+        L.sage_commit_path.restype = _ci
+        L.sage_commit_path.argtypes = [_vp, _vp, _vp, _vp, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _cl, _cl, _vp, _vp, _ci, _vp]
+        L.sage_advance_kv_len.restype = _ci
+        L.sage_advance_kv_len.argtypes = [_vp, _vp, _ci, _ci, _vp]
+        L.sage_update_history.restype = _ci
+        L.sage_update_history.argtypes = [_vp, _ci, _ci, _cf, _cf, _ci, _ci, _vp, _vp, _vp, _vp, _vp]
         L.sage_build_info.restype = ctypes.c_char_p
         _lib = L
     return _lib
@@ -107,10 +113,10 @@ def _args_entropy_topk(logits, k, entropy, topk_idx, topk_prob, topk_renorm, top
 
 
 def _args_build_tree(topk_renorm, alpha, params: TreeParams, n_nodes, parent, depth, rank, anc_mask, cum_prob=None,
-                     topk_idx=None, node_token=None, stream=None):
+                     topk_idx=None, node_token=None, stream=None, d_max_seq=None):
     B, k = topk_renorm.shape
-    return [_ptr(topk_renorm), _ptr(alpha), _ptr(topk_idx), B, k, ctypes.byref(params), _ptr(n_nodes), _ptr(parent),
-            _ptr(depth), _ptr(rank), _ptr(anc_mask), _ptr(cum_prob), _ptr(node_token), _stream(stream)]
+    return [_ptr(topk_renorm), _ptr(alpha), _ptr(topk_idx), B, k, ctypes.byref(params), _ptr(d_max_seq), _ptr(n_nodes),
+            _ptr(parent), _ptr(depth), _ptr(rank), _ptr(anc_mask), _ptr(cum_prob), _ptr(node_token), _stream(stream)]
 
 
 def _args_tree_attention(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_token_stride, kv_head_stride, anc_mask,
@@ -129,8 +135,27 @@ def _args_verify_accept(token, target_argmax, parent, depth, anc_mask, n_nodes, 
             _ptr(accept_len), _ptr(best_node), _ptr(path_nodes), _ptr(out_tokens), _stream(stream)]
 
 
+def _args_commit_path(Kt, Vt, Kc, Vc, kv_start, kv_len, kv_capacity, kv_token_stride, kv_head_stride, path_nodes,
+                      accept_len, stream=None):
+    B, _, Hkv, d = Kt.shape
+    return [_ptr(Kt), _ptr(Vt), _ptr(Kc), _ptr(Vc), _dtype_code(Kt), B, Hkv, d, _ptr(kv_start), _ptr(kv_len), kv_capacity,
+            kv_token_stride, kv_head_stride, _ptr(path_nodes), _ptr(accept_len), path_nodes.shape[1], _stream(stream)]
+
+
+def _args_advance_kv_len(kv_len, accept_len, kv_capacity, stream=None):
+    return [_ptr(kv_len), _ptr(accept_len), kv_len.shape[0], kv_capacity, _stream(stream)]
+
+
+def _args_update_history(accept_len, hist, count, d_max, lo, hi, d_floor, d_cap, avg_out=None, stream=None):
+    B, window = hist.shape
+    return [_ptr(accept_len), B, window, lo, hi, d_floor, d_cap, _ptr(hist), _ptr(count), _ptr(d_max), _ptr(avg_out),
+            _stream(stream)]
+
+
 _MARSHAL = {"sage_entropy_topk": _args_entropy_topk, "sage_build_tree": _args_build_tree,
-            "sage_tree_attention": _args_tree_attention, "sage_verify_accept": _args_verify_accept}
+            "sage_tree_attention": _args_tree_attention, "sage_verify_accept": _args_verify_accept,
+            "sage_commit_path": _args_commit_path, "sage_advance_kv_len": _args_advance_kv_len,
+            "sage_update_history": _args_update_history}
 
 
 def sage_entropy_topk(*a, **kw):
@@ -147,6 +172,18 @@ def sage_tree_attention(*a, **kw):
 
 def sage_verify_accept(*a, **kw):
     _check("sage_verify_accept", lib().sage_verify_accept(*_args_verify_accept(*a, **kw)))
+
+
+def sage_commit_path(*a, **kw):
+    _check("sage_commit_path", lib().sage_commit_path(*_args_commit_path(*a, **kw)))
+
+
+def sage_advance_kv_len(*a, **kw):
+    _check("sage_advance_kv_len", lib().sage_advance_kv_len(*_args_advance_kv_len(*a, **kw)))
+
+
+def sage_update_history(*a, **kw):
+    _check("sage_update_history", lib().sage_update_history(*_args_update_history(*a, **kw)))
 
 
 def prepare(name: str, *a, **kw):

@@ -49,7 +49,7 @@ def gpu_entropy_topk(logits_np, k, n_valid=None, rows_per_group=1):
     return {key: v.cpu().numpy() for key, v in out.items()}
 
 
-def gpu_build_tree(topk_renorm_np, alpha_np, prm: dict, topk_idx_np=None):
+def gpu_build_tree(topk_renorm_np, alpha_np, prm: dict, topk_idx_np=None, d_max_seq_np=None):
     pt, al = to_dev(np.ascontiguousarray(topk_renorm_np, np.float32)), to_dev(np.ascontiguousarray(alpha_np, np.float32))
     B = pt.shape[0]
     i32 = lambda fill: torch.full((B, MAX_NODES), fill, device=DEV, dtype=torch.int32)
@@ -58,8 +58,9 @@ def gpu_build_tree(topk_renorm_np, alpha_np, prm: dict, topk_idx_np=None):
                cum_prob=torch.full((B, MAX_NODES), float("nan"), device=DEV, dtype=torch.float32),
                node_token=i32(-2))
     ti = None if topk_idx_np is None else to_dev(np.ascontiguousarray(topk_idx_np, np.int32))
+    dm = None if d_max_seq_np is None else to_dev(np.ascontiguousarray(d_max_seq_np, np.int32))
     sage.sage_build_tree(pt, al, sage.tree_params(**prm), out["n_nodes"], out["parent"], out["depth"], out["rank"],
-                         out["anc_mask"], out["cum_prob"], ti, out["node_token"] if ti is not None else None)
+                         out["anc_mask"], out["cum_prob"], ti, out["node_token"] if ti is not None else None, d_max_seq=dm)
     torch.cuda.synchronize()
     res = {key: v.cpu().numpy() for key, v in out.items()}
     res["anc_mask"] = res["anc_mask"].view(np.uint64)
@@ -114,3 +115,25 @@ def assert_attention_close(gpu64, ref64, n_nodes, tol):
         assert l2.max() <= tol, f"seq {b}: rel L2 {l2.max():.3e} > {tol}"
         assert mx.max() <= tol, f"seq {b}: rel max {mx.max():.3e} > {tol}"
     return worst
+
+
+def gpu_commit_path(Kt_np, Vt_np, Kc_np, Vc_np, kv_start, kv_len, kv_capacity, ts, hs, path_nodes, accept_len):
+    """Returns the caches after the commit and the advanced lengths (numpy)."""
+    Kt, Vt, Kc, Vc = (to_dev(a) for a in (Kt_np, Vt_np, Kc_np, Vc_np))
+    ks = to_dev(np.ascontiguousarray(kv_start, np.int64))
+    kl = to_dev(np.ascontiguousarray(kv_len, np.int32))
+    pn = to_dev(np.ascontiguousarray(path_nodes, np.int32))
+    al = to_dev(np.ascontiguousarray(accept_len, np.int32))
+    sage.sage_commit_path(Kt, Vt, Kc, Vc, ks, kl, int(kv_capacity), int(ts), int(hs), pn, al)
+    sage.sage_advance_kv_len(kl, al, int(kv_capacity))
+    torch.cuda.synchronize()
+    return to_host(Kc), to_host(Vc), kl.cpu().numpy()
+
+
+def gpu_update_history(accept_len, hist, count, d_max, lo, hi, d_floor, d_cap):
+    """hist/count/d_max are device tensors updated in place; returns the averages (numpy)."""
+    al = to_dev(np.ascontiguousarray(accept_len, np.int32))
+    avg = torch.zeros(al.shape[0], device=DEV, dtype=torch.float32)
+    sage.sage_update_history(al, hist, count, d_max, float(lo), float(hi), int(d_floor), int(d_cap), avg)
+    torch.cuda.synchronize()
+    return avg.cpu().numpy()

@@ -24,9 +24,10 @@ def declared_functions():
     return sorted(set(re.findall(r"\b(sage_[a-z_0-9]+)\s*\(", text)))
 
 
-def test_header_declares_the_four_calls():
+def test_header_declares_the_calls():
     names = declared_functions()
-    for need in ("sage_entropy_topk", "sage_build_tree", "sage_tree_attention", "sage_verify_accept"):
+    for need in ("sage_entropy_topk", "sage_build_tree", "sage_tree_attention", "sage_verify_accept",
+                 "sage_commit_path", "sage_advance_kv_len", "sage_update_history"):
         assert need in names
 
 
@@ -60,10 +61,10 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
     bad = [P(3, 8, 2, 10, 10, 65), P(3, 8, 2, 11, 10, 64), P(9, 8, 2, 10, 10, 64), P(3, 40, 2, 10, 10, 64),
            P(3, 8, 0, 10, 10, 64), P(3, 8, 2, 10, 9, 64)]
     for p in bad:
-        assert lib.sage_build_tree(one, one, null, 1, 10, ctypes.byref(p), one, one, one, one, one, null, null, null) == INVALID
+        assert lib.sage_build_tree(one, one, null, 1, 10, ctypes.byref(p), null, one, one, one, one, one, null, null, null) == INVALID
     ok = P(3, 8, 2, 10, 10, 64)
-    assert lib.sage_build_tree(one, one, null, 1, 10, ctypes.byref(ok), one, one, one, one, one, null, one, null) == INVALID
-    assert lib.sage_build_tree(one, one, null, 0, 10, ctypes.byref(ok), one, one, one, one, one, null, null, null) == 0
+    assert lib.sage_build_tree(one, one, null, 1, 10, ctypes.byref(ok), null, one, one, one, one, one, null, one, null) == INVALID
+    assert lib.sage_build_tree(one, one, null, 0, 10, ctypes.byref(ok), null, one, one, one, one, one, null, null, null) == 0
 
     lib.sage_entropy_topk.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_long,
                                       ctypes.c_int, ctypes.c_void_p, ctypes.c_int] + [ctypes.c_void_p] * 7 + \
@@ -92,3 +93,30 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
     assert lib.sage_tree_attention(*att(ts=1004)) == INVALID               # token rows must stay 16-byte aligned
     assert lib.sage_tree_attention(*att(wsb=1024)) == 3
     assert lib.sage_tree_attention(*att(B=0)) == 0
+    assert lib.sage_tree_attention(*att(ts=(1 << 24) + 8)) == 2            # 64 token rows must fit 32-bit byte offsets
+
+    lib.sage_commit_path.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int] * 4 + [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
+                                    ctypes.c_long, ctypes.c_long, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+    com = lambda **kw: [kw.get("kt", 256), 256, 256, 256, kw.get("dtype", 1), kw.get("B", 1), 8, kw.get("d", 128), 256, 256,
+                        kw.get("cap", 4096), kw.get("ts", 1024), 128, 256, 256, kw.get("pc", 9), None]
+    assert lib.sage_commit_path(*com(kt=None)) == INVALID
+    assert lib.sage_commit_path(*com(dtype=5)) == INVALID
+    assert lib.sage_commit_path(*com(d=4)) == INVALID                      # a head row must be whole 16-byte pieces
+    assert lib.sage_commit_path(*com(ts=1004)) == INVALID
+    assert lib.sage_commit_path(*com(pc=0)) == INVALID
+    assert lib.sage_commit_path(*com(pc=65)) == 2
+    assert lib.sage_commit_path(*com(B=0)) == 0
+    lib.sage_advance_kv_len.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+    assert lib.sage_advance_kv_len(None, 256, 1, 10, None) == INVALID
+    assert lib.sage_advance_kv_len(256, 256, 0, 10, None) == 0
+    lib.sage_update_history.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_float, ctypes.c_int,
+                                       ctypes.c_int] + [ctypes.c_void_p] * 5
+    his = lambda **kw: [256, kw.get("B", 1), kw.get("w", 10), kw.get("lo", 2.0), kw.get("hi", 3.0), kw.get("df", 3),
+                        kw.get("dc", 8), kw.get("hist", 256), 256, 256, None, None]
+    assert lib.sage_update_history(*his(w=0)) == INVALID
+    assert lib.sage_update_history(*his(w=65)) == INVALID
+    assert lib.sage_update_history(*his(lo=4.0)) == INVALID
+    assert lib.sage_update_history(*his(df=9)) == INVALID
+    assert lib.sage_update_history(*his(dc=32)) == INVALID
+    assert lib.sage_update_history(*his(hist=None)) == INVALID
+    assert lib.sage_update_history(*his(B=0)) == 0
