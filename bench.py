@@ -104,6 +104,7 @@ class Workload:
         else:
             scales = np.array([wl.scale_for_entropy(h) for h in wl.entropy_targets(name, self.slots * B)])
         self.draft, self.target = [], []
+        rows, betas = [], []
         for s in range(self.slots):
             z = torch.randn(B, V, generator=gen, device=dev, dtype=torch.float32)
             beta = torch.tensor(scales[s * B:(s + 1) * B], device=dev, dtype=torch.float32)[:, None]
@@ -113,11 +114,20 @@ class Workload:
                 pos = torch.randperm(V, generator=gen, device=dev)[:64]
                 row[:, pos] = -math.log(2.0) * torch.arange(64, device=dev, dtype=torch.float32)
                 beta = torch.ones_like(beta)
+            rows.append(row)
+            betas.append(beta)
+            self.draft.append(row.to(self.dtype).contiguous())
+            del z
+        # The tree verified with input set s was planned one step earlier from the draft row of set s-1 and carries
+        # that row's candidates as node tokens, so the target logits of set s are that row plus noise: confident
+        # (low-entropy) draft rows are then accepted deep, uncertain ones shallow.
+        for s in range(self.slots):
+            row, beta = rows[(s - 1) % self.slots], betas[(s - 1) % self.slots]
             noise = torch.randn(B, MAX_NODES, V, generator=gen, device=dev, dtype=torch.float32)
             tgt = (row[:, None, :] + 0.5 * beta[:, None, :] * noise).reshape(B * MAX_NODES, V)
-            self.draft.append(row.to(self.dtype).contiguous())
             self.target.append(tgt.to(self.dtype).contiguous())
-            del z, noise, tgt, row
+            del noise, tgt
+        del rows, betas
 
         f32 = lambda *s: torch.zeros(*s, device=dev, dtype=torch.float32)
         i32 = lambda *s: torch.zeros(*s, device=dev, dtype=torch.int32)
@@ -393,6 +403,117 @@ def long_kv_attention(names, launches=48):
     return out
 
 
+def closed_loop(name="c2", steps=512):
+    """The step with its loop closed on the device: after acceptance the path's K/V rows are committed to the
+    cache, the sequence length advances and the acceptance history adapts the maximum depth that the next tree may
+    reach (Alg. 1 Phase 3; Sec. 3.3 adaptive history tracking).  One input-set cycle is captured as a HIP graph whose
+    replays carry the state (cache, lengths, history, trees) forward; the final state of `steps` replayed steps is
+    checked against the same number of eager steps from the same start."""
+    import torch
+    w = Workload(name, None)
+    sg, dev = w.sage, "cuda:0"
+    B, Hkv, d = w.B, w.Hkv, w.d
+    cycle = w.slots if w.slots % 2 == 0 else 2 * w.slots
+    steps = max(cycle, steps // cycle * cycle)
+    cap = w.max_len + steps * w.path_cap                      # positions per sequence, enough for every step
+    Kc = torch.zeros(B * cap, Hkv, d, device=dev, dtype=w.dtype)
+    Vc = torch.zeros_like(Kc)
+    kv0 = w.kv_start.cpu().numpy()
+    for b in range(B):
+        L = int(w.kv_lens[b])
+        Kc[b * cap:b * cap + L] = w.Kc[0][0][kv0[b]:kv0[b] + L]
+        Vc[b * cap:b * cap + L] = w.Vc[0][0][kv0[b]:kv0[b] + L]
+    kv_start = torch.arange(B, device=dev, dtype=torch.int64) * cap
+    kv_len0 = w.kv_len.clone()
+    kv_len = kv_len0.clone()
+    window, lo, hi = 10, 2.0, 3.0                             # Sec. 5 "Implementation details"
+    hist = torch.zeros(B, window, device=dev, dtype=torch.int32)
+    count = torch.zeros(B, device=dev, dtype=torch.int32)
+    d_max = torch.full((B,), w.tree_prm["d_max"], device=dev, dtype=torch.int32)
+    code = sg.F32 if w.dtype == torch.float32 else sg.BF16
+    ws3 = torch.empty(sg.sage_tree_attention_workspace_bytes(code, B, w.Hq, Hkv, d, cap), device=dev, dtype=torch.uint8)
+    tree0 = [{k: v.clone() for k, v in t.items()} for t in w.tree]
+    acc_sum = torch.zeros(B, device=dev, dtype=torch.int32)
+
+    def prep(stream):
+        c = dict(a1=[sg.prepare("sage_entropy_topk", w.draft[s], w.k, w.H, w.idx, w.prob, w.renorm, w.Hk, w.alpha, w.ws1,
+                                stream=stream) for s in range(w.slots)], a2=[], a3=[], a1t=[], a4=[], commit=[])
+        for cur in range(2):
+            t, nxt = w.tree[cur], w.tree[cur ^ 1]
+            c["a2"].append(sg.prepare("sage_build_tree", w.renorm, w.alpha, w.prm, nxt["n_nodes"], nxt["parent"], nxt["depth"],
+                                      nxt["rank"], nxt["anc_mask"], None, w.idx, nxt["node_token"], stream=stream,
+                                      d_max_seq=d_max))
+            c["a3"].append([sg.prepare("sage_tree_attention", w.Q[s], Kc, Vc, w.Kt[s], w.Vt[s], w.O, kv_start, kv_len, cap,
+                                       Hkv * d, d, t["anc_mask"], t["n_nodes"], w.scale, ws3, stream=stream)
+                            for s in range(w.slots)])
+            c["a1t"].append([sg.prepare("sage_entropy_topk", w.target[s], 1, w.tH, w.tgt_idx, None, None, w.tHk, w.talpha,
+                                        w.ws1t, t["n_nodes"], MAX_NODES, stream=stream) for s in range(w.slots)])
+            c["a4"].append(sg.prepare("sage_verify_accept", t["node_token"], w.tgt_idx, t["parent"], t["depth"],
+                                      t["anc_mask"], t["n_nodes"], w.path_cap, w.acc_len, w.best, w.path, w.out_tok,
+                                      stream=stream))
+        c["commit"] = [sg.prepare("sage_commit_path", w.Kt[s], w.Vt[s], Kc, Vc, kv_start, kv_len, cap, Hkv * d, d, w.path,
+                                  w.acc_len, stream=stream) for s in range(w.slots)]
+        c["advance"] = sg.prepare("sage_advance_kv_len", kv_len, w.acc_len, cap, stream=stream)
+        c["history"] = sg.prepare("sage_update_history", w.acc_len, hist, count, d_max, lo, hi, w.tree_prm["d_min"],
+                                  w.tree_prm["d_max"], None, stream=stream)
+        return c
+
+    state = dict(cur=0, step=0)
+
+    def step(c):
+        s, cur = state["step"] % w.slots, state["cur"]
+        c["a1"][s](); c["a2"][cur](); c["a3"][cur][s](); c["a1t"][cur][s](); c["a4"][cur]()
+        c["commit"][s](); c["advance"](); c["history"]()
+        acc_sum.add_(w.acc_len)
+        state["cur"] ^= 1
+        state["step"] += 1
+
+    def reset():
+        kv_len.copy_(kv_len0); hist.zero_(); count.zero_(); d_max.fill_(w.tree_prm["d_max"]); acc_sum.zero_()
+        for t, t0 in zip(w.tree, tree0):
+            for k in t:
+                t[k].copy_(t0[k])
+        state.update(cur=0, step=0)
+
+    def snapshot_state():
+        grown = int((kv_len - kv_len0).max().item())
+        rows = torch.cat([Kc[b * cap + int(w.kv_lens[b]):b * cap + int(w.kv_lens[b]) + grown] for b in range(B)])
+        return [x.clone() for x in (kv_len, hist, count, d_max, acc_sum, w.acc_len, w.O, rows)]
+
+    eager = prep(None)
+    reset()
+    for _ in range(steps):
+        step(eager)
+    torch.cuda.synchronize()
+    want = snapshot_state()
+    reset()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graphed = prep(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for _ in range(cycle):
+            step(graphed)
+    reset()                                                    # capture does not execute, but keep the start exact
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps // cycle):
+        graph.replay()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    got = snapshot_state()
+    verified = all(torch.equal(a, b) for a, b in zip(want, got))
+    out = dict(workload=name, steps=steps, steps_per_s=steps / wall, ms_per_step=wall * 1e3 / steps,
+               calls_per_step="entropy_topk, build_tree (per-sequence depth), tree_attention, entropy_topk (k=1), "
+                              "verify_accept, commit_path, advance_kv_len, update_history",
+               kv_len_start=[int(x) for x in w.kv_lens], kv_len_end=[int(x) for x in kv_len.cpu().numpy()],
+               mean_accept_len=float(acc_sum.sum().item()) / (steps * B), d_max_end=[int(x) for x in d_max.cpu().numpy()],
+               replay_equals_eager=bool(verified))
+    del w
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -453,6 +574,7 @@ def main():
     torch.cuda.empty_cache()
     if not args.no_extras and args.workload == "c2":
         result["attention_long_kv"] = long_kv_attention(["c3", "c4", "c5"])
+        result["closed_loop"] = closed_loop("c2")
     print(json.dumps(result))
 
 
