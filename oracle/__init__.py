@@ -191,3 +191,31 @@ def update_history(accept_len, hist, count, d_max, window: int, lo: float, hi: f
     if rc:
         raise ValueError(f"oracle_update_history status {rc}")
     return avg
+
+
+def lm_head_topk(hidden: np.ndarray, weight: np.ndarray, k: int, n_valid=None, rows_per_group: int = 1,
+                 return_logits: bool = False):
+    """O7: O1 on logits = hidden @ weight.T evaluated in fp64 (hidden [rows, dim], weight [vocab, dim])."""
+    assert hidden.ndim == 2 and weight.ndim == 2 and hidden.shape[1] == weight.shape[1]
+    assert hidden.strides[1] == hidden.itemsize and weight.strides[1] == weight.itemsize
+    code = _dtype_code(hidden)
+    assert _dtype_code(weight) == code
+    rows, dim = hidden.shape
+    vocab = weight.shape[0]
+    out = dict(
+        entropy=np.full(rows, np.nan), topk_idx=np.full((rows, k), -1, np.int32),
+        topk_prob=np.full((rows, k), np.nan), topk_renorm=np.full((rows, k), np.nan),
+        topk_entropy=np.full(rows, np.nan), alpha=np.full(rows, np.nan))
+    logits = np.full((rows, vocab), np.nan) if return_logits else None
+    if n_valid is not None:
+        n_valid = np.ascontiguousarray(n_valid, np.int32)
+    rc = lib().oracle_lm_head_topk(
+        _p(hidden), _p(weight), code, rows, dim, vocab, ctypes.c_long(hidden.strides[0] // hidden.itemsize),
+        ctypes.c_long(weight.strides[0] // weight.itemsize), k, _p(n_valid), rows_per_group,
+        _p(out["entropy"]), _p(out["topk_idx"]), _p(out["topk_prob"]), _p(out["topk_renorm"]),
+        _p(out["topk_entropy"]), _p(out["alpha"]), _p(logits))
+    if rc:
+        raise ValueError(f"oracle_lm_head_topk status {rc}")
+    if return_logits:
+        out["logits"] = logits
+    return out

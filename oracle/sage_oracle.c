@@ -25,6 +25,10 @@
  *                            to the KV cache and the sequence length advances.
  *   O6 oracle_update_history Sec. 3.3 "Adaptive History Tracking" with the window
  *                            and thresholds of Sec. 5 "Implementation details".
+ *   O7 oracle_lm_head_topk   O1 applied to logits that are not stored but defined
+ *                            as hidden . weight^T (the target's output projection,
+ *                            Eq. 1 / Sec. 2.2: the distribution the greedy token of
+ *                            Def. 4.1 is taken from).
  *
  * Arithmetic: O1 and O3 are plain definitions and are evaluated in fp64 from
  * the exact input bits (bf16/fp32 widened exactly), two-pass softmax, no
@@ -41,7 +45,8 @@
  * enumeration of the membership rule for O2, textbook causal attention for O3
  * on chain trees, brute-force path enumeration for O4; for O5 the attention of
  * a lone root over the extended cache must equal the tree attention of the
- * deepest accepted node before the commit (O3 is the independent witness); for
+ * deepest accepted node before the commit (O3 is the independent witness); O7
+ * against a library matrix product followed by O1, and closed forms; for
  * O6 hand-computed depth sequences for constant and step-change acceptance
  * lengths and a full-history recomputation of the moving average.
  * parity unpinned: the integerisation of Eq. (10)/(11)/(12) in O2 (the paper
@@ -443,6 +448,71 @@ int oracle_update_history(const int* accept_len, int B, int window, float lo, fl
         if (dm < d_floor) dm = d_floor;
         if (dm > d_cap) dm = d_cap;
         d_max[b] = dm;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ O7 */
+
+/*
+ * O1 on logits x[r][v] = sum_c hidden[r][c] * weight[v][c], evaluated in fp64
+ * from the exact stored bits (hidden [rows, dim], weight [vocab, dim], both
+ * row-major with the given row strides, same storage type).  The logits are
+ * never rounded to a storage type: the statistics and the order are those of
+ * the fp64 products.  Row groups and n_valid as in O1.
+ */
+int oracle_lm_head_topk(const void* hidden, const void* weight, int dtype, int rows, int dim, int vocab,
+                        long hidden_stride, long weight_stride, int k, const int* n_valid, int rows_per_group,
+                        double* entropy, int* topk_idx, double* topk_prob, double* topk_renorm,
+                        double* topk_entropy, double* alpha, double* logits_out) {
+    if (!hidden || !weight || rows < 0 || dim < 1 || vocab < 1 || k < 1 || k > vocab) return 1;
+    for (int r = 0; r < rows; ++r) {
+        if (n_valid) {
+            int g = r / rows_per_group, j = r % rows_per_group;
+            if (j >= n_valid[g]) continue;
+        }
+        val_idx* s = (val_idx*)malloc(sizeof(val_idx) * (size_t)vocab);
+        double* h = (double*)malloc(sizeof(double) * (size_t)dim);
+        if (!s || !h) { free(s); free(h); return 4; }
+        for (int c = 0; c < dim; ++c) h[c] = load_elem(hidden, dtype, (long)r * hidden_stride + c);
+#pragma omp parallel for schedule(static)
+        for (int v = 0; v < vocab; ++v) {
+            double x = 0.0;
+            for (int c = 0; c < dim; ++c) x += h[c] * load_elem(weight, dtype, (long)v * weight_stride + c);
+            s[v].v = x;
+            s[v].i = v;
+        }
+        if (logits_out)
+            for (int v = 0; v < vocab; ++v) logits_out[(long)r * vocab + v] = s[v].v;
+        double m = -INFINITY;
+        for (int v = 0; v < vocab; ++v) if (s[v].v > m) m = s[v].v;
+        double Z = 0.0;
+        for (int v = 0; v < vocab; ++v) Z += exp(s[v].v - m);
+        double H = 0.0;
+        for (int v = 0; v < vocab; ++v) {
+            double p = exp(s[v].v - m) / Z;
+            if (p > 0.0) H -= p * log(p);
+        }
+        entropy[r] = H;
+        qsort(s, (size_t)vocab, sizeof(val_idx), cmp_desc_then_index);
+        double mass = 0.0;
+        for (int j = 0; j < k; ++j) {
+            double p = exp(s[j].v - m) / Z;
+            topk_idx[(long)r * k + j] = s[j].i;
+            topk_prob[(long)r * k + j] = p;
+            mass += p;
+        }
+        double Hk = 0.0;
+        for (int j = 0; j < k; ++j) {
+            double q = topk_prob[(long)r * k + j] / mass;
+            topk_renorm[(long)r * k + j] = q;
+            if (q > 0.0) Hk -= q * log(q);
+        }
+        topk_entropy[r] = Hk;
+        double a = (k == 1) ? 1.0 : 1.0 - Hk / log((double)k);
+        alpha[r] = a < 0.0 ? 0.0 : (a > 1.0 ? 1.0 : a);
+        free(s);
+        free(h);
     }
     return 0;
 }
