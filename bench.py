@@ -514,6 +514,43 @@ def closed_loop(name="c2", steps=512):
     return out
 
 
+def lm_head_projection(rows=64, dim=8192, vocab=152064, launches=12):
+    """The target's greedy token and softmax statistics taken straight from the output projection at the 72B shape
+    (sage_lm_head_topk): the [vocab, dim] weight matrix (2.5 GB) is streamed once, the 64 x vocab logits never exist
+    in memory.  Weights ~ N(0, 9/dim), hidden rows ~ N(0,1): logits ~ N(0, 9)."""
+    import torch
+    from paper_2602_00523_amd import sage
+    dev = "cuda:0"
+    g = torch.Generator(device=dev)
+    g.manual_seed(523007)
+    W = (torch.randn(vocab, dim, generator=g, device=dev, dtype=torch.float32) * (3.0 / math.sqrt(dim))).to(torch.bfloat16)
+    H = torch.randn(rows, dim, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    ent = torch.zeros(rows, device=dev)
+    idx = torch.zeros(rows, 1, device=dev, dtype=torch.int32)
+    ws = torch.empty(sage.sage_lm_head_topk_workspace_bytes(rows, vocab), device=dev, dtype=torch.uint8)
+    call = sage.prepare("sage_lm_head_topk", H, W, 1, ent, idx, None, None, None, None, ws)
+    for _ in range(3):
+        call()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * launches)]
+    for i in range(launches):
+        ev[2 * i].record()
+        call()
+        ev[2 * i + 1].record()
+    torch.cuda.synchronize()
+    t = [ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(launches)]
+    avg_ms = sum(t) / len(t)
+    byts = 2.0 * vocab * dim + 2.0 * rows * dim
+    ref = (H.float() @ W.float().T).argmax(1)
+    out = dict(rows=rows, dim=dim, vocab=vocab, avg_us=avg_ms * 1e3, min_us=min(t) * 1e3,
+               algorithmic_bytes=byts, hbm_GBps=byts / (avg_ms * 1e-3) / 1e9, hbm_frac=byts / (avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+               mfma_TFLOPs=2.0 * rows * dim * vocab / (avg_ms * 1e-3) / 1e12,
+               argmax_agrees_with_fp32_matmul=float((ref == idx[:, 0].long()).float().mean().item()))
+    del W, H
+    torch.cuda.empty_cache()
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -575,6 +612,7 @@ def main():
     if not args.no_extras and args.workload == "c2":
         result["attention_long_kv"] = long_kv_attention(["c3", "c4", "c5"])
         result["closed_loop"] = closed_loop("c2")
+        result["lm_head_projection"] = lm_head_projection()
     print(json.dumps(result))
 
 

@@ -203,6 +203,28 @@ int sage_advance_kv_len(int* kv_len, const int* accept_len, int B, int kv_capaci
 int sage_update_history(const int* accept_len, int B, int window, float lo, float hi, int d_floor, int d_cap,
                         int* hist, int* count, int* d_max, float* avg_out, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * sage_lm_head_topk -- sage_entropy_topk on logits that are never stored: row r of the
+ * logits is hidden[r, :] . weight[v, :] over v < vocab (the target's output projection,
+ * whose softmax is the distribution of Eq. 1 and whose argmax is the greedy token of
+ * Def. 4.1).  Products are accumulated in fp32 and not rounded to a storage type; outputs,
+ * row groups and n_valid exactly as in sage_entropy_topk.
+ *
+ * hidden [rows, dim], weight [vocab, dim], row-major with row strides in elements, rows
+ * 16-byte aligned.  This build: bf16, k = 1, dim a multiple of 128, row strides <= 2^24
+ * elements, vocab <= 655360 (others: UNSUPPORTED).  The weight matrix is
+ * read once per block of 64 rows.
+ * workspace: sage_lm_head_topk_workspace_bytes(rows, vocab) bytes, 16-byte aligned.
+ * Errors: INVALID_ARG (null pointers, sizes, strides, alignment), UNSUPPORTED,
+ * WORKSPACE_TOO_SMALL.
+ */
+size_t sage_lm_head_topk_workspace_bytes(int rows, int vocab);
+int sage_lm_head_topk(const void* hidden, const void* weight, int dtype, int rows, int dim, int vocab,
+                      long hidden_stride, long weight_stride, int k, const int* n_valid, int rows_per_group,
+                      float* entropy, int* topk_idx, float* topk_prob, float* topk_renorm,
+                      float* topk_entropy, float* alpha,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
 /* Library build identification (host): returns a static string naming the target architecture. */
 const char* sage_build_info(void);
 

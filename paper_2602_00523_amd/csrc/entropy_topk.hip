@@ -10,6 +10,9 @@
 // Pass 2 (one wave per row) combines the slice statistics by log-sum-exp, merges the sorted per-slice lists with
 // a k-round tournament over the list heads (lists staged in LDS), and evaluates Eq. 7-9 on the k winners.
 #include "sage_internal.h"
+#include "topk_common.h"
+
+using namespace sage::topk;
 
 namespace {
 
@@ -19,31 +22,6 @@ constexpr int UNIT = 64 * EPT;           // logits per wave
 constexpr int WAVES = THREADS / 64;
 constexpr int MERGE_LDS_KEYS = 6144;     // lists are staged in LDS when they fit (48 KB)
 constexpr int MAX_OWN = 16;              // lists per lane in pass 2: up to 1024 slices = 1M logits
-
-struct UnitStats { float m, Z, T, pad; };
-
-// Order-preserving map float -> uint32 (larger float -> larger code); -0 is folded into +0 so that equal
-// values compare equal before the index tie-break.
-__device__ __forceinline__ uint32_t sortable(float v) {
-    uint32_t u = __float_as_uint(v);
-    if (u == 0x80000000u) u = 0;
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-__device__ __forceinline__ float unsortable(uint32_t s) {
-    uint32_t u = (s & 0x80000000u) ? (s & 0x7FFFFFFFu) : ~s;
-    return __uint_as_float(u);
-}
-// key: high word = value code, low word = ~index, so a larger key is a better candidate; 0 = no candidate.
-struct Key { uint32_t hi, lo; };
-__device__ __forceinline__ Key make_key(float v, int idx) { return Key{sortable(v), 0xFFFFFFFFu - static_cast<uint32_t>(idx)}; }
-__device__ __forceinline__ bool key_less(Key a, Key b) { return a.hi < b.hi || (a.hi == b.hi && a.lo < b.lo); }
-__device__ __forceinline__ bool key_equal(Key a, Key b) { return a.hi == b.hi && a.lo == b.lo; }
-__device__ __forceinline__ bool key_none(Key a) { return (a.hi | a.lo) == 0; }
-__device__ __forceinline__ Key key_max(Key a, Key b) { return key_less(a, b) ? b : a; }
-__device__ __forceinline__ int key_index(Key k) { return static_cast<int>(0xFFFFFFFFu - k.lo); }
-__device__ __forceinline__ float key_value(Key k) { return unsortable(k.hi); }
-__device__ __forceinline__ uint64_t key_pack(Key k) { return (static_cast<uint64_t>(k.hi) << 32) | k.lo; }
-__device__ __forceinline__ Key key_unpack(uint64_t v) { return Key{static_cast<uint32_t>(v >> 32), static_cast<uint32_t>(v)}; }
 
 // Wave-wide maximum, result in every lane: four rotations inside each row of 16 lanes, then the 16-lane and
 // 32-lane swaps combine the four rows.  A key is reduced in two passes: the value code first, then the index
@@ -389,6 +367,24 @@ inline size_t stats_bytes(int rows, int vocab) {
 
 }  // namespace
 
+namespace sage {
+
+int topk_max_units() { return 64 * MAX_OWN; }
+
+// Pass 2 for `rows` rows whose `nunits` slices each left UnitStats and k sorted keys in stats / keys ([row][unit]).
+void topk_merge(int rows, int k, const int* n_valid, int rows_per_group, int nunits, const UnitStats* stats,
+                const uint64_t* keys, float* entropy, int* topk_idx, float* topk_prob, float* topk_renorm,
+                float* topk_entropy, float* alpha, hipStream_t s) {
+    if (nunits <= 256)
+        hipLaunchKernelGGL(merge_kernel<4>, dim3(rows), dim3(THREADS), 0, s, k, n_valid, rows_per_group, nunits, stats, keys,
+                           entropy, topk_idx, topk_prob, topk_renorm, topk_entropy, alpha);
+    else
+        hipLaunchKernelGGL(merge_kernel<MAX_OWN>, dim3(rows), dim3(THREADS), 0, s, k, n_valid, rows_per_group, nunits, stats,
+                           keys, entropy, topk_idx, topk_prob, topk_renorm, topk_entropy, alpha);
+}
+
+}  // namespace sage
+
 extern "C" size_t sage_entropy_topk_workspace_bytes(int rows, int vocab, int k) {
     if (rows < 0 || vocab < 1 || k < 1) return 0;
     return stats_bytes(rows, vocab) + static_cast<size_t>(rows) * num_units(vocab) * k * sizeof(uint64_t) + 256;
@@ -432,11 +428,7 @@ extern "C" int sage_entropy_topk(const void* logits, int dtype, int rows, int vo
                                vocab, row_stride, k, n_valid, rows_per_group, nunits, stats, keys);
     }
     if (hipGetLastError() != hipSuccess) return SAGE_LAUNCH_FAILED;
-    if (nunits <= 256)
-        hipLaunchKernelGGL(merge_kernel<4>, dim3(rows), dim3(THREADS), 0, s, k, n_valid, rows_per_group, nunits, stats, keys,
-                           entropy, topk_idx, topk_prob, topk_renorm, topk_entropy, alpha);
-    else
-        hipLaunchKernelGGL(merge_kernel<MAX_OWN>, dim3(rows), dim3(THREADS), 0, s, k, n_valid, rows_per_group, nunits, stats,
-                           keys, entropy, topk_idx, topk_prob, topk_renorm, topk_entropy, alpha);
+    sage::topk_merge(rows, k, n_valid, rows_per_group, nunits, stats, keys, entropy, topk_idx, topk_prob, topk_renorm,
+                     topk_entropy, alpha, s);
     return sage::launch_status();
 }

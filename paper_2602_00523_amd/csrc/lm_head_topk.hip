@@ -1,0 +1,334 @@
+// sage_lm_head_topk: the target's greedy token and softmax statistics per row (Sec. 2.2 / Def. 4.1, Eq. 1) taken
+// straight from the output projection, logits = hidden . weight^T, so that the rows x vocabulary logits never
+// exist in memory.  HBM-bound: the weight matrix ([vocab, dim] bf16, 2.5 GB at the 72B shape) is streamed exactly
+// once per block of 64 rows; the hidden rows (1 MB) are read once per workgroup from L2.
+//
+// A workgroup of 4 waves owns T consecutive 64-row vocabulary tiles and keeps the logits of ALL of them in
+// registers (T accumulators of 32 x 32 per wave; with one wave per SIMD a wave has 512 registers).  The loop runs
+// over chunks of 128 hidden elements on the outside and the T tiles on the inside, so a hidden chunk is fetched once
+// and its MFMA operands stay in registers for T steps, while the weight tiles (64 rows x 256 B) stream from global
+// memory straight into LDS through a 5-stage ring, four steps ahead of the MFMAs, in the same padded layout as the
+// attention kernel's K tiles (conflict-free 16-byte reads with compile-time offsets).  Wave (vt, rt) accumulates
+// logits^T[32 vocabulary rows of half vt][32 hidden rows of half rt] with v_mfma_f32_32x32x16_bf16 (A = weight rows,
+// B = hidden rows, both as stored), so a lane owns one hidden row and 16 vocabulary entries of it per tile.  After
+// the last chunk every lane folds its 16 T logits into statistics of its row (maximum m, Z = sum exp(x - m),
+// T = sum exp(x - m)(m - x), best (value, index) key); the four partial statistics of a row are combined through LDS
+// and written as one "slice" per workgroup, in the format of the stored-logits first pass, whose second pass
+// finishes the row.
+#include <type_traits>
+
+#include "sage_internal.h"
+#include "topk_common.h"
+
+using namespace sage::topk;
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
+#define LDS_AS __attribute__((address_space(3)))
+
+constexpr int TILE_V = 64;               // vocabulary rows per tile
+constexpr int TILE_R = 64;               // hidden rows per launch block
+constexpr int CHUNK = 128;               // hidden elements per stage
+constexpr int ROW_B = CHUNK * 2;         // bytes of one row of a stage
+constexpr int THREADS = 256;
+constexpr int STAGES = 5;              // weight ring
+// stage layout: row t at (t % 16) * GROUP + (t / 16) * ROW_B; a group is the 1 KB one wave-level LDS-direct load
+// writes (rows t, t+16, t+32, t+48) plus 16 bytes, which staggers consecutive rows across the banks
+constexpr int GROUP = 4 * ROW_B + 16;
+constexpr int STAGE_B = 16 * GROUP;
+constexpr int LOADS_PER_TILE = TILE_V * ROW_B / (THREADS * 16);       // 16-byte loads per thread and tile
+
+struct Params {
+    const unsigned char* hidden; const unsigned char* weight;
+    long hidden_stride_b, weight_stride_b;
+    int rows, dim, vocab, k, nunits, ntiles;
+    UnitStats* stats; uint64_t* keys;    // [rows][nunits]
+};
+
+template <int N> __device__ __forceinline__ void wait_vm() {
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+// bare barrier with wavefront-scope fences (a workgroup-scope release would wait for every load in flight)
+__device__ __forceinline__ void stage_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+template <int T>
+__global__ __launch_bounds__(THREADS) void lm_head_kernel(const Params prm) {
+    static_assert(T % STAGES == 0, "the ring position of a step must be a compile-time constant");
+    __shared__ __align__(1024) unsigned char sW0[STAGE_B];
+    __shared__ __align__(1024) unsigned char sW1[STAGE_B];
+    __shared__ __align__(1024) unsigned char sW2[STAGE_B];
+    __shared__ __align__(1024) unsigned char sW3[STAGE_B];
+    __shared__ __align__(1024) unsigned char sW4[STAGE_B];
+    __shared__ __align__(1024) unsigned char sH0[STAGE_B];
+    __shared__ __align__(1024) unsigned char sH1[STAGE_B];
+    __shared__ float s_part[TILE_R][4][3];                   // per hidden row: 4 partial (m, Z, T)
+    __shared__ uint64_t s_key[TILE_R][4];
+#define SW(i) ((i) == 0 ? sW0 : (i) == 1 ? sW1 : (i) == 2 ? sW2 : (i) == 3 ? sW3 : sW4)
+#define SH(i) ((i) == 0 ? sH0 : sH1)
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int r32 = lane & 31, half = lane >> 5;
+    const int vt = wave & 1, rt = wave >> 1;
+    const int unit = blockIdx.x;
+    const int row0 = blockIdx.y * TILE_R;                    // first hidden row of this launch block
+    // this unit's tiles: an even share of the vocabulary, at most T; missing ones are phantom steps that re-read one
+    // row (an L2 hit) and whose logits are masked, so that every unit runs the same step sequence
+    const int tile_begin = static_cast<int>(static_cast<long>(unit) * prm.ntiles / prm.nunits);
+    const int tile_end = static_cast<int>(static_cast<long>(unit + 1) * prm.ntiles / prm.nunits);
+    const int v_end = min(prm.vocab, tile_end * TILE_V);     // one past this unit's last vocabulary row
+    const int nchunk = prm.dim / CHUNK;
+    const int nsteps = nchunk * T;
+
+    // ---- loader: instruction i of wave w copies rows r, r+16, r+32, r+48 (r = 4w + i) of a 64-row tile: lane l fills
+    // chunk l%16 of row r + 16 (l/16).  Vocabulary rows past the end (the last unit's missing tiles, a partial last
+    // tile) and hidden rows past the end re-read the last valid row; their results are masked or never written.
+    const int ld_row = (lane >> 4) * 16 + wave * 4;
+    const unsigned ld_chunk_b = (lane & 15) * 16;
+    unsigned h_off[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int hr = min(row0 + ld_row + i, prm.rows - 1);
+        h_off[i] = static_cast<unsigned>(hr - row0) * static_cast<unsigned>(prm.hidden_stride_b) + ld_chunk_b;
+    }
+    const unsigned char* h_base = prm.hidden + static_cast<long>(row0) * prm.hidden_stride_b;
+    const unsigned char* w_base = prm.weight + static_cast<long>(tile_begin) * TILE_V * prm.weight_stride_b;
+    const int rows_mine = v_end - tile_begin * TILE_V;       // vocabulary rows of this unit (>= 1)
+    const int full_tiles = rows_mine / TILE_V;               // tiles that need no clamping
+    // per-lane pointers into the first tile / first chunk; a step adds one wave-uniform offset to them.  (The offset is
+    // made opaque to the compiler, which would otherwise keep a separate address pair per tile and load alive across
+    // the whole loop: 8 registers instead of 8 T.)
+    const unsigned char* w_ptr[4];
+    const unsigned char* h_ptr[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        w_ptr[i] = w_base + static_cast<long>(ld_row + i) * prm.weight_stride_b + ld_chunk_b;
+        h_ptr[i] = h_base + h_off[i];
+    }
+
+    auto issue_w = [&](int kc, int t, auto stc) __attribute__((always_inline)) {
+        constexpr int ST = decltype(stc)::value;
+        LDS_AS unsigned char* dst = (LDS_AS unsigned char*)(&SW(ST)[wave * 4 * GROUP]);
+        if (t < full_tiles) {
+            long off = static_cast<long>(t) * TILE_V * prm.weight_stride_b + static_cast<long>(kc) * ROW_B;
+            asm volatile("" : "+s"(off));
+#pragma unroll
+            for (int i = 0; i < 4; ++i) __builtin_amdgcn_global_load_lds(w_ptr[i] + off, dst + i * GROUP, 16, 0, 0);
+        } else {
+            const unsigned char* wb = w_base + static_cast<long>(kc) * ROW_B;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const long r = min(t * TILE_V + ld_row + i, rows_mine - 1);
+                __builtin_amdgcn_global_load_lds(wb + r * prm.weight_stride_b + ld_chunk_b, dst + i * GROUP, 16, 0, 0);
+            }
+        }
+    };
+    auto issue_h = [&](int kc, auto slotc) __attribute__((always_inline)) {
+        constexpr int SL = decltype(slotc)::value;
+        LDS_AS unsigned char* dst = (LDS_AS unsigned char*)(&SH(SL)[wave * 4 * GROUP]);
+        long off = static_cast<long>(kc) * ROW_B;
+        asm volatile("" : "+s"(off));
+#pragma unroll
+        for (int i = 0; i < 4; ++i) __builtin_amdgcn_global_load_lds(h_ptr[i] + off, dst + i * GROUP, 16, 0, 0);
+    };
+
+    // ---- per-lane read offsets: fragment kk of row r32 of this wave's half: chunk 2kk + half
+    const int w_lane = (r32 & 15) * GROUP + (2 * vt + (r32 >> 4)) * ROW_B + half * 16;
+    const int h_lane = (r32 & 15) * GROUP + (2 * rt + (r32 >> 4)) * ROW_B + half * 16;
+
+    f32x16 acc[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+    bf16x8 hb_frag[8];                                       // this wave's hidden rows of the current chunk (B operands)
+
+    // one hidden chunk: T steps, step t consumes weight stage t % STAGES
+    auto chunk = [&](int kc, auto slotc) __attribute__((always_inline)) {
+        constexpr int SL = decltype(slotc)::value;
+        auto step = [&](auto tc) __attribute__((always_inline)) {
+            constexpr int t = decltype(tc)::value;
+            constexpr int ST = t % STAGES;
+            const int s = kc * T + t;
+            // this thread's loads of step s have landed; younger ones may stay in flight: the weight tiles of up to
+            // three steps and, during steps 1-4 of a chunk, the next hidden chunk (requested in step 0)
+            constexpr int HX = (t >= 1 && t <= 4) ? LOADS_PER_TILE : 0;
+            if (s + 3 < nsteps) {
+                if (HX && kc + 1 < nchunk) wait_vm<3 * LOADS_PER_TILE + HX>();
+                else wait_vm<3 * LOADS_PER_TILE>();
+            } else if (s + 2 < nsteps) wait_vm<2 * LOADS_PER_TILE>();
+            else if (s + 1 < nsteps) wait_vm<LOADS_PER_TILE>();
+            else wait_vm<0>();
+            stage_barrier();                                 // ... for every wave, and the stage read last step is free
+            if (s + 4 < nsteps) {
+                constexpr int t4 = (t + 4) % T;
+                issue_w(kc + (t + 4) / T, t4, std::integral_constant<int, (ST + 4) % STAGES>{});
+            }
+            if (t == 0) {
+                if (kc + 1 < nchunk) issue_h(kc + 1, std::integral_constant<int, SL ^ 1>{});
+                const lds_byte* hst = (const lds_byte*)(SH(SL)) + h_lane;
+#pragma unroll
+                for (int kk = 0; kk < 8; ++kk) hb_frag[kk] = __builtin_bit_cast(bf16x8, *(const LDS_AS uint4*)(hst + kk * 32));
+            }
+            const lds_byte* wst = (const lds_byte*)(SW(ST)) + w_lane;
+            bf16x8 a[8];
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) a[kk] = __builtin_bit_cast(bf16x8, *(const LDS_AS uint4*)(wst + kk * 32));
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk], hb_frag[kk], acc[t], 0, 0, 0);
+        };
+        [&]<int... Is>(std::integer_sequence<int, Is...>) __attribute__((always_inline)) {
+            (step(std::integral_constant<int, Is>{}), ...);
+        }(std::make_integer_sequence<int, T>{});
+    };
+
+    issue_h(0, std::integral_constant<int, 0>{});
+    if (0 < nsteps) issue_w(0, 0, std::integral_constant<int, 0>{});
+    if (1 < nsteps) issue_w(1 / T, 1 % T, std::integral_constant<int, 1>{});
+    if (2 < nsteps) issue_w(2 / T, 2 % T, std::integral_constant<int, 2>{});
+    if (3 < nsteps) issue_w(3 / T, 3 % T, std::integral_constant<int, 3>{});
+    for (int kc = 0; kc < nchunk; kc += 2) {
+        chunk(kc, std::integral_constant<int, 0>{});
+        if (kc + 1 < nchunk) chunk(kc + 1, std::integral_constant<int, 1>{});
+    }
+
+    // ---- fold the logits into softmax statistics and the best candidate of this lane's hidden row
+    float m_run = -INFINITY, Z = 0.f, Tm = 0.f;
+    Key best = Key{0, 0};
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        // vocabulary index of accumulator register i: tile*64 + 32 vt + 8 (i/4) + 4 half + i%4
+        const int v0 = (tile_begin + t) * TILE_V + 32 * vt + 4 * half;
+        float x[16];
+        float tmax = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int v = v0 + 8 * (i >> 2) + (i & 3);
+            x[i] = v < v_end ? acc[t][i] : -INFINITY;
+            tmax = fmaxf(tmax, x[i]);
+            if (v < v_end) best = key_max(best, make_key(x[i], v));
+        }
+        if (tmax > m_run) {                                  // move the statistics to the new maximum
+            if (m_run > -INFINITY) {
+                const float dlt = tmax - m_run;
+                const float sc = expf(-dlt);
+                Tm = (Tm + dlt * Z) * sc;
+                Z *= sc;
+            }
+            m_run = tmax;
+        }
+        if (m_run > -INFINITY) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float dlt = m_run - x[i];              // >= 0, +inf for masked entries
+                const float e = expf(-dlt);
+                Z += e;
+                Tm += (e > 0.f) ? e * dlt : 0.f;
+            }
+        }
+    }
+
+    // ---- combine the four partial statistics of every hidden row (two lane halves x two vocabulary halves)
+    const int hr = rt * 32 + r32;
+    s_part[hr][vt * 2 + half][0] = m_run;
+    s_part[hr][vt * 2 + half][1] = Z;
+    s_part[hr][vt * 2 + half][2] = Tm;
+    s_key[hr][vt * 2 + half] = key_pack(best);
+    __syncthreads();
+    if (tid < TILE_R && row0 + tid < prm.rows) {
+        float m = -INFINITY;
+        Key bk = Key{0, 0};
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            m = fmaxf(m, s_part[tid][p][0]);
+            bk = key_max(bk, key_unpack(s_key[tid][p]));
+        }
+        float z = 0.f, t = 0.f;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const float mp = s_part[tid][p][0];
+            if (mp > -INFINITY) {
+                const float dlt = m - mp;
+                const float sc = expf(-dlt);
+                z += sc * s_part[tid][p][1];
+                t += sc * (s_part[tid][p][2] + s_part[tid][p][1] * dlt);
+            }
+        }
+        const long o = static_cast<long>(row0 + tid) * prm.nunits + unit;
+        prm.stats[o] = UnitStats{m, z, t, 0.f};
+        prm.keys[o] = key_pack(bk);
+    }
+#undef SW
+#undef SH
+}
+
+inline size_t align256(size_t b) { return (b + 255) & ~static_cast<size_t>(255); }
+
+// Launch shape: T = 5 or 10 tiles per workgroup (more accumulators do not fit the register file without spills) and
+// about one workgroup per CU, each with an even share of the tiles; a vocabulary too large for that takes more
+// workgroups (several rounds).
+struct Shape { int nunits, tiles_per_unit, ntiles; };
+inline Shape launch_shape(int vocab) {
+    Shape sh;
+    sh.ntiles = (vocab + TILE_V - 1) / TILE_V;
+    sh.tiles_per_unit = sh.ntiles <= 5 * 256 ? 5 : 10;
+    const int need = (sh.ntiles + sh.tiles_per_unit - 1) / sh.tiles_per_unit;
+    sh.nunits = need > 256 ? need : (sh.ntiles < 256 ? sh.ntiles : 256);
+    return sh;
+}
+
+}  // namespace
+
+extern "C" size_t sage_lm_head_topk_workspace_bytes(int rows, int vocab) {
+    if (rows < 0 || vocab < 1) return 0;
+    const Shape sh = launch_shape(vocab);
+    return align256(static_cast<size_t>(rows) * sh.nunits * sizeof(UnitStats)) +
+           static_cast<size_t>(rows) * sh.nunits * sizeof(uint64_t) + 256;
+}
+
+extern "C" int sage_lm_head_topk(const void* hidden, const void* weight, int dtype, int rows, int dim, int vocab,
+                                 long hidden_stride, long weight_stride, int k, const int* n_valid, int rows_per_group,
+                                 float* entropy, int* topk_idx, float* topk_prob, float* topk_renorm,
+                                 float* topk_entropy, float* alpha, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!hidden || !weight || !topk_idx || !workspace) return SAGE_INVALID_ARG;
+    if (rows < 0 || dim < 1 || vocab < 1 || k < 1 || hidden_stride < dim || weight_stride < dim) return SAGE_INVALID_ARG;
+    if (dtype != SAGE_F32 && dtype != SAGE_BF16) return SAGE_INVALID_ARG;
+    if (n_valid && rows_per_group < 1) return SAGE_INVALID_ARG;
+    if (dtype != SAGE_BF16 || k != 1 || dim % CHUNK != 0) return SAGE_UNSUPPORTED;
+    if ((hidden_stride % 8) != 0 || (weight_stride % 8) != 0 || !sage::aligned(hidden, 16) || !sage::aligned(weight, 16) ||
+        !sage::aligned(workspace, 16))
+        return SAGE_INVALID_ARG;
+    if (weight_stride > (1L << 24) || hidden_stride > (1L << 24)) return SAGE_UNSUPPORTED;   // 64 rows: 32-bit byte offsets
+    if (rows > 65535 * TILE_R) return SAGE_UNSUPPORTED;
+    if (workspace_bytes < sage_lm_head_topk_workspace_bytes(rows, vocab)) return SAGE_WORKSPACE_TOO_SMALL;
+    if (rows == 0) return SAGE_OK;
+    const Shape sh = launch_shape(vocab);
+    if (sh.nunits > sage::topk_max_units()) return SAGE_UNSUPPORTED;
+
+    Params p;
+    p.hidden = static_cast<const unsigned char*>(hidden);
+    p.weight = static_cast<const unsigned char*>(weight);
+    p.hidden_stride_b = hidden_stride * 2;
+    p.weight_stride_b = weight_stride * 2;
+    p.rows = rows; p.dim = dim; p.vocab = vocab; p.k = k; p.nunits = sh.nunits; p.ntiles = sh.ntiles;
+    p.stats = static_cast<UnitStats*>(workspace);
+    p.keys = reinterpret_cast<uint64_t*>(static_cast<char*>(workspace) +
+                                         align256(static_cast<size_t>(rows) * sh.nunits * sizeof(UnitStats)));
+    hipStream_t s = sage::as_stream(stream);
+    const dim3 grid(sh.nunits, (rows + TILE_R - 1) / TILE_R);
+    if (sh.tiles_per_unit == 5) hipLaunchKernelGGL(lm_head_kernel<5>, grid, dim3(THREADS), 0, s, p);
+    else hipLaunchKernelGGL(lm_head_kernel<10>, grid, dim3(THREADS), 0, s, p);
+    if (hipGetLastError() != hipSuccess) return SAGE_LAUNCH_FAILED;
+    sage::topk_merge(rows, k, n_valid, rows_per_group, sh.nunits, p.stats, p.keys, entropy, topk_idx, topk_prob, topk_renorm,
+                     topk_entropy, alpha, s);
+    return sage::launch_status();
+}

@@ -58,6 +58,11 @@ def lib():
         L.sage_advance_kv_len.argtypes = [_vp, _vp, _ci, _ci, _vp]
         L.sage_update_history.restype = _ci
         L.sage_update_history.argtypes = [_vp, _ci, _ci, _cf, _cf, _ci, _ci, _vp, _vp, _vp, _vp, _vp]
+        L.sage_lm_head_topk_workspace_bytes.restype = _sz
+        L.sage_lm_head_topk_workspace_bytes.argtypes = [_ci, _ci]
+        L.sage_lm_head_topk.restype = _ci
+        L.sage_lm_head_topk.argtypes = [_vp, _vp, _ci, _ci, _ci, _ci, _cl, _cl, _ci, _vp, _ci, _vp, _vp, _vp, _vp, _vp, _vp,
+                                        _vp, _sz, _vp]
         L.sage_build_info.restype = ctypes.c_char_p
         _lib = L
     return _lib
@@ -91,6 +96,10 @@ def tree_params(d_min, d_max, w_min, w_max, k, n_max) -> TreeParams:
 
 def sage_entropy_topk_workspace_bytes(rows: int, vocab: int, k: int) -> int:
     return int(lib().sage_entropy_topk_workspace_bytes(rows, vocab, k))
+
+
+def sage_lm_head_topk_workspace_bytes(rows: int, vocab: int) -> int:
+    return int(lib().sage_lm_head_topk_workspace_bytes(rows, vocab))
 
 
 def sage_tree_attention_workspace_bytes(dtype_code: int, B: int, Hq: int, Hkv: int, d: int, max_kv_len: int) -> int:
@@ -152,10 +161,19 @@ def _args_update_history(accept_len, hist, count, d_max, lo, hi, d_floor, d_cap,
             _stream(stream)]
 
 
+def _args_lm_head_topk(hidden, weight, k, entropy, topk_idx, topk_prob, topk_renorm, topk_entropy, alpha, workspace,
+                       n_valid=None, rows_per_group=1, stream=None):
+    rows, dim = hidden.shape
+    vocab = weight.shape[0]
+    return [_ptr(hidden), _ptr(weight), _dtype_code(hidden), rows, dim, vocab, hidden.stride(0), weight.stride(0), k,
+            _ptr(n_valid), rows_per_group, _ptr(entropy), _ptr(topk_idx), _ptr(topk_prob), _ptr(topk_renorm),
+            _ptr(topk_entropy), _ptr(alpha), _ptr(workspace), _nbytes(workspace), _stream(stream)]
+
+
 _MARSHAL = {"sage_entropy_topk": _args_entropy_topk, "sage_build_tree": _args_build_tree,
             "sage_tree_attention": _args_tree_attention, "sage_verify_accept": _args_verify_accept,
             "sage_commit_path": _args_commit_path, "sage_advance_kv_len": _args_advance_kv_len,
-            "sage_update_history": _args_update_history}
+            "sage_update_history": _args_update_history, "sage_lm_head_topk": _args_lm_head_topk}
 
 
 def sage_entropy_topk(*a, **kw):
@@ -184,6 +202,10 @@ def sage_advance_kv_len(*a, **kw):
 
 def sage_update_history(*a, **kw):
     _check("sage_update_history", lib().sage_update_history(*_args_update_history(*a, **kw)))
+
+
+def sage_lm_head_topk(*a, **kw):
+    _check("sage_lm_head_topk", lib().sage_lm_head_topk(*_args_lm_head_topk(*a, **kw)))
 
 
 def prepare(name: str, *a, **kw):

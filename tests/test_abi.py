@@ -106,6 +106,22 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
     assert lib.sage_commit_path(*com(pc=0)) == INVALID
     assert lib.sage_commit_path(*com(pc=65)) == 2
     assert lib.sage_commit_path(*com(B=0)) == 0
+    lib.sage_lm_head_topk.argtypes = [ctypes.c_void_p, ctypes.c_void_p] + [ctypes.c_int] * 4 + [ctypes.c_long, ctypes.c_long, ctypes.c_int,
+                                     ctypes.c_void_p, ctypes.c_int] + [ctypes.c_void_p] * 7 + [ctypes.c_size_t, ctypes.c_void_p]
+    lm = lambda **kw: [256, kw.get("w", 256), kw.get("dtype", 1), kw.get("rows", 64), kw.get("dim", 8192), kw.get("vocab", 152064),
+                       kw.get("hs", 8192), 8192, kw.get("k", 1), None, 1, 256, kw.get("idx", 256), None, None, 256, 256, 256,
+                       kw.get("wsb", 1 << 24), None]
+    assert lib.sage_lm_head_topk(*lm(w=None)) == INVALID
+    assert lib.sage_lm_head_topk(*lm(idx=None)) == INVALID
+    assert lib.sage_lm_head_topk(*lm(hs=100)) == INVALID                   # row stride shorter than a row
+    assert lib.sage_lm_head_topk(*lm(hs=8196)) == INVALID                  # rows must stay 16-byte aligned
+    assert lib.sage_lm_head_topk(*lm(k=2)) == 2                            # only the greedy token so far
+    assert lib.sage_lm_head_topk(*lm(dtype=0)) == 2
+    assert lib.sage_lm_head_topk(*lm(dim=8100)) == 2                          # hidden size must be whole 128-element chunks
+    assert lib.sage_lm_head_topk(*lm(wsb=64)) == 3
+    assert lib.sage_lm_head_topk(*lm(rows=0)) == 0
+    lib.sage_lm_head_topk_workspace_bytes.restype = ctypes.c_size_t
+    assert 0 < lib.sage_lm_head_topk_workspace_bytes(64, 152064) < (1 << 22)
     lib.sage_advance_kv_len.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
     assert lib.sage_advance_kv_len(None, 256, 1, 10, None) == INVALID
     assert lib.sage_advance_kv_len(256, 256, 0, 10, None) == 0
