@@ -44,7 +44,10 @@ def parse():
     ap.add_argument("--workload", default="c2", choices=["toy", "c2", "c3", "c4", "c5"])
     ap.add_argument("--slots", type=int, default=None, help="number of rotating input sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extras", action="store_true", help="skip the long-KV attention measurements")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the long-KV attention, closed-loop and output-projection measurements")
+    ap.add_argument("--only", default=None, choices=["long_kv", "closed_loop", "lm_head"],
+                    help="run one of the extra measurements alone and print its JSON (for profiling it)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--eager", action="store_true", help="time the steps eagerly instead of as HIP-graph replays")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -562,6 +565,18 @@ def main():
         sys.exit(3)
     from paper_2602_00523_amd import sage
     sage.lib()                                          # fail loudly if the HIP library is not built
+    if args.only:
+        if args.calibrate_copy:
+            src = torch.empty(64 << 20, device="cuda:0", dtype=torch.uint8).random_()
+            dst = torch.empty_like(src)
+            for _ in range(5):
+                dst.copy_(src)
+            torch.cuda.synchronize()
+            del src, dst
+        extra = {"long_kv": lambda: long_kv_attention(["c3", "c4", "c5"]), "closed_loop": lambda: closed_loop("c2"),
+                 "lm_head": lm_head_projection}[args.only]()
+        print(json.dumps({args.only: extra}))
+        return
     defaults = {"toy": (2000, 50), "c2": (2000, 100), "c3": (1024, 64), "c4": (300, 20), "c5": (24, 3)}
     steps = args.steps if args.steps is not None else defaults[args.workload][0]
     warmup = args.warmup if args.warmup is not None else defaults[args.workload][1]
