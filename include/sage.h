@@ -129,7 +129,7 @@ int sage_build_tree(const float* topk_renorm, const float* alpha, const int* top
  *         + g * kv_head_stride + c  (strides in elements; rows 16-byte aligned);
  * kv_start [B] i64, kv_len [B] i32 (device); max_kv_len (host) >= every kv_len[b], used
  * only to size the launch; dtype applies to Q, K, V and O alike.
- * bf16: MFMA path, requires d == 128, Hq / Hkv in {1,2,4,8,16}, kv_token_stride <= 2^24 elements;
+ * bf16: MFMA path, requires d == 128, Hq / Hkv <= 16, kv_token_stride <= 2^24 elements;
  * fp32: d <= 256, multiple of 4.
  * Accumulation is fp32; bf16 outputs are rounded to nearest even.
  * workspace: sage_tree_attention_workspace_bytes(...) bytes, 256-byte aligned.

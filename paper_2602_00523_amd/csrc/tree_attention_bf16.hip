@@ -546,7 +546,7 @@ int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const voi
                         long kv_token_stride, long kv_head_stride, const uint64_t* anc_mask, const int* n_nodes,
                         float scale, void* workspace, size_t workspace_bytes, hipStream_t stream) {
     const int G = Hq / Hkv;
-    if (d != D || !(G == 1 || G == 2 || G == 4 || G == 8 || G == 16)) return SAGE_UNSUPPORTED;
+    if (d != D || G < 1 || G > 16) return SAGE_UNSUPPORTED;   // 64 nodes x 16 heads per KV head = 8 groups of 128 rows
     if ((kv_token_stride % 8) != 0 || (kv_head_stride % 8) != 0) return SAGE_INVALID_ARG;
     if (kv_token_stride > (1L << 24)) return SAGE_UNSUPPORTED;   // the byte offsets inside a 64-token tile are 32-bit
     if (!aligned(Q, 16) || !aligned(Kc, 16) || !aligned(Vc, 16) || !aligned(Kt, 16) || !aligned(Vt, 16) || !aligned(workspace, 16))

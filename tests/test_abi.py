@@ -89,7 +89,7 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
     assert lib.sage_tree_attention(*att(Hq=63)) == INVALID
     assert lib.sage_tree_attention(*att(scale=0.0)) == INVALID
     assert lib.sage_tree_attention(*att(d=96)) == 2                        # UNSUPPORTED head_dim on the bf16 path
-    assert lib.sage_tree_attention(*att(Hq=24, Hkv=8)) == 2                # group size 3
+    assert lib.sage_tree_attention(*att(Hq=136, Hkv=8)) == 2               # group size 17
     assert lib.sage_tree_attention(*att(ts=1004)) == INVALID               # token rows must stay 16-byte aligned
     assert lib.sage_tree_attention(*att(wsb=1024)) == 3
     assert lib.sage_tree_attention(*att(B=0)) == 0

@@ -206,7 +206,7 @@ def test_attention_bf16_ragged_batch(gu):
     run_attention_case(gu, 81, "bf16", B, 64, 8, 128, lens, sizes)
 
 
-@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (16, 4), (32, 2)])
+@pytest.mark.parametrize("Hq,Hkv", [(8, 8), (16, 4), (32, 2), (28, 4), (12, 4), (10, 2), (13, 1)])
 def test_attention_bf16_other_group_sizes(gu, Hq, Hkv):
     run_attention_case(gu, 90 + Hq, "bf16", 2, Hq, Hkv, 128, [333, 70], sizes=[64, 11])
 
