@@ -46,7 +46,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the long-KV attention, closed-loop and output-projection measurements")
-    ap.add_argument("--only", default=None, choices=["long_kv", "closed_loop", "lm_head"],
+    ap.add_argument("--only", default=None, choices=["long_kv", "closed_loop", "lm_head", "entropy_topk"],
                     help="run one of the extra measurements alone and print its JSON (for profiling it)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--eager", action="store_true", help="time the steps eagerly instead of as HIP-graph replays")
@@ -554,6 +554,49 @@ def lm_head_projection(rows=64, dim=8192, vocab=152064, launches=12):
     return out
 
 
+def entropy_topk_streams(vocab=152064):
+    """sage_entropy_topk alone: the target rows of one tree (64 x vocab, k = 1), a batch of them (512 rows) and the
+    draft row (k = 10), as HIP-graph replays over rotating inputs (> 512 MB for the k = 1 cases)."""
+    import torch
+    from paper_2602_00523_amd import sage
+    dev = "cuda:0"
+    g = torch.Generator(device=dev)
+    g.manual_seed(523011)
+    out = []
+    for rows, k, nbuf in ((64, 1, 32), (512, 1, 4), (1, 10, 64)):
+        X = [(torch.randn(rows, vocab, generator=g, device=dev, dtype=torch.float32) * 2.0).to(torch.bfloat16) for _ in range(nbuf)]
+        f = lambda *s: torch.zeros(*s, device=dev)
+        H, pr, rn, hk, al = f(rows), f(rows, k), f(rows, k), f(rows), f(rows)
+        idx = torch.zeros(rows, k, device=dev, dtype=torch.int32)
+        ws = torch.empty(sage.sage_entropy_topk_workspace_bytes(rows, vocab, k), device=dev, dtype=torch.uint8)
+        side = torch.cuda.Stream()
+        calls = [sage.prepare("sage_entropy_topk", x, k, H, idx, pr, rn, hk, al, ws, stream=side) for x in X]
+        with torch.cuda.stream(side):
+            for c in calls:
+                c()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for c in calls:
+                c()
+        graph.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 10
+        e0.record()
+        for _ in range(reps):
+            graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / (reps * nbuf)
+        byts = 2.0 * rows * vocab
+        out.append(dict(rows=rows, k=k, vocab=vocab, us_per_call=us, algorithmic_bytes=byts, hbm_GBps=byts / us / 1e3,
+                        hbm_frac=byts / us / 1e3 / HBM_PEAK_GBPS))
+        del X
+        torch.cuda.empty_cache()
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -574,7 +617,7 @@ def main():
             torch.cuda.synchronize()
             del src, dst
         extra = {"long_kv": lambda: long_kv_attention(["c3", "c4", "c5"]), "closed_loop": lambda: closed_loop("c2"),
-                 "lm_head": lm_head_projection}[args.only]()
+                 "lm_head": lm_head_projection, "entropy_topk": entropy_topk_streams}[args.only]()
         print(json.dumps({args.only: extra}))
         return
     defaults = {"toy": (2000, 50), "c2": (2000, 100), "c3": (1024, 64), "c4": (300, 20), "c5": (24, 3)}
@@ -628,6 +671,7 @@ def main():
         result["attention_long_kv"] = long_kv_attention(["c3", "c4", "c5"])
         result["closed_loop"] = closed_loop("c2")
         result["lm_head_projection"] = lm_head_projection()
+        result["entropy_topk_streams"] = entropy_topk_streams()
     print(json.dumps(result))
 
 

@@ -90,7 +90,11 @@ template <> struct Loader<uint16_t> {
     __device__ static float one(const uint16_t* p) { return sage::bf16_bits_to_float(*p); }
 };
 
-// Pass 1: one wave per (slice, row).
+// Pass 1 for k = 1 (many rows, one candidate per slice): one wave per (slice, row), 16 logits per lane.  HBM-bound,
+// so the arithmetic per logit is kept to a compare-and-select for the argmax (strictly greater in index order keeps
+// the lowest index among equals, the same total order as the composite key) and, once the slice maximum is known,
+// one exp2 and two fused multiply-adds for the statistics.  Differences to the maximum are capped at 87, where
+// exp is below 2^-125: a -inf logit or a padding slot then adds about 1e-38 instead of 0 to sums that are >= 1.
 template <typename T>
 __global__ __launch_bounds__(THREADS) void slice_kernel(const T* __restrict__ logits, int vocab, long row_stride, int k,
                                                         const int* __restrict__ n_valid, int rows_per_group, int nunits,
@@ -119,40 +123,29 @@ __global__ __launch_bounds__(THREADS) void slice_kernel(const T* __restrict__ lo
         }
     }
 
-    // ---- k rounds of wave-wide argmax on the composite key
-    Key cand[EPT];
+    // ---- this lane's best candidate, then the slice's
+    float bv = v[0];
+    int bi = first[0];
 #pragma unroll
-    for (int s = 0; s < EPT; ++s) {
+    for (int s = 1; s < EPT; ++s) {
         const int idx = first[s / VEC] + (s % VEC);
-        cand[s] = idx < vocab ? make_key(v[s], idx) : Key{0, 0};
+        const bool better = v[s] > bv;                       // indices ascend with s: equal values keep the earlier one
+        bv = better ? v[s] : bv;
+        bi = better ? idx : bi;
     }
-    uint64_t* out_keys = keys + (static_cast<long>(row) * nunits + unit) * k;
-    float unit_max = -INFINITY;
-    Key mine = Key{0, 0};                            // lane j keeps the winner of round j (k <= 64)
-    for (int round = 0; round < k; ++round) {
-        Key best = cand[0];
-#pragma unroll
-        for (int s = 1; s < EPT; ++s) best = key_max(best, cand[s]);
-        const Key g = wave_max_key(best);
-        if (!key_none(g)) {
-#pragma unroll
-            for (int s = 0; s < EPT; ++s)
-                if (key_equal(cand[s], g)) cand[s] = Key{0, 0};      // keys are unique: exactly one lane, one slot
-        }
-        if (round == 0) unit_max = key_none(g) ? -INFINITY : key_value(g);
-        if (lane == round) mine = g;
-    }
-    if (lane < k) out_keys[lane] = key_pack(mine);
+    const Key g = wave_max_key(bi < vocab ? make_key(bv, bi) : Key{0, 0});   // a lane past the end starts past the end
+    const float unit_max = key_none(g) ? -INFINITY : key_value(g);
+    if (lane == 0) keys[(static_cast<long>(row) * nunits + unit) * k] = key_pack(g);
 
     // ---- softmax statistics of the slice relative to its own maximum
     float Z = 0.f, Tm = 0.f;
     if (unit_max > -INFINITY) {
 #pragma unroll
         for (int s = 0; s < EPT; ++s) {
-            const float dlt = unit_max - v[s];               // >= 0, +inf for padding and -inf logits
-            const float e = expf(-dlt);
+            const float dlt = fminf(unit_max - v[s], 87.0f);
+            const float e = __builtin_amdgcn_exp2f(dlt * -1.4426950408889634f);
             Z += e;
-            Tm += (e > 0.f) ? e * dlt : 0.f;
+            Tm = fmaf(e, dlt, Tm);
         }
     }
     Z = wave_sum(Z);
