@@ -7,7 +7,7 @@
 // registers (T accumulators of 32 x 32 per wave; with one wave per SIMD a wave has 512 registers).  The loop runs
 // over chunks of 128 hidden elements on the outside and the T tiles on the inside, so a hidden chunk is fetched once
 // and its MFMA operands stay in registers for T steps, while the weight tiles (64 rows x 256 B) stream from global
-// memory straight into LDS through a 5-stage ring, four steps ahead of the MFMAs, in the same padded layout as the
+// memory straight into LDS through an 8-stage ring, seven steps ahead of the MFMAs, in the same padded layout as the
 // attention kernel's K tiles (conflict-free 16-byte reads with compile-time offsets).  Wave (vt, rt) accumulates
 // logits^T[32 vocabulary rows of half vt][32 hidden rows of half rt] with v_mfma_f32_32x32x16_bf16 (A = weight rows,
 // B = hidden rows, both as stored), so a lane owns one hidden row and 16 vocabulary entries of it per tile.  After
@@ -34,7 +34,8 @@ constexpr int TILE_R = 64;               // hidden rows per launch block
 constexpr int CHUNK = 128;               // hidden elements per stage
 constexpr int ROW_B = CHUNK * 2;         // bytes of one row of a stage
 constexpr int THREADS = 256;
-constexpr int STAGES = 5;              // weight ring
+constexpr int STAGES = 8;              // weight ring: seven tiles in flight per workgroup
+constexpr int AHEAD = STAGES - 1;
 // stage layout: row t at (t % 16) * GROUP + (t / 16) * ROW_B; a group is the 1 KB one wave-level LDS-direct load
 // writes (rows t, t+16, t+32, t+48) plus 16 bytes, which staggers consecutive rows across the banks
 constexpr int GROUP = 4 * ROW_B + 16;
@@ -51,6 +52,19 @@ struct Params {
 template <int N> __device__ __forceinline__ void wait_vm() {
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
+// wait until at most `tiles` tiles' worth of this thread's loads are outstanding (0..AHEAD)
+__device__ __forceinline__ void wait_vm_tiles(int tiles) {
+    switch (tiles) {
+        case 0: wait_vm<0>(); break;
+        case 1: wait_vm<1 * LOADS_PER_TILE>(); break;
+        case 2: wait_vm<2 * LOADS_PER_TILE>(); break;
+        case 3: wait_vm<3 * LOADS_PER_TILE>(); break;
+        case 4: wait_vm<4 * LOADS_PER_TILE>(); break;
+        case 5: wait_vm<5 * LOADS_PER_TILE>(); break;
+        case 6: wait_vm<6 * LOADS_PER_TILE>(); break;
+        default: wait_vm<7 * LOADS_PER_TILE>(); break;
+    }
+}
 // bare barrier with wavefront-scope fences (a workgroup-scope release would wait for every load in flight)
 __device__ __forceinline__ void stage_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -60,18 +74,23 @@ __device__ __forceinline__ void stage_barrier() {
 
 template <int T>
 __global__ __launch_bounds__(THREADS) void lm_head_kernel(const Params prm) {
-    static_assert(T % STAGES == 0, "the ring position of a step must be a compile-time constant");
-    __shared__ __align__(1024) unsigned char sW0[STAGE_B];
-    __shared__ __align__(1024) unsigned char sW1[STAGE_B];
-    __shared__ __align__(1024) unsigned char sW2[STAGE_B];
-    __shared__ __align__(1024) unsigned char sW3[STAGE_B];
-    __shared__ __align__(1024) unsigned char sW4[STAGE_B];
-    __shared__ __align__(1024) unsigned char sH0[STAGE_B];
-    __shared__ __align__(1024) unsigned char sH1[STAGE_B];
+    // The ring position of a step must be a compile-time constant (every stage is its own LDS object, so that loads
+    // in flight into one stage are known not to alias reads of another): step t of chunk kc uses stage
+    // (kc T + t) mod STAGES, which is static once the chunk loop is unrolled UNROLL times.
+    constexpr int UNROLL = (T % 8 == 0) ? 1 : (T % 4 == 0) ? 2 : (T % 2 == 0) ? 4 : 8;
+    static_assert((UNROLL * T) % STAGES == 0 && STAGES == 8, "unroll factor assumes an 8-stage ring");
+    __shared__ __align__(16) unsigned char sW0[STAGE_B];
+    __shared__ __align__(16) unsigned char sW1[STAGE_B];
+    __shared__ __align__(16) unsigned char sW2[STAGE_B];
+    __shared__ __align__(16) unsigned char sW3[STAGE_B];
+    __shared__ __align__(16) unsigned char sW4[STAGE_B];
+    __shared__ __align__(16) unsigned char sW5[STAGE_B];
+    __shared__ __align__(16) unsigned char sW6[STAGE_B];
+    __shared__ __align__(16) unsigned char sW7[STAGE_B];
+    __shared__ __align__(16) unsigned char sH0[STAGE_B];    // the current hidden chunk (read into registers in step 0)
     __shared__ float s_part[TILE_R][4][3];                   // per hidden row: 4 partial (m, Z, T)
     __shared__ uint64_t s_key[TILE_R][4];
-#define SW(i) ((i) == 0 ? sW0 : (i) == 1 ? sW1 : (i) == 2 ? sW2 : (i) == 3 ? sW3 : sW4)
-#define SH(i) ((i) == 0 ? sH0 : sH1)
+#define SW(i) ((i) == 0 ? sW0 : (i) == 1 ? sW1 : (i) == 2 ? sW2 : (i) == 3 ? sW3 : (i) == 4 ? sW4 : (i) == 5 ? sW5 : (i) == 6 ? sW6 : sW7)
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -131,9 +150,8 @@ __global__ __launch_bounds__(THREADS) void lm_head_kernel(const Params prm) {
             }
         }
     };
-    auto issue_h = [&](int kc, auto slotc) __attribute__((always_inline)) {
-        constexpr int SL = decltype(slotc)::value;
-        LDS_AS unsigned char* dst = (LDS_AS unsigned char*)(&SH(SL)[wave * 4 * GROUP]);
+    auto issue_h = [&](int kc) __attribute__((always_inline)) {
+        LDS_AS unsigned char* dst = (LDS_AS unsigned char*)(&sH0[wave * 4 * GROUP]);
         long off = static_cast<long>(kc) * ROW_B;
         asm volatile("" : "+s"(off));
 #pragma unroll
@@ -151,30 +169,29 @@ __global__ __launch_bounds__(THREADS) void lm_head_kernel(const Params prm) {
         for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
     bf16x8 hb_frag[8];                                       // this wave's hidden rows of the current chunk (B operands)
 
-    // one hidden chunk: T steps, step t consumes weight stage t % STAGES
-    auto chunk = [&](int kc, auto slotc) __attribute__((always_inline)) {
-        constexpr int SL = decltype(slotc)::value;
+    // one hidden chunk: T steps; J = kc mod UNROLL fixes the ring positions
+    auto chunk = [&](int kc, auto jc) __attribute__((always_inline)) {
+        constexpr int J = decltype(jc)::value;
         auto step = [&](auto tc) __attribute__((always_inline)) {
             constexpr int t = decltype(tc)::value;
-            constexpr int ST = t % STAGES;
+            constexpr int ST = (J * T + t) % STAGES;
             const int s = kc * T + t;
-            // this thread's loads of step s have landed; younger ones may stay in flight: the weight tiles of up to
-            // three steps and, during steps 1-4 of a chunk, the next hidden chunk (requested in step 0)
-            constexpr int HX = (t >= 1 && t <= 4) ? LOADS_PER_TILE : 0;
-            if (s + 3 < nsteps) {
-                if (HX && kc + 1 < nchunk) wait_vm<3 * LOADS_PER_TILE + HX>();
-                else wait_vm<3 * LOADS_PER_TILE>();
-            } else if (s + 2 < nsteps) wait_vm<2 * LOADS_PER_TILE>();
-            else if (s + 1 < nsteps) wait_vm<LOADS_PER_TILE>();
-            else wait_vm<0>();
+            // This thread's loads of step s have landed; younger ones may stay in flight (the counter retires loads in
+            // order): the weight tiles of the next AHEAD - 1 steps and, during steps 2..AHEAD of a chunk, the next
+            // hidden chunk, requested in step 1.  Step 0 also needs the hidden chunk itself, which only the weight
+            // tiles requested after it (steps 2..T-1 of the previous chunk) are younger than.
+            int younger = min(AHEAD - 1, nsteps - 1 - s);
+            if (t >= 2 && t <= AHEAD && kc + 1 < nchunk) younger += 1;
+            if (t == 0 && kc > 0) younger = min(younger, max(0, min(T - 2, nsteps - AHEAD - ((kc - 1) * T + 2))));
+            wait_vm_tiles(younger);
             stage_barrier();                                 // ... for every wave, and the stage read last step is free
-            if (s + 4 < nsteps) {
-                constexpr int t4 = (t + 4) % T;
-                issue_w(kc + (t + 4) / T, t4, std::integral_constant<int, (ST + 4) % STAGES>{});
+            if (s + AHEAD < nsteps) {
+                constexpr int ta = (t + AHEAD) % T;
+                issue_w(kc + (t + AHEAD) / T, ta, std::integral_constant<int, (ST + AHEAD) % STAGES>{});
             }
+            if (t == 1 && kc + 1 < nchunk) issue_h(kc + 1);  // every wave has taken its fragments of chunk kc in step 0
             if (t == 0) {
-                if (kc + 1 < nchunk) issue_h(kc + 1, std::integral_constant<int, SL ^ 1>{});
-                const lds_byte* hst = (const lds_byte*)(SH(SL)) + h_lane;
+                const lds_byte* hst = (const lds_byte*)(sH0) + h_lane;
 #pragma unroll
                 for (int kk = 0; kk < 8; ++kk) hb_frag[kk] = __builtin_bit_cast(bf16x8, *(const LDS_AS uint4*)(hst + kk * 32));
             }
@@ -191,14 +208,15 @@ __global__ __launch_bounds__(THREADS) void lm_head_kernel(const Params prm) {
         }(std::make_integer_sequence<int, T>{});
     };
 
-    issue_h(0, std::integral_constant<int, 0>{});
-    if (0 < nsteps) issue_w(0, 0, std::integral_constant<int, 0>{});
-    if (1 < nsteps) issue_w(1 / T, 1 % T, std::integral_constant<int, 1>{});
-    if (2 < nsteps) issue_w(2 / T, 2 % T, std::integral_constant<int, 2>{});
-    if (3 < nsteps) issue_w(3 / T, 3 % T, std::integral_constant<int, 3>{});
-    for (int kc = 0; kc < nchunk; kc += 2) {
-        chunk(kc, std::integral_constant<int, 0>{});
-        if (kc + 1 < nchunk) chunk(kc + 1, std::integral_constant<int, 1>{});
+    static_assert(T >= 2 && AHEAD == 7, "prologue below issues the first seven steps");
+    issue_h(0);
+    [&]<int... Is>(std::integer_sequence<int, Is...>) __attribute__((always_inline)) {
+        ((Is < nsteps ? issue_w(Is / T, Is % T, std::integral_constant<int, Is % STAGES>{}) : (void)0), ...);
+    }(std::make_integer_sequence<int, AHEAD>{});
+    for (int kc = 0; kc < nchunk; kc += UNROLL) {
+        [&]<int... Js>(std::integer_sequence<int, Js...>) __attribute__((always_inline)) {
+            ((kc + Js < nchunk ? chunk(kc + Js, std::integral_constant<int, Js>{}) : (void)0), ...);
+        }(std::make_integer_sequence<int, UNROLL>{});
     }
 
     // ---- fold the logits into softmax statistics and the best candidate of this lane's hidden row
@@ -268,7 +286,6 @@ __global__ __launch_bounds__(THREADS) void lm_head_kernel(const Params prm) {
         prm.keys[o] = key_pack(bk);
     }
 #undef SW
-#undef SH
 }
 
 inline size_t align256(size_t b) { return (b + 255) & ~static_cast<size_t>(255); }

@@ -38,7 +38,8 @@ def check(gu, h, w, n_valid=None, rpg=1, rows_checked=None):
     return exact, len(sel)
 
 
-@pytest.mark.parametrize("rows,dim,vocab", [(5, 256, 1000), (64, 512, 4096), (33, 128, 64), (70, 128, 700), (1, 1024, 130)])
+@pytest.mark.parametrize("rows,dim,vocab", [(5, 256, 1000), (64, 512, 4096), (33, 128, 64), (70, 128, 700), (1, 1024, 130),
+                                            (4, 384, 81920), (3, 384, 81900), (3, 128, 152064), (2, 640, 100003 * 1 + 5)])
 def test_small_shapes(gu, rows, dim, vocab):
     h = wl.gaussian(rows, (rows, dim), "bf16", 1.0)
     w = wl.gaussian(vocab, (vocab, dim), "bf16", 3.0 / np.sqrt(dim))
