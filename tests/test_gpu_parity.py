@@ -211,6 +211,23 @@ def test_attention_bf16_other_group_sizes(gu, Hq, Hkv):
     run_attention_case(gu, 90 + Hq, "bf16", 2, Hq, Hkv, 128, [333, 70], sizes=[64, 11])
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_attention_bf16_random_configurations(gu, seed):
+    """Random head counts (any group size up to 16), batch sizes, ragged lengths around tile and split boundaries,
+    tree sizes and shapes."""
+    g = wl.rng(1000 + seed)
+    Hkv = int(g.choice([1, 2, 4, 8]))
+    G = int(g.integers(1, 17))
+    B = int(g.integers(1, 5))
+    edges = np.array([0, 1, 63, 64, 65, 127, 128, 129, 191, 192, 255, 256, 257, 2047, 2048, 2049])
+    lens = [int(g.choice(edges)) if g.random() < 0.6 else int(g.integers(0, 3000)) for _ in range(B)]
+    sizes = [int(g.choice([1, 2, 4, 16, 17, 32, 33, 64])) if g.random() < 0.5 else int(g.integers(1, 65)) for _ in range(B)]
+    kind = str(g.choice(["random", "chain", "star"]))
+    if kind == "chain":
+        sizes = [min(n, 32) for n in sizes]
+    run_attention_case(gu, 2000 + seed, "bf16", B, Hkv * G, Hkv, 128, lens, sizes, kind, pad=int(g.integers(0, 5)))
+
+
 def test_attention_is_deterministic(gu):
     inp = wl.attention_inputs(3, 1, 64, 8, 128, [2000], "bf16")
     mask, nn = tree_batch(wl.rng(3), 1, [40])
