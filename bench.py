@@ -46,7 +46,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the long-KV attention, closed-loop and output-projection measurements")
-    ap.add_argument("--only", default=None, choices=["long_kv", "closed_loop", "lm_head", "entropy_topk"],
+    ap.add_argument("--only", default=None, choices=["long_kv", "closed_loop", "lm_head", "entropy_topk", "draft_side"],
                     help="run one of the extra measurements alone and print its JSON (for profiling it)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--eager", action="store_true", help="time the steps eagerly instead of as HIP-graph replays")
@@ -597,6 +597,59 @@ def entropy_topk_streams(vocab=152064):
     return out
 
 
+def draft_side_attention(launches=40):
+    """The same attention call at a draft-model shape: 28 query / 4 KV heads (group size 7), head_dim 128, and a cache
+    whose visual positions were pruned to 10-20 % (Sec. 5 "Implementation details": 90 % pruning for video, 80 % for
+    image), i.e. short caches: 3072 image + 1024 text -> 614 + 1024; 15360 video + 1024 text -> 1536 + 1024.  Trees of
+    12 and 25 nodes with random topology.  HIP events around each launch, rotating K/V buffers."""
+    import torch
+    import numpy as np
+    from paper_2602_00523_amd import sage
+    dev = "cuda:0"
+    Hq, Hkv, d = 28, 4, 128
+    g = torch.Generator(device=dev)
+    g.manual_seed(523013)
+    rn = lambda *s: torch.randn(*s, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    rng = np.random.default_rng(13)
+    out = []
+    for L, n in ((1638, 12), (2560, 12), (2560, 25)):
+        nbuf = 16
+        Kc = [rn(L, Hkv, d) for _ in range(nbuf)]
+        Vc = [rn(L, Hkv, d) for _ in range(nbuf)]
+        Q, Kt, Vt = rn(1, MAX_NODES, Hq, d), rn(1, MAX_NODES, Hkv, d), rn(1, MAX_NODES, Hkv, d)
+        O = torch.zeros_like(Q)
+        mask = np.zeros((1, MAX_NODES), np.uint64)
+        par = [-1] + [int(rng.integers(0, v)) for v in range(1, n)]
+        for v in range(n):
+            u, bits = v, 0
+            while u >= 0:
+                bits |= 1 << u
+                u = par[u]
+            mask[0, v] = bits
+        maskd = torch.from_numpy(mask.view(np.int64)).to(dev)
+        nn = torch.full((1,), n, device=dev, dtype=torch.int32)
+        kv_start = torch.zeros(1, device=dev, dtype=torch.int64)
+        kv_len = torch.full((1,), L, device=dev, dtype=torch.int32)
+        ws = torch.empty(sage.sage_tree_attention_workspace_bytes(sage.BF16, 1, Hq, Hkv, d, L), device=dev, dtype=torch.uint8)
+        calls = [sage.prepare("sage_tree_attention", Q, Kc[i], Vc[i], Kt, Vt, O, kv_start, kv_len, L, Hkv * d, d, maskd, nn,
+                              1.0 / math.sqrt(d), ws) for i in range(nbuf)]
+        for c in calls:
+            c()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * launches)]
+        for i in range(launches):
+            ev[2 * i].record()
+            calls[i % nbuf]()
+            ev[2 * i + 1].record()
+        torch.cuda.synchronize()
+        t = [ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(launches)]
+        avg_ms = sum(t) / len(t)
+        byts = 2.0 * 2 * L * Hkv * d + n * (2.0 * 2 * Hkv * d + 2.0 * 2 * Hq * d)
+        out.append(dict(heads=f"{Hq}/{Hkv}", kv_len=L, nodes=n, avg_us=avg_ms * 1e3, min_us=min(t) * 1e3,
+                        algorithmic_bytes=byts, hbm_GBps=byts / (avg_ms * 1e-3) / 1e9))
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -617,7 +670,7 @@ def main():
             torch.cuda.synchronize()
             del src, dst
         extra = {"long_kv": lambda: long_kv_attention(["c3", "c4", "c5"]), "closed_loop": lambda: closed_loop("c2"),
-                 "lm_head": lm_head_projection, "entropy_topk": entropy_topk_streams}[args.only]()
+                 "lm_head": lm_head_projection, "entropy_topk": entropy_topk_streams, "draft_side": draft_side_attention}[args.only]()
         print(json.dumps({args.only: extra}))
         return
     defaults = {"toy": (2000, 50), "c2": (2000, 100), "c3": (1024, 64), "c4": (300, 20), "c5": (24, 3)}
@@ -672,6 +725,7 @@ def main():
         result["closed_loop"] = closed_loop("c2")
         result["lm_head_projection"] = lm_head_projection()
         result["entropy_topk_streams"] = entropy_topk_streams()
+        result["draft_side_attention"] = draft_side_attention()
     print(json.dumps(result))
 
 
