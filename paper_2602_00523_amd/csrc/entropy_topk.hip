@@ -41,7 +41,12 @@ __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
 }
 __device__ __forceinline__ Key wave_max_key(Key k) {
     const uint32_t hi = wave_max_u32(k.hi);
-    const uint32_t lo = wave_max_u32(k.hi == hi ? k.lo : 0u);
+    const uint64_t holders = __ballot(k.hi == hi);
+    uint32_t lo;
+    if (__builtin_popcountll(holders) == 1)          // the usual case: no second reduction, just fetch the winner's index
+        lo = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(k.lo), __builtin_ctzll(holders)));
+    else
+        lo = wave_max_u32(k.hi == hi ? k.lo : 0u);
     return Key{hi, lo};
 }
 template <int CTRL> __device__ __forceinline__ float f_dpp(float v) {
@@ -151,6 +156,97 @@ __global__ __launch_bounds__(THREADS) void slice_kernel(const T* __restrict__ lo
     Z = wave_sum(Z);
     Tm = wave_sum(Tm);
     if (lane == 0) stats[static_cast<long>(row) * nunits + unit] = UnitStats{unit_max, Z, Tm, 0.f};
+}
+
+// Pass 1 for bf16 logits and 1 < k <= 16 (the draft row of a step; pure latency, so the serial selection rounds are
+// kept as short as they can be): the same decomposition as the generic kernel below, but the rounds run on ONE
+// 32-bit word per candidate, (16-bit value code << 16) | (1024 - position in the slice), whose order is the total
+// order (value descending, index ascending) inside a slice; 0 = no candidate.  Each wave selects the k best of its
+// 256 logits, wave 0 then selects the k best of the 4k survivors held one per lane.
+constexpr int FAST_MAX_K = 16;
+__global__ __launch_bounds__(THREADS) void slice_topk_bf16_kernel(const uint16_t* __restrict__ logits, int vocab, long row_stride,
+                                                                  int k, const int* __restrict__ n_valid, int rows_per_group,
+                                                                  int nunits, UnitStats* __restrict__ stats,
+                                                                  uint64_t* __restrict__ keys) {
+    __shared__ uint32_t s_list[WAVES * FAST_MAX_K];
+    __shared__ float s_red[3][WAVES];
+    const int row = blockIdx.y;
+    const int unit = blockIdx.x;
+    if (!row_is_valid(row, n_valid, rows_per_group)) return;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const uint16_t* rowp = logits + static_cast<long>(row) * row_stride;
+    const int local0 = threadIdx.x * 4;
+    const int e0 = unit * UNIT + local0;
+
+    float v[4];
+    if (e0 + 4 <= vocab) {
+        const uint2 q = *reinterpret_cast<const uint2*>(rowp + e0);
+        v[0] = __uint_as_float(q.x << 16); v[1] = __uint_as_float(q.x & 0xFFFF0000u);
+        v[2] = __uint_as_float(q.y << 16); v[3] = __uint_as_float(q.y & 0xFFFF0000u);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (e0 + e < vocab) ? Loader<uint16_t>::one(rowp + e0 + e) : -INFINITY;
+    }
+    uint32_t cand[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        cand[e] = (e0 + e < vocab) ? ((sortable(v[e]) & 0xFFFF0000u) | static_cast<uint32_t>(UNIT - (local0 + e))) : 0u;
+
+    uint32_t mine = 0, top = 0;                      // lane j keeps the wave's winner of round j
+    for (int round = 0; round < k; ++round) {
+        const uint32_t g = wave_max_u32(max(max(cand[0], cand[1]), max(cand[2], cand[3])));
+        if (round == 0) top = g;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) cand[e] = (cand[e] == g) ? 0u : cand[e];
+        if (lane == round) mine = g;
+    }
+    if (lane < k) s_list[wave * k + lane] = mine;
+    // a bf16 value's 32-bit code is its 16-bit code followed by sixteen zeros (non-negative) or ones (negative)
+    auto full_code = [](uint32_t key) { return (key & 0xFFFF0000u) | ((key & 0x80000000u) ? 0u : 0xFFFFu); };
+    const float wmax = top ? unsortable(full_code(top)) : -INFINITY;
+    float Z = 0.f, Tm = 0.f;
+    if (wmax > -INFINITY) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float dlt = wmax - v[e];
+            const float ex = __builtin_amdgcn_exp2f(dlt * -1.4426950408889634f);   // exactly 0 for a -inf logit
+            Z += ex;
+            Tm += (ex > 0.f) ? ex * dlt : 0.f;
+        }
+    }
+    Z = wave_sum(Z);
+    Tm = wave_sum(Tm);
+    if (lane == 0) { s_red[0][wave] = wmax; s_red[1][wave] = Z; s_red[2][wave] = Tm; }
+    __syncthreads();
+    if (wave != 0) return;
+
+    uint32_t key = lane < WAVES * k ? s_list[lane] : 0u;
+    uint32_t out = 0;
+    for (int round = 0; round < k; ++round) {
+        const uint32_t g = wave_max_u32(key);
+        key = (key == g) ? 0u : key;
+        if (lane == round) out = g;
+    }
+    if (lane < k) {
+        const Key full = out ? Key{full_code(out), 0xFFFFFFFFu - static_cast<uint32_t>(unit * UNIT + UNIT - static_cast<int>(out & 0xFFFFu))}
+                             : Key{0, 0};
+        keys[(static_cast<long>(row) * nunits + unit) * k + lane] = key_pack(full);
+    }
+    if (lane == 0) {
+        float m = fmaxf(fmaxf(s_red[0][0], s_red[0][1]), fmaxf(s_red[0][2], s_red[0][3]));
+        float z = 0.f, t = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) {
+            if (s_red[0][w] > -INFINITY) {
+                const float dlt = m - s_red[0][w];
+                const float sc = expf(-dlt);
+                z += sc * s_red[1][w];
+                t += sc * (s_red[2][w] + s_red[1][w] * dlt);
+            }
+        }
+        stats[static_cast<long>(row) * nunits + unit] = UnitStats{m, z, t, 0.f};
+    }
 }
 
 // Pass 1 for k > 1 (few rows, latency matters more than bandwidth): one WORKGROUP per slice, 4 logits per lane.
@@ -415,6 +511,9 @@ extern "C" int sage_entropy_topk(const void* logits, int dtype, int rows, int vo
         const dim3 grid(nunits, rows);
         if (dtype == SAGE_F32)
             hipLaunchKernelGGL(slice_topk_kernel<float>, grid, dim3(THREADS), 0, s, static_cast<const float*>(logits), vocab,
+                               row_stride, k, n_valid, rows_per_group, nunits, stats, keys);
+        else if (k <= FAST_MAX_K)
+            hipLaunchKernelGGL(slice_topk_bf16_kernel, grid, dim3(THREADS), 0, s, static_cast<const uint16_t*>(logits), vocab,
                                row_stride, k, n_valid, rows_per_group, nunits, stats, keys);
         else
             hipLaunchKernelGGL(slice_topk_kernel<uint16_t>, grid, dim3(THREADS), 0, s, static_cast<const uint16_t*>(logits),
