@@ -58,7 +58,7 @@ def parse():
 class Workload:
     """Device-resident synthetic inputs of one configuration plus every output/scratch buffer of a step."""
 
-    def __init__(self, name: str, slots: int | None):
+    def __init__(self, name: str, slots: int | None, fused: bool = True):
         import numpy as np
         import torch
         from paper_2602_00523_amd import sage, workloads as wl
@@ -157,6 +157,7 @@ class Workload:
         self.cur = 0
         self.step_no = 0
         self.ev_used = 0
+        self.fused = fused
         self._prepare()
         torch.cuda.synchronize()
 
@@ -164,25 +165,42 @@ class Workload:
     def _prepare(self, stream=None):
         """Marshal every call of a step once for the given stream (None = the current stream)."""
         sg = self.sage
-        self.c_a1 = [sg.prepare("sage_entropy_topk", self.draft[s], self.k, self.H, self.idx, self.prob, self.renorm,
-                                self.Hk, self.alpha, self.ws1, stream=stream) for s in range(self.slots)]
+        V = self.cfg["vocab"]
+        if self.fused:                               # the per-row top-k pass runs inside the call that consumes it
+            self.c_a1 = [sg.prepare("sage_entropy_topk_slices", self.draft[s], self.k, self.ws1, stream=stream)
+                         for s in range(self.slots)]
+        else:
+            self.c_a1 = [sg.prepare("sage_entropy_topk", self.draft[s], self.k, self.H, self.idx, self.prob, self.renorm,
+                                    self.Hk, self.alpha, self.ws1, stream=stream) for s in range(self.slots)]
         self.c_a2, self.c_a3, self.c_a1t, self.c_a4 = [], [], [], []
         for cur in range(2):
             t, nxt = self.tree[cur], self.tree[cur ^ 1]
-            self.c_a2.append(sg.prepare("sage_build_tree", self.renorm, self.alpha, self.prm, nxt["n_nodes"], nxt["parent"],
-                                        nxt["depth"], nxt["rank"], nxt["anc_mask"], None, self.idx, nxt["node_token"],
-                                        stream=stream))
+            if self.fused:
+                self.c_a2.append(sg.prepare("sage_build_tree_from_slices", self.ws1, V, self.prm, self.H, self.idx, self.prob,
+                                            self.renorm, self.Hk, self.alpha, nxt["n_nodes"], nxt["parent"], nxt["depth"],
+                                            nxt["rank"], nxt["anc_mask"], None, nxt["node_token"], stream=stream))
+            else:
+                self.c_a2.append(sg.prepare("sage_build_tree", self.renorm, self.alpha, self.prm, nxt["n_nodes"],
+                                            nxt["parent"], nxt["depth"], nxt["rank"], nxt["anc_mask"], None, self.idx,
+                                            nxt["node_token"], stream=stream))
             self.c_a3.append([[sg.prepare("sage_tree_attention", self.Q[s], self.Kc[s % self.kv_slots][layer],
                                           self.Vc[s % self.kv_slots][layer], self.Kt[s], self.Vt[s], self.O, self.kv_start,
                                           self.kv_len, self.max_len, self.Hkv * self.d, self.d, t["anc_mask"], t["n_nodes"],
                                           self.scale, self.ws3, stream=stream) for layer in range(self.layers)]
                               for s in range(self.slots)])
-            self.c_a1t.append([sg.prepare("sage_entropy_topk", self.target[s], 1, self.tH, self.tgt_idx, None, None, self.tHk,
-                                          self.talpha, self.ws1t, t["n_nodes"], MAX_NODES, stream=stream)
-                               for s in range(self.slots)])
-            self.c_a4.append(sg.prepare("sage_verify_accept", t["node_token"], self.tgt_idx, t["parent"], t["depth"],
-                                        t["anc_mask"], t["n_nodes"], self.path_cap, self.acc_len, self.best, self.path,
-                                        self.out_tok, stream=stream))
+            if self.fused:
+                self.c_a1t.append([sg.prepare("sage_entropy_topk_slices", self.target[s], 1, self.ws1t, t["n_nodes"], MAX_NODES,
+                                              stream=stream) for s in range(self.slots)])
+                self.c_a4.append(sg.prepare("sage_verify_accept_from_slices", self.ws1t, V, t["node_token"], t["parent"],
+                                            t["depth"], t["anc_mask"], t["n_nodes"], self.path_cap, self.tH, self.tgt_idx,
+                                            self.acc_len, self.best, self.path, self.out_tok, stream=stream))
+            else:
+                self.c_a1t.append([sg.prepare("sage_entropy_topk", self.target[s], 1, self.tH, self.tgt_idx, None, None,
+                                              self.tHk, self.talpha, self.ws1t, t["n_nodes"], MAX_NODES, stream=stream)
+                                   for s in range(self.slots)])
+                self.c_a4.append(sg.prepare("sage_verify_accept", t["node_token"], self.tgt_idx, t["parent"], t["depth"],
+                                            t["anc_mask"], t["n_nodes"], self.path_cap, self.acc_len, self.best, self.path,
+                                            self.out_tok, stream=stream))
 
     def draft_confidence(self, s):
         self.c_a1[s]()
@@ -411,7 +429,7 @@ def closed_loop(name="c2", steps=512):
     cache, the sequence length advances and the acceptance history adapts the maximum depth that the next tree may
     reach (Alg. 1 Phase 3; Sec. 3.3 adaptive history tracking).  One input-set cycle is captured as a HIP graph whose
     replays carry the state (cache, lengths, history, trees) forward; the final state of `steps` replayed steps is
-    checked against the same number of eager steps from the same start."""
+    checked against the same number of eager steps from the same start.  The top-k calls are the fused ones."""
     import torch
     w = Workload(name, None)
     sg, dev = w.sage, "cuda:0"
@@ -439,21 +457,22 @@ def closed_loop(name="c2", steps=512):
     acc_sum = torch.zeros(B, device=dev, dtype=torch.int32)
 
     def prep(stream):
-        c = dict(a1=[sg.prepare("sage_entropy_topk", w.draft[s], w.k, w.H, w.idx, w.prob, w.renorm, w.Hk, w.alpha, w.ws1,
-                                stream=stream) for s in range(w.slots)], a2=[], a3=[], a1t=[], a4=[], commit=[])
+        V = w.cfg["vocab"]
+        c = dict(a1=[sg.prepare("sage_entropy_topk_slices", w.draft[s], w.k, w.ws1, stream=stream) for s in range(w.slots)],
+                 a2=[], a3=[], a1t=[], a4=[], commit=[])
         for cur in range(2):
             t, nxt = w.tree[cur], w.tree[cur ^ 1]
-            c["a2"].append(sg.prepare("sage_build_tree", w.renorm, w.alpha, w.prm, nxt["n_nodes"], nxt["parent"], nxt["depth"],
-                                      nxt["rank"], nxt["anc_mask"], None, w.idx, nxt["node_token"], stream=stream,
-                                      d_max_seq=d_max))
+            c["a2"].append(sg.prepare("sage_build_tree_from_slices", w.ws1, V, w.prm, w.H, w.idx, w.prob, w.renorm, w.Hk, w.alpha,
+                                      nxt["n_nodes"], nxt["parent"], nxt["depth"], nxt["rank"], nxt["anc_mask"], None,
+                                      nxt["node_token"], stream=stream, d_max_seq=d_max))
             c["a3"].append([sg.prepare("sage_tree_attention", w.Q[s], Kc, Vc, w.Kt[s], w.Vt[s], w.O, kv_start, kv_len, cap,
                                        Hkv * d, d, t["anc_mask"], t["n_nodes"], w.scale, ws3, stream=stream)
                             for s in range(w.slots)])
-            c["a1t"].append([sg.prepare("sage_entropy_topk", w.target[s], 1, w.tH, w.tgt_idx, None, None, w.tHk, w.talpha,
-                                        w.ws1t, t["n_nodes"], MAX_NODES, stream=stream) for s in range(w.slots)])
-            c["a4"].append(sg.prepare("sage_verify_accept", t["node_token"], w.tgt_idx, t["parent"], t["depth"],
-                                      t["anc_mask"], t["n_nodes"], w.path_cap, w.acc_len, w.best, w.path, w.out_tok,
-                                      stream=stream))
+            c["a1t"].append([sg.prepare("sage_entropy_topk_slices", w.target[s], 1, w.ws1t, t["n_nodes"], MAX_NODES,
+                                        stream=stream) for s in range(w.slots)])
+            c["a4"].append(sg.prepare("sage_verify_accept_from_slices", w.ws1t, V, t["node_token"], t["parent"], t["depth"],
+                                      t["anc_mask"], t["n_nodes"], w.path_cap, w.tH, w.tgt_idx, w.acc_len, w.best, w.path,
+                                      w.out_tok, stream=stream))
         c["commit"] = [sg.prepare("sage_commit_path", w.Kt[s], w.Vt[s], Kc, Vc, kv_start, kv_len, cap, Hkv * d, d, w.path,
                                   w.acc_len, stream=stream) for s in range(w.slots)]
         c["advance"] = sg.prepare("sage_advance_kv_len", kv_len, w.acc_len, cap, stream=stream)
@@ -677,8 +696,18 @@ def main():
     steps = args.steps if args.steps is not None else defaults[args.workload][0]
     warmup = args.warmup if args.warmup is not None else defaults[args.workload][1]
 
-    w = Workload(args.workload, args.slots)
+    # the same steps through the five separate calls first (its final state is the reference for the fused run)
+    w = Workload(args.workload, args.slots, fused=False)
+    sep_wall, _ = time_steps(w, steps, warmup, not args.eager)
+    sep_state = snapshot(w)
+    sep_step_no = w.step_no
+    del w
+    torch.cuda.empty_cache()
+    w = Workload(args.workload, args.slots, fused=True)
     wall, graphed = time_steps(w, steps, warmup, not args.eager)
+    if w.step_no != sep_step_no or not all(torch.equal(a, b) for a, b in zip(snapshot(w), sep_state)):
+        print("bench.py: the fused calls and the separate calls ended in different states", file=sys.stderr)
+        sys.exit(4)
     att_ms, n_log, eager_wall = time_attention_launches(w, min(steps, 2000))
     ms_per_step = wall * 1e3 / steps
     att_avg_ms = sum(att_ms) / len(att_ms)
@@ -701,6 +730,10 @@ def main():
             "kv_len": [int(x) for x in w.kv_lens], "layers": w.layers, "batch": w.B, "input_sets": w.slots,
             "mean_tree_nodes": mean_nodes, "tree_params": w.tree_prm,
             "launch_mode": "HIP graph replay of whole input-set cycles" if graphed else "eager launches",
+            "calls_per_step": "sage_entropy_topk_slices, sage_build_tree_from_slices, sage_tree_attention x layers, "
+                              "sage_entropy_topk_slices, sage_verify_accept_from_slices (final state equal, bit for bit, "
+                              "to the same steps through the five separate calls)",
+            "separate_calls_steps_per_s": steps / sep_wall, "separate_calls_ms_per_step": sep_wall * 1e3 / steps,
             "eager_ms_per_step": eager_wall * 1e3 / len(n_log) * w.layers / w.layers},
         "roofline": {"bound": "hbm", "kernel": "sage_tree_attention (bf16 MFMA kernel + split merge, per layer launch)",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,

@@ -225,6 +225,43 @@ int sage_lm_head_topk(const void* hidden, const void* weight, int dtype, int row
                       float* topk_entropy, float* alpha,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * The step with two launches fewer.  A step (Alg. 1) is a chain of small dependent launches;
+ * each costs a few microseconds however little it computes.  sage_entropy_topk is two
+ * launches (per-slice pass, per-row pass); these calls split it so that the per-row pass runs
+ * inside the launch that consumes its result.  Results are bit-identical to the separate calls.
+ *
+ * sage_entropy_topk_slices: the per-slice pass of sage_entropy_topk only (Sec. 3.1 inputs:
+ * same logits / dtype / rows / vocab / row_stride / k / n_valid / rows_per_group arguments,
+ * same checks); leaves statistics and candidates in `workspace` (device,
+ * sage_entropy_topk_workspace_bytes(rows, vocab, k) bytes, layout private to the library),
+ * which must stay untouched until the consuming call below has run on the same stream.
+ *
+ * sage_build_tree_from_slices: finishes Eq. 7-9 for B draft rows (one per sequence: slices
+ * filled with rows = B and this vocab and k) and builds each sequence's tree (Sec. 3.2) in
+ * the same launch.  Outputs: those of sage_entropy_topk ([B] / [B,k]; topk_idx required, the
+ * others nullable) and those of sage_build_tree (node_token nullable; cum_prob nullable).
+ *
+ * sage_verify_accept_from_slices: finishes the k = 1 reduction of the B * 64 target rows
+ * (slices filled with rows = B * 64, k = 1, n_valid = n_nodes, rows_per_group = 64) and
+ * applies the acceptance rule (Sec. 2.2, Sec. 3.3 Phase 2).  Outputs: target_argmax [B,64]
+ * (required), entropy [B,64] (nullable; full-vocabulary entropy of each live target row) and
+ * those of sage_verify_accept.  Rows of nodes >= n_nodes[b] are neither read nor written.
+ * Errors as for the calls they replace; `slices` 16-byte aligned.
+ */
+int sage_entropy_topk_slices(const void* logits, int dtype, int rows, int vocab, long row_stride, int k,
+                             const int* n_valid, int rows_per_group, void* workspace, size_t workspace_bytes,
+                             void* stream);
+int sage_build_tree_from_slices(void* slices, int vocab, int B, int k, const sage_tree_params* params,
+                                const int* d_max_seq, float* entropy, int* topk_idx, float* topk_prob,
+                                float* topk_renorm, float* topk_entropy, float* alpha, int* n_nodes, int* parent,
+                                int* depth, int* rank, uint64_t* anc_mask, float* cum_prob, int* node_token,
+                                void* stream);
+int sage_verify_accept_from_slices(void* slices, int vocab, const int* token, const int* parent, const int* depth,
+                                   const uint64_t* anc_mask, const int* n_nodes, int B, int path_cap,
+                                   float* entropy, int* target_argmax, int* accept_len, int* best_node,
+                                   int* path_nodes, int* out_tokens, void* stream);
+
 /* Library build identification (host): returns a static string naming the target architecture. */
 const char* sage_build_info(void);
 

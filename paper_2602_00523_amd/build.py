@@ -13,7 +13,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsage_hip.so")
 
 SOURCES = ["entropy_topk.hip", "build_tree.hip", "tree_attention.hip", "tree_attention_f32.hip",
-           "tree_attention_bf16.hip", "verify_accept.hip", "commit_history.hip", "lm_head_topk.hip"]
+           "tree_attention_bf16.hip", "verify_accept.hip", "commit_history.hip", "lm_head_topk.hip", "fused_steps.hip"]
 # packed-fp32 instructions are switched off for every translation unit; the tree rule additionally forbids
 # contraction so that its fp32 decisions are reproducible bit for bit.
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-Xclang", "-target-feature", "-Xclang",

@@ -11,6 +11,7 @@
 // a k-round tournament over the list heads (lists staged in LDS), and evaluates Eq. 7-9 on the k winners.
 #include "sage_internal.h"
 #include "topk_common.h"
+#include "topk_device.h"
 
 using namespace sage::topk;
 
@@ -20,57 +21,6 @@ constexpr int THREADS = 256;
 constexpr int EPT = 16;                  // logits per lane
 constexpr int UNIT = 64 * EPT;           // logits per wave
 constexpr int WAVES = THREADS / 64;
-constexpr int MERGE_LDS_KEYS = 6144;     // lists are staged in LDS when they fit (48 KB)
-constexpr int MAX_OWN = 16;              // lists per lane in pass 2: up to 1024 slices = 1M logits
-
-// Wave-wide maximum, result in every lane: four rotations inside each row of 16 lanes, then the 16-lane and
-// 32-lane swaps combine the four rows.  A key is reduced in two passes: the value code first, then the index
-// code among the lanes that hold the winning value.
-template <int CTRL> __device__ __forceinline__ uint32_t u_dpp(uint32_t v) {
-    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, false));
-}
-__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
-    v = max(v, u_dpp<0x128>(v));         // row_ror:8
-    v = max(v, u_dpp<0x124>(v));         // row_ror:4
-    v = max(v, u_dpp<0x122>(v));         // row_ror:2
-    v = max(v, u_dpp<0x121>(v));         // row_ror:1
-    auto a = __builtin_amdgcn_permlane16_swap(v, v, false, false);
-    v = max(a[0], a[1]);
-    a = __builtin_amdgcn_permlane32_swap(v, v, false, false);
-    return max(a[0], a[1]);
-}
-__device__ __forceinline__ Key wave_max_key(Key k) {
-    const uint32_t hi = wave_max_u32(k.hi);
-    const uint64_t holders = __ballot(k.hi == hi);
-    uint32_t lo;
-    if (__builtin_popcountll(holders) == 1)          // the usual case: no second reduction, just fetch the winner's index
-        lo = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(k.lo), __builtin_ctzll(holders)));
-    else
-        lo = wave_max_u32(k.hi == hi ? k.lo : 0u);
-    return Key{hi, lo};
-}
-template <int CTRL> __device__ __forceinline__ float f_dpp(float v) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
-}
-__device__ __forceinline__ float wave_sum(float v) {
-    v += f_dpp<0x128>(v); v += f_dpp<0x124>(v); v += f_dpp<0x122>(v); v += f_dpp<0x121>(v);
-    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
-    a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    return __uint_as_float(a[0]) + __uint_as_float(a[1]);
-}
-__device__ __forceinline__ float wave_max(float v) {
-    v = fmaxf(v, f_dpp<0x128>(v)); v = fmaxf(v, f_dpp<0x124>(v)); v = fmaxf(v, f_dpp<0x122>(v)); v = fmaxf(v, f_dpp<0x121>(v));
-    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
-    a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    return fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
-}
-
-__device__ __forceinline__ bool row_is_valid(int row, const int* n_valid, int rows_per_group) {
-    if (!n_valid) return true;
-    return (row % rows_per_group) < n_valid[row / rows_per_group];
-}
 
 template <typename T> struct Loader;
 template <> struct Loader<float> {
@@ -344,108 +294,18 @@ __global__ __launch_bounds__(THREADS) void slice_topk_kernel(const T* __restrict
     }
 }
 
-// Pass 2: one wave per row: combine slice statistics, k-way merge of the per-slice sorted key lists, Eq. 7-9.
-// OWN = lists per lane (lane owns lists lane, lane+64, ...); the head of every owned list stays in registers and
-// only the lane whose list wins a round fetches its next entry.
+// Pass 2 as a launch of its own: one workgroup per row (see merge_row).
 template <int OWN>
-__global__ __launch_bounds__(THREADS) void merge_kernel(int k, const int* __restrict__ n_valid, int rows_per_group, int nunits,
-                                                        const UnitStats* __restrict__ stats, const uint64_t* __restrict__ keys,
-                                                        float* __restrict__ entropy, int* __restrict__ topk_idx,
-                                                        float* __restrict__ topk_prob, float* __restrict__ topk_renorm,
-                                                        float* __restrict__ topk_entropy, float* __restrict__ alpha) {
-    __shared__ uint64_t s_keys[MERGE_LDS_KEYS];
-    __shared__ UnitStats s_stats[64 * OWN];
+__global__ __launch_bounds__(MERGE_THREADS) void merge_kernel(int k, const int* __restrict__ n_valid, int rows_per_group, int nunits,
+                                                              const UnitStats* __restrict__ stats, const uint64_t* __restrict__ keys,
+                                                              float* __restrict__ entropy, int* __restrict__ topk_idx,
+                                                              float* __restrict__ topk_prob, float* __restrict__ topk_renorm,
+                                                              float* __restrict__ topk_entropy, float* __restrict__ alpha) {
+    __shared__ MergeShared<OWN> sh;
     const int row = blockIdx.x;
     if (!row_is_valid(row, n_valid, rows_per_group)) return;
-    const int tid = threadIdx.x;
-    const UnitStats* st = stats + static_cast<long>(row) * nunits;
-    const uint64_t* kk = keys + static_cast<long>(row) * nunits * k;
-    const int total = nunits * k;
-    const bool in_lds = total <= MERGE_LDS_KEYS;
-    // ---- the whole workgroup stages statistics and lists in LDS, eight independent loads per thread at a time
-    for (int c = tid; c < nunits; c += THREADS) s_stats[c] = st[c];
-    if (in_lds) {
-        for (int i0 = tid; i0 < total; i0 += THREADS * 8) {
-            uint64_t tmp[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) tmp[j] = (i0 + j * THREADS < total) ? kk[i0 + j * THREADS] : 0;
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (i0 + j * THREADS < total) s_keys[i0 + j * THREADS] = tmp[j];
-        }
-    }
-    __syncthreads();
-    if (tid >= 64) return;                           // wave 0 finishes the row
-    const int lane = tid;
-
-    Key head[OWN];
-    int cursor[OWN];
-#pragma unroll
-    for (int i = 0; i < OWN; ++i) {
-        const int c = lane + 64 * i;
-        head[i] = c < nunits ? key_unpack(in_lds ? s_keys[c * k] : kk[static_cast<long>(c) * k]) : Key{0, 0};
-        cursor[i] = 0;
-    }
-    float m = -INFINITY;
-#pragma unroll
-    for (int i = 0; i < OWN; ++i)
-        if (lane + 64 * i < nunits) m = fmaxf(m, s_stats[lane + 64 * i].m);
-    m = wave_max(m);
-    float Z = 0.f, Tm = 0.f;
-#pragma unroll
-    for (int i = 0; i < OWN; ++i) {
-        if (lane + 64 * i < nunits) {
-            const UnitStats u = s_stats[lane + 64 * i];
-            if (u.m > -INFINITY) {
-                const float dlt = m - u.m;
-                const float w = expf(-dlt);
-                Z += w * u.Z;
-                Tm += w * (u.T + u.Z * dlt);
-            }
-        }
-    }
-    Z = wave_sum(Z);
-    Tm = wave_sum(Tm);
-    if (lane == 0 && entropy) entropy[row] = logf(Z) + Tm / Z;
-
-    Key mine = Key{0, 0};                            // lane j keeps winner j
-    for (int round = 0; round < k; ++round) {
-        Key best = head[0];
-#pragma unroll
-        for (int i = 1; i < OWN; ++i) best = key_max(best, head[i]);
-        const Key g = wave_max_key(best);
-        if (lane == round) mine = g;
-        if (!key_none(g) && key_equal(best, g) && round + 1 < k) {   // the owning lane advances the winning list
-#pragma unroll
-            for (int i = 0; i < OWN; ++i) {
-                if (key_equal(head[i], g)) {
-                    const int nxt = ++cursor[i];
-                    const long at = static_cast<long>(lane + 64 * i) * k + nxt;
-                    head[i] = nxt < k ? key_unpack(in_lds ? s_keys[at] : kk[at]) : Key{0, 0};
-                }
-            }
-        }
-    }
-
-    const bool have = lane < k;
-    const float x = have ? key_value(mine) : -INFINITY;
-    const float p = have ? expf(x - m) / Z : 0.f;
-    const float mass = wave_sum(p);
-    const float q = have ? p / mass : 0.f;
-    const float hk = wave_sum(q > 0.f ? -q * logf(q) : 0.f);
-    if (have) {
-        const long o = static_cast<long>(row) * k + lane;
-        topk_idx[o] = key_index(mine);
-        if (topk_prob) topk_prob[o] = p;
-        if (topk_renorm) topk_renorm[o] = q;
-    }
-    if (lane == 0) {
-        if (topk_entropy) topk_entropy[row] = hk;
-        if (alpha) {
-            float a = (k == 1) ? 1.0f : 1.0f - hk / logf(static_cast<float>(k));
-            alpha[row] = fminf(fmaxf(a, 0.0f), 1.0f);
-        }
-    }
+    MergedRow r;
+    merge_row<OWN>(row, k, nunits, stats, keys, sh, entropy, topk_idx, topk_prob, topk_renorm, topk_entropy, alpha, r);
 }
 
 inline int num_units(int vocab) { return (vocab + UNIT - 1) / UNIT; }
@@ -465,10 +325,10 @@ void topk_merge(int rows, int k, const int* n_valid, int rows_per_group, int nun
                 const uint64_t* keys, float* entropy, int* topk_idx, float* topk_prob, float* topk_renorm,
                 float* topk_entropy, float* alpha, hipStream_t s) {
     if (nunits <= 256)
-        hipLaunchKernelGGL(merge_kernel<4>, dim3(rows), dim3(THREADS), 0, s, k, n_valid, rows_per_group, nunits, stats, keys,
+        hipLaunchKernelGGL(merge_kernel<4>, dim3(rows), dim3(MERGE_THREADS), 0, s, k, n_valid, rows_per_group, nunits, stats, keys,
                            entropy, topk_idx, topk_prob, topk_renorm, topk_entropy, alpha);
     else
-        hipLaunchKernelGGL(merge_kernel<MAX_OWN>, dim3(rows), dim3(THREADS), 0, s, k, n_valid, rows_per_group, nunits, stats,
+        hipLaunchKernelGGL(merge_kernel<MAX_OWN>, dim3(rows), dim3(MERGE_THREADS), 0, s, k, n_valid, rows_per_group, nunits, stats,
                            keys, entropy, topk_idx, topk_prob, topk_renorm, topk_entropy, alpha);
 }
 
@@ -479,11 +339,21 @@ extern "C" size_t sage_entropy_topk_workspace_bytes(int rows, int vocab, int k) 
     return stats_bytes(rows, vocab) + static_cast<size_t>(rows) * num_units(vocab) * k * sizeof(uint64_t) + 256;
 }
 
-extern "C" int sage_entropy_topk(const void* logits, int dtype, int rows, int vocab, long row_stride, int k,
-                                 const int* n_valid, int rows_per_group, float* entropy, int* topk_idx,
-                                 float* topk_prob, float* topk_renorm, float* topk_entropy, float* alpha,
-                                 void* workspace, size_t workspace_bytes, void* stream) {
-    if (!logits || !topk_idx || !workspace) return SAGE_INVALID_ARG;
+namespace sage {
+
+// Where the first pass leaves its results inside a workspace of sage_entropy_topk_workspace_bytes(rows, vocab, k).
+void topk_workspace_layout(int rows, int vocab, void* workspace, UnitStats** stats, uint64_t** keys, int* nunits) {
+    *stats = static_cast<UnitStats*>(workspace);
+    *keys = reinterpret_cast<uint64_t*>(static_cast<char*>(workspace) + stats_bytes(rows, vocab));
+    *nunits = num_units(vocab);
+}
+
+}  // namespace sage
+
+// Argument checks and the first pass, common to sage_entropy_topk and sage_entropy_topk_slices.
+static int run_first_pass(const void* logits, int dtype, int rows, int vocab, long row_stride, int k, const int* n_valid,
+                          int rows_per_group, void* workspace, size_t workspace_bytes, hipStream_t s) {
+    if (!logits || !workspace) return SAGE_INVALID_ARG;
     if (rows < 0 || vocab < 1 || k < 1 || k > SAGE_MAX_TOPK || k > vocab || row_stride < vocab) return SAGE_INVALID_ARG;
     if (dtype != SAGE_F32 && dtype != SAGE_BF16) return SAGE_INVALID_ARG;
     if (n_valid && rows_per_group < 1) return SAGE_INVALID_ARG;
@@ -498,7 +368,6 @@ extern "C" int sage_entropy_topk(const void* logits, int dtype, int rows, int vo
 
     UnitStats* stats = static_cast<UnitStats*>(workspace);
     uint64_t* keys = reinterpret_cast<uint64_t*>(static_cast<char*>(workspace) + stats_bytes(rows, vocab));
-    hipStream_t s = sage::as_stream(stream);
     if (k == 1) {                                    // many rows, one round: a wave per slice, 16 logits per lane
         const dim3 grid((nunits + WAVES - 1) / WAVES, rows);
         if (dtype == SAGE_F32)
@@ -519,8 +388,29 @@ extern "C" int sage_entropy_topk(const void* logits, int dtype, int rows, int vo
             hipLaunchKernelGGL(slice_topk_kernel<uint16_t>, grid, dim3(THREADS), 0, s, static_cast<const uint16_t*>(logits),
                                vocab, row_stride, k, n_valid, rows_per_group, nunits, stats, keys);
     }
-    if (hipGetLastError() != hipSuccess) return SAGE_LAUNCH_FAILED;
+    return sage::launch_status();
+}
+
+extern "C" int sage_entropy_topk(const void* logits, int dtype, int rows, int vocab, long row_stride, int k,
+                                 const int* n_valid, int rows_per_group, float* entropy, int* topk_idx,
+                                 float* topk_prob, float* topk_renorm, float* topk_entropy, float* alpha,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+    if (!topk_idx) return SAGE_INVALID_ARG;
+    hipStream_t s = sage::as_stream(stream);
+    const int rc = run_first_pass(logits, dtype, rows, vocab, row_stride, k, n_valid, rows_per_group, workspace, workspace_bytes, s);
+    if (rc != SAGE_OK || rows == 0) return rc;
+    UnitStats* stats;
+    uint64_t* keys;
+    int nunits;
+    sage::topk_workspace_layout(rows, vocab, workspace, &stats, &keys, &nunits);
     sage::topk_merge(rows, k, n_valid, rows_per_group, nunits, stats, keys, entropy, topk_idx, topk_prob, topk_renorm,
                      topk_entropy, alpha, s);
     return sage::launch_status();
+}
+
+extern "C" int sage_entropy_topk_slices(const void* logits, int dtype, int rows, int vocab, long row_stride, int k,
+                                        const int* n_valid, int rows_per_group, void* workspace, size_t workspace_bytes,
+                                        void* stream) {
+    return run_first_pass(logits, dtype, rows, vocab, row_stride, k, n_valid, rows_per_group, workspace, workspace_bytes,
+                          sage::as_stream(stream));
 }

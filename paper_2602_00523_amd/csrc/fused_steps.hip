@@ -1,0 +1,196 @@
+// The second pass of sage_entropy_topk folded into the launch that consumes its result.  A step of the method is a
+// chain of small dependent launches (Alg. 1: plan the tree from the draft distribution, verify, accept), each of which
+// costs a few microseconds of launch and memory latency however little it computes; these entry points remove two of
+// them without changing a single result:
+//   sage_build_tree_from_slices     = second pass over the draft rows (Eq. 7-9) + the tree rule (Sec. 3.2, Eq. 10-12),
+//   sage_verify_accept_from_slices  = second pass over the target rows (greedy token per node, Sec. 2.2) + acceptance.
+// Both read the workspace that sage_entropy_topk_slices filled and run exactly the device code of the separate calls
+// (topk_device.h, build_tree_device.h, verify_accept_device.h), so their outputs are bit-identical to the unfused
+// sequence sage_entropy_topk -> sage_build_tree / sage_verify_accept.
+#include "build_tree_device.h"
+#include "topk_device.h"
+#include "verify_accept_device.h"
+
+using namespace sage::topk;
+
+namespace {
+
+// One workgroup per sequence: merge the sequence's draft row, then wave 0 builds its tree from the winners it holds.
+template <int OWN>
+__global__ __launch_bounds__(MERGE_THREADS) void plan_kernel(int k, int nunits, const UnitStats* __restrict__ stats,
+                                                             const uint64_t* __restrict__ keys, float* __restrict__ entropy,
+                                                             int* __restrict__ topk_idx, float* __restrict__ topk_prob,
+                                                             float* __restrict__ topk_renorm, float* __restrict__ topk_entropy,
+                                                             float* __restrict__ alpha, sage_tree_params prm,
+                                                             const int* __restrict__ d_max_seq, int* __restrict__ n_nodes,
+                                                             int* __restrict__ parent, int* __restrict__ depth,
+                                                             int* __restrict__ rank, uint64_t* __restrict__ anc_mask,
+                                                             float* __restrict__ cum_prob, int* __restrict__ node_token) {
+    __shared__ MergeShared<OWN> sh;
+    const int b = blockIdx.x;
+    MergedRow r;
+    if (!merge_row<OWN>(b, k, nunits, stats, keys, sh, entropy, topk_idx, topk_prob, topk_renorm, topk_entropy, alpha, r)) return;
+    const int lane = threadIdx.x;
+    sage::tree::build_tree_wave(b, lane, lane < k ? r.q : 0.0f, lane < k ? r.idx : -1, r.alpha, k, prm, d_max_seq, n_nodes, parent,
+                                depth, rank, anc_mask, cum_prob, node_token);
+}
+
+// One workgroup of 16 waves per sequence.  Wave w finishes the k = 1 reduction of the target rows of nodes w, w+16, ...
+// (log-sum-exp of the slice statistics in the order merge_row uses, maximum of the slice candidates); the greedy tokens
+// meet in LDS and wave 0 runs the acceptance rule on them.
+constexpr int ACCEPT_WAVES = 16;
+constexpr int ROWS_PER_WAVE = SAGE_MAX_NODES / ACCEPT_WAVES;
+template <int OWN>
+__global__ __launch_bounds__(64 * ACCEPT_WAVES) void accept_kernel(int nunits, const UnitStats* __restrict__ stats,
+                                                                   const uint64_t* __restrict__ keys,
+                                                                   const int* __restrict__ token, const int* __restrict__ parent,
+                                                                   const int* __restrict__ depth,
+                                                                   const uint64_t* __restrict__ anc_mask,
+                                                                   const int* __restrict__ n_nodes, int path_cap,
+                                                                   float* __restrict__ entropy, int* __restrict__ target_argmax,
+                                                                   int* __restrict__ accept_len, int* __restrict__ best_node,
+                                                                   int* __restrict__ path_nodes, int* __restrict__ out_tokens) {
+    __shared__ int s_tgt[SAGE_MAX_NODES];
+    __shared__ sage::accept::AcceptShared sh;
+    const int b = blockIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const long base = static_cast<long>(b) * SAGE_MAX_NODES;
+    int n = n_nodes[b];
+    n = n < 1 ? 1 : (n > SAGE_MAX_NODES ? SAGE_MAX_NODES : n);
+
+    // wave 0 asks for its node fields now, so they arrive while the reductions run
+    int par = -1, tok = 0, dep = 0;
+    uint64_t am = 0;
+    if (wave == 0 && lane < n) {
+        par = parent[base + lane];
+        tok = token[base + lane];
+        dep = depth[base + lane];
+        am = anc_mask[base + lane];
+    }
+
+    // ---- with few lists per lane all of this wave's rows are requested before the first one is reduced (one memory
+    //      round trip); with many, a row at a time, to stay within the register file
+    constexpr bool AHEAD = OWN <= 4;
+    constexpr int HELD = AHEAD ? ROWS_PER_WAVE : 1;
+    UnitStats st[HELD][OWN];
+    uint64_t ky[HELD][OWN];
+    auto request = [&](int j, int slot) __attribute__((always_inline)) {
+        const int node = wave + j * ACCEPT_WAVES;
+        const long row = base + node;
+#pragma unroll
+        for (int i = 0; i < OWN; ++i) {
+            const int c = lane + 64 * i;
+            const bool live = node < n && c < nunits;
+            st[slot][i] = live ? stats[row * nunits + c] : UnitStats{-INFINITY, 0.f, 0.f, 0.f};
+            ky[slot][i] = live ? keys[row * nunits + c] : 0ull;
+        }
+    };
+    if (AHEAD) {
+#pragma unroll
+        for (int j = 0; j < ROWS_PER_WAVE; ++j) request(j, j);
+    }
+#pragma unroll
+    for (int jj = 0; jj < ROWS_PER_WAVE; ++jj) {
+        const int node = wave + jj * ACCEPT_WAVES;
+        if (node >= n) continue;                     // wave-uniform
+        if (!AHEAD) request(jj, 0);
+        const int j = AHEAD ? jj : 0;
+        float m = -INFINITY;
+#pragma unroll
+        for (int i = 0; i < OWN; ++i)
+            if (lane + 64 * i < nunits) m = fmaxf(m, st[j][i].m);
+        m = wave_max(m);
+        float Z = 0.f, Tm = 0.f;
+#pragma unroll
+        for (int i = 0; i < OWN; ++i) {
+            if (lane + 64 * i < nunits) {
+                const UnitStats u = st[j][i];
+                if (u.m > -INFINITY) {
+                    const float dlt = m - u.m;
+                    const float w = expf(-dlt);
+                    Z += w * u.Z;
+                    Tm += w * (u.T + u.Z * dlt);
+                }
+            }
+        }
+        Z = wave_sum(Z);
+        Tm = wave_sum(Tm);
+        Key best = key_unpack(ky[j][0]);
+#pragma unroll
+        for (int i = 1; i < OWN; ++i) best = key_max(best, key_unpack(ky[j][i]));
+        const Key g = wave_max_key(best);
+        if (lane == 0) {
+            const int idx = key_index(g);
+            s_tgt[node] = idx;
+            target_argmax[base + node] = idx;
+            if (entropy) entropy[base + node] = logf(Z) + Tm / Z;
+        }
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    const int tgt = lane < n ? s_tgt[lane] : 0;
+    const int tgt_par = (lane < n && par >= 0 && par < n) ? s_tgt[par] : 0;
+    sage::accept::verify_accept_wave(b, lane, n, par, tok, dep, am, tgt, tgt_par, path_cap, sh, accept_len, best_node, path_nodes,
+                                     out_tokens);
+}
+
+}  // namespace
+
+extern "C" int sage_build_tree_from_slices(void* slices, int vocab, int B, int k, const sage_tree_params* params,
+                                           const int* d_max_seq, float* entropy, int* topk_idx, float* topk_prob,
+                                           float* topk_renorm, float* topk_entropy, float* alpha, int* n_nodes, int* parent,
+                                           int* depth, int* rank, uint64_t* anc_mask, float* cum_prob, int* node_token,
+                                           void* stream) {
+    if (!slices || !params || !topk_idx || !n_nodes || !parent || !depth || !rank || !anc_mask) return SAGE_INVALID_ARG;
+    const sage_tree_params p = *params;
+    if (B < 0 || vocab < 1 || k != p.k || k < 1 || k > SAGE_MAX_TOPK || k > vocab) return SAGE_INVALID_ARG;
+    if (p.n_max < 1 || p.n_max > SAGE_MAX_NODES) return SAGE_INVALID_ARG;
+    if (p.d_min < 1 || p.d_min > p.d_max || p.d_max > SAGE_MAX_DEPTH) return SAGE_INVALID_ARG;
+    if (p.w_min < 1 || p.w_min > p.w_max || p.w_max > k) return SAGE_INVALID_ARG;
+    if (!sage::aligned(slices, 16)) return SAGE_INVALID_ARG;
+    if (B > 65535) return SAGE_UNSUPPORTED;
+    UnitStats* stats;
+    uint64_t* keys;
+    int nunits;
+    sage::topk_workspace_layout(B, vocab, slices, &stats, &keys, &nunits);
+    if (nunits > sage::topk_max_units()) return SAGE_UNSUPPORTED;
+    if (B == 0) return SAGE_OK;
+    hipStream_t s = sage::as_stream(stream);
+    if (nunits <= 256)
+        hipLaunchKernelGGL(plan_kernel<4>, dim3(B), dim3(MERGE_THREADS), 0, s, k, nunits, stats, keys, entropy, topk_idx, topk_prob,
+                           topk_renorm, topk_entropy, alpha, p, d_max_seq, n_nodes, parent, depth, rank, anc_mask, cum_prob,
+                           node_token);
+    else
+        hipLaunchKernelGGL(plan_kernel<MAX_OWN>, dim3(B), dim3(MERGE_THREADS), 0, s, k, nunits, stats, keys, entropy, topk_idx,
+                           topk_prob, topk_renorm, topk_entropy, alpha, p, d_max_seq, n_nodes, parent, depth, rank, anc_mask,
+                           cum_prob, node_token);
+    return sage::launch_status();
+}
+
+extern "C" int sage_verify_accept_from_slices(void* slices, int vocab, const int* token, const int* parent, const int* depth,
+                                              const uint64_t* anc_mask, const int* n_nodes, int B, int path_cap,
+                                              float* entropy, int* target_argmax, int* accept_len, int* best_node,
+                                              int* path_nodes, int* out_tokens, void* stream) {
+    if (!slices || !token || !parent || !depth || !anc_mask || !n_nodes || !target_argmax || !accept_len || !best_node ||
+        !path_nodes || !out_tokens)
+        return SAGE_INVALID_ARG;
+    if (B < 0 || vocab < 1 || path_cap < 1) return SAGE_INVALID_ARG;
+    if (!sage::aligned(slices, 16)) return SAGE_INVALID_ARG;
+    if (static_cast<long>(B) * SAGE_MAX_NODES > 65535) return SAGE_UNSUPPORTED;   // the limit of the call that fills `slices`
+    UnitStats* stats;
+    uint64_t* keys;
+    int nunits;
+    sage::topk_workspace_layout(B * SAGE_MAX_NODES, vocab, slices, &stats, &keys, &nunits);
+    if (nunits > sage::topk_max_units()) return SAGE_UNSUPPORTED;
+    if (B == 0) return SAGE_OK;
+    hipStream_t s = sage::as_stream(stream);
+    if (nunits <= 256)
+        hipLaunchKernelGGL(accept_kernel<4>, dim3(B), dim3(64 * ACCEPT_WAVES), 0, s, nunits, stats, keys, token, parent, depth,
+                           anc_mask, n_nodes, path_cap, entropy, target_argmax, accept_len, best_node, path_nodes, out_tokens);
+    else
+        hipLaunchKernelGGL(accept_kernel<MAX_OWN>, dim3(B), dim3(64 * ACCEPT_WAVES), 0, s, nunits, stats, keys, token, parent,
+                           depth, anc_mask, n_nodes, path_cap, entropy, target_argmax, accept_len, best_node, path_nodes,
+                           out_tokens);
+    return sage::launch_status();
+}

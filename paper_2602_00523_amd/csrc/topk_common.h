@@ -35,6 +35,7 @@ __host__ __device__ __forceinline__ Key key_unpack(uint64_t v) { return Key{stat
 }  // namespace topk
 
 int topk_max_units();
+void topk_workspace_layout(int rows, int vocab, void* workspace, topk::UnitStats** stats, uint64_t** keys, int* nunits);
 void topk_merge(int rows, int k, const int* n_valid, int rows_per_group, int nunits, const topk::UnitStats* stats,
                 const uint64_t* keys, float* entropy, int* topk_idx, float* topk_prob, float* topk_renorm,
                 float* topk_entropy, float* alpha, hipStream_t s);

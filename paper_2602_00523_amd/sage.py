@@ -59,6 +59,12 @@ def lib():
         L.sage_update_history.restype = _ci
         L.sage_update_history.argtypes = [_vp, _ci, _ci, _cf, _cf, _ci, _ci, _vp, _vp, _vp, _vp, _vp]
         L.sage_lm_head_topk_workspace_bytes.restype = _sz
+        L.sage_entropy_topk_slices.restype = _ci
+        L.sage_entropy_topk_slices.argtypes = [_vp, _ci, _ci, _ci, _cl, _ci, _vp, _ci, _vp, _sz, _vp]
+        L.sage_build_tree_from_slices.restype = _ci
+        L.sage_build_tree_from_slices.argtypes = [_vp, _ci, _ci, _ci, ctypes.POINTER(TreeParams)] + [_vp] * 15
+        L.sage_verify_accept_from_slices.restype = _ci
+        L.sage_verify_accept_from_slices.argtypes = [_vp, _ci, _vp, _vp, _vp, _vp, _vp, _ci, _ci] + [_vp] * 7
         L.sage_lm_head_topk_workspace_bytes.argtypes = [_ci, _ci]
         L.sage_lm_head_topk.restype = _ci
         L.sage_lm_head_topk.argtypes = [_vp, _vp, _ci, _ci, _ci, _ci, _cl, _cl, _ci, _vp, _ci, _vp, _vp, _vp, _vp, _vp, _vp,
@@ -170,7 +176,34 @@ def _args_lm_head_topk(hidden, weight, k, entropy, topk_idx, topk_prob, topk_ren
             _ptr(topk_entropy), _ptr(alpha), _ptr(workspace), _nbytes(workspace), _stream(stream)]
 
 
-_MARSHAL = {"sage_entropy_topk": _args_entropy_topk, "sage_build_tree": _args_build_tree,
+def _args_entropy_topk_slices(logits, k, workspace, n_valid=None, rows_per_group=1, stream=None):
+    rows, vocab = logits.shape
+    assert logits.stride(1) == 1
+    return [_ptr(logits), _dtype_code(logits), rows, vocab, logits.stride(0), k, _ptr(n_valid), rows_per_group,
+            _ptr(workspace), _nbytes(workspace), _stream(stream)]
+
+
+def _args_build_tree_from_slices(slices, vocab, params: TreeParams, entropy, topk_idx, topk_prob, topk_renorm, topk_entropy,
+                                 alpha, n_nodes, parent, depth, rank, anc_mask, cum_prob=None, node_token=None, stream=None,
+                                 d_max_seq=None):
+    B, k = topk_idx.shape
+    return [_ptr(slices), vocab, B, k, ctypes.byref(params), _ptr(d_max_seq), _ptr(entropy), _ptr(topk_idx), _ptr(topk_prob),
+            _ptr(topk_renorm), _ptr(topk_entropy), _ptr(alpha), _ptr(n_nodes), _ptr(parent), _ptr(depth), _ptr(rank),
+            _ptr(anc_mask), _ptr(cum_prob), _ptr(node_token), _stream(stream)]
+
+
+def _args_verify_accept_from_slices(slices, vocab, token, parent, depth, anc_mask, n_nodes, path_cap, entropy, target_argmax,
+                                    accept_len, best_node, path_nodes, out_tokens, stream=None):
+    B = n_nodes.shape[0]
+    return [_ptr(slices), vocab, _ptr(token), _ptr(parent), _ptr(depth), _ptr(anc_mask), _ptr(n_nodes), B, path_cap,
+            _ptr(entropy), _ptr(target_argmax), _ptr(accept_len), _ptr(best_node), _ptr(path_nodes), _ptr(out_tokens),
+            _stream(stream)]
+
+
+_MARSHAL = {"sage_entropy_topk_slices": _args_entropy_topk_slices,
+            "sage_build_tree_from_slices": _args_build_tree_from_slices,
+            "sage_verify_accept_from_slices": _args_verify_accept_from_slices,
+            "sage_entropy_topk": _args_entropy_topk, "sage_build_tree": _args_build_tree,
             "sage_tree_attention": _args_tree_attention, "sage_verify_accept": _args_verify_accept,
             "sage_commit_path": _args_commit_path, "sage_advance_kv_len": _args_advance_kv_len,
             "sage_update_history": _args_update_history, "sage_lm_head_topk": _args_lm_head_topk}
@@ -206,6 +239,19 @@ def sage_update_history(*a, **kw):
 
 def sage_lm_head_topk(*a, **kw):
     _check("sage_lm_head_topk", lib().sage_lm_head_topk(*_args_lm_head_topk(*a, **kw)))
+
+
+def sage_entropy_topk_slices(*a, **kw):
+    _check("sage_entropy_topk_slices", lib().sage_entropy_topk_slices(*_args_entropy_topk_slices(*a, **kw)))
+
+
+def sage_build_tree_from_slices(*a, **kw):
+    _check("sage_build_tree_from_slices", lib().sage_build_tree_from_slices(*_args_build_tree_from_slices(*a, **kw)))
+
+
+def sage_verify_accept_from_slices(*a, **kw):
+    _check("sage_verify_accept_from_slices",
+           lib().sage_verify_accept_from_slices(*_args_verify_accept_from_slices(*a, **kw)))
 
 
 def prepare(name: str, *a, **kw):

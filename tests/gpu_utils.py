@@ -151,3 +151,50 @@ def gpu_lm_head_topk(hidden_np, weight_np, k, n_valid=None, rows_per_group=1):
                            out["topk_entropy"], out["alpha"], ws, nv, rows_per_group)
     torch.cuda.synchronize()
     return {key: v.cpu().numpy() for key, v in out.items()}
+
+
+def gpu_plan_from_slices(logits_np, k, prm: dict, d_max_seq_np=None):
+    """sage_entropy_topk_slices + sage_build_tree_from_slices on B draft rows: the outputs of both separate calls."""
+    x = to_dev(logits_np)
+    B, vocab = x.shape
+    f = lambda *s: torch.full(s, float("nan"), device=DEV, dtype=torch.float32)
+    i32 = lambda fill: torch.full((B, MAX_NODES), fill, device=DEV, dtype=torch.int32)
+    a1 = dict(entropy=f(B), topk_idx=torch.full((B, k), -1, device=DEV, dtype=torch.int32), topk_prob=f(B, k),
+              topk_renorm=f(B, k), topk_entropy=f(B), alpha=f(B))
+    a2 = dict(n_nodes=torch.zeros(B, device=DEV, dtype=torch.int32), parent=i32(-2), depth=i32(-2), rank=i32(-2),
+              anc_mask=torch.zeros((B, MAX_NODES), device=DEV, dtype=torch.int64),
+              cum_prob=torch.full((B, MAX_NODES), float("nan"), device=DEV, dtype=torch.float32), node_token=i32(-2))
+    ws = torch.empty(sage.sage_entropy_topk_workspace_bytes(B, vocab, k), device=DEV, dtype=torch.uint8)
+    dm = None if d_max_seq_np is None else to_dev(np.ascontiguousarray(d_max_seq_np, np.int32))
+    sage.sage_entropy_topk_slices(x, k, ws)
+    sage.sage_build_tree_from_slices(ws, vocab, sage.tree_params(**prm), a1["entropy"], a1["topk_idx"], a1["topk_prob"],
+                                     a1["topk_renorm"], a1["topk_entropy"], a1["alpha"], a2["n_nodes"], a2["parent"],
+                                     a2["depth"], a2["rank"], a2["anc_mask"], a2["cum_prob"], a2["node_token"], d_max_seq=dm)
+    torch.cuda.synchronize()
+    r1 = {key: v.cpu().numpy() for key, v in a1.items()}
+    r2 = {key: v.cpu().numpy() for key, v in a2.items()}
+    r2["anc_mask"] = r2["anc_mask"].view(np.uint64)
+    return r1, r2
+
+
+def gpu_accept_from_slices(target_logits_np, token, parent, depth, anc_mask, n_nodes, path_cap):
+    """sage_entropy_topk_slices (k = 1, rows grouped by sequence) + sage_verify_accept_from_slices."""
+    x = to_dev(target_logits_np)
+    rows, vocab = x.shape
+    B = len(n_nodes)
+    assert rows == B * MAX_NODES
+    args = [to_dev(np.ascontiguousarray(a, np.int32)) for a in (token, parent, depth)]
+    mask, nn = to_dev(np.ascontiguousarray(anc_mask, np.uint64)), to_dev(np.ascontiguousarray(n_nodes, np.int32))
+    out = dict(entropy=torch.full((rows,), float("nan"), device=DEV, dtype=torch.float32),
+               target_argmax=torch.full((rows,), -1, device=DEV, dtype=torch.int32),
+               accept_len=torch.full((B,), -9, device=DEV, dtype=torch.int32),
+               best_node=torch.full((B,), -9, device=DEV, dtype=torch.int32),
+               path_nodes=torch.full((B, path_cap), -9, device=DEV, dtype=torch.int32),
+               out_tokens=torch.full((B, path_cap), -9, device=DEV, dtype=torch.int32))
+    ws = torch.empty(sage.sage_entropy_topk_workspace_bytes(rows, vocab, 1), device=DEV, dtype=torch.uint8)
+    sage.sage_entropy_topk_slices(x, 1, ws, nn, MAX_NODES)
+    sage.sage_verify_accept_from_slices(ws, vocab, args[0], args[1], args[2], mask, nn, path_cap, out["entropy"],
+                                        out["target_argmax"], out["accept_len"], out["best_node"], out["path_nodes"],
+                                        out["out_tokens"])
+    torch.cuda.synchronize()
+    return {key: v.cpu().numpy() for key, v in out.items()}

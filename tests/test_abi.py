@@ -136,3 +136,40 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
     assert lib.sage_update_history(*his(dc=32)) == INVALID
     assert lib.sage_update_history(*his(hist=None)) == INVALID
     assert lib.sage_update_history(*his(B=0)) == 0
+
+
+def test_fused_calls_validate_on_the_host(lib):
+    INVALID, UNSUPPORTED, TOO_SMALL = 1, 2, 3
+    vp, ci, cl, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_size_t
+    null, one = vp(0), vp(4096)          # never dereferenced: validation fails first, or B == 0 returns early
+
+    class P(ctypes.Structure):
+        _fields_ = [(n, ci) for n in ("d_min", "d_max", "w_min", "w_max", "k", "n_max")]
+
+    lib.sage_entropy_topk_slices.argtypes = [vp, ci, ci, ci, cl, ci, vp, ci, vp, sz, vp]
+    sl = lambda logits=one, dtype=1, rows=1, vocab=1024, stride=1024, k=4, ws=one, wsb=1 << 20: \
+        lib.sage_entropy_topk_slices(logits, dtype, rows, vocab, stride, k, null, 1, ws, wsb, null)
+    assert sl(logits=null) == INVALID and sl(ws=null) == INVALID and sl(dtype=7) == INVALID
+    assert sl(k=0) == INVALID and sl(k=65) == INVALID and sl(stride=1000) == INVALID
+    assert sl(wsb=16) == TOO_SMALL
+    assert sl(vocab=2_000_000, stride=2_000_000) == UNSUPPORTED
+    assert sl(rows=0) == 0
+
+    lib.sage_build_tree_from_slices.argtypes = [vp, ci, ci, ci, ctypes.POINTER(P)] + [vp] * 15
+    good = P(3, 8, 2, 10, 10, 64)
+    bt = lambda slices=one, vocab=152064, B=0, k=10, prm=good, idx=one, nn=one: lib.sage_build_tree_from_slices(
+        slices, vocab, B, k, ctypes.byref(prm), null, one, idx, one, one, one, one, nn, one, one, one, one, null, null, null)
+    assert bt() == 0
+    assert bt(slices=null) == INVALID and bt(idx=null) == INVALID and bt(nn=null) == INVALID
+    assert bt(k=9) == INVALID and bt(B=-1) == INVALID and bt(vocab=0) == INVALID
+    assert bt(prm=P(3, 40, 2, 10, 10, 64)) == INVALID and bt(prm=P(3, 8, 2, 10, 10, 65)) == INVALID
+    assert bt(slices=vp(4100)) == INVALID
+    assert bt(vocab=2_000_000) == UNSUPPORTED
+
+    lib.sage_verify_accept_from_slices.argtypes = [vp, ci, vp, vp, vp, vp, vp, ci, ci] + [vp] * 7
+    va = lambda slices=one, vocab=152064, tok=one, B=0, cap=9, tgt=one: lib.sage_verify_accept_from_slices(
+        slices, vocab, tok, one, one, one, one, B, cap, null, tgt, one, one, one, one, null)
+    assert va() == 0
+    assert va(slices=null) == INVALID and va(tok=null) == INVALID and va(tgt=null) == INVALID
+    assert va(cap=0) == INVALID and va(B=-1) == INVALID and va(vocab=0) == INVALID
+    assert va(B=2000) == UNSUPPORTED and va(vocab=2_000_000) == UNSUPPORTED

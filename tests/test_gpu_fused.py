@@ -1,0 +1,106 @@
+"""GPU parity of the calls that fold the second top-k pass into its consumer (sage_entropy_topk_slices +
+sage_build_tree_from_slices / sage_verify_accept_from_slices): bit-identical to the separate calls on the same
+inputs, and equal to the CPU oracle by the same rules as those (integers exact, floats to 1e-5)."""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import MAX_NODES, pad_tree, random_parents
+from paper_2602_00523_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gu():
+    import gpu_utils
+    from paper_2602_00523_amd import sage
+    print("\n[lib]", sage.sage_build_info(), flush=True)
+    return gpu_utils
+
+
+def same_bits(a, b, name):
+    assert a.dtype == b.dtype and a.shape == b.shape, name
+    assert (a.view(np.uint8) == b.view(np.uint8)).all(), name
+
+
+@pytest.mark.parametrize("vocab,k,dtype,prm", [
+    (152064, 10, "bf16", wl.CONFIGS["c2"]["tree"]),
+    (152064, 16, "bf16", wl.CONFIGS["c3"]["tree"]),
+    (4100, 8, "f32", wl.CONFIGS["toy"]["tree"]),
+    (300000, 20, "bf16", dict(d_min=2, d_max=12, w_min=2, w_max=20, k=20, n_max=64)),    # more than 256 slices per row
+    (1000, 1, "f32", dict(d_min=1, d_max=4, w_min=1, w_max=1, k=1, n_max=8)),
+])
+def test_plan_from_slices_equals_separate_calls_and_oracle(gu, vocab, k, dtype, prm):
+    B = 9
+    scales = np.array([0.2, 0.5, 1.0, 2.0, 3.0, 4.5, 6.0, 9.0, 30.0], np.float32)
+    z = wl.rng(vocab * 3 + k).standard_normal((B, vocab), dtype=np.float32) * scales[:, None]
+    z[4, 17] = z[4, 18] = z[4].max() + 1.0                                # an exact tie for the best token
+    x = wl.to_storage(z, dtype)
+    d_max_seq = np.array([prm["d_max"], prm["d_min"], 31, 0, 5, 7, 3, 9, 4], np.int32)
+    for dms in (None, d_max_seq):
+        a1, a2 = gu.gpu_plan_from_slices(x, k, prm, dms)
+        s1 = gu.gpu_entropy_topk(x, k)
+        s2 = gu.gpu_build_tree(s1["topk_renorm"], s1["alpha"], prm, s1["topk_idx"], dms)
+        for key in s1:
+            same_bits(a1[key], s1[key], key)
+        n = s2["n_nodes"]
+        same_bits(a2["n_nodes"], n, "n_nodes")
+        for key in ("parent", "depth", "rank", "anc_mask", "cum_prob", "node_token"):
+            for b in range(B):
+                same_bits(a2[key][b, :n[b]], s2[key][b, :n[b]], f"{key}[{b}]")
+                assert (a2[key][b, n[b]:] == (0 if key == "anc_mask" else -2)).all() or key == "cum_prob", key
+        # the oracle on the same logits (a1) and on the GPU's own probabilities (a2, so that rounding cannot flip a tree)
+        o1 = oracle.entropy_topk(x, k)
+        np.testing.assert_array_equal(a1["topk_idx"], o1["topk_idx"])
+        for key in ("entropy", "topk_prob", "topk_renorm", "topk_entropy", "alpha"):
+            assert (np.abs(a1[key] - o1[key]) <= 1e-5 * np.maximum(np.abs(o1[key]), 1.0)).all(), key
+        o2 = oracle.build_tree(a1["topk_renorm"], a1["alpha"], prm, a1["topk_idx"], dms)
+        np.testing.assert_array_equal(a2["n_nodes"], o2["n_nodes"])
+        for key in ("parent", "depth", "rank", "anc_mask", "node_token"):
+            for b in range(B):
+                np.testing.assert_array_equal(a2[key][b, :n[b]], o2[key][b, :n[b]], err_msg=f"{key}[{b}]")
+
+
+@pytest.mark.parametrize("vocab,dtype,B", [(152064, "bf16", 4), (5000, "f32", 7), (300000, "bf16", 2)])
+def test_accept_from_slices_equals_separate_calls_and_oracle(gu, vocab, dtype, B):
+    g = wl.rng(vocab + B)
+    rows = B * MAX_NODES
+    parent = np.full((B, MAX_NODES), -7, np.int32)
+    depth = np.full((B, MAX_NODES), -7, np.int32)
+    mask = np.zeros((B, MAX_NODES), np.uint64)
+    nn = np.zeros(B, np.int32)
+    pars = []
+    for b in range(B):
+        n = (64, 1, 13, 33, 2, 50, 17)[b % 7]
+        par = random_parents(g, n, chain_bias=0.6)
+        p, d, m, _ = pad_tree(par)
+        parent[b], depth[b], mask[b], nn[b] = p[0], d[0], m[0], n
+        pars.append(par)
+    z = g.standard_normal((rows, vocab), dtype=np.float32) * 3.0
+    x = wl.to_storage(z, dtype)
+    # the target's greedy token per live row, from the oracle; draft tokens match it along most edges
+    o1 = oracle.entropy_topk(x, 1, nn, MAX_NODES)
+    tgt = o1["topk_idx"][:, 0].reshape(B, MAX_NODES)
+    tok = g.integers(0, vocab, (B, MAX_NODES)).astype(np.int32)
+    for b in range(B):
+        n = int(nn[b])
+        for v in range(1, n):
+            if g.random() < 0.8:
+                tok[b, v] = tgt[b, pars[b][v]]
+    cap = 40
+    f = gu.gpu_accept_from_slices(x, tok, parent, depth, mask, nn, cap)
+    s1 = gu.gpu_entropy_topk(x, 1, nn, MAX_NODES)
+    s4 = gu.gpu_verify_accept(tok, s1["topk_idx"][:, 0].reshape(B, MAX_NODES), parent, depth, mask, nn, cap)
+    live = (np.arange(MAX_NODES)[None, :] < nn[:, None]).reshape(-1)
+    same_bits(f["target_argmax"][live], s1["topk_idx"][live, 0], "target_argmax")
+    same_bits(f["entropy"][live], s1["entropy"][live], "entropy")
+    assert (f["target_argmax"][~live] == -1).all() and np.isnan(f["entropy"][~live]).all()      # skipped rows untouched
+    for key in ("accept_len", "best_node", "path_nodes", "out_tokens"):
+        same_bits(f[key], s4[key], key)
+    np.testing.assert_array_equal(f["target_argmax"][live], o1["topk_idx"][live, 0])
+    assert (np.abs(f["entropy"][live] - o1["entropy"][live]) <= 1e-5 * np.maximum(np.abs(o1["entropy"][live]), 1.0)).all()
+    o4 = oracle.verify_accept(tok, tgt, parent, depth, nn, cap)
+    for key in ("accept_len", "best_node", "path_nodes", "out_tokens"):
+        np.testing.assert_array_equal(f[key], o4[key], err_msg=key)
+    assert o4["accept_len"].max() >= 3
