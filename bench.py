@@ -526,8 +526,8 @@ def closed_loop(name="c2", steps=512):
     got = snapshot_state()
     verified = all(torch.equal(a, b) for a, b in zip(want, got))
     out = dict(workload=name, steps=steps, steps_per_s=steps / wall, ms_per_step=wall * 1e3 / steps,
-               calls_per_step="entropy_topk, build_tree (per-sequence depth), tree_attention, entropy_topk (k=1), "
-                              "verify_accept, commit_path, advance_kv_len, update_history",
+               calls_per_step="entropy_topk_slices, build_tree_from_slices (per-sequence depth), tree_attention, "
+                              "entropy_topk_slices (k=1), verify_accept_from_slices, commit_path, advance_kv_len, update_history",
                kv_len_start=[int(x) for x in w.kv_lens], kv_len_end=[int(x) for x in kv_len.cpu().numpy()],
                mean_accept_len=float(acc_sum.sum().item()) / (steps * B), d_max_end=[int(x) for x in d_max.cpu().numpy()],
                replay_equals_eager=bool(verified))
