@@ -22,7 +22,8 @@
 // Every stage is its own LDS object so that loads in flight into one stage are known not to alias reads of another.
 //
 // Decomposition (decided on the device from n_nodes/kv_len, so no host round trip): a workgroup of 8 waves
-// owns (sequence, KV head, group of up to 4 column tiles = 128 query rows, KV split).  Waves w and w+4 share
+// owns (sequence, KV head, group of up to 4 column tiles = 128 query rows, KV split); with 2..64 sequences the
+// splits are equal ranges of one list of all sequences' tiles, so ragged lengths leave no CU idle (see the kernel).  Waves w and w+4 share
 // column tile w and each takes one 32-token half of every tile; the halves are combined through LDS at the end.
 // Workgroups of one KV head are congruent modulo the KV-head count, which with 8 KV heads pins a head to one
 // XCD and its L2: the column groups of a large tree re-read K/V from that L2, not from HBM.  Each workgroup
@@ -67,9 +68,10 @@ struct Params {
     const uint16_t* Q; const uint16_t* Kc; const uint16_t* Vc; const uint16_t* Kt; const uint16_t* Vt;
     uint16_t* O;
     const int64_t* kv_start; const int* kv_len; const uint64_t* anc_mask; const int* n_nodes;
-    float* part;                         // [B][Hkv][nslot][ROWS_PER_WG][PART_FLOATS]
+    float* part;                         // [B][Hkv][nslot][ROWS_PER_WG][PART_FLOATS]; batched launches: [Hkv][nslot][..][..]
     long kv_token_stride, kv_head_stride;
     int B, Hq, Hkv, G, nslot, min_tiles_per_split;
+    int nrange;                          // batched launches: ranges (workgroups) per KV head
     float scale_log2e;                   // softmax scale times log2(e): probabilities are exp2 of scaled differences
 };
 
@@ -89,6 +91,38 @@ __device__ __forceinline__ Split make_split(int n_nodes, int kv_len, int G, int 
     s.tiles_per_split = max(min_tps, (s.tiles + max_split - 1) / max_split);
     s.nsplit = (s.tiles + s.tiles_per_split - 1) / s.tiles_per_split;
     return s;
+}
+
+// Batched decomposition: lane b of a wave holds the shape of sequence b.  Every (sequence, column group) segment
+// occupies SEG_COST_TILES + tiles positions of one line per KV head (the first SEG_COST_TILES stand for the prologue and
+// epilogue a pass costs, about that many tile steps); the line of `total` positions is cut into ranges of q, so a
+// workgroup whose range starts several segments gets fewer tiles.  Evaluated identically by both kernels.
+constexpr int SEG_COST_TILES = 4;
+struct BatchShape {
+    int n, L, tiles, col_groups, start_lo, start_hi;         // per lane (sequence)
+    int total, q;                                            // wave-uniform
+};
+__device__ __forceinline__ int wave_sum_i32(int v) {
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+    return v;
+}
+__device__ __forceinline__ BatchShape make_batch_shape(const Params& prm, int lane) {
+    BatchShape bs;
+    bs.n = 1; bs.L = 0; bs.tiles = 0; bs.col_groups = 0; bs.start_lo = 0; bs.start_hi = 0;
+    if (lane < prm.B) {
+        const int nn = prm.n_nodes[lane];
+        const int len = prm.kv_len[lane];
+        const int64_t st = prm.kv_start[lane];
+        bs.n = nn < 1 ? 1 : (nn > SAGE_MAX_NODES ? SAGE_MAX_NODES : nn);
+        bs.L = len > 0 ? len : 0;
+        bs.tiles = (bs.L + TILE - 1) / TILE + 1;             // cache tiles, then one tile holding the tree's keys
+        bs.col_groups = (bs.n * prm.G + ROWS_PER_WG - 1) / ROWS_PER_WG;
+        bs.start_lo = static_cast<int>(static_cast<uint32_t>(st));
+        bs.start_hi = static_cast<int>(st >> 32);
+    }
+    bs.total = wave_sum_i32((bs.tiles + SEG_COST_TILES) * bs.col_groups);   // tiles = 0 in lanes past the batch, so is col_groups
+    bs.q = max(prm.min_tiles_per_split, (bs.total + prm.nrange - 1) / prm.nrange);
+    return bs;
 }
 
 // s_waitcnt on the vector-memory counter only (expcnt and lgkmcnt fields left at "no wait")
@@ -116,6 +150,11 @@ __device__ __forceinline__ float cross_half_sum(float v) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
+// BATCH = false: one sequence per launch slot, every (sequence, KV head) cut into equal splits (see make_split).
+// BATCH = true (2..64 sequences): the tiles of all sequences form one list per KV head (sequence-major, then column
+// group), cut into prm.nrange equal ranges; a workgroup owns one range and runs one pass (prologue, tile loop,
+// epilogue) per (sequence, column group) segment its range touches, so ragged lengths cannot unbalance the launch.
+template <bool BATCH>
 __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Params prm) {
     // one LDS object per stage and operand (see header)
     __shared__ __align__(1024) unsigned char sK0[K_STAGE_B];
@@ -138,20 +177,14 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
 
     int id = blockIdx.x;
     const int g = id % prm.Hkv; id /= prm.Hkv;
-    const int slot = id % prm.nslot;
-    const int b = id / prm.nslot;
-    const int L = prm.kv_len[b] > 0 ? prm.kv_len[b] : 0;
-    const Split sp = make_split(prm.n_nodes[b], L, prm.G, prm.nslot, prm.min_tiles_per_split);
-    if (sp.col_groups > prm.nslot) return;                  // host guarantees nslot >= the largest group count
-    const int cg = slot % sp.col_groups;
-    const int split = slot / sp.col_groups;
-    if (split >= sp.nsplit) return;
-    const int t_begin = split * sp.tiles_per_split;
-    const int t_end = min(sp.tiles, t_begin + sp.tiles_per_split);
-    const int tree_tile = sp.tiles - 1;
 
+    // One pass over tiles [t_begin, t_end) of sequence b for column group cg; the un-normalised partial goes to out_base.
+    auto run_segment = [&](const int b, const int L, const int seq_n, const int seq_rows, const int cg, const int t_begin,
+                           const int t_end, const int tree_tile, const long kv_start_b, float* const out_base)
+                           __attribute__((always_inline)) {
+    if (BATCH) __syncthreads();                              // the previous segment's epilogue has left the stage buffers
     // ---- wave roles: waves w and w+4 share column tile w; each takes one 32-token half of every tile
-    const int group_rows = min(ROWS_PER_WG, sp.rows - cg * ROWS_PER_WG);
+    const int group_rows = min(ROWS_PER_WG, seq_rows - cg * ROWS_PER_WG);
     const int group_ct = (group_rows + 31) / 32;             // 1..4 column tiles in this group
     const int ct = wave & 3;
     const int sub_lo = wave >> 2;
@@ -161,16 +194,16 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
     const int m_local = ct * 32 + r32;                       // row within the group
     const int m = cg * ROWS_PER_WG + m_local;                // row within the KV head
     const int node = m / prm.G;
-    const bool row_valid = ct < group_ct && m < sp.rows;
+    const bool row_valid = ct < group_ct && m < seq_rows;
     // ---- loader: instruction i of wave w copies tokens r, r+16, r+32, r+48 (r = 2w + i) of K and of V, 1 KB of
     //      LDS each: lane l fills chunk l%16 of token r + 16 (l/16).  Addresses are a wave-uniform tile base plus a
     //      32-bit per-lane offset that is the same for every full tile, so a tile costs no address arithmetic.
     const int ld_tok = (lane >> 4) * 16 + wave * 2;          // token within the tile for i = 0 (i = 1: the next one)
     const unsigned ld_chunk_b = (lane & 15) * 16;
     const unsigned char* k_cache = reinterpret_cast<const unsigned char*>(
-        prm.Kc + prm.kv_start[b] * prm.kv_token_stride + static_cast<long>(g) * prm.kv_head_stride);
+        prm.Kc + kv_start_b * prm.kv_token_stride + static_cast<long>(g) * prm.kv_head_stride);
     const unsigned char* v_cache = reinterpret_cast<const unsigned char*>(
-        prm.Vc + prm.kv_start[b] * prm.kv_token_stride + static_cast<long>(g) * prm.kv_head_stride);
+        prm.Vc + kv_start_b * prm.kv_token_stride + static_cast<long>(g) * prm.kv_head_stride);
     const unsigned char* k_tree = reinterpret_cast<const unsigned char*>(
         prm.Kt + (static_cast<long>(b) * SAGE_MAX_NODES * prm.Hkv + g) * D);
     const unsigned char* v_tree = reinterpret_cast<const unsigned char*>(
@@ -196,7 +229,7 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
             const unsigned char* kb = is_tree ? k_tree : k_cache + static_cast<long>(tile) * TILE * cache_row_b;   // masked later,
             const unsigned char* vb = is_tree ? v_tree : v_cache + static_cast<long>(tile) * TILE * cache_row_b;   // reads stay in range
             const unsigned row_b = is_tree ? tree_row_b : cache_row_b;
-            const int last = is_tree ? sp.n - 1 : L - 1 - tile * TILE;
+            const int last = is_tree ? seq_n - 1 : L - 1 - tile * TILE;
             const unsigned o0 = static_cast<unsigned>(min(ld_tok, last)) * row_b + ld_chunk_b;
             const unsigned o1 = static_cast<unsigned>(min(ld_tok + 1, last)) * row_b + ld_chunk_b;
             __builtin_amdgcn_global_load_lds(kb + o0, k_dst, 16, 0, 0);
@@ -210,7 +243,7 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
     uint64_t my_mask = 0ull;                                 // threads 0..127: mask of row `tid` of this group
     if (tid < ROWS_PER_WG) {
         const int mm = cg * ROWS_PER_WG + tid;
-        if (mm < sp.rows) my_mask = prm.anc_mask[static_cast<long>(b) * SAGE_MAX_NODES + mm / prm.G];
+        if (mm < seq_rows) my_mask = prm.anc_mask[static_cast<long>(b) * SAGE_MAX_NODES + mm / prm.G];
     }
     bf16x8 qf[8];
     {
@@ -404,7 +437,6 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
     }
     __syncthreads();
     {
-        float* out_base = prm.part + ((static_cast<long>(b) * prm.Hkv + g) * prm.nslot + slot) * ROWS_PER_WG * PART_FLOATS;
         for (int it = tid; it < group_rows * 32; it += THREADS) {
             const int row = it >> 5, ch = it & 31;           // row of the group, 16-byte chunk of its 128 dims
             const int rct = row >> 5;
@@ -422,6 +454,48 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
             if (ch == 0) { out[D] = m_new; out[D + 1] = l0 * w0 + l1 * w1; }
         }
     }
+    };   // run_segment
+
+    if (!BATCH) {
+        const int slot = id % prm.nslot;
+        const int b = id / prm.nslot;
+        const int L = prm.kv_len[b] > 0 ? prm.kv_len[b] : 0;
+        const Split sp = make_split(prm.n_nodes[b], L, prm.G, prm.nslot, prm.min_tiles_per_split);
+        if (sp.col_groups > prm.nslot) return;              // host guarantees nslot >= the largest group count
+        const int cg = slot % sp.col_groups;
+        const int split = slot / sp.col_groups;
+        if (split >= sp.nsplit) return;
+        const int t_begin = split * sp.tiles_per_split;
+        const int t_end = min(sp.tiles, t_begin + sp.tiles_per_split);
+        run_segment(b, L, sp.n, sp.rows, cg, t_begin, t_end, sp.tiles - 1, prm.kv_start[b],
+                    prm.part + ((static_cast<long>(b) * prm.Hkv + g) * prm.nslot + slot) * ROWS_PER_WG * PART_FLOATS);
+    } else {
+        const BatchShape bs = make_batch_shape(prm, lane);  // lane b holds sequence b
+        const int r0 = id * bs.q;                            // this workgroup's range of the tile list
+        const int r1 = min(bs.total, r0 + bs.q);
+        if (r0 >= r1) return;
+        int first = 0, groups_before = 0;                    // first position / number of segments of the sequences before b
+        for (int b = 0; b < prm.B && first < r1; ++b) {
+            const int tiles_b = __builtin_amdgcn_readlane(bs.tiles, b);
+            const int cgs_b = __builtin_amdgcn_readlane(bs.col_groups, b);
+            const int seg_len = tiles_b + SEG_COST_TILES;
+            if (first + seg_len * cgs_b > r0) {
+                const int n_b = __builtin_amdgcn_readlane(bs.n, b);
+                const int L_b = __builtin_amdgcn_readlane(bs.L, b);
+                const long start_b = (static_cast<long>(__builtin_amdgcn_readlane(bs.start_hi, b)) << 32) |
+                                     static_cast<uint32_t>(__builtin_amdgcn_readlane(bs.start_lo, b));
+                for (int cg = 0; cg < cgs_b; ++cg) {
+                    const int tile0 = first + cg * seg_len + SEG_COST_TILES;      // position of the segment's first tile
+                    const int lo = max(r0, tile0), hi = min(r1, tile0 + tiles_b);
+                    if (lo < hi)
+                        run_segment(b, L_b, n_b, n_b * prm.G, cg, lo - tile0, hi - tile0, tiles_b - 1, start_b,
+                                    prm.part + (static_cast<long>(g) * prm.nslot + id + groups_before + cg) * ROWS_PER_WG * PART_FLOATS);
+                }
+            }
+            first += seg_len * cgs_b;
+            groups_before += cgs_b;
+        }
+    }
 #undef SK
 #undef SV
 }
@@ -429,49 +503,67 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
 // Merge the splits of one (sequence, node, query head) in split order and write bf16.  One wave per row:
 // lane = split for the (max, sum) pairs and their weights, lane = pair of output dims for the accumulation.
 // Every partial of the row is requested before the first one is used, so the merge costs one memory round trip.
-constexpr int MERGE_ROWS = 4;            // rows (waves) per workgroup
-__global__ __launch_bounds__(64 * MERGE_ROWS) void tree_attention_merge_kernel(const Params prm) {
-    // blockIdx = ((b * 64 + node) * (G / rows-per-block) + head group) * Hkv + KV head: like the main kernel, a KV
-    // head's blocks are congruent modulo the KV-head count, so with 8 KV heads they run on the XCD whose L2 still
-    // holds that head's partials.
+// ROWS = rows (waves) per workgroup.  MAXS = splits handled per pass (one per lane for the (max, sum) pairs, one
+// register pair each for the accumulation); the host picks the smallest instantiation that covers the launch's slot
+// count, which keeps the register count, and with it the number of resident waves, in proportion to the work.
+constexpr int MERGE_ROWS_SINGLE = 4;     // one sequence: many small workgroups spread best over the CUs
+constexpr int MERGE_ROWS_BATCH = 4;      // (16 rows per workgroup measured 6 % slower on the ragged batch of 8)
+template <int MAXS, bool BATCH, int ROWS>
+__global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const Params prm) {
+    static_assert(MAXS <= 64, "one split per lane");
+    // blockIdx = ((b * blocks-per-head) + block of ROWS rows) * Hkv + KV head: like the main kernel, a KV head's blocks
+    // are congruent modulo the KV-head count, so with 8 KV heads they run on the XCD whose L2 still holds that head's
+    // partials.  Rows of a KV head are numbered as in the main kernel: node * G + head-in-group.
     const int lane = threadIdx.x & 63;
     int id = blockIdx.x;
     const int g = id % prm.Hkv; id /= prm.Hkv;
-    const int per_node = (prm.G + MERGE_ROWS - 1) / MERGE_ROWS;
-    const int hg = (id % per_node) * MERGE_ROWS + (threadIdx.x >> 6); id /= per_node;
-    const int node = id % SAGE_MAX_NODES, b = id / SAGE_MAX_NODES;
-    const int L = prm.kv_len[b] > 0 ? prm.kv_len[b] : 0;
-    const Split sp = make_split(prm.n_nodes[b], L, prm.G, prm.nslot, prm.min_tiles_per_split);
-    if (node >= sp.n || hg >= prm.G || sp.col_groups > prm.nslot) return;
+    const int per_head = (SAGE_MAX_NODES * prm.G + ROWS - 1) / ROWS;
+    const int m_row = (id % per_head) * ROWS + (threadIdx.x >> 6);
+    const int b = id / per_head;
+    if (m_row >= SAGE_MAX_NODES * prm.G) return;
+    const int node = m_row / prm.G, hg = m_row % prm.G;
     const int hh = g * prm.G + hg;
-    const int m = node * prm.G + hg;
+    const int m = m_row;
     const int cg = m / ROWS_PER_WG;
     const int row = m % ROWS_PER_WG;
     const float c = prm.scale_log2e;
-    const float* base = prm.part + ((static_cast<long>(b) * prm.Hkv + g) * prm.nslot) * ROWS_PER_WG * PART_FLOATS;
-    const long split_stride = static_cast<long>(sp.col_groups) * ROWS_PER_WG * PART_FLOATS;
-    const float* first = base + (static_cast<long>(cg) * ROWS_PER_WG + row) * PART_FLOATS;
-    const int nsplit = sp.nsplit;
+    const float* first;                                      // this row in the first of its partials
+    long split_stride;                                       // distance to the same row in the next one
+    int nsplit;
+    if (!BATCH) {
+        const int L = prm.kv_len[b] > 0 ? prm.kv_len[b] : 0;
+        const Split sp = make_split(prm.n_nodes[b], L, prm.G, prm.nslot, prm.min_tiles_per_split);
+        if (node >= sp.n || hg >= prm.G || sp.col_groups > prm.nslot) return;
+        const float* base = prm.part + ((static_cast<long>(b) * prm.Hkv + g) * prm.nslot) * ROWS_PER_WG * PART_FLOATS;
+        split_stride = static_cast<long>(sp.col_groups) * ROWS_PER_WG * PART_FLOATS;
+        first = base + (static_cast<long>(cg) * ROWS_PER_WG + row) * PART_FLOATS;
+        nsplit = sp.nsplit;
+    } else {
+        const BatchShape bs = make_batch_shape(prm, lane);
+        if (node >= __builtin_amdgcn_readlane(bs.n, b) || hg >= prm.G) return;
+        const int tiles_b = __builtin_amdgcn_readlane(bs.tiles, b);
+        const int before = wave_sum_i32(lane < b ? (bs.tiles + SEG_COST_TILES) * bs.col_groups : 0);
+        const int groups_before = wave_sum_i32(lane < b ? bs.col_groups : 0);
+        const int u0 = before + cg * (tiles_b + SEG_COST_TILES) + SEG_COST_TILES;   // position of the first tile of segment (b, cg)
+        const int s_first = u0 / bs.q;
+        nsplit = (u0 + tiles_b - 1) / bs.q - s_first + 1;
+        split_stride = static_cast<long>(ROWS_PER_WG) * PART_FLOATS;
+        first = prm.part + ((static_cast<long>(g) * prm.nslot + s_first + groups_before + cg) * ROWS_PER_WG + row) * PART_FLOATS;
+    }
 
     float2 o = make_float2(0.f, 0.f);
     float m_all = -INFINITY, l_all = 0.f;
-    for (int s0 = 0; s0 < nsplit; s0 += 64) {                 // 64 splits at a time (one per lane)
-        const int cnt = min(64, nsplit - s0);
+    for (int s0 = 0; s0 < nsplit; s0 += MAXS) {               // MAXS splits at a time
+        const int cnt = min(MAXS, nsplit - s0);
         float ms = -INFINITY, ls = 0.f;
         if (lane < cnt) {
             ms = first[(s0 + lane) * split_stride + D];
             ls = first[(s0 + lane) * split_stride + D + 1];
         }
-        float2 v[64];
-        if (cnt <= 32) {
+        float2 v[MAXS];
 #pragma unroll
-            for (int s = 0; s < 32; ++s)
-                v[s] = s < cnt ? *reinterpret_cast<const float2*>(first + (s0 + s) * split_stride + 2 * lane) : make_float2(0.f, 0.f);
-        } else {
-#pragma unroll
-            for (int s = 0; s < 64; ++s)
-                v[s] = s < cnt ? *reinterpret_cast<const float2*>(first + (s0 + s) * split_stride + 2 * lane) : make_float2(0.f, 0.f);
-        }
+        for (int s = 0; s < MAXS; ++s)
+            v[s] = s < cnt ? *reinterpret_cast<const float2*>(first + (s0 + s) * split_stride + 2 * lane) : make_float2(0.f, 0.f);
         float m_blk = ms;
         for (int off = 32; off > 0; off >>= 1) m_blk = fmaxf(m_blk, __shfl_xor(m_blk, off));
         const float m_new = fmaxf(m_all, m_blk);
@@ -482,18 +574,10 @@ __global__ __launch_bounds__(64 * MERGE_ROWS) void tree_attention_merge_kernel(c
         l_all = l_all * keep + l_blk;
         o.x *= keep; o.y *= keep;
         m_all = m_new;
-        if (cnt <= 32) {
 #pragma unroll
-            for (int s = 0; s < 32; ++s) {
-                const float ws = __shfl(w, s);
-                o.x += ws * v[s].x; o.y += ws * v[s].y;
-            }
-        } else {
-#pragma unroll
-            for (int s = 0; s < 64; ++s) {
-                const float ws = __shfl(w, s);
-                o.x += ws * v[s].x; o.y += ws * v[s].y;
-            }
+        for (int s = 0; s < MAXS; ++s) {
+            const float ws = __shfl(w, s);
+            o.x += ws * v[s].x; o.y += ws * v[s].y;
         }
     }
     const float inv = 1.0f / l_all;
@@ -506,16 +590,31 @@ __global__ __launch_bounds__(64 * MERGE_ROWS) void tree_attention_merge_kernel(c
 
 namespace sage {
 
-// Launch shape.  Slots = workgroups per (sequence, KV head); a slot is (KV split, column group).  A single
-// sequence is cut into about one 8-wave workgroup per CU (one round, no tail).  A batch is cut into splits of a
-// fixed number of tiles instead (every workgroup pays a few microseconds of prologue and epilogue, so long splits
-// win), sized for about one workgroup per CU in total, so that ragged sequences get splits in proportion to
-// their length.
-struct LaunchShape { int nslot, min_tiles_per_split; };
+// Launch shape.  A single sequence (and batches of more than 64): slots = workgroups per (sequence, KV head); a slot is
+// (KV split, column group); the sequence is cut into about one 8-wave workgroup per CU (one round, no tail).
+// Batches of 2..64 sequences: the tile list of all sequences is cut into `nrange` ranges per KV head, about one
+// workgroup per CU in total whatever the lengths turn out to be on the device; a range is at least MIN_RANGE_TILES
+// tiles (every pass pays a few microseconds of prologue and epilogue), and the partial slots of a KV head are one per
+// range plus one per (sequence, column group), the most that range and segment boundaries can produce together.
+constexpr int MAX_BATCH_LANES = 64;      // a lane per sequence in make_batch_shape
+constexpr int MIN_RANGE_TILES = 8;      // positions of the line, pass cost included
+struct LaunchShape { int nslot, min_tiles_per_split, nrange; bool batch; };
 LaunchShape attention_bf16_shape(int B, int Hkv, int G, int max_kv_len) {
     const int max_groups = (SAGE_MAX_NODES * G + ROWS_PER_WG - 1) / ROWS_PER_WG;
     const int tiles = (max_kv_len + TILE - 1) / TILE + 1;
     LaunchShape sh;
+    sh.batch = B >= 2 && B <= MAX_BATCH_LANES;
+    sh.nrange = 0;
+    if (sh.batch) {
+        long want = 256 / Hkv;
+        if (want < 1) want = 1;
+        const long cap = (static_cast<long>(B) * (tiles + SEG_COST_TILES) * max_groups + MIN_RANGE_TILES - 1) / MIN_RANGE_TILES;
+        if (want > cap) want = cap;
+        sh.nrange = static_cast<int>(want);
+        sh.min_tiles_per_split = MIN_RANGE_TILES;
+        sh.nslot = sh.nrange + B * max_groups;
+        return sh;
+    }
     if (B <= 1) {
         long want = 256 / Hkv;
         if (want < max_groups) want = max_groups;
@@ -537,8 +636,9 @@ LaunchShape attention_bf16_shape(int B, int Hkv, int G, int max_kv_len) {
 }
 
 size_t attention_bf16_workspace_bytes(int B, int Hkv, int G, int max_kv_len) {
-    const size_t slots = attention_bf16_shape(B, Hkv, G, max_kv_len).nslot;
-    return static_cast<size_t>(B) * Hkv * slots * ROWS_PER_WG * PART_FLOATS * sizeof(float);
+    const LaunchShape sh = attention_bf16_shape(B, Hkv, G, max_kv_len);
+    const size_t per_slot = static_cast<size_t>(ROWS_PER_WG) * PART_FLOATS * sizeof(float);
+    return (sh.batch ? static_cast<size_t>(1) : static_cast<size_t>(B)) * Hkv * sh.nslot * per_slot;
 }
 
 int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const void* Kt, const void* Vt, void* O, int B,
@@ -566,13 +666,28 @@ int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const voi
     p.min_tiles_per_split = sh.min_tiles_per_split;
     p.scale_log2e = scale * 1.4426950408889634f;
 
-    const long blocks = static_cast<long>(B) * p.nslot * Hkv;
+    p.nrange = sh.nrange;
+    const long blocks = sh.batch ? static_cast<long>(p.nrange) * Hkv : static_cast<long>(B) * p.nslot * Hkv;
     if (blocks > 0x7FFFFFFFL) return SAGE_UNSUPPORTED;
-    hipLaunchKernelGGL(tree_attention_bf16_kernel, dim3(static_cast<unsigned>(blocks)), dim3(THREADS), 0, stream, p);
+    const dim3 grid(static_cast<unsigned>(blocks)), block(THREADS);
+    if (sh.batch) hipLaunchKernelGGL(tree_attention_bf16_kernel<true>, grid, block, 0, stream, p);
+    else hipLaunchKernelGGL(tree_attention_bf16_kernel<false>, grid, block, 0, stream, p);
     if (hipGetLastError() != hipSuccess) return SAGE_LAUNCH_FAILED;
-    const long merge_blocks = static_cast<long>(B) * SAGE_MAX_NODES * ((G + MERGE_ROWS - 1) / MERGE_ROWS) * Hkv;
+    const int mrows = sh.batch ? MERGE_ROWS_BATCH : MERGE_ROWS_SINGLE;
+    const long merge_blocks = static_cast<long>(B) * ((SAGE_MAX_NODES * G + mrows - 1) / mrows) * Hkv;
     if (merge_blocks > 0x7FFFFFFFL) return SAGE_UNSUPPORTED;
-    hipLaunchKernelGGL(tree_attention_merge_kernel, dim3(static_cast<unsigned>(merge_blocks)), dim3(64 * MERGE_ROWS), 0, stream, p);
+    const dim3 mgrid(static_cast<unsigned>(merge_blocks)), mblock(64 * mrows);
+    const int most = sh.batch ? p.nrange : p.nslot;   // upper bound of the splits of a row
+    if (sh.batch) {
+        if (most <= 8) hipLaunchKernelGGL((tree_attention_merge_kernel<8, true, MERGE_ROWS_BATCH>), mgrid, mblock, 0, stream, p);
+        else if (most <= 16) hipLaunchKernelGGL((tree_attention_merge_kernel<16, true, MERGE_ROWS_BATCH>), mgrid, mblock, 0, stream, p);
+        else hipLaunchKernelGGL((tree_attention_merge_kernel<64, true, MERGE_ROWS_BATCH>), mgrid, mblock, 0, stream, p);
+    } else {
+        if (most <= 8) hipLaunchKernelGGL((tree_attention_merge_kernel<8, false, MERGE_ROWS_SINGLE>), mgrid, mblock, 0, stream, p);
+        else if (most <= 16) hipLaunchKernelGGL((tree_attention_merge_kernel<16, false, MERGE_ROWS_SINGLE>), mgrid, mblock, 0, stream, p);
+        else if (most <= 32) hipLaunchKernelGGL((tree_attention_merge_kernel<32, false, MERGE_ROWS_SINGLE>), mgrid, mblock, 0, stream, p);
+        else hipLaunchKernelGGL((tree_attention_merge_kernel<64, false, MERGE_ROWS_SINGLE>), mgrid, mblock, 0, stream, p);
+    }
     return launch_status();
 }
 

@@ -228,6 +228,22 @@ def test_attention_bf16_random_configurations(gu, seed):
     run_attention_case(gu, 2000 + seed, "bf16", B, Hkv * G, Hkv, 128, lens, sizes, kind, pad=int(g.integers(0, 5)))
 
 
+@pytest.mark.parametrize("B,Hq,Hkv,max_len,seed", [
+    (64, 16, 2, 300, 1),       # every workgroup's range spans several short sequences (some of them empty)
+    (33, 64, 8, 900, 2),       # 72B heads: ranges cut sequences and column groups at arbitrary tiles
+    (8, 64, 8, 3000, 3),
+    (2, 8, 1, 5000, 4),        # one KV head: 256 ranges over two sequences
+    (70, 8, 2, 200, 5),        # more sequences than the batched decomposition takes: per-sequence splits
+])
+def test_attention_bf16_many_sequences(gu, B, Hq, Hkv, max_len, seed):
+    g = wl.rng(300 + seed)
+    lens = g.integers(0, max_len + 1, size=B)
+    lens[g.integers(0, B)] = 0
+    lens[g.integers(0, B)] = max_len
+    sizes = [int(g.choice([1, 3, 16, 17, 40, 64])) for _ in range(B)]
+    run_attention_case(gu, 3000 + seed, "bf16", B, Hq, Hkv, 128, lens, sizes)
+
+
 def test_attention_is_deterministic(gu):
     inp = wl.attention_inputs(3, 1, 64, 8, 128, [2000], "bf16")
     mask, nn = tree_batch(wl.rng(3), 1, [40])
