@@ -3,8 +3,9 @@
 // carries the 72B-shape workloads.
 //
 // One workgroup per (node, query head, sequence).  Keys are taken 256 at a time: lane = key for the scores
-// (q broadcast from LDS, the key row read with 16-byte loads), then thread = output dimension for the
-// probability-weighted sum of values (coalesced across the workgroup), with an online softmax across blocks.
+// (q broadcast from LDS, the key row read with 16-byte loads), then thread = (output dimension, slice of the block's
+// keys) for the probability-weighted sum of values (coalesced across the dimension, eight independent loads in
+// flight per thread), with an online softmax across blocks; the key slices are summed through LDS at the end.
 // The tree's own keys form the last block, admitted by the node's ancestor-or-self mask.
 #include "sage_internal.h"
 
@@ -53,6 +54,9 @@ __global__ __launch_bounds__(THREADS) void tree_attention_f32_kernel(
     const float* vtree = Vt + (static_cast<long>(b) * SAGE_MAX_NODES * Hkv + g) * d;
     const long tree_stride = static_cast<long>(Hkv) * d;
 
+    const int dpad = d <= 64 ? 64 : (d <= 128 ? 128 : 256);  // threads per key slice in the value pass
+    const int nslices = THREADS / dpad;
+    const int dim = tid % dpad, slice = tid / dpad;
     float m = -INFINITY, l = 0.f, acc = 0.f;
     const int nblocks = (L + THREADS - 1) / THREADS + 1;     // cache blocks, then one block of tree keys
     for (int blk = 0; blk < nblocks; ++blk) {
@@ -83,18 +87,36 @@ __global__ __launch_bounds__(THREADS) void tree_attention_f32_kernel(
         __syncthreads();                                     // previous block's s_p fully consumed
         s_p[tid] = p;
         __syncthreads();
-        if (tid < d) {
-            acc *= corr;
+        acc *= corr;
+        if (dim < d) {
             const int cnt = tree ? n : min(THREADS, L - blk * THREADS);
-            const float* vrow0 = tree ? vtree : vbase + static_cast<long>(blk) * THREADS * kv_token_stride;
+            const float* vcol = (tree ? vtree : vbase + static_cast<long>(blk) * THREADS * kv_token_stride) + dim;
             const long vstride = tree ? tree_stride : kv_token_stride;
-            for (int t = 0; t < cnt; ++t) {
+            int t = slice;
+            for (; t + 7 * nslices < cnt; t += 8 * nslices) {
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = vcol[(t + u * nslices) * vstride];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const float pt = s_p[t + u * nslices];
+                    acc = (pt != 0.f) ? fmaf(pt, v[u], acc) : acc;
+                }
+            }
+            for (; t < cnt; t += nslices) {
                 const float pt = s_p[t];
-                if (pt != 0.f) acc = fmaf(pt, vrow0[t * vstride + tid], acc);
+                if (pt != 0.f) acc = fmaf(pt, vcol[t * vstride], acc);
             }
         }
     }
-    if (tid < d) O[qoff + tid] = acc / l;
+    __syncthreads();                                         // s_p is free: sum the key slices
+    s_p[tid] = acc;
+    __syncthreads();
+    if (tid < d) {
+        float sum = 0.f;
+        for (int sl = 0; sl < nslices; ++sl) sum += s_p[tid + sl * dpad];
+        O[qoff + tid] = sum / l;
+    }
 }
 
 }  // namespace
