@@ -25,16 +25,16 @@ constexpr int WAVES = THREADS / 64;
 template <typename T> struct Loader;
 template <> struct Loader<float> {
     static constexpr int VEC = 4;   // elements per 16-byte load
-    __device__ static void load(const float* p, float* out) {
-        const float4 v = *reinterpret_cast<const float4*>(p);
-        out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
-    }
+    using Raw = float4;
+    __device__ static Raw fetch(const float* p) { return *reinterpret_cast<const float4*>(p); }
+    __device__ static void unpack(Raw v, float* out) { out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w; }
     __device__ static float one(const float* p) { return *p; }
 };
 template <> struct Loader<uint16_t> {
     static constexpr int VEC = 8;
-    __device__ static void load(const uint16_t* p, float* out) {
-        const uint4 v = *reinterpret_cast<const uint4*>(p);
+    using Raw = uint4;
+    __device__ static Raw fetch(const uint16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+    __device__ static void unpack(Raw v, float* out) {
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -50,20 +50,25 @@ template <> struct Loader<uint16_t> {
 // the lowest index among equals, the same total order as the composite key) and, once the slice maximum is known,
 // one exp2 and two fused multiply-adds for the statistics.  Differences to the maximum are capped at 87, where
 // exp is below 2^-125: a -inf logit or a padding slot then adds about 1e-38 instead of 0 to sums that are >= 1.
-template <typename T>
-__global__ __launch_bounds__(THREADS) void slice_kernel(const T* __restrict__ logits, int vocab, long row_stride, int k,
-                                                        const int* __restrict__ n_valid, int rows_per_group, int nunits,
-                                                        UnitStats* __restrict__ stats, uint64_t* __restrict__ keys) {
+//
+// The 16-byte loads of a (row, slice) are requested by request_unit and consumed by reduce_unit, so that a wave that
+// walks several rows can have the next row's loads in flight while it reduces the current one.
+template <typename T, int NV>
+__device__ __forceinline__ void request_unit(const T* __restrict__ rowp, int base, int lane, int vocab,
+                                             typename Loader<T>::Raw (&raw)[NV]) {
+    using L = Loader<T>;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int e0 = base + (j * 64 + lane) * L::VEC;
+        if (e0 + L::VEC <= vocab) raw[j] = L::fetch(rowp + e0);      // the ragged end is read element by element later
+    }
+}
+template <typename T, int NV>
+__device__ __forceinline__ void reduce_unit(const T* __restrict__ rowp, int base, int lane, int vocab,
+                                            const typename Loader<T>::Raw (&raw)[NV], UnitStats* __restrict__ stat_out,
+                                            uint64_t* __restrict__ key_out) {
     using L = Loader<T>;
     constexpr int VEC = L::VEC;
-    constexpr int NV = EPT / VEC;
-    const int row = blockIdx.y;
-    const int unit = blockIdx.x * WAVES + (threadIdx.x >> 6);
-    if (unit >= nunits || !row_is_valid(row, n_valid, rows_per_group)) return;
-    const int lane = threadIdx.x & 63;
-    const T* rowp = logits + static_cast<long>(row) * row_stride;
-    const int base = unit * UNIT;
-
     float v[EPT];
     int first[NV];
 #pragma unroll
@@ -71,7 +76,7 @@ __global__ __launch_bounds__(THREADS) void slice_kernel(const T* __restrict__ lo
         const int e0 = base + (j * 64 + lane) * VEC;
         first[j] = e0;
         if (e0 + VEC <= vocab) {
-            L::load(rowp + e0, v + j * VEC);
+            L::unpack(raw[j], v + j * VEC);
         } else {
 #pragma unroll
             for (int e = 0; e < VEC; ++e) v[j * VEC + e] = (e0 + e < vocab) ? L::one(rowp + e0 + e) : -INFINITY;
@@ -90,7 +95,7 @@ __global__ __launch_bounds__(THREADS) void slice_kernel(const T* __restrict__ lo
     }
     const Key g = wave_max_key(bi < vocab ? make_key(bv, bi) : Key{0, 0});   // a lane past the end starts past the end
     const float unit_max = key_none(g) ? -INFINITY : key_value(g);
-    if (lane == 0) keys[(static_cast<long>(row) * nunits + unit) * k] = key_pack(g);
+    if (lane == 0) *key_out = key_pack(g);
 
     // ---- softmax statistics of the slice relative to its own maximum
     float Z = 0.f, Tm = 0.f;
@@ -105,7 +110,56 @@ __global__ __launch_bounds__(THREADS) void slice_kernel(const T* __restrict__ lo
     }
     Z = wave_sum(Z);
     Tm = wave_sum(Tm);
-    if (lane == 0) stats[static_cast<long>(row) * nunits + unit] = UnitStats{unit_max, Z, Tm, 0.f};
+    if (lane == 0) *stat_out = UnitStats{unit_max, Z, Tm, 0.f};
+}
+
+// Every row is valid (n_valid == null): grid (slices / 4, rows).
+template <typename T>
+__global__ __launch_bounds__(THREADS) void slice_kernel(const T* __restrict__ logits, int vocab, long row_stride, int nunits,
+                                                        UnitStats* __restrict__ stats, uint64_t* __restrict__ keys) {
+    constexpr int NV = EPT / Loader<T>::VEC;
+    const int row = blockIdx.y;
+    const int unit = blockIdx.x * WAVES + (threadIdx.x >> 6);
+    if (unit >= nunits) return;
+    const int lane = threadIdx.x & 63;
+    const T* rowp = logits + static_cast<long>(row) * row_stride;
+    typename Loader<T>::Raw raw[NV];
+    request_unit<T, NV>(rowp, unit * UNIT, lane, vocab, raw);
+    const long o = static_cast<long>(row) * nunits + unit;
+    reduce_unit<T, NV>(rowp, unit * UNIT, lane, vocab, raw, stats + o, keys + o);
+}
+
+// Rows in groups of which only the first n_valid[group] count (the target rows of a tree): grid (slices / 4, phases,
+// groups).  A workgroup walks the live rows phase, phase + phases, ... of its group, the next row's loads in flight
+// while the current one is reduced, so rows past n_valid cost no workgroup of their own.
+constexpr int ROW_PHASES = 16;
+template <typename T>
+__global__ __launch_bounds__(THREADS) void slice_rows_kernel(const T* __restrict__ logits, int vocab, long row_stride,
+                                                             const int* __restrict__ n_valid, int rows_per_group, int rows,
+                                                             int nunits, UnitStats* __restrict__ stats,
+                                                             uint64_t* __restrict__ keys) {
+    constexpr int NV = EPT / Loader<T>::VEC;
+    const int group = blockIdx.z;
+    const int phases = gridDim.y;
+    const int unit = blockIdx.x * WAVES + (threadIdx.x >> 6);
+    const int n = min(n_valid[group], min(rows_per_group, rows - group * rows_per_group));   // the last group may be short
+    int r = blockIdx.y;
+    if (unit >= nunits || r >= n) return;
+    const int lane = threadIdx.x & 63;
+    const int base = unit * UNIT;
+    const long row0 = static_cast<long>(group) * rows_per_group;
+    typename Loader<T>::Raw cur[NV], nxt[NV];
+    request_unit<T, NV>(logits + (row0 + r) * row_stride, base, lane, vocab, cur);
+    while (true) {
+        const int rn = r + phases;
+        const bool more = rn < n;                            // wave-uniform
+        if (more) request_unit<T, NV>(logits + (row0 + rn) * row_stride, base, lane, vocab, nxt);
+        const long o = (row0 + r) * nunits + unit;
+        reduce_unit<T, NV>(logits + (row0 + r) * row_stride, base, lane, vocab, cur, stats + o, keys + o);
+        if (!more) break;
+        for (int j = 0; j < NV; ++j) cur[j] = nxt[j];
+        r = rn;
+    }
 }
 
 // Pass 1 for bf16 logits and 1 < k <= 16 (the draft row of a step; pure latency, so the serial selection rounds are
@@ -368,14 +422,23 @@ static int run_first_pass(const void* logits, int dtype, int rows, int vocab, lo
 
     UnitStats* stats = static_cast<UnitStats*>(workspace);
     uint64_t* keys = reinterpret_cast<uint64_t*>(static_cast<char*>(workspace) + stats_bytes(rows, vocab));
-    if (k == 1) {                                    // many rows, one round: a wave per slice, 16 logits per lane
+    if (k == 1 && !n_valid) {                        // many rows, one round: a wave per slice, 16 logits per lane
         const dim3 grid((nunits + WAVES - 1) / WAVES, rows);
         if (dtype == SAGE_F32)
             hipLaunchKernelGGL(slice_kernel<float>, grid, dim3(THREADS), 0, s, static_cast<const float*>(logits), vocab,
-                               row_stride, k, n_valid, rows_per_group, nunits, stats, keys);
+                               row_stride, nunits, stats, keys);
         else
             hipLaunchKernelGGL(slice_kernel<uint16_t>, grid, dim3(THREADS), 0, s, static_cast<const uint16_t*>(logits),
-                               vocab, row_stride, k, n_valid, rows_per_group, nunits, stats, keys);
+                               vocab, row_stride, nunits, stats, keys);
+    } else if (k == 1) {                             // grouped rows: workgroups walk the live rows of their group
+        const int groups = (rows + rows_per_group - 1) / rows_per_group;
+        const dim3 grid((nunits + WAVES - 1) / WAVES, rows_per_group < ROW_PHASES ? rows_per_group : ROW_PHASES, groups);
+        if (dtype == SAGE_F32)
+            hipLaunchKernelGGL(slice_rows_kernel<float>, grid, dim3(THREADS), 0, s, static_cast<const float*>(logits), vocab,
+                               row_stride, n_valid, rows_per_group, rows, nunits, stats, keys);
+        else
+            hipLaunchKernelGGL(slice_rows_kernel<uint16_t>, grid, dim3(THREADS), 0, s, static_cast<const uint16_t*>(logits),
+                               vocab, row_stride, n_valid, rows_per_group, rows, nunits, stats, keys);
     } else {                                         // k rounds: a workgroup per slice, 4 logits per lane
         const dim3 grid(nunits, rows);
         if (dtype == SAGE_F32)

@@ -681,6 +681,7 @@ int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const voi
     if (sh.batch) {
         if (most <= 8) hipLaunchKernelGGL((tree_attention_merge_kernel<8, true, MERGE_ROWS_BATCH>), mgrid, mblock, 0, stream, p);
         else if (most <= 16) hipLaunchKernelGGL((tree_attention_merge_kernel<16, true, MERGE_ROWS_BATCH>), mgrid, mblock, 0, stream, p);
+        else if (most <= 32) hipLaunchKernelGGL((tree_attention_merge_kernel<32, true, MERGE_ROWS_BATCH>), mgrid, mblock, 0, stream, p);
         else hipLaunchKernelGGL((tree_attention_merge_kernel<64, true, MERGE_ROWS_BATCH>), mgrid, mblock, 0, stream, p);
     } else {
         if (most <= 8) hipLaunchKernelGGL((tree_attention_merge_kernel<8, false, MERGE_ROWS_SINGLE>), mgrid, mblock, 0, stream, p);

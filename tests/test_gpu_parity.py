@@ -89,6 +89,17 @@ def test_entropy_topk_row_groups_k1(gu):
     assert (g["alpha"][:9] == 1.0).all()
 
 
+@pytest.mark.parametrize("rows,rpg,n_valid,vocab,dtype", [
+    (150, 64, [64, 33, 22], 5000, "f32"),            # a short last group (22 rows): every one of its rows counts
+    (150, 64, [17, 0, 99], 70008, "bf16"),           # n_valid beyond the group's rows is clamped
+    (40, 5, [5, 0, 1, 3, 5, 2, 4, 0], 2048, "bf16"), # groups smaller than the row phases of a launch
+    (7, 1, [1, 0, 1, 1, 0, 0, 1], 3000, "f32"),
+])
+def test_entropy_topk_row_groups_k1_shapes(gu, rows, rpg, n_valid, vocab, dtype):
+    z = wl.rng(rows * 7 + vocab).standard_normal((rows, vocab), dtype=np.float32) * 3.0
+    check_entropy(gu, wl.to_storage(z, dtype), 1, np.array(n_valid, np.int32), rpg)
+
+
 # ------------------------------------------------------------------ a2
 
 def test_build_tree_bit_exact(gu):
