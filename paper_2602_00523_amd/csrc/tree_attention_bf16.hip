@@ -72,6 +72,7 @@ struct Params {
     long kv_token_stride, kv_head_stride;
     int B, Hq, Hkv, G, nslot, min_tiles_per_split;
     int nrange;                          // batched launches: ranges (workgroups) per KV head
+    int merge_phases;                    // batched launches: merge workgroups per (sequence, KV head)
     float scale_log2e;                   // softmax scale times log2(e): probabilities are exp2 of scaled differences
 };
 
@@ -508,82 +509,88 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
 // count, which keeps the register count, and with it the number of resident waves, in proportion to the work.
 constexpr int MERGE_ROWS_SINGLE = 4;     // one sequence: many small workgroups spread best over the CUs
 constexpr int MERGE_ROWS_BATCH = 4;      // (16 rows per workgroup measured 6 % slower on the ragged batch of 8)
+constexpr int MERGE_PHASES_BATCH = 32;   // batches: workgroups per (sequence, KV head), each walking the live rows
 template <int MAXS, bool BATCH, int ROWS>
 __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const Params prm) {
     static_assert(MAXS <= 64, "one split per lane");
-    // blockIdx = ((b * blocks-per-head) + block of ROWS rows) * Hkv + KV head: like the main kernel, a KV head's blocks
-    // are congruent modulo the KV-head count, so with 8 KV heads they run on the XCD whose L2 still holds that head's
-    // partials.  Rows of a KV head are numbered as in the main kernel: node * G + head-in-group.
+    // As in the main kernel, a KV head's blocks are congruent modulo the KV-head count, so with 8 KV heads they run on
+    // the XCD whose L2 still holds that head's partials.  Rows of a KV head are numbered as there: node * G + head-in-group.
     const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
     int id = blockIdx.x;
     const int g = id % prm.Hkv; id /= prm.Hkv;
-    const int per_head = (SAGE_MAX_NODES * prm.G + ROWS - 1) / ROWS;
-    const int m_row = (id % per_head) * ROWS + (threadIdx.x >> 6);
-    const int b = id / per_head;
-    if (m_row >= SAGE_MAX_NODES * prm.G) return;
-    const int node = m_row / prm.G, hg = m_row % prm.G;
-    const int hh = g * prm.G + hg;
-    const int m = m_row;
-    const int cg = m / ROWS_PER_WG;
-    const int row = m % ROWS_PER_WG;
     const float c = prm.scale_log2e;
-    const float* first;                                      // this row in the first of its partials
-    long split_stride;                                       // distance to the same row in the next one
-    int nsplit;
+
+    // one row: `first` = the row in the first of its nsplit partials, split_stride = distance to the next one
+    auto merge_row = [&](int b, int node, int hg, const float* first, long split_stride, int nsplit) __attribute__((always_inline)) {
+        float2 o = make_float2(0.f, 0.f);
+        float m_all = -INFINITY, l_all = 0.f;
+        for (int s0 = 0; s0 < nsplit; s0 += MAXS) {           // MAXS splits at a time
+            const int cnt = min(MAXS, nsplit - s0);
+            float ms = -INFINITY, ls = 0.f;
+            if (lane < cnt) {
+                ms = first[(s0 + lane) * split_stride + D];
+                ls = first[(s0 + lane) * split_stride + D + 1];
+            }
+            float2 v[MAXS];
+#pragma unroll
+            for (int s = 0; s < MAXS; ++s)
+                v[s] = s < cnt ? *reinterpret_cast<const float2*>(first + (s0 + s) * split_stride + 2 * lane) : make_float2(0.f, 0.f);
+            float m_blk = ms;
+            for (int off = 32; off > 0; off >>= 1) m_blk = fmaxf(m_blk, __shfl_xor(m_blk, off));
+            const float m_new = fmaxf(m_all, m_blk);
+            const float keep = (m_all == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_all - m_new) * c);
+            const float w = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((ms - m_new) * c);
+            float l_blk = w * ls;
+            for (int off = 32; off > 0; off >>= 1) l_blk += __shfl_xor(l_blk, off);
+            l_all = l_all * keep + l_blk;
+            o.x *= keep; o.y *= keep;
+            m_all = m_new;
+#pragma unroll
+            for (int s = 0; s < MAXS; ++s) {
+                const float ws = __shfl(w, s);
+                o.x += ws * v[s].x; o.y += ws * v[s].y;
+            }
+        }
+        const float inv = 1.0f / l_all;
+        const uint32_t packed = static_cast<uint32_t>(sage::float_to_bf16_bits(o.x * inv)) |
+                                (static_cast<uint32_t>(sage::float_to_bf16_bits(o.y * inv)) << 16);
+        reinterpret_cast<uint32_t*>(prm.O + ((static_cast<long>(b) * SAGE_MAX_NODES + node) * prm.Hq + g * prm.G + hg) * D)[lane] = packed;
+    };
+
     if (!BATCH) {
+        // blockIdx = ((b * blocks-per-head) + block of ROWS rows) * Hkv + KV head
+        const int per_head = (SAGE_MAX_NODES * prm.G + ROWS - 1) / ROWS;
+        const int m = (id % per_head) * ROWS + wave;
+        const int b = id / per_head;
+        if (m >= SAGE_MAX_NODES * prm.G) return;
+        const int node = m / prm.G, hg = m % prm.G;
         const int L = prm.kv_len[b] > 0 ? prm.kv_len[b] : 0;
         const Split sp = make_split(prm.n_nodes[b], L, prm.G, prm.nslot, prm.min_tiles_per_split);
-        if (node >= sp.n || hg >= prm.G || sp.col_groups > prm.nslot) return;
+        if (node >= sp.n || sp.col_groups > prm.nslot) return;
         const float* base = prm.part + ((static_cast<long>(b) * prm.Hkv + g) * prm.nslot) * ROWS_PER_WG * PART_FLOATS;
-        split_stride = static_cast<long>(sp.col_groups) * ROWS_PER_WG * PART_FLOATS;
-        first = base + (static_cast<long>(cg) * ROWS_PER_WG + row) * PART_FLOATS;
-        nsplit = sp.nsplit;
+        merge_row(b, node, hg, base + (static_cast<long>(m / ROWS_PER_WG) * ROWS_PER_WG + m % ROWS_PER_WG) * PART_FLOATS,
+                  static_cast<long>(sp.col_groups) * ROWS_PER_WG * PART_FLOATS, sp.nsplit);
     } else {
+        // blockIdx = ((b * phases) + phase) * Hkv + KV head; a wave walks the live rows phase * ROWS + wave, + phases *
+        // ROWS, ... of its (sequence, KV head), so that rows of nodes past n_nodes cost no workgroup of their own
+        const int phases = prm.merge_phases;
+        const int phase = id % phases;
+        const int b = id / phases;
         const BatchShape bs = make_batch_shape(prm, lane);
-        if (node >= __builtin_amdgcn_readlane(bs.n, b) || hg >= prm.G) return;
+        const int live = __builtin_amdgcn_readlane(bs.n, b) * prm.G;
         const int tiles_b = __builtin_amdgcn_readlane(bs.tiles, b);
         const int before = wave_sum_i32(lane < b ? (bs.tiles + SEG_COST_TILES) * bs.col_groups : 0);
         const int groups_before = wave_sum_i32(lane < b ? bs.col_groups : 0);
-        const int u0 = before + cg * (tiles_b + SEG_COST_TILES) + SEG_COST_TILES;   // position of the first tile of segment (b, cg)
-        const int s_first = u0 / bs.q;
-        nsplit = (u0 + tiles_b - 1) / bs.q - s_first + 1;
-        split_stride = static_cast<long>(ROWS_PER_WG) * PART_FLOATS;
-        first = prm.part + ((static_cast<long>(g) * prm.nslot + s_first + groups_before + cg) * ROWS_PER_WG + row) * PART_FLOATS;
-    }
-
-    float2 o = make_float2(0.f, 0.f);
-    float m_all = -INFINITY, l_all = 0.f;
-    for (int s0 = 0; s0 < nsplit; s0 += MAXS) {               // MAXS splits at a time
-        const int cnt = min(MAXS, nsplit - s0);
-        float ms = -INFINITY, ls = 0.f;
-        if (lane < cnt) {
-            ms = first[(s0 + lane) * split_stride + D];
-            ls = first[(s0 + lane) * split_stride + D + 1];
-        }
-        float2 v[MAXS];
-#pragma unroll
-        for (int s = 0; s < MAXS; ++s)
-            v[s] = s < cnt ? *reinterpret_cast<const float2*>(first + (s0 + s) * split_stride + 2 * lane) : make_float2(0.f, 0.f);
-        float m_blk = ms;
-        for (int off = 32; off > 0; off >>= 1) m_blk = fmaxf(m_blk, __shfl_xor(m_blk, off));
-        const float m_new = fmaxf(m_all, m_blk);
-        const float keep = (m_all == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_all - m_new) * c);
-        const float w = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((ms - m_new) * c);
-        float l_blk = w * ls;
-        for (int off = 32; off > 0; off >>= 1) l_blk += __shfl_xor(l_blk, off);
-        l_all = l_all * keep + l_blk;
-        o.x *= keep; o.y *= keep;
-        m_all = m_new;
-#pragma unroll
-        for (int s = 0; s < MAXS; ++s) {
-            const float ws = __shfl(w, s);
-            o.x += ws * v[s].x; o.y += ws * v[s].y;
+        for (int m = phase * ROWS + wave; m < live; m += phases * ROWS) {
+            const int cg = m / ROWS_PER_WG;
+            const int u0 = before + cg * (tiles_b + SEG_COST_TILES) + SEG_COST_TILES;   // first tile of segment (b, cg)
+            const int s_first = u0 / bs.q;
+            merge_row(b, m / prm.G, m % prm.G,
+                      prm.part + ((static_cast<long>(g) * prm.nslot + s_first + groups_before + cg) * ROWS_PER_WG + m % ROWS_PER_WG) * PART_FLOATS,
+                      static_cast<long>(ROWS_PER_WG) * PART_FLOATS, (u0 + tiles_b - 1) / bs.q - s_first + 1);
         }
     }
-    const float inv = 1.0f / l_all;
-    const uint32_t packed = static_cast<uint32_t>(sage::float_to_bf16_bits(o.x * inv)) |
-                            (static_cast<uint32_t>(sage::float_to_bf16_bits(o.y * inv)) << 16);
-    reinterpret_cast<uint32_t*>(prm.O + ((static_cast<long>(b) * SAGE_MAX_NODES + node) * prm.Hq + hh) * D)[lane] = packed;
 }
 
 }  // namespace
@@ -674,7 +681,9 @@ int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const voi
     else hipLaunchKernelGGL(tree_attention_bf16_kernel<false>, grid, block, 0, stream, p);
     if (hipGetLastError() != hipSuccess) return SAGE_LAUNCH_FAILED;
     const int mrows = sh.batch ? MERGE_ROWS_BATCH : MERGE_ROWS_SINGLE;
-    const long merge_blocks = static_cast<long>(B) * ((SAGE_MAX_NODES * G + mrows - 1) / mrows) * Hkv;
+    const int row_blocks = (SAGE_MAX_NODES * G + mrows - 1) / mrows;
+    p.merge_phases = row_blocks < MERGE_PHASES_BATCH ? row_blocks : MERGE_PHASES_BATCH;
+    const long merge_blocks = static_cast<long>(B) * (sh.batch ? p.merge_phases : row_blocks) * Hkv;
     if (merge_blocks > 0x7FFFFFFFL) return SAGE_UNSUPPORTED;
     const dim3 mgrid(static_cast<unsigned>(merge_blocks)), mblock(64 * mrows);
     const int most = sh.batch ? p.nrange : p.nslot;   // upper bound of the splits of a row
