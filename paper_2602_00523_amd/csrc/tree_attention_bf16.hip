@@ -72,7 +72,7 @@ struct Params {
     long kv_token_stride, kv_head_stride;
     int B, Hq, Hkv, G, nslot, min_tiles_per_split;
     int nrange;                          // batched launches: ranges (workgroups) per KV head
-    int merge_phases;                    // batched launches: merge workgroups per (sequence, KV head)
+    int merge_phases;                    // merge workgroups per (sequence, KV head)
     float scale_log2e;                   // softmax scale times log2(e): probabilities are exp2 of scaled differences
 };
 
@@ -509,7 +509,8 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
 // count, which keeps the register count, and with it the number of resident waves, in proportion to the work.
 constexpr int MERGE_ROWS_SINGLE = 4;     // one sequence: many small workgroups spread best over the CUs
 constexpr int MERGE_ROWS_BATCH = 4;      // (16 rows per workgroup measured 6 % slower on the ragged batch of 8)
-constexpr int MERGE_PHASES_BATCH = 32;   // batches: workgroups per (sequence, KV head), each walking the live rows
+constexpr int MERGE_PHASES_BATCH = 32;   // batches: workgroups per (sequence, KV head), each walking the live rows; a
+                                         // single sequence gets a wave per possible row (fewer measured no faster)
 template <int MAXS, bool BATCH, int ROWS>
 __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const Params prm) {
     static_assert(MAXS <= 64, "one split per lane");
@@ -558,25 +559,20 @@ __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const P
         reinterpret_cast<uint32_t*>(prm.O + ((static_cast<long>(b) * SAGE_MAX_NODES + node) * prm.Hq + g * prm.G + hg) * D)[lane] = packed;
     };
 
+    // blockIdx = ((b * phases) + phase) * Hkv + KV head; a wave walks the live rows phase * ROWS + wave, + phases * ROWS,
+    // ... of its (sequence, KV head), so that rows of nodes past n_nodes cost no workgroup of their own
+    const int phases = prm.merge_phases;
+    const int phase = id % phases;
+    const int b = id / phases;
     if (!BATCH) {
-        // blockIdx = ((b * blocks-per-head) + block of ROWS rows) * Hkv + KV head
-        const int per_head = (SAGE_MAX_NODES * prm.G + ROWS - 1) / ROWS;
-        const int m = (id % per_head) * ROWS + wave;
-        const int b = id / per_head;
-        if (m >= SAGE_MAX_NODES * prm.G) return;
-        const int node = m / prm.G, hg = m % prm.G;
         const int L = prm.kv_len[b] > 0 ? prm.kv_len[b] : 0;
         const Split sp = make_split(prm.n_nodes[b], L, prm.G, prm.nslot, prm.min_tiles_per_split);
-        if (node >= sp.n || sp.col_groups > prm.nslot) return;
+        if (sp.col_groups > prm.nslot) return;
         const float* base = prm.part + ((static_cast<long>(b) * prm.Hkv + g) * prm.nslot) * ROWS_PER_WG * PART_FLOATS;
-        merge_row(b, node, hg, base + (static_cast<long>(m / ROWS_PER_WG) * ROWS_PER_WG + m % ROWS_PER_WG) * PART_FLOATS,
-                  static_cast<long>(sp.col_groups) * ROWS_PER_WG * PART_FLOATS, sp.nsplit);
+        for (int m = phase * ROWS + wave; m < sp.rows; m += phases * ROWS)
+            merge_row(b, m / prm.G, m % prm.G, base + (static_cast<long>(m / ROWS_PER_WG) * ROWS_PER_WG + m % ROWS_PER_WG) * PART_FLOATS,
+                      static_cast<long>(sp.col_groups) * ROWS_PER_WG * PART_FLOATS, sp.nsplit);
     } else {
-        // blockIdx = ((b * phases) + phase) * Hkv + KV head; a wave walks the live rows phase * ROWS + wave, + phases *
-        // ROWS, ... of its (sequence, KV head), so that rows of nodes past n_nodes cost no workgroup of their own
-        const int phases = prm.merge_phases;
-        const int phase = id % phases;
-        const int b = id / phases;
         const BatchShape bs = make_batch_shape(prm, lane);
         const int live = __builtin_amdgcn_readlane(bs.n, b) * prm.G;
         const int tiles_b = __builtin_amdgcn_readlane(bs.tiles, b);
@@ -682,8 +678,9 @@ int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const voi
     if (hipGetLastError() != hipSuccess) return SAGE_LAUNCH_FAILED;
     const int mrows = sh.batch ? MERGE_ROWS_BATCH : MERGE_ROWS_SINGLE;
     const int row_blocks = (SAGE_MAX_NODES * G + mrows - 1) / mrows;
-    p.merge_phases = row_blocks < MERGE_PHASES_BATCH ? row_blocks : MERGE_PHASES_BATCH;
-    const long merge_blocks = static_cast<long>(B) * (sh.batch ? p.merge_phases : row_blocks) * Hkv;
+    const int want_phases = sh.batch ? MERGE_PHASES_BATCH : row_blocks;
+    p.merge_phases = row_blocks < want_phases ? row_blocks : want_phases;
+    const long merge_blocks = static_cast<long>(B) * p.merge_phases * Hkv;
     if (merge_blocks > 0x7FFFFFFFL) return SAGE_UNSUPPORTED;
     const dim3 mgrid(static_cast<unsigned>(merge_blocks)), mblock(64 * mrows);
     const int most = sh.batch ? p.nrange : p.nslot;   // upper bound of the splits of a row
