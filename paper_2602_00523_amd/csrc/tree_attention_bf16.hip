@@ -513,7 +513,7 @@ constexpr int MERGE_PHASES_BATCH = 32;   // batches: workgroups per (sequence, K
                                          // single sequence gets a wave per possible row (fewer measured no faster)
 template <int MAXS, bool BATCH, int ROWS>
 __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const Params prm) {
-    static_assert(MAXS <= 64, "one split per lane");
+    static_assert(MAXS <= 32, "one split per lane, one register pair per split");
     // As in the main kernel, a KV head's blocks are congruent modulo the KV-head count, so with 8 KV heads they run on
     // the XCD whose L2 still holds that head's partials.  Rows of a KV head are numbered as there: node * G + head-in-group.
     const int lane = threadIdx.x & 63;
@@ -683,17 +683,19 @@ int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const voi
     const long merge_blocks = static_cast<long>(B) * p.merge_phases * Hkv;
     if (merge_blocks > 0x7FFFFFFFL) return SAGE_UNSUPPORTED;
     const dim3 mgrid(static_cast<unsigned>(merge_blocks)), mblock(64 * mrows);
-    const int most = sh.batch ? p.nrange : p.nslot;   // upper bound of the splits of a row
+    const int max_tiles = (max_kv_len + TILE - 1) / TILE + 1;
+    int most = sh.batch ? p.nrange : p.nslot;         // upper bound of the splits of a row: no more than slots, or tiles
+    if (most > max_tiles) most = max_tiles;
+    // more than 32 splits take several passes of 32: 64 register pairs per lane cost more in resident waves than the
+    // second round trip does
     if (sh.batch) {
         if (most <= 8) hipLaunchKernelGGL((tree_attention_merge_kernel<8, true, MERGE_ROWS_BATCH>), mgrid, mblock, 0, stream, p);
         else if (most <= 16) hipLaunchKernelGGL((tree_attention_merge_kernel<16, true, MERGE_ROWS_BATCH>), mgrid, mblock, 0, stream, p);
-        else if (most <= 32) hipLaunchKernelGGL((tree_attention_merge_kernel<32, true, MERGE_ROWS_BATCH>), mgrid, mblock, 0, stream, p);
-        else hipLaunchKernelGGL((tree_attention_merge_kernel<64, true, MERGE_ROWS_BATCH>), mgrid, mblock, 0, stream, p);
+        else hipLaunchKernelGGL((tree_attention_merge_kernel<32, true, MERGE_ROWS_BATCH>), mgrid, mblock, 0, stream, p);
     } else {
         if (most <= 8) hipLaunchKernelGGL((tree_attention_merge_kernel<8, false, MERGE_ROWS_SINGLE>), mgrid, mblock, 0, stream, p);
         else if (most <= 16) hipLaunchKernelGGL((tree_attention_merge_kernel<16, false, MERGE_ROWS_SINGLE>), mgrid, mblock, 0, stream, p);
-        else if (most <= 32) hipLaunchKernelGGL((tree_attention_merge_kernel<32, false, MERGE_ROWS_SINGLE>), mgrid, mblock, 0, stream, p);
-        else hipLaunchKernelGGL((tree_attention_merge_kernel<64, false, MERGE_ROWS_SINGLE>), mgrid, mblock, 0, stream, p);
+        else hipLaunchKernelGGL((tree_attention_merge_kernel<32, false, MERGE_ROWS_SINGLE>), mgrid, mblock, 0, stream, p);
     }
     return launch_status();
 }
