@@ -16,10 +16,10 @@
 // uses the same reference maximum for numerator and denominator, so the result is unchanged.
 //
 // Data movement.  K/V tiles of 64 tokens go from global memory straight into LDS (16-byte LDS-direct loads, no
-// staging registers) through a 4-stage ring, three tiles ahead of the MFMAs.  A wave-level load writes 1 KB of
+// staging registers; issued through inline assembly, see dma16) through a 4-stage ring, three tiles ahead of the MFMAs.  A wave-level load writes 1 KB of
 // contiguous LDS; it carries four tokens that are 16 apart, and the 1 KB groups are padded so that consecutive
 // tokens are staggered across the banks (conflict-free reads with compile-time offsets, see the layout constants).
-// Every stage is its own LDS object so that loads in flight into one stage are known not to alias reads of another.
+// Every stage is its own LDS object, so every stage address is a compile-time constant.
 //
 // Decomposition (decided on the device from n_nodes/kv_len, so no host round trip): a workgroup of 8 waves
 // owns (sequence, KV head, group of up to 4 column tiles = 128 query rows, KV split); with 2..64 sequences the
@@ -126,6 +126,24 @@ __device__ __forceinline__ BatchShape make_batch_shape(const Params& prm, int la
     return bs;
 }
 
+// 16 bytes per lane from global memory straight into LDS (lane l lands at lds + 16 l).  Written as inline assembly so
+// that these loads stay out of the compiler's own bookkeeping of outstanding memory operations.  With the builtin, any
+// LDS read of a stage that was filled earlier in the same loop iteration made the compiler wait for ALL loads in flight
+// (it treats the loads as operations that may complete out of order), which drained the three-tile prefetch once every
+// four steps and turned every LDS wait into a wait for all LDS reads.  Which tiles have landed is known from wait_vm
+// and the stage barrier, not from program order; the "memory" clobber keeps LDS reads from moving across an issue.
+// M0 carries the LDS address of the load; nothing else in these kernels uses it.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void dma16(const unsigned char* gptr, LDS_AS unsigned char* lds) {
+    const unsigned m0v = static_cast<unsigned>(reinterpret_cast<uintptr_t>(lds));
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gptr), "s"(m0v)
+                 : "m0", "memory");
+}
+#pragma clang diagnostic pop
+
 // s_waitcnt on the vector-memory counter only (expcnt and lgkmcnt fields left at "no wait")
 template <int N> __device__ __forceinline__ void wait_vm() {
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
@@ -219,13 +237,21 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
         LDS_AS unsigned char* k_dst = (LDS_AS unsigned char*)(&SK(ST)[wave * 2 * K_GROUP]);
         LDS_AS unsigned char* v_dst = (LDS_AS unsigned char*)(&SV(ST)[wave * 2 * V_GROUP]);
         const bool is_tree = (tile == tree_tile);
-        if (!is_tree && tile * TILE + TILE <= L) {           // full cache tile
+        if (tile >= t_end) {
+            // Nothing left to fetch, but every step issues the same number of loads, so the wait for a tile is one fixed
+            // count on every path.  Four loads of one valid 16-byte piece (served by L2) into the free stage.
+            const unsigned char* any = reinterpret_cast<const unsigned char*>(prm.Q);
+            dma16(any, k_dst);
+            dma16(any, v_dst);
+            dma16(any, k_dst + K_GROUP);
+            dma16(any, v_dst + V_GROUP);
+        } else if (!is_tree && tile * TILE + TILE <= L) {    // full cache tile
             const unsigned char* kb = k_cache + static_cast<long>(tile) * TILE * cache_row_b;
             const unsigned char* vb = v_cache + static_cast<long>(tile) * TILE * cache_row_b;
-            __builtin_amdgcn_global_load_lds(kb + ld_off0, k_dst, 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(vb + ld_off0, v_dst, 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(kb + ld_off1, k_dst + K_GROUP, 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(vb + ld_off1, v_dst + V_GROUP, 16, 0, 0);
+            dma16(kb + ld_off0, k_dst);
+            dma16(vb + ld_off0, v_dst);
+            dma16(kb + ld_off1, k_dst + K_GROUP);
+            dma16(vb + ld_off1, v_dst + V_GROUP);
         } else {                                             // ragged tail or the tree's keys: rows past the end are
             const unsigned char* kb = is_tree ? k_tree : k_cache + static_cast<long>(tile) * TILE * cache_row_b;   // masked later,
             const unsigned char* vb = is_tree ? v_tree : v_cache + static_cast<long>(tile) * TILE * cache_row_b;   // reads stay in range
@@ -233,10 +259,10 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
             const int last = is_tree ? seq_n - 1 : L - 1 - tile * TILE;
             const unsigned o0 = static_cast<unsigned>(min(ld_tok, last)) * row_b + ld_chunk_b;
             const unsigned o1 = static_cast<unsigned>(min(ld_tok + 1, last)) * row_b + ld_chunk_b;
-            __builtin_amdgcn_global_load_lds(kb + o0, k_dst, 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(vb + o0, v_dst, 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(kb + o1, k_dst + K_GROUP, 16, 0, 0);
-            __builtin_amdgcn_global_load_lds(vb + o1, v_dst + V_GROUP, 16, 0, 0);
+            dma16(kb + o0, k_dst);
+            dma16(vb + o0, v_dst);
+            dma16(kb + o1, k_dst + K_GROUP);
+            dma16(vb + o1, v_dst + V_GROUP);
         }
     };
     // Everything the prologue needs from memory is requested back to back (ancestor masks, Q rows, the first three
@@ -256,9 +282,9 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
             qf[kk] = __builtin_bit_cast(bf16x8, v);
         }
     }
-    if (t_begin < t_end) issue_loads(t_begin, std::integral_constant<int, 0>{});
-    if (t_begin + 1 < t_end) issue_loads(t_begin + 1, std::integral_constant<int, 1>{});
-    if (t_begin + 2 < t_end) issue_loads(t_begin + 2, std::integral_constant<int, 2>{});
+    issue_loads(t_begin, std::integral_constant<int, 0>{});
+    issue_loads(t_begin + 1, std::integral_constant<int, 1>{});
+    issue_loads(t_begin + 2, std::integral_constant<int, 2>{});
     // the rows' masks wait in LDS until the tree tile comes; the store is complete before this wave's first barrier
     if (tid < ROWS_PER_WG) s_mask[tid] = my_mask;
     __builtin_amdgcn_s_waitcnt(0xc07f);                      // lgkmcnt(0)
@@ -372,11 +398,9 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
 
     auto process = [&](int tile, auto stc) __attribute__((always_inline)) {
         constexpr int ST = decltype(stc)::value;
-        if (tile + 2 < t_end) wait_vm<2 * LOADS_PER_TILE>();     // the next two tiles' loads may stay in flight
-        else if (tile + 1 < t_end) wait_vm<LOADS_PER_TILE>();
-        else wait_vm<0>();                                   // this thread's part of `tile` has landed
+        wait_vm<2 * LOADS_PER_TILE>();                       // this thread's part of `tile` has landed (two tiles may fly)
         stage_barrier();                                     // ... everyone's has, and the stage read last step is free
-        if (tile + 3 < t_end) issue_loads(tile + 3, std::integral_constant<int, (ST + 3) % STAGES>{});
+        issue_loads(tile + 3, std::integral_constant<int, (ST + 3) % STAGES>{});
         if (!wave_active) return;
 
         const bool is_tree = (tile == tree_tile);
@@ -412,15 +436,19 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
         pv_mfma(va, I0{});
         pv_mfma(va, I2{});
     };
-    for (int tile = t_begin; tile < t_end; tile += STAGES) {
+    for (int tile = t_begin; tile < t_end; tile += STAGES) {    // no path reaches a step without the steps before it
         process(tile, std::integral_constant<int, 0>{});
-        if (tile + 1 < t_end) process(tile + 1, std::integral_constant<int, 1>{});
-        if (tile + 2 < t_end) process(tile + 2, std::integral_constant<int, 2>{});
-        if (tile + 3 < t_end) process(tile + 3, std::integral_constant<int, 3>{});
+        if (tile + 1 >= t_end) break;
+        process(tile + 1, std::integral_constant<int, 1>{});
+        if (tile + 2 >= t_end) break;
+        process(tile + 2, std::integral_constant<int, 2>{});
+        if (tile + 3 >= t_end) break;
+        process(tile + 3, std::integral_constant<int, 3>{});
     }
 #undef FENCE
 
     const float l_tot = cross_half_sum(l_run);
+    wait_vm<0>();                                            // the placeholder loads of the last steps have landed too
 
     // ---- epilogue: every wave parks its block (O^T, max, sum) in the stage buffer of its (column tile, token half)
     // as [32 rows][EPI_ROW_F floats]; then the whole workgroup combines the two halves of each row and writes the
