@@ -140,13 +140,13 @@ __global__ __launch_bounds__(THREADS) void lm_head_kernel(const Params prm) {
             long off = static_cast<long>(t) * TILE_V * prm.weight_stride_b + static_cast<long>(kc) * ROW_B;
             asm volatile("" : "+s"(off));
 #pragma unroll
-            for (int i = 0; i < 4; ++i) __builtin_amdgcn_global_load_lds(w_ptr[i] + off, dst + i * GROUP, 16, 0, 0);
+            for (int i = 0; i < 4; ++i) sage::lds_direct_load16(reinterpret_cast<const unsigned char*>(w_ptr[i] + off), dst + i * GROUP);
         } else {
             const unsigned char* wb = w_base + static_cast<long>(kc) * ROW_B;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const long r = min(t * TILE_V + ld_row + i, rows_mine - 1);
-                __builtin_amdgcn_global_load_lds(wb + r * prm.weight_stride_b + ld_chunk_b, dst + i * GROUP, 16, 0, 0);
+                sage::lds_direct_load16(reinterpret_cast<const unsigned char*>(wb + r * prm.weight_stride_b + ld_chunk_b), dst + i * GROUP);
             }
         }
     };
@@ -155,7 +155,7 @@ __global__ __launch_bounds__(THREADS) void lm_head_kernel(const Params prm) {
         long off = static_cast<long>(kc) * ROW_B;
         asm volatile("" : "+s"(off));
 #pragma unroll
-        for (int i = 0; i < 4; ++i) __builtin_amdgcn_global_load_lds(h_ptr[i] + off, dst + i * GROUP, 16, 0, 0);
+        for (int i = 0; i < 4; ++i) sage::lds_direct_load16(reinterpret_cast<const unsigned char*>(h_ptr[i] + off), dst + i * GROUP);
     };
 
     // ---- per-lane read offsets: fragment kk of row r32 of this wave's half: chunk 2kk + half

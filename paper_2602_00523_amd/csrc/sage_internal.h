@@ -23,4 +23,23 @@ __device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
     return static_cast<uint16_t>(u >> 16);
 }
 
+
+// 16 bytes per lane from global memory straight into LDS (lane l lands at lds + 16 l; LDS-direct load of gfx950).
+// Written as inline assembly so that these loads stay out of the compiler's own bookkeeping of outstanding memory
+// operations.  With the builtin the compiler treats them as operations that may complete out of order: every LDS read
+// then waits for all earlier LDS reads instead of its own, and a read of a stage that was filled earlier in the same
+// loop iteration waits for ALL loads in flight, which drains a prefetch ring.  Kernels that use this keep their own
+// count of loads in flight (s_waitcnt vmcnt(N) plus a barrier); the "memory" clobber keeps LDS reads from moving
+// across an issue.  M0 carries the LDS address of the load; nothing else in these kernels uses it.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void lds_direct_load16(const unsigned char* gptr, __attribute__((address_space(3))) unsigned char* lds) {
+    const unsigned m0v = static_cast<unsigned>(reinterpret_cast<uintptr_t>(lds));
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(gptr), "s"(m0v)
+                 : "m0", "memory");
+}
+#pragma clang diagnostic pop
+
 }  // namespace sage

@@ -16,7 +16,7 @@
 // uses the same reference maximum for numerator and denominator, so the result is unchanged.
 //
 // Data movement.  K/V tiles of 64 tokens go from global memory straight into LDS (16-byte LDS-direct loads, no
-// staging registers; issued through inline assembly, see dma16) through a 4-stage ring, three tiles ahead of the MFMAs.  A wave-level load writes 1 KB of
+// staging registers; issued through inline assembly, see lds_direct_load16) through a 4-stage ring, three tiles ahead of the MFMAs.  A wave-level load writes 1 KB of
 // contiguous LDS; it carries four tokens that are 16 apart, and the 1 KB groups are padded so that consecutive
 // tokens are staggered across the banks (conflict-free reads with compile-time offsets, see the layout constants).
 // Every stage is its own LDS object, so every stage address is a compile-time constant.
@@ -126,24 +126,6 @@ __device__ __forceinline__ BatchShape make_batch_shape(const Params& prm, int la
     return bs;
 }
 
-// 16 bytes per lane from global memory straight into LDS (lane l lands at lds + 16 l).  Written as inline assembly so
-// that these loads stay out of the compiler's own bookkeeping of outstanding memory operations.  With the builtin, any
-// LDS read of a stage that was filled earlier in the same loop iteration made the compiler wait for ALL loads in flight
-// (it treats the loads as operations that may complete out of order), which drained the three-tile prefetch once every
-// four steps and turned every LDS wait into a wait for all LDS reads.  Which tiles have landed is known from wait_vm
-// and the stage barrier, not from program order; the "memory" clobber keeps LDS reads from moving across an issue.
-// M0 carries the LDS address of the load; nothing else in these kernels uses it.
-#pragma clang diagnostic push
-#pragma clang diagnostic ignored "-Winline-asm"
-__device__ __forceinline__ void dma16(const unsigned char* gptr, LDS_AS unsigned char* lds) {
-    const unsigned m0v = static_cast<unsigned>(reinterpret_cast<uintptr_t>(lds));
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                 :
-                 : "v"(gptr), "s"(m0v)
-                 : "m0", "memory");
-}
-#pragma clang diagnostic pop
-
 // s_waitcnt on the vector-memory counter only (expcnt and lgkmcnt fields left at "no wait")
 template <int N> __device__ __forceinline__ void wait_vm() {
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
@@ -241,17 +223,17 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
             // Nothing left to fetch, but every step issues the same number of loads, so the wait for a tile is one fixed
             // count on every path.  Four loads of one valid 16-byte piece (served by L2) into the free stage.
             const unsigned char* any = reinterpret_cast<const unsigned char*>(prm.Q);
-            dma16(any, k_dst);
-            dma16(any, v_dst);
-            dma16(any, k_dst + K_GROUP);
-            dma16(any, v_dst + V_GROUP);
+            sage::lds_direct_load16(any, k_dst);
+            sage::lds_direct_load16(any, v_dst);
+            sage::lds_direct_load16(any, k_dst + K_GROUP);
+            sage::lds_direct_load16(any, v_dst + V_GROUP);
         } else if (!is_tree && tile * TILE + TILE <= L) {    // full cache tile
             const unsigned char* kb = k_cache + static_cast<long>(tile) * TILE * cache_row_b;
             const unsigned char* vb = v_cache + static_cast<long>(tile) * TILE * cache_row_b;
-            dma16(kb + ld_off0, k_dst);
-            dma16(vb + ld_off0, v_dst);
-            dma16(kb + ld_off1, k_dst + K_GROUP);
-            dma16(vb + ld_off1, v_dst + V_GROUP);
+            sage::lds_direct_load16(kb + ld_off0, k_dst);
+            sage::lds_direct_load16(vb + ld_off0, v_dst);
+            sage::lds_direct_load16(kb + ld_off1, k_dst + K_GROUP);
+            sage::lds_direct_load16(vb + ld_off1, v_dst + V_GROUP);
         } else {                                             // ragged tail or the tree's keys: rows past the end are
             const unsigned char* kb = is_tree ? k_tree : k_cache + static_cast<long>(tile) * TILE * cache_row_b;   // masked later,
             const unsigned char* vb = is_tree ? v_tree : v_cache + static_cast<long>(tile) * TILE * cache_row_b;   // reads stay in range
@@ -259,10 +241,10 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
             const int last = is_tree ? seq_n - 1 : L - 1 - tile * TILE;
             const unsigned o0 = static_cast<unsigned>(min(ld_tok, last)) * row_b + ld_chunk_b;
             const unsigned o1 = static_cast<unsigned>(min(ld_tok + 1, last)) * row_b + ld_chunk_b;
-            dma16(kb + o0, k_dst);
-            dma16(vb + o0, v_dst);
-            dma16(kb + o1, k_dst + K_GROUP);
-            dma16(vb + o1, v_dst + V_GROUP);
+            sage::lds_direct_load16(kb + o0, k_dst);
+            sage::lds_direct_load16(vb + o0, v_dst);
+            sage::lds_direct_load16(kb + o1, k_dst + K_GROUP);
+            sage::lds_direct_load16(vb + o1, v_dst + V_GROUP);
         }
     };
     // Everything the prologue needs from memory is requested back to back (ancestor masks, Q rows, the first three
