@@ -28,7 +28,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
 MAX_NODES = 64
 # HBM bytes of one attention launch (main kernel + split merge) from rocprofv3 FETCH_SIZE/WRITE_SIZE runs, scaled by
 # the counters' readings for a 64 MiB copy (profiles/tree_attention_c2_hbm_traffic.md); workloads not profiled: null.
-MEASURED_TRAFFIC_BYTES = {"c2": 35.8e6}
+MEASURED_TRAFFIC_BYTES = {"c2": 35.5e6}
 
 # Trees of the 80-layer configuration are asked to have 64 nodes every step.  With the paper's own parameters the
 # rule never grows a tree that large, so that workload plants a geometric top-64 distribution (ratio 1/2) in the
