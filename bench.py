@@ -49,6 +49,7 @@ def parse():
     ap.add_argument("--only", default=None, choices=["long_kv", "closed_loop", "lm_head", "entropy_topk", "draft_side"],
                     help="run one of the extra measurements alone and print its JSON (for profiling it)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--no-overlap", action="store_true", help="time the single-stream step instead of the overlapped one")
     ap.add_argument("--eager", action="store_true", help="time the steps eagerly instead of as HIP-graph replays")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain 64 MiB device copies, the known-size reference for rocprofv3 FETCH_SIZE/WRITE_SIZE")
@@ -58,7 +59,7 @@ def parse():
 class Workload:
     """Device-resident synthetic inputs of one configuration plus every output/scratch buffer of a step."""
 
-    def __init__(self, name: str, slots: int | None, fused: bool = True):
+    def __init__(self, name: str, slots: int | None, fused: bool = True, overlap: bool = False):
         import numpy as np
         import torch
         from paper_2602_00523_amd import sage, workloads as wl
@@ -158,6 +159,11 @@ class Workload:
         self.step_no = 0
         self.ev_used = 0
         self.fused = fused
+        # Sec. 3.2 lookahead: the tree planned from this step's draft row is verified in the NEXT step, so planning
+        # (a1 + a2) and verification (a3, a1', a4) of a step touch disjoint data; with `overlap` they run on two streams
+        # that fork at the start of a step and join at its end.
+        self.overlap = overlap
+        self.plan_stream = torch.cuda.Stream() if overlap else None
         self._prepare()
         torch.cuda.synchronize()
 
@@ -166,23 +172,24 @@ class Workload:
         """Marshal every call of a step once for the given stream (None = the current stream)."""
         sg = self.sage
         V = self.cfg["vocab"]
+        pstream = self.plan_stream if self.overlap else stream
         if self.fused:                               # the per-row top-k pass runs inside the call that consumes it
-            self.c_a1 = [sg.prepare("sage_entropy_topk_slices", self.draft[s], self.k, self.ws1, stream=stream)
+            self.c_a1 = [sg.prepare("sage_entropy_topk_slices", self.draft[s], self.k, self.ws1, stream=pstream)
                          for s in range(self.slots)]
         else:
             self.c_a1 = [sg.prepare("sage_entropy_topk", self.draft[s], self.k, self.H, self.idx, self.prob, self.renorm,
-                                    self.Hk, self.alpha, self.ws1, stream=stream) for s in range(self.slots)]
+                                    self.Hk, self.alpha, self.ws1, stream=pstream) for s in range(self.slots)]
         self.c_a2, self.c_a3, self.c_a1t, self.c_a4 = [], [], [], []
         for cur in range(2):
             t, nxt = self.tree[cur], self.tree[cur ^ 1]
             if self.fused:
                 self.c_a2.append(sg.prepare("sage_build_tree_from_slices", self.ws1, V, self.prm, self.H, self.idx, self.prob,
                                             self.renorm, self.Hk, self.alpha, nxt["n_nodes"], nxt["parent"], nxt["depth"],
-                                            nxt["rank"], nxt["anc_mask"], None, nxt["node_token"], stream=stream))
+                                            nxt["rank"], nxt["anc_mask"], None, nxt["node_token"], stream=pstream))
             else:
                 self.c_a2.append(sg.prepare("sage_build_tree", self.renorm, self.alpha, self.prm, nxt["n_nodes"],
                                             nxt["parent"], nxt["depth"], nxt["rank"], nxt["anc_mask"], None, self.idx,
-                                            nxt["node_token"], stream=stream))
+                                            nxt["node_token"], stream=pstream))
             self.c_a3.append([[sg.prepare("sage_tree_attention", self.Q[s], self.Kc[s % self.kv_slots][layer],
                                           self.Vc[s % self.kv_slots][layer], self.Kt[s], self.Vt[s], self.O, self.kv_start,
                                           self.kv_len, self.max_len, self.Hkv * self.d, self.d, t["anc_mask"], t["n_nodes"],
@@ -214,6 +221,9 @@ class Workload:
     def step(self, events=None):
         s = self.step_no % self.slots
         cur = self.cur
+        if self.overlap:                             # fork: the plan branch starts where the main stream stands
+            main = self.torch.cuda.current_stream()
+            self.plan_stream.wait_stream(main)
         self.c_a1[s]()
         self.c_a2[cur]()
         if events is None:
@@ -229,6 +239,8 @@ class Workload:
                 e1.record()
         self.c_a1t[cur][s]()
         self.c_a4[cur]()
+        if self.overlap:                             # join: the next step verifies the tree planned in this one
+            main.wait_stream(self.plan_stream)
         self.cur ^= 1
         self.step_no += 1
 
@@ -495,15 +507,17 @@ def closed_loop(name="c2", steps=512):
     tree0 = [{k: v.clone() for k, v in t.items()} for t in w.tree]
     acc_sum = torch.zeros(B, device=dev, dtype=torch.int32)
 
+    plan_stream = torch.cuda.Stream()                         # planning runs beside verification (see Workload)
+
     def prep(stream):
         V = w.cfg["vocab"]
-        c = dict(a1=[sg.prepare("sage_entropy_topk_slices", w.draft[s], w.k, w.ws1, stream=stream) for s in range(w.slots)],
+        c = dict(a1=[sg.prepare("sage_entropy_topk_slices", w.draft[s], w.k, w.ws1, stream=plan_stream) for s in range(w.slots)],
                  a2=[], a3=[], a1t=[], a4=[], commit=[])
         for cur in range(2):
             t, nxt = w.tree[cur], w.tree[cur ^ 1]
             c["a2"].append(sg.prepare("sage_build_tree_from_slices", w.ws1, V, w.prm, w.H, w.idx, w.prob, w.renorm, w.Hk, w.alpha,
                                       nxt["n_nodes"], nxt["parent"], nxt["depth"], nxt["rank"], nxt["anc_mask"], None,
-                                      nxt["node_token"], stream=stream, d_max_seq=d_max))
+                                      nxt["node_token"], stream=plan_stream, d_max_seq=d_max))
             c["a3"].append([sg.prepare("sage_tree_attention", w.Q[s], Kc, Vc, w.Kt[s], w.Vt[s], w.O, kv_start, kv_len, cap,
                                        Hkv * d, d, t["anc_mask"], t["n_nodes"], w.scale, ws3, stream=stream)
                             for s in range(w.slots)])
@@ -523,9 +537,13 @@ def closed_loop(name="c2", steps=512):
 
     def step(c):
         s, cur = state["step"] % w.slots, state["cur"]
-        c["a1"][s](); c["a2"][cur](); c["a3"][cur][s](); c["a1t"][cur][s](); c["a4"][cur]()
+        main = torch.cuda.current_stream()
+        plan_stream.wait_stream(main)                         # fork: the plan uses the depth limit of the previous step
+        c["a1"][s](); c["a2"][cur]()
+        c["a3"][cur][s](); c["a1t"][cur][s](); c["a4"][cur]()
         c["commit"][s](); c["advance"](); c["history"]()
         acc_sum.add_(w.acc_len)
+        main.wait_stream(plan_stream)                         # join: the next step verifies the tree planned here
         state["cur"] ^= 1
         state["step"] += 1
 
@@ -566,7 +584,8 @@ def closed_loop(name="c2", steps=512):
     verified = all(torch.equal(a, b) for a, b in zip(want, got))
     out = dict(workload=name, steps=steps, steps_per_s=steps / wall, ms_per_step=wall * 1e3 / steps,
                calls_per_step="entropy_topk_slices, build_tree_from_slices (per-sequence depth), tree_attention, "
-                              "entropy_topk_slices (k=1), verify_accept_from_slices, commit_path, advance_kv_len, update_history",
+                              "entropy_topk_slices (k=1), verify_accept_from_slices, commit_path, advance_kv_len, update_history; "
+                              "the first two on a second stream beside the rest",
                kv_len_start=[int(x) for x in w.kv_lens], kv_len_end=[int(x) for x in kv_len.cpu().numpy()],
                mean_accept_len=float(acc_sum.sum().item()) / (steps * B), d_max_end=[int(x) for x in d_max.cpu().numpy()],
                replay_equals_eager=bool(verified))
@@ -735,18 +754,34 @@ def main():
     steps = args.steps if args.steps is not None else defaults[args.workload][0]
     warmup = args.warmup if args.warmup is not None else defaults[args.workload][1]
 
-    # the same steps through the five separate calls first (its final state is the reference for the fused run)
+    # the same steps through the five separate calls first (its final state is the reference for the other runs), then
+    # the fused calls on one stream, then the fused calls with planning and verification overlapped (the timed run)
+    def same_state(w, ref_state, ref_step_no):
+        return w.step_no == ref_step_no and all(torch.equal(a, b) for a, b in zip(snapshot(w), ref_state))
+
     w = Workload(args.workload, args.slots, fused=False)
     sep_wall, _ = time_steps(w, steps, warmup, not args.eager)
-    sep_state = snapshot(w)
-    sep_step_no = w.step_no
+    sep_state, sep_step_no = snapshot(w), w.step_no
     del w
     torch.cuda.empty_cache()
     w = Workload(args.workload, args.slots, fused=True)
-    wall, graphed = time_steps(w, steps, warmup, not args.eager)
-    if w.step_no != sep_step_no or not all(torch.equal(a, b) for a, b in zip(snapshot(w), sep_state)):
+    one_wall, _ = time_steps(w, steps, warmup, not args.eager)
+    if not same_state(w, sep_state, sep_step_no):
         print("bench.py: the fused calls and the separate calls ended in different states", file=sys.stderr)
         sys.exit(4)
+    if args.no_overlap:
+        wall, graphed = one_wall, not args.eager
+    else:
+        del w
+        torch.cuda.empty_cache()
+        w = Workload(args.workload, args.slots, fused=True, overlap=True)
+        wall, graphed = time_steps(w, steps, warmup, not args.eager)
+        torch.cuda.synchronize()
+        if not same_state(w, sep_state, sep_step_no):
+            print("bench.py: overlapped planning and the single-stream step ended in different states", file=sys.stderr)
+            sys.exit(4)
+        w.overlap = False                            # the measurement passes below run on one stream
+        w._prepare(None)
     att_ms, n_log, eager_wall = time_attention_launches(w, min(steps, 2000))
     ms_per_step = wall * 1e3 / steps
     eager_att_us = sum(att_ms) / len(att_ms) * 1e3
@@ -780,6 +815,10 @@ def main():
             "calls_per_step": "sage_entropy_topk_slices, sage_build_tree_from_slices, sage_tree_attention x layers, "
                               "sage_entropy_topk_slices, sage_verify_accept_from_slices (final state equal, bit for bit, "
                               "to the same steps through the five separate calls)",
+            "streams": ("planning (a1, a2) and verification (a3, a1', a4) of a step on two streams, forked and joined every step: "
+                        "the tree planned in a step is verified in the next one (Sec. 3.2 lookahead)") if not args.no_overlap
+                       else "one stream",
+            "one_stream_steps_per_s": steps / one_wall, "one_stream_ms_per_step": one_wall * 1e3 / steps,
             "separate_calls_steps_per_s": steps / sep_wall, "separate_calls_ms_per_step": sep_wall * 1e3 / steps,
             "eager_ms_per_step": eager_wall * 1e3 / len(n_log) * w.layers / w.layers},
         "roofline": {"bound": "hbm", "kernel": "sage_tree_attention (bf16 MFMA kernel + split merge, per layer launch)",
