@@ -409,7 +409,7 @@ def cpu_baseline(w: Workload, budget_s: float):
     prm = w.tree_prm
     n_steps, spent, att_spent = 0, 0.0, 0.0
     tree = oracle.build_tree(np.full((w.B, w.k), 1.0 / w.k, np.float32), np.full(w.B, 0.5, np.float32), prm)
-    while spent < budget_s and n_steps < min(w.slots, 8):
+    while spent < budget_s and n_steps < 8 * w.slots:        # about budget_s seconds of oracle work, cycling the input sets
         s = n_steps % w.slots
         draft, target = host(w.draft[s]), host(w.target[s])
         Q, Kt, Vt = host(w.Q[s]), host(w.Kt[s]), host(w.Vt[s])
