@@ -544,11 +544,12 @@ def closed_loop(name="c2", steps=512):
         s, cur = state["step"] % w.slots, state["cur"]
         main = torch.cuda.current_stream()
         plan_stream.wait_stream(main)                         # fork: the plan uses the depth limit of the previous step
-        c["a1"][s](); c["a2"][cur]()
         c["a3"][cur][s](); c["a1t"][cur][s](); c["a4"][cur]()
-        c["commit"][s](); c["advance"](); c["history"]()
+        c["commit"][s](); c["advance"]()
         acc_sum.add_(w.acc_len)
-        main.wait_stream(plan_stream)                         # join: the next step verifies the tree planned here
+        c["a1"][s](); c["a2"][cur]()                          # plan branch, enqueued after the verification branch
+        main.wait_stream(plan_stream)                         # join: the next step verifies the tree planned here, and
+        c["history"]()                                        # the depth limit this plan has read may now be updated
         state["cur"] ^= 1
         state["step"] += 1
 
