@@ -11,7 +11,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsage_hip.so")
+LIB_PATH = os.environ.get("SAGE_HIP_LIBRARY") or os.path.join(_HERE, "libsage_hip.so")   # the in-tree build unless told otherwise
 MAX_NODES = 64
 F32, BF16 = 0, 1
 STATUS = {0: "OK", 1: "INVALID_ARG", 2: "UNSUPPORTED", 3: "WORKSPACE_TOO_SMALL", 4: "LAUNCH_FAILED"}
