@@ -122,9 +122,11 @@ __device__ __forceinline__ void build_tree_wave(int b, int lane, float pt, int t
             if (wl < 1) wl = 1;
             if (wl > k) wl = k;
             const uint64_t pass = __ballot(lane < wl && mul_rn(c, pt) > lane_read(theta_l, l2));
-            if (lane == sp) { st_node = f_node; st_rest = f_rest; }
-            ++sp;
-            f_node = v; f_depth = l; f_cum = c; f_nmask = vm; f_rest = pass;
+            if (pass != 0) {                         // v has candidates: park this frame and expand v (a node without any
+                if (lane == sp) { st_node = f_node; st_rest = f_rest; }   // would be left again at once: same tree)
+                ++sp;
+                f_node = v; f_depth = l; f_cum = c; f_nmask = vm; f_rest = pass;
+            }
         }
     }
 
