@@ -96,26 +96,8 @@ __global__ __launch_bounds__(64 * ACCEPT_WAVES) void accept_kernel(int nunits, c
         if (node >= n) continue;                     // wave-uniform
         if (!AHEAD) request(jj, 0);
         const int j = AHEAD ? jj : 0;
-        float m = -INFINITY;
-#pragma unroll
-        for (int i = 0; i < OWN; ++i)
-            if (lane + 64 * i < nunits) m = fmaxf(m, st[j][i].m);
-        m = wave_max(m);
-        float Z = 0.f, Tm = 0.f;
-#pragma unroll
-        for (int i = 0; i < OWN; ++i) {
-            if (lane + 64 * i < nunits) {
-                const UnitStats u = st[j][i];
-                if (u.m > -INFINITY) {
-                    const float dlt = m - u.m;
-                    const float w = expf(-dlt);
-                    Z += w * u.Z;
-                    Tm += w * (u.T + u.Z * dlt);
-                }
-            }
-        }
-        Z = wave_sum(Z);
-        Tm = wave_sum(Tm);
+        float m, Z, Tm;
+        combine_unit_stats<OWN>(st[j], lane, nunits, m, Z, Tm);
         Key best = key_unpack(ky[j][0]);
 #pragma unroll
         for (int i = 1; i < OWN; ++i) best = key_max(best, key_unpack(ky[j][i]));
