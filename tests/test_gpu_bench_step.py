@@ -1,0 +1,82 @@
+"""Whole steps of the default benchmark workload, executed exactly as bench.py times them (fused calls, planning and
+verification on two streams, one HIP graph per cycle of input sets), checked against the CPU oracle call by call.
+
+bench.capture_cycle itself proves graph replay == eager execution bit for bit; this test adds that every eager step of
+that configuration equals the oracle on the same device inputs: top-k indices, trees, greedy tokens and acceptance
+exact, entropies to 1e-5, attention to 2e-2 (bf16), and that the state after a replayed cycle is the state after the
+checked eager cycle.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from helpers import MAX_NODES
+
+pytestmark = pytest.mark.gpu
+
+
+def close(a, b, tol=1e-5):
+    return (np.abs(a - b) <= tol * np.maximum(np.abs(b), 1.0)).all()
+
+
+@pytest.mark.parametrize("name,slots", [("c2", 4), ("toy", 6), ("c4", 2)])
+def test_steps_in_the_timed_configuration_match_the_oracle(name, slots):
+    import torch
+    import bench
+    import gpu_utils as gu
+
+    w = bench.Workload(name, slots, fused=True, overlap=True)
+    for _ in range(3):                                   # leave the start-up tree behind
+        w.step()
+    graph, cycle = bench.capture_cycle(w)
+    assert graph is not None, "the timed configuration is a graph replay"
+    assert cycle % w.slots == 0 and w.step_no % cycle == 0
+    prm, k, B = w.tree_prm, w.k, w.B
+    tol = 1e-5 if name == "toy" else 2e-2
+    accepted, sizes = [], []
+    for _ in range(cycle):
+        s, cur = w.step_no % w.slots, w.cur
+        tree = {key: gu.to_host(v).copy() for key, v in w.tree[cur].items()}        # planned by the previous step
+        tree["anc_mask"] = tree["anc_mask"].view(np.uint64)
+        print(f" {name}: input set {s}, nodes {tree['n_nodes'].tolist()}", flush=True)
+        w.step()
+        torch.cuda.synchronize()
+        n = tree["n_nodes"]
+        sizes.append(int(n[0]))
+        # -- planning branch: draft row -> entropy, top-k, confidence -> next tree
+        draft = gu.to_host(w.draft[s])
+        o1 = oracle.entropy_topk(draft, k)
+        np.testing.assert_array_equal(gu.to_host(w.idx), o1["topk_idx"])
+        for got, key in ((w.H, "entropy"), (w.prob, "topk_prob"), (w.renorm, "topk_renorm"), (w.Hk, "topk_entropy"),
+                         (w.alpha, "alpha")):
+            assert close(gu.to_host(got), o1[key]), key
+        nxt = {key: gu.to_host(v) for key, v in w.tree[cur ^ 1].items()}
+        o2 = oracle.build_tree(gu.to_host(w.renorm), gu.to_host(w.alpha), prm, gu.to_host(w.idx))
+        np.testing.assert_array_equal(nxt["n_nodes"], o2["n_nodes"])
+        for b in range(B):
+            m = int(o2["n_nodes"][b])
+            for key in ("parent", "depth", "rank", "node_token"):
+                np.testing.assert_array_equal(nxt[key][b, :m], o2[key][b, :m], err_msg=key)
+            np.testing.assert_array_equal(nxt["anc_mask"].view(np.uint64)[b, :m], o2["anc_mask"][b, :m])
+        # -- verification branch: attention under the tree mask, greedy token per node, acceptance
+        ref = oracle.tree_attention(gu.to_host(w.Q[s]), gu.to_host(w.Kc[s % w.kv_slots][0]), gu.to_host(w.Vc[s % w.kv_slots][0]),
+                                    gu.to_host(w.Kt[s]), gu.to_host(w.Vt[s]), gu.to_host(w.kv_start), w.kv_lens,
+                                    w.Hkv * w.d, w.d, tree["anc_mask"], n, w.Hq, w.Hkv, w.d)
+        gu.assert_attention_close(gu.widen(gu.to_host(w.O)), ref, n, tol)
+        o1t = oracle.entropy_topk(gu.to_host(w.target[s]), 1, n, MAX_NODES)
+        live = (np.arange(MAX_NODES)[None, :] < n[:, None]).reshape(-1)
+        tgt = gu.to_host(w.tgt_idx)[:, 0]
+        np.testing.assert_array_equal(tgt[live], o1t["topk_idx"][live, 0])
+        assert close(gu.to_host(w.tH)[live], o1t["entropy"][live])
+        tgt_full = np.where(live, tgt, 0).reshape(B, MAX_NODES)
+        o4 = oracle.verify_accept(tree["node_token"], tgt_full, tree["parent"], tree["depth"], n, w.path_cap)
+        for got, key in ((w.acc_len, "accept_len"), (w.best, "best_node"), (w.path, "path_nodes"), (w.out_tok, "out_tokens")):
+            np.testing.assert_array_equal(gu.to_host(got), o4[key], err_msg=key)
+        accepted.append(int(o4["accept_len"][0]))
+    assert max(accepted) >= 1                            # drafts do get accepted
+    assert name == "toy" or len(set(sizes)) > 1          # and at the 72B shapes the trees change from step to step
+    want = bench.snapshot(w)
+    graph.replay()
+    torch.cuda.synchronize()
+    got = bench.snapshot(w)
+    assert all(torch.equal(a, b) for a, b in zip(want, got))
