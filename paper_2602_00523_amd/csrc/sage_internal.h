@@ -40,6 +40,14 @@ __device__ __forceinline__ void lds_direct_load16(const unsigned char* gptr, __a
                  : "v"(gptr), "s"(m0v)
                  : "m0", "memory");
 }
+// The 4-byte form: lane l lands at lds + 4 l.
+__device__ __forceinline__ void lds_direct_load4(const unsigned char* gptr, __attribute__((address_space(3))) unsigned char* lds) {
+    const unsigned m0v = static_cast<unsigned>(reinterpret_cast<uintptr_t>(lds));
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off"
+                 :
+                 : "v"(gptr), "s"(m0v)
+                 : "m0", "memory");
+}
 #pragma clang diagnostic pop
 
 }  // namespace sage

@@ -178,6 +178,7 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
 
     int id = blockIdx.x;
     const int g = id % prm.Hkv; id /= prm.Hkv;
+    const int inv_G = (65536 + prm.G - 1) / prm.G;           // (m * inv_G) >> 16 == m / G for the rows of a KV head
 
     // One pass over tiles [t_begin, t_end) of sequence b for column group cg; the un-normalised partial goes to out_base.
     auto run_segment = [&](const int b, const int L, const int seq_n, const int seq_rows, const int cg, const int t_begin,
@@ -193,9 +194,6 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
 
     // ---- this lane's query row
     const int m_local = ct * 32 + r32;                       // row within the group
-    const int m = cg * ROWS_PER_WG + m_local;                // row within the KV head
-    const int node = m / prm.G;
-    const bool row_valid = ct < group_ct && m < seq_rows;
     // ---- loader: instruction i of wave w copies tokens r, r+16, r+32, r+48 (r = 2w + i) of K and of V, 1 KB of
     //      LDS each: lane l fills chunk l%16 of token r + 16 (l/16).  Addresses are a wave-uniform tile base plus a
     //      32-bit per-lane offset that is the same for every full tile, so a tile costs no address arithmetic.
@@ -247,29 +245,52 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
             sage::lds_direct_load16(vb + o1, v_dst + V_GROUP);
         }
     };
-    // Everything the prologue needs from memory is requested back to back (ancestor masks, Q rows, the first three
-    // K/V tiles) so that the workgroup pays one memory round trip before its first MFMA, not three.
-    uint64_t my_mask = 0ull;                                 // threads 0..127: mask of row `tid` of this group
-    if (tid < ROWS_PER_WG) {
-        const int mm = cg * ROWS_PER_WG + tid;
-        if (mm < seq_rows) my_mask = prm.anc_mask[static_cast<long>(b) * SAGE_MAX_NODES + mm / prm.G];
-    }
-    bf16x8 qf[8];
+    // Everything the prologue needs from memory goes straight into LDS, requested back to back in this order: the rows'
+    // ancestor masks, the Q rows (into the ring's fourth stage, idle until the first tile step refills it), the first
+    // three K/V tiles.  No load returns into a register, so the compiler never waits on the vector-memory counter here
+    // and the only waits are the counted ones: loads complete in order, so masks and Q have landed once no more than the
+    // tile loads are outstanding, and the first tile is processed while the second and third are still arriving.
+    // Rows past the group's last one repeat that row (their results are never written).
+    auto row_of = [&](int local) __attribute__((always_inline)) {      // row `local` of this group -> (node, head in group)
+        const int mm = min(cg * ROWS_PER_WG + local, seq_rows - 1);
+        const int nd = (mm * inv_G) >> 16;                               // exact for mm < 512, G <= 16
+        return make_int2(nd, mm - nd * prm.G);
+    };
     {
-        const uint16_t* qrow = prm.Q + ((static_cast<long>(b) * SAGE_MAX_NODES + node) * prm.Hq + g * prm.G + (m % prm.G)) * D;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (row_valid) v = *reinterpret_cast<const uint4*>(qrow + kk * 16 + half * 8);
-            qf[kk] = __builtin_bit_cast(bf16x8, v);
-        }
+        // wave w (and w + 4 again: every wave issues the same number of loads) brings both words of the masks of rows
+        // 32 (w % 4) + lane / 2
+        const int2 r = row_of((wave & 3) * 32 + (lane >> 1));
+        sage::lds_direct_load4(
+            reinterpret_cast<const unsigned char*>(prm.anc_mask + static_cast<long>(b) * SAGE_MAX_NODES + r.x) + (lane & 1) * 4,
+            (LDS_AS unsigned char*)(&s_mask[(wave & 3) * 32]));
     }
+    // Q rows as two blocks of 64 in the layout of a K tile (K buffer) and of a V tile (V buffer) of stage 3: row q of a
+    // block sits at (q % 16) * GROUP + (q / 16) * ROW_B.
+#pragma unroll
+    for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int2 r = row_of(blk * 64 + wave * 2 + i + 16 * (lane >> 4));
+            const unsigned char* src = reinterpret_cast<const unsigned char*>(
+                prm.Q + ((static_cast<long>(b) * SAGE_MAX_NODES + r.x) * prm.Hq + g * prm.G + r.y) * D) + ld_chunk_b;
+            if (blk == 0) sage::lds_direct_load16(src, (LDS_AS unsigned char*)(&sK3[(wave * 2 + i) * K_GROUP]));
+            else sage::lds_direct_load16(src, (LDS_AS unsigned char*)(&sV3[(wave * 2 + i) * V_GROUP]));
+        }
     issue_loads(t_begin, std::integral_constant<int, 0>{});
     issue_loads(t_begin + 1, std::integral_constant<int, 1>{});
     issue_loads(t_begin + 2, std::integral_constant<int, 2>{});
-    // the rows' masks wait in LDS until the tree tile comes; the store is complete before this wave's first barrier
-    if (tid < ROWS_PER_WG) s_mask[tid] = my_mask;
-    __builtin_amdgcn_s_waitcnt(0xc07f);                      // lgkmcnt(0)
+    wait_vm<3 * LOADS_PER_TILE>();                           // this thread's mask and Q loads have landed
+    stage_barrier();                                         // ... everyone's have
+    bf16x8 qf[8];                                            // this lane's query row: the B operand of every score MFMA
+    {
+        const int q = (ct & 1) * 32 + r32;                   // row within its block of 64
+        const lds_byte* qb = (ct >> 1) ? (const lds_byte*)sV3 + (q & 15) * V_GROUP : (const lds_byte*)sK3 + (q & 15) * K_GROUP;
+        qb += (q >> 4) * ROW_B + half * 16;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) qf[kk] = __builtin_bit_cast(bf16x8, *(const LDS_AS uint4*)(qb + kk * 32));
+    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);                      // lgkmcnt(0): Q is in registers before this wave reaches the
+                                                             // first step's barrier, after which stage 3 is refilled
 
     // ---- per-lane LDS read offsets (this wave's 32-token half starts sub_lo * 2 * ROW_B into every group).
     // K fragment kk: token r32 of the half, chunk 2kk + half -> k_lane + 32 kk.
@@ -470,15 +491,18 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
     if (!BATCH) {
         const int slot = id % prm.nslot;
         const int b = id / prm.nslot;
-        const int L = prm.kv_len[b] > 0 ? prm.kv_len[b] : 0;
-        const Split sp = make_split(prm.n_nodes[b], L, prm.G, prm.nslot, prm.min_tiles_per_split);
+        const int len_b = prm.kv_len[b];                     // the three per-sequence words are requested together
+        const int n_b = prm.n_nodes[b];
+        const long start_b = prm.kv_start[b];
+        const int L = len_b > 0 ? len_b : 0;
+        const Split sp = make_split(n_b, L, prm.G, prm.nslot, prm.min_tiles_per_split);
         if (sp.col_groups > prm.nslot) return;              // host guarantees nslot >= the largest group count
         const int cg = slot % sp.col_groups;
         const int split = slot / sp.col_groups;
         if (split >= sp.nsplit) return;
         const int t_begin = split * sp.tiles_per_split;
         const int t_end = min(sp.tiles, t_begin + sp.tiles_per_split);
-        run_segment(b, L, sp.n, sp.rows, cg, t_begin, t_end, sp.tiles - 1, prm.kv_start[b],
+        run_segment(b, L, sp.n, sp.rows, cg, t_begin, t_end, sp.tiles - 1, start_b,
                     prm.part + ((static_cast<long>(b) * prm.Hkv + g) * prm.nslot + slot) * ROWS_PER_WG * PART_FLOATS);
     } else {
         const BatchShape bs = make_batch_shape(prm, lane);  // lane b holds sequence b
@@ -527,26 +551,31 @@ __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const P
     // As in the main kernel, a KV head's blocks are congruent modulo the KV-head count, so with 8 KV heads they run on
     // the XCD whose L2 still holds that head's partials.  Rows of a KV head are numbered as there: node * G + head-in-group.
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // a row's address is wave-uniform: scalar registers
     int id = blockIdx.x;
     const int g = id % prm.Hkv; id /= prm.Hkv;
     const float c = prm.scale_log2e;
 
-    // one row: `first` = the row in the first of its nsplit partials, split_stride = distance to the next one
-    auto merge_row = [&](int b, int node, int hg, const float* first, long split_stride, int nsplit) __attribute__((always_inline)) {
+    // one row: `first_row` = the row in the first of its nsplit partials, stride_b = bytes to the next one.  Addresses are
+    // the uniform row pointer plus 32-bit offsets (a launch's partials span far less than 4 GB from any row), which
+    // keeps the address arithmetic of up to 32 loads per lane off the critical path of this latency-bound kernel.
+    auto merge_row = [&](int b, int node, int hg, const float* first_row, unsigned stride_b, int nsplit) __attribute__((always_inline)) {
+        const unsigned char* first = reinterpret_cast<const unsigned char*>(first_row);
         float2 o = make_float2(0.f, 0.f);
         float m_all = -INFINITY, l_all = 0.f;
         for (int s0 = 0; s0 < nsplit; s0 += MAXS) {           // MAXS splits at a time
             const int cnt = min(MAXS, nsplit - s0);
             float ms = -INFINITY, ls = 0.f;
             if (lane < cnt) {
-                ms = first[(s0 + lane) * split_stride + D];
-                ls = first[(s0 + lane) * split_stride + D + 1];
+                const float2 pair = *reinterpret_cast<const float2*>(first + static_cast<unsigned>(s0 + lane) * stride_b + D * 4u);
+                ms = pair.x;
+                ls = pair.y;
             }
             float2 v[MAXS];
 #pragma unroll
             for (int s = 0; s < MAXS; ++s)
-                v[s] = s < cnt ? *reinterpret_cast<const float2*>(first + (s0 + s) * split_stride + 2 * lane) : make_float2(0.f, 0.f);
+                v[s] = s < cnt ? *reinterpret_cast<const float2*>(first + static_cast<unsigned>(s0 + s) * stride_b + 8u * lane)
+                               : make_float2(0.f, 0.f);
             float m_blk = ms;
             for (int off = 32; off > 0; off >>= 1) m_blk = fmaxf(m_blk, __shfl_xor(m_blk, off));
             const float m_new = fmaxf(m_all, m_blk);
@@ -575,13 +604,15 @@ __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const P
     const int phase = id % phases;
     const int b = id / phases;
     if (!BATCH) {
-        const int L = prm.kv_len[b] > 0 ? prm.kv_len[b] : 0;
-        const Split sp = make_split(prm.n_nodes[b], L, prm.G, prm.nslot, prm.min_tiles_per_split);
+        const int len_b = prm.kv_len[b];                     // requested together
+        const int n_b = prm.n_nodes[b];
+        const int L = len_b > 0 ? len_b : 0;
+        const Split sp = make_split(n_b, L, prm.G, prm.nslot, prm.min_tiles_per_split);
         if (sp.col_groups > prm.nslot) return;
         const float* base = prm.part + ((static_cast<long>(b) * prm.Hkv + g) * prm.nslot) * ROWS_PER_WG * PART_FLOATS;
         for (int m = phase * ROWS + wave; m < sp.rows; m += phases * ROWS)
             merge_row(b, m / prm.G, m % prm.G, base + (static_cast<long>(m / ROWS_PER_WG) * ROWS_PER_WG + m % ROWS_PER_WG) * PART_FLOATS,
-                      static_cast<long>(sp.col_groups) * ROWS_PER_WG * PART_FLOATS, sp.nsplit);
+                      static_cast<unsigned>(sp.col_groups) * (ROWS_PER_WG * PART_FLOATS * 4u), sp.nsplit);
     } else {
         const BatchShape bs = make_batch_shape(prm, lane);
         const int live = __builtin_amdgcn_readlane(bs.n, b) * prm.G;
@@ -594,7 +625,7 @@ __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const P
             const int s_first = u0 / bs.q;
             merge_row(b, m / prm.G, m % prm.G,
                       prm.part + ((static_cast<long>(g) * prm.nslot + s_first + groups_before + cg) * ROWS_PER_WG + m % ROWS_PER_WG) * PART_FLOATS,
-                      static_cast<long>(ROWS_PER_WG) * PART_FLOATS, (u0 + tiles_b - 1) / bs.q - s_first + 1);
+                      ROWS_PER_WG * PART_FLOATS * 4u, (u0 + tiles_b - 1) / bs.q - s_first + 1);
         }
     }
 }
