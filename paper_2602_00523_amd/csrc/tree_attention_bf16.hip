@@ -176,8 +176,10 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
     const int r32 = lane & 31;           // MFMA row (A) / column (B, C) owned by this lane
     const int half = lane >> 5;
 
-    int id = blockIdx.x;
-    const int g = id % prm.Hkv; id /= prm.Hkv;
+    // grid = (KV head, slot or range, sequence): the KV head is the fastest index of the launch order, and no index
+    // costs a division
+    const int g = blockIdx.x;
+    const int id = blockIdx.y;
     const int inv_G = (65536 + prm.G - 1) / prm.G;           // (m * inv_G) >> 16 == m / G for the rows of a KV head
 
     // One pass over tiles [t_begin, t_end) of sequence b for column group cg; the un-normalised partial goes to out_base.
@@ -489,11 +491,12 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
     };   // run_segment
 
     if (!BATCH) {
-        const int slot = id % prm.nslot;
-        const int b = id / prm.nslot;
-        const int len_b = prm.kv_len[b];                     // the three per-sequence words are requested together
-        const int n_b = prm.n_nodes[b];
-        const long start_b = prm.kv_start[b];
+        const int slot = id;
+        const int b = blockIdx.z;
+        int len_b = prm.kv_len[b];                           // the three per-sequence words are requested together and
+        int n_b = prm.n_nodes[b];                            // waited for once (the empty statement pins that point)
+        long start_b = prm.kv_start[b];
+        asm volatile("" : "+s"(len_b), "+s"(n_b), "+s"(start_b));
         const int L = len_b > 0 ? len_b : 0;
         const Split sp = make_split(n_b, L, prm.G, prm.nslot, prm.min_tiles_per_split);
         if (sp.col_groups > prm.nslot) return;              // host guarantees nslot >= the largest group count
@@ -552,8 +555,7 @@ __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const P
     // the XCD whose L2 still holds that head's partials.  Rows of a KV head are numbered as there: node * G + head-in-group.
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // a row's address is wave-uniform: scalar registers
-    int id = blockIdx.x;
-    const int g = id % prm.Hkv; id /= prm.Hkv;
+    const int g = blockIdx.x;                                // grid = (KV head, phase, sequence), as in the main kernel
     const float c = prm.scale_log2e;
 
     // one row: `first_row` = the row in the first of its nsplit partials, stride_b = bytes to the next one.  Addresses are
@@ -598,14 +600,15 @@ __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const P
         reinterpret_cast<uint32_t*>(prm.O + ((static_cast<long>(b) * SAGE_MAX_NODES + node) * prm.Hq + g * prm.G + hg) * D)[lane] = packed;
     };
 
-    // blockIdx = ((b * phases) + phase) * Hkv + KV head; a wave walks the live rows phase * ROWS + wave, + phases * ROWS,
+    // blockIdx = (KV head, phase, sequence); a wave walks the live rows phase * ROWS + wave, + phases * ROWS,
     // ... of its (sequence, KV head), so that rows of nodes past n_nodes cost no workgroup of their own
     const int phases = prm.merge_phases;
-    const int phase = id % phases;
-    const int b = id / phases;
+    const int phase = blockIdx.y;
+    const int b = blockIdx.z;
     if (!BATCH) {
-        const int len_b = prm.kv_len[b];                     // requested together
-        const int n_b = prm.n_nodes[b];
+        int len_b = prm.kv_len[b];                           // requested together, waited for once
+        int n_b = prm.n_nodes[b];
+        asm volatile("" : "+s"(len_b), "+s"(n_b));
         const int L = len_b > 0 ? len_b : 0;
         const Split sp = make_split(n_b, L, prm.G, prm.nslot, prm.min_tiles_per_split);
         if (sp.col_groups > prm.nslot) return;
@@ -711,9 +714,7 @@ int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const voi
     p.scale_log2e = scale * 1.4426950408889634f;
 
     p.nrange = sh.nrange;
-    const long blocks = sh.batch ? static_cast<long>(p.nrange) * Hkv : static_cast<long>(B) * p.nslot * Hkv;
-    if (blocks > 0x7FFFFFFFL) return SAGE_UNSUPPORTED;
-    const dim3 grid(static_cast<unsigned>(blocks)), block(THREADS);
+    const dim3 grid(Hkv, sh.batch ? p.nrange : p.nslot, sh.batch ? 1 : B), block(THREADS);
     if (sh.batch) hipLaunchKernelGGL(tree_attention_bf16_kernel<true>, grid, block, 0, stream, p);
     else hipLaunchKernelGGL(tree_attention_bf16_kernel<false>, grid, block, 0, stream, p);
     if (hipGetLastError() != hipSuccess) return SAGE_LAUNCH_FAILED;
@@ -721,9 +722,7 @@ int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const voi
     const int row_blocks = (SAGE_MAX_NODES * G + mrows - 1) / mrows;
     const int want_phases = sh.batch ? MERGE_PHASES_BATCH : row_blocks;
     p.merge_phases = row_blocks < want_phases ? row_blocks : want_phases;
-    const long merge_blocks = static_cast<long>(B) * p.merge_phases * Hkv;
-    if (merge_blocks > 0x7FFFFFFFL) return SAGE_UNSUPPORTED;
-    const dim3 mgrid(static_cast<unsigned>(merge_blocks)), mblock(64 * mrows);
+    const dim3 mgrid(Hkv, p.merge_phases, B), mblock(64 * mrows);
     const int max_tiles = (max_kv_len + TILE - 1) / TILE + 1;
     int most = sh.batch ? p.nrange : p.nslot;         // upper bound of the splits of a row: no more than slots, or tiles
     if (most > max_tiles) most = max_tiles;
