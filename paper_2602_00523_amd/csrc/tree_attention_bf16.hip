@@ -493,10 +493,15 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
     if (!BATCH) {
         const int slot = id;
         const int b = blockIdx.z;
-        int len_b = prm.kv_len[b];                           // the three per-sequence words are requested together and
-        int n_b = prm.n_nodes[b];                            // waited for once (the empty statement pins that point)
-        long start_b = prm.kv_start[b];
-        asm volatile("" : "+s"(len_b), "+s"(n_b), "+s"(start_b));
+        // the three per-sequence words are requested together and waited for once: the empty statement needs all of
+        // them in scalar registers at one point (readfirstlane: uniform values, wherever the compiler loaded them)
+        int len_b = __builtin_amdgcn_readfirstlane(prm.kv_len[b]);
+        int n_b = __builtin_amdgcn_readfirstlane(prm.n_nodes[b]);
+        const int64_t start_w = prm.kv_start[b];
+        int start_lo = __builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(start_w)));
+        int start_hi = __builtin_amdgcn_readfirstlane(static_cast<int>(start_w >> 32));
+        asm("" : "+s"(len_b), "+s"(n_b), "+s"(start_lo), "+s"(start_hi));
+        const long start_b = (static_cast<long>(start_hi) << 32) | static_cast<uint32_t>(start_lo);
         const int L = len_b > 0 ? len_b : 0;
         const Split sp = make_split(n_b, L, prm.G, prm.nslot, prm.min_tiles_per_split);
         if (sp.col_groups > prm.nslot) return;              // host guarantees nslot >= the largest group count
@@ -561,23 +566,38 @@ __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const P
     // one row: `first_row` = the row in the first of its nsplit partials, stride_b = bytes to the next one.  Addresses are
     // the uniform row pointer plus 32-bit offsets (a launch's partials span far less than 4 GB from any row), which
     // keeps the address arithmetic of up to 32 loads per lane off the critical path of this latency-bound kernel.
-    auto merge_row = [&](int b, int node, int hg, const float* first_row, unsigned stride_b, int nsplit) __attribute__((always_inline)) {
-        const unsigned char* first = reinterpret_cast<const unsigned char*>(first_row);
+    auto merge_row = [&](int b, int node, int hg, const float* first_row, unsigned stride_b, int nsplit_v) __attribute__((always_inline)) {
+        // wave-uniform by construction; said to the compiler, which cannot see it through the lane exchanges of a batch
+        const uintptr_t first_v = reinterpret_cast<uintptr_t>(first_row);
+        typedef const __attribute__((address_space(1))) unsigned char* global_bytes;    // rebuilt from integers: say "global"
+        global_bytes first = reinterpret_cast<global_bytes>(
+            (static_cast<uintptr_t>(static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(first_v >> 32)))) << 32) |
+            static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(first_v))));   // (the builtin returns int)
+        stride_b = __builtin_amdgcn_readfirstlane(stride_b);
+        const int nsplit = __builtin_amdgcn_readfirstlane(nsplit_v);
         float2 o = make_float2(0.f, 0.f);
         float m_all = -INFINITY, l_all = 0.f;
         for (int s0 = 0; s0 < nsplit; s0 += MAXS) {           // MAXS splits at a time
             const int cnt = min(MAXS, nsplit - s0);
             float ms = -INFINITY, ls = 0.f;
+            global_bytes ps = first + static_cast<size_t>(s0) * stride_b;   // uniform: partial s0 of this row
             if (lane < cnt) {
-                const float2 pair = *reinterpret_cast<const float2*>(first + static_cast<unsigned>(s0 + lane) * stride_b + D * 4u);
-                ms = pair.x;
-                ls = pair.y;
+                const f32x2 pair = *reinterpret_cast<const __attribute__((address_space(1))) f32x2*>(
+                    ps + (static_cast<unsigned>(lane) * stride_b + D * 4u));
+                ms = pair[0];
+                ls = pair[1];
             }
             float2 v[MAXS];
+            const unsigned lane_off = 8u * lane;
 #pragma unroll
-            for (int s = 0; s < MAXS; ++s)
-                v[s] = s < cnt ? *reinterpret_cast<const float2*>(first + static_cast<unsigned>(s0 + s) * stride_b + 8u * lane)
-                               : make_float2(0.f, 0.f);
+            for (int s = 0; s < MAXS; ++s) {
+                f32x2 x = {0.f, 0.f};
+                if (s < cnt) x = *reinterpret_cast<const __attribute__((address_space(1))) f32x2*>(ps + lane_off);
+                v[s] = make_float2(x[0], x[1]);
+                uintptr_t next = reinterpret_cast<uintptr_t>(ps) + stride_b;
+                asm("" : "+s"(next));                         // one scalar add per split, in place: left alone the compiler
+                ps = reinterpret_cast<global_bytes>(next);   // builds 32 pointers with 64-bit multiplies ahead of the loop
+            }
             float m_blk = ms;
             for (int off = 32; off > 0; off >>= 1) m_blk = fmaxf(m_blk, __shfl_xor(m_blk, off));
             const float m_new = fmaxf(m_all, m_blk);
@@ -606,9 +626,9 @@ __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const P
     const int phase = blockIdx.y;
     const int b = blockIdx.z;
     if (!BATCH) {
-        int len_b = prm.kv_len[b];                           // requested together, waited for once
-        int n_b = prm.n_nodes[b];
-        asm volatile("" : "+s"(len_b), "+s"(n_b));
+        int len_b = __builtin_amdgcn_readfirstlane(prm.kv_len[b]);   // requested together, waited for once
+        int n_b = __builtin_amdgcn_readfirstlane(prm.n_nodes[b]);
+        asm("" : "+s"(len_b), "+s"(n_b));
         const int L = len_b > 0 ? len_b : 0;
         const Split sp = make_split(n_b, L, prm.G, prm.nslot, prm.min_tiles_per_split);
         if (sp.col_groups > prm.nslot) return;
