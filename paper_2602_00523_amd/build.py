@@ -17,7 +17,10 @@ SOURCES = ["entropy_topk.hip", "build_tree.hip", "tree_attention.hip", "tree_att
 # packed-fp32 instructions are switched off for every translation unit; the tree rule additionally forbids
 # contraction so that its fp32 decisions are reproducible bit for bit.
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
-          "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wno-unused-command-line-argument"]
+          "-packed-fp32-ops", "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wno-unused-command-line-argument",
+          # leading scalar kernel arguments arrive in registers at wave launch instead of through a first memory fetch:
+          # these kernels are short and launched in dependent chains, where that round trip is a visible share
+          "-mllvm", "-amdgpu-kernarg-preload-count=16"]
 EXTRA = {"build_tree.hip": ["-ffp-contract=off"]}
 
 

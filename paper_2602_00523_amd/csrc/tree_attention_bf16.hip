@@ -155,8 +155,14 @@ __device__ __forceinline__ float cross_half_sum(float v) {
 // BATCH = true (2..64 sequences): the tiles of all sequences form one list per KV head (sequence-major, then column
 // group), cut into prm.nrange equal ranges; a workgroup owns one range and runs one pass (prologue, tile loop,
 // epilogue) per (sequence, column group) segment its range touches, so ragged lengths cannot unbalance the launch.
+// The leading arguments repeat fields of prm: explicit scalar arguments are preloaded into registers at wave launch
+// (the library is built with kernel-argument preloading), so the first thing a workgroup does, fetching its sequence's
+// length and node count, does not wait for a fetch of the argument block first.
 template <bool BATCH>
-__global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Params prm) {
+__global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const int* __restrict__ kv_len_arg,
+                                                                      const int* __restrict__ n_nodes_arg,
+                                                                      const int64_t* __restrict__ kv_start_arg, int nslot_arg,
+                                                                      int min_tps_arg, int G_arg, const Params prm) {
     // one LDS object per stage and operand (see header)
     __shared__ __align__(1024) unsigned char sK0[K_STAGE_B];
     __shared__ __align__(1024) unsigned char sK1[K_STAGE_B];
@@ -180,7 +186,7 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
     // costs a division
     const int g = blockIdx.x;
     const int id = blockIdx.y;
-    const int inv_G = (65536 + prm.G - 1) / prm.G;           // (m * inv_G) >> 16 == m / G for the rows of a KV head
+    const int inv_G = (65536 + G_arg - 1) / G_arg;           // (m * inv_G) >> 16 == m / G for the rows of a KV head
 
     // One pass over tiles [t_begin, t_end) of sequence b for column group cg; the un-normalised partial goes to out_base.
     auto run_segment = [&](const int b, const int L, const int seq_n, const int seq_rows, const int cg, const int t_begin,
@@ -495,16 +501,16 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const Para
         const int b = blockIdx.z;
         // the three per-sequence words are requested together and waited for once: the empty statement needs all of
         // them in scalar registers at one point (readfirstlane: uniform values, wherever the compiler loaded them)
-        int len_b = __builtin_amdgcn_readfirstlane(prm.kv_len[b]);
-        int n_b = __builtin_amdgcn_readfirstlane(prm.n_nodes[b]);
-        const int64_t start_w = prm.kv_start[b];
+        int len_b = __builtin_amdgcn_readfirstlane(kv_len_arg[b]);
+        int n_b = __builtin_amdgcn_readfirstlane(n_nodes_arg[b]);
+        const int64_t start_w = kv_start_arg[b];
         int start_lo = __builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(start_w)));
         int start_hi = __builtin_amdgcn_readfirstlane(static_cast<int>(start_w >> 32));
         asm("" : "+s"(len_b), "+s"(n_b), "+s"(start_lo), "+s"(start_hi));
         const long start_b = (static_cast<long>(start_hi) << 32) | static_cast<uint32_t>(start_lo);
         const int L = len_b > 0 ? len_b : 0;
-        const Split sp = make_split(n_b, L, prm.G, prm.nslot, prm.min_tiles_per_split);
-        if (sp.col_groups > prm.nslot) return;              // host guarantees nslot >= the largest group count
+        const Split sp = make_split(n_b, L, G_arg, nslot_arg, min_tps_arg);
+        if (sp.col_groups > nslot_arg) return;              // host guarantees nslot >= the largest group count
         const int cg = slot % sp.col_groups;
         const int split = slot / sp.col_groups;
         if (split >= sp.nsplit) return;
@@ -554,7 +560,10 @@ constexpr int MERGE_ROWS_BATCH = 4;      // (16 rows per workgroup measured 6 % 
 constexpr int MERGE_PHASES_BATCH = 32;   // batches: workgroups per (sequence, KV head), each walking the live rows; a
                                          // single sequence gets a wave per possible row (fewer measured no faster)
 template <int MAXS, bool BATCH, int ROWS>
-__global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const Params prm) {
+__global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const int* __restrict__ kv_len_arg,
+                                                                         const int* __restrict__ n_nodes_arg, int nslot_arg,
+                                                                         int min_tps_arg, int G_arg, int phases_arg,
+                                                                         const Params prm) {
     static_assert(MAXS <= 32, "one split per lane, one register pair per split");
     // As in the main kernel, a KV head's blocks are congruent modulo the KV-head count, so with 8 KV heads they run on
     // the XCD whose L2 still holds that head's partials.  Rows of a KV head are numbered as there: node * G + head-in-group.
@@ -622,16 +631,16 @@ __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const P
 
     // blockIdx = (KV head, phase, sequence); a wave walks the live rows phase * ROWS + wave, + phases * ROWS,
     // ... of its (sequence, KV head), so that rows of nodes past n_nodes cost no workgroup of their own
-    const int phases = prm.merge_phases;
+    const int phases = phases_arg;
     const int phase = blockIdx.y;
     const int b = blockIdx.z;
     if (!BATCH) {
-        int len_b = __builtin_amdgcn_readfirstlane(prm.kv_len[b]);   // requested together, waited for once
-        int n_b = __builtin_amdgcn_readfirstlane(prm.n_nodes[b]);
+        int len_b = __builtin_amdgcn_readfirstlane(kv_len_arg[b]);   // requested together, waited for once
+        int n_b = __builtin_amdgcn_readfirstlane(n_nodes_arg[b]);
         asm("" : "+s"(len_b), "+s"(n_b));
         const int L = len_b > 0 ? len_b : 0;
-        const Split sp = make_split(n_b, L, prm.G, prm.nslot, prm.min_tiles_per_split);
-        if (sp.col_groups > prm.nslot) return;
+        const Split sp = make_split(n_b, L, G_arg, nslot_arg, min_tps_arg);
+        if (sp.col_groups > nslot_arg) return;
         const float* base = prm.part + ((static_cast<long>(b) * prm.Hkv + g) * prm.nslot) * ROWS_PER_WG * PART_FLOATS;
         for (int m = phase * ROWS + wave; m < sp.rows; m += phases * ROWS)
             merge_row(b, m / prm.G, m % prm.G, base + (static_cast<long>(m / ROWS_PER_WG) * ROWS_PER_WG + m % ROWS_PER_WG) * PART_FLOATS,
@@ -735,8 +744,12 @@ int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const voi
 
     p.nrange = sh.nrange;
     const dim3 grid(Hkv, sh.batch ? p.nrange : p.nslot, sh.batch ? 1 : B), block(THREADS);
-    if (sh.batch) hipLaunchKernelGGL(tree_attention_bf16_kernel<true>, grid, block, 0, stream, p);
-    else hipLaunchKernelGGL(tree_attention_bf16_kernel<false>, grid, block, 0, stream, p);
+    if (sh.batch)
+        hipLaunchKernelGGL(tree_attention_bf16_kernel<true>, grid, block, 0, stream, kv_len, n_nodes, kv_start, p.nslot,
+                           p.min_tiles_per_split, G, p);
+    else
+        hipLaunchKernelGGL(tree_attention_bf16_kernel<false>, grid, block, 0, stream, kv_len, n_nodes, kv_start, p.nslot,
+                           p.min_tiles_per_split, G, p);
     if (hipGetLastError() != hipSuccess) return SAGE_LAUNCH_FAILED;
     const int mrows = sh.batch ? MERGE_ROWS_BATCH : MERGE_ROWS_SINGLE;
     const int row_blocks = (SAGE_MAX_NODES * G + mrows - 1) / mrows;
@@ -749,13 +762,19 @@ int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const voi
     // more than 32 splits take several passes of 32: 64 register pairs per lane cost more in resident waves than the
     // second round trip does
     if (sh.batch) {
-        if (most <= 8) hipLaunchKernelGGL((tree_attention_merge_kernel<8, true, MERGE_ROWS_BATCH>), mgrid, mblock, 0, stream, p);
-        else if (most <= 16) hipLaunchKernelGGL((tree_attention_merge_kernel<16, true, MERGE_ROWS_BATCH>), mgrid, mblock, 0, stream, p);
-        else hipLaunchKernelGGL((tree_attention_merge_kernel<32, true, MERGE_ROWS_BATCH>), mgrid, mblock, 0, stream, p);
+        if (most <= 8) hipLaunchKernelGGL((tree_attention_merge_kernel<8, true, MERGE_ROWS_BATCH>), mgrid, mblock, 0, stream, kv_len, n_nodes, p.nslot,
+                               p.min_tiles_per_split, G, p.merge_phases, p);
+        else if (most <= 16) hipLaunchKernelGGL((tree_attention_merge_kernel<16, true, MERGE_ROWS_BATCH>), mgrid, mblock, 0, stream, kv_len, n_nodes, p.nslot,
+                               p.min_tiles_per_split, G, p.merge_phases, p);
+        else hipLaunchKernelGGL((tree_attention_merge_kernel<32, true, MERGE_ROWS_BATCH>), mgrid, mblock, 0, stream, kv_len, n_nodes, p.nslot,
+                               p.min_tiles_per_split, G, p.merge_phases, p);
     } else {
-        if (most <= 8) hipLaunchKernelGGL((tree_attention_merge_kernel<8, false, MERGE_ROWS_SINGLE>), mgrid, mblock, 0, stream, p);
-        else if (most <= 16) hipLaunchKernelGGL((tree_attention_merge_kernel<16, false, MERGE_ROWS_SINGLE>), mgrid, mblock, 0, stream, p);
-        else hipLaunchKernelGGL((tree_attention_merge_kernel<32, false, MERGE_ROWS_SINGLE>), mgrid, mblock, 0, stream, p);
+        if (most <= 8) hipLaunchKernelGGL((tree_attention_merge_kernel<8, false, MERGE_ROWS_SINGLE>), mgrid, mblock, 0, stream, kv_len, n_nodes, p.nslot,
+                               p.min_tiles_per_split, G, p.merge_phases, p);
+        else if (most <= 16) hipLaunchKernelGGL((tree_attention_merge_kernel<16, false, MERGE_ROWS_SINGLE>), mgrid, mblock, 0, stream, kv_len, n_nodes, p.nslot,
+                               p.min_tiles_per_split, G, p.merge_phases, p);
+        else hipLaunchKernelGGL((tree_attention_merge_kernel<32, false, MERGE_ROWS_SINGLE>), mgrid, mblock, 0, stream, kv_len, n_nodes, p.nslot,
+                               p.min_tiles_per_split, G, p.merge_phases, p);
     }
     return launch_status();
 }
