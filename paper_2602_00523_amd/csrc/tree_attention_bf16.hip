@@ -477,21 +477,37 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const int*
     }
     __syncthreads();
     {
-        for (int it = tid; it < group_rows * 32; it += THREADS) {
-            const int row = it >> 5, ch = it & 31;           // row of the group, 16-byte chunk of its 128 dims
-            const int rct = row >> 5;
-            const float* b0 = reinterpret_cast<const float*>(SK(rct)) + (row & 31) * EPI_ROW_F;
-            const float* b1 = reinterpret_cast<const float*>(SV(rct)) + (row & 31) * EPI_ROW_F;
-            const float m0 = b0[D], l0 = b0[D + 1], m1 = b1[D], l1 = b1[D + 1];
-            const float m_new = fmaxf(m0, m1);
-            const float w0 = (m0 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m0 - m_new) * c);
-            const float w1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m1 - m_new) * c);
-            const float4 x = *reinterpret_cast<const float4*>(b0 + ch * 4);
-            const float4 y = *reinterpret_cast<const float4*>(b1 + ch * 4);
-            float* out = out_base + row * PART_FLOATS;
-            *reinterpret_cast<float4*>(out + ch * 4) =
-                make_float4(x.x * w0 + y.x * w1, x.y * w0 + y.y * w1, x.z * w0 + y.z * w1, x.w * w0 + y.w * w1);
-            if (ch == 0) { out[D] = m_new; out[D + 1] = l0 * w0 + l1 * w1; }
+        // thread -> 16-byte chunk tid % 32 of rows tid / 32, + 16, ...: every row's LDS reads are requested before the first
+        // one is used, so the pass costs one LDS round trip, not one per row
+        constexpr int PASSES = ROWS_PER_WG * 32 / THREADS;
+        const int ch = tid & 31;
+        float4 x[PASSES], y[PASSES];
+        float2 ml0[PASSES], ml1[PASSES];
+#pragma unroll
+        for (int i = 0; i < PASSES; ++i) {
+            const int row = (tid >> 5) + i * (THREADS / 32);
+            if (row < group_rows) {
+                const float* b0 = reinterpret_cast<const float*>(SK(row >> 5)) + (row & 31) * EPI_ROW_F;
+                const float* b1 = reinterpret_cast<const float*>(SV(row >> 5)) + (row & 31) * EPI_ROW_F;
+                ml0[i] = *reinterpret_cast<const float2*>(b0 + D);
+                ml1[i] = *reinterpret_cast<const float2*>(b1 + D);
+                x[i] = *reinterpret_cast<const float4*>(b0 + ch * 4);
+                y[i] = *reinterpret_cast<const float4*>(b1 + ch * 4);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < PASSES; ++i) {
+            const int row = (tid >> 5) + i * (THREADS / 32);
+            if (row < group_rows) {
+                const float m0 = ml0[i].x, l0 = ml0[i].y, m1 = ml1[i].x, l1 = ml1[i].y;
+                const float m_new = fmaxf(m0, m1);
+                const float w0 = (m0 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m0 - m_new) * c);
+                const float w1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m1 - m_new) * c);
+                float* out = out_base + row * PART_FLOATS;
+                *reinterpret_cast<float4*>(out + ch * 4) = make_float4(x[i].x * w0 + y[i].x * w1, x[i].y * w0 + y[i].y * w1,
+                                                                       x[i].z * w0 + y[i].z * w1, x[i].w * w0 + y[i].w * w1);
+                if (ch == 0) { out[D] = m_new; out[D + 1] = l0 * w0 + l1 * w1; }
+            }
         }
     }
     };   // run_segment
