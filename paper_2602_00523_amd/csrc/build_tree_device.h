@@ -57,9 +57,13 @@ __device__ __forceinline__ void build_tree_wave(int b, int lane, float pt, int t
                                                 uint64_t* __restrict__ anc_mask, float* __restrict__ cum_prob,
                                                 int* __restrict__ node_token) {
 
+    // The confidence and the depth limit are the same in every lane, but arrive through per-lane loads or lane
+    // exchanges; said explicitly, everything that steers the walk below (depth, width, node count, stack pointer, the
+    // candidate masks) lives in scalar registers and the walk branches on scalar conditions instead of masking lanes.
+    a = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(a)));
     // the maximum depth of Eq. 10 is per sequence when adaptive history tracking (Sec. 3.3) maintains one
     int d_max = prm.d_max;
-    if (d_max_seq) d_max = min(max(d_max_seq[b], prm.d_min), SAGE_MAX_DEPTH);
+    if (d_max_seq) d_max = min(max(__builtin_amdgcn_readfirstlane(d_max_seq[b]), prm.d_min), SAGE_MAX_DEPTH);
     // Eq. 10 / Eq. 11, rounded half up
     const float Df = floorf(add_rn(add_rn((float)prm.d_min, mul_rn(a, (float)(d_max - prm.d_min))), 0.5f));
     float W = floorf(add_rn(add_rn((float)prm.w_min, mul_rn(sub_rn(1.0f, a), (float)(prm.w_max - prm.w_min))), 0.5f));
