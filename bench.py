@@ -506,7 +506,9 @@ def closed_loop(name="c2", steps=512):
     window, lo, hi = 10, 2.0, 3.0                             # Sec. 5 "Implementation details"
     hist = torch.zeros(B, window, device=dev, dtype=torch.int32)
     count = torch.zeros(B, device=dev, dtype=torch.int32)
-    d_max = torch.full((B,), w.tree_prm["d_max"], device=dev, dtype=torch.int32)
+    # two depth-limit arrays: a step's plan and its closing call both read [cur]; the closing call writes [cur ^ 1], so the
+    # plan branch, which runs beside it on another stream, never sees a limit change under it
+    d_max = [torch.full((B,), w.tree_prm["d_max"], device=dev, dtype=torch.int32) for _ in range(2)]
     code = sg.F32 if w.dtype == torch.float32 else sg.BF16
     ws3 = torch.empty(sg.sage_tree_attention_workspace_bytes(code, B, w.Hq, Hkv, d, cap), device=dev, dtype=torch.uint8)
     tree0 = [{k: v.clone() for k, v in t.items()} for t in w.tree]
@@ -522,7 +524,7 @@ def closed_loop(name="c2", steps=512):
             t, nxt = w.tree[cur], w.tree[cur ^ 1]
             c["a2"].append(sg.prepare("sage_build_tree_from_slices", w.ws1, V, w.prm, w.H, w.idx, w.prob, w.renorm, w.Hk, w.alpha,
                                       nxt["n_nodes"], nxt["parent"], nxt["depth"], nxt["rank"], nxt["anc_mask"], None,
-                                      nxt["node_token"], stream=plan_stream, d_max_seq=d_max))
+                                      nxt["node_token"], stream=plan_stream, d_max_seq=d_max[cur]))
             c["a3"].append([sg.prepare("sage_tree_attention", w.Q[s], Kc, Vc, w.Kt[s], w.Vt[s], w.O, kv_start, kv_len, cap,
                                        Hkv * d, d, t["anc_mask"], t["n_nodes"], w.scale, ws3, stream=stream)
                             for s in range(w.slots)])
@@ -531,11 +533,9 @@ def closed_loop(name="c2", steps=512):
             c["a4"].append(sg.prepare("sage_verify_accept_from_slices", w.ws1t, V, t["node_token"], t["parent"], t["depth"],
                                       t["anc_mask"], t["n_nodes"], w.path_cap, w.tH, w.tgt_idx, w.acc_len, w.best, w.path,
                                       w.out_tok, stream=stream))
-        c["commit"] = [sg.prepare("sage_commit_path", w.Kt[s], w.Vt[s], Kc, Vc, kv_start, kv_len, cap, Hkv * d, d, w.path,
-                                  w.acc_len, stream=stream) for s in range(w.slots)]
-        c["advance"] = sg.prepare("sage_advance_kv_len", kv_len, w.acc_len, cap, stream=stream)
-        c["history"] = sg.prepare("sage_update_history", w.acc_len, hist, count, d_max, lo, hi, w.tree_prm["d_min"],
-                                  w.tree_prm["d_max"], None, stream=stream)
+        c["close"] = [[sg.prepare("sage_close_step", w.Kt[s], w.Vt[s], Kc, Vc, kv_start, kv_len, cap, Hkv * d, d, w.path, w.acc_len,
+                                  hist, count, d_max[cur], d_max[cur ^ 1], lo, hi, w.tree_prm["d_min"], w.tree_prm["d_max"],
+                                  stream=stream) for s in range(w.slots)] for cur in range(2)]
         return c
 
     state = dict(cur=0, step=0)
@@ -545,16 +545,17 @@ def closed_loop(name="c2", steps=512):
         main = torch.cuda.current_stream()
         plan_stream.wait_stream(main)                         # fork: the plan uses the depth limit of the previous step
         c["a3"][cur][s](); c["a1t"][cur][s](); c["a4"][cur]()
-        c["commit"][s](); c["advance"]()
+        c["close"][cur][s]()                                  # commit, advance, history in one launch
         acc_sum.add_(w.acc_len)
         c["a1"][s](); c["a2"][cur]()                          # plan branch, enqueued after the verification branch
-        main.wait_stream(plan_stream)                         # join: the next step verifies the tree planned here, and
-        c["history"]()                                        # the depth limit this plan has read may now be updated
+        main.wait_stream(plan_stream)                         # join: the next step verifies the tree planned here
         state["cur"] ^= 1
         state["step"] += 1
 
     def reset():
-        kv_len.copy_(kv_len0); hist.zero_(); count.zero_(); d_max.fill_(w.tree_prm["d_max"]); acc_sum.zero_()
+        kv_len.copy_(kv_len0); hist.zero_(); count.zero_(); acc_sum.zero_()
+        for dm in d_max:
+            dm.fill_(w.tree_prm["d_max"])
         for t, t0 in zip(w.tree, tree0):
             for k in t:
                 t[k].copy_(t0[k])
@@ -563,7 +564,7 @@ def closed_loop(name="c2", steps=512):
     def snapshot_state():
         grown = int((kv_len - kv_len0).max().item())
         rows = torch.cat([Kc[b * cap + int(w.kv_lens[b]):b * cap + int(w.kv_lens[b]) + grown] for b in range(B)])
-        return [x.clone() for x in (kv_len, hist, count, d_max, acc_sum, w.acc_len, w.O, rows)]
+        return [x.clone() for x in (kv_len, hist, count, d_max[state["cur"]], acc_sum, w.acc_len, w.O, rows)]
 
     eager = prep(None)
     reset()
@@ -590,10 +591,11 @@ def closed_loop(name="c2", steps=512):
     verified = all(torch.equal(a, b) for a, b in zip(want, got))
     out = dict(workload=name, steps=steps, steps_per_s=steps / wall, ms_per_step=wall * 1e3 / steps,
                calls_per_step="entropy_topk_slices, build_tree_from_slices (per-sequence depth), tree_attention, "
-                              "entropy_topk_slices (k=1), verify_accept_from_slices, commit_path, advance_kv_len, update_history; "
+                              "entropy_topk_slices (k=1), verify_accept_from_slices, close_step (commit, advance, history); "
                               "the first two on a second stream beside the rest",
                kv_len_start=[int(x) for x in w.kv_lens], kv_len_end=[int(x) for x in kv_len.cpu().numpy()],
-               mean_accept_len=float(acc_sum.sum().item()) / (steps * B), d_max_end=[int(x) for x in d_max.cpu().numpy()],
+               mean_accept_len=float(acc_sum.sum().item()) / (steps * B),
+               d_max_end=[int(x) for x in d_max[state["cur"]].cpu().numpy()],
                replay_equals_eager=bool(verified))
     del w
     torch.cuda.empty_cache()

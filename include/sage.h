@@ -204,6 +204,25 @@ int sage_update_history(const int* accept_len, int B, int window, float lo, floa
                         int* hist, int* count, int* d_max, float* avg_out, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * sage_close_step -- what closes a step of Alg. 1 (Phase 3 update of the context, Sec. 3.3
+ * adaptive history tracking) in one launch: sage_commit_path for one layer, then
+ * sage_advance_kv_len, then sage_update_history, with the same arguments, semantics and
+ * results (one workgroup per sequence does all three in that order; the path rows are copied
+ * against the old kv_len[b], which is then advanced in place).  For models with several
+ * layers, commit the other layers with sage_commit_path first.
+ * d_max_in / d_max_out [B] i32 (device): the depth limit is read from d_max_in and the updated
+ * one written to d_max_out.  They may be the same array; two arrays let a tree-planning call
+ * that runs concurrently on another stream keep reading the limit of the previous step.
+ * Errors: as for the three calls it replaces.
+ */
+int sage_close_step(const void* Kt, const void* Vt, void* Kc, void* Vc, int dtype, int B, int Hkv, int d,
+                    const int64_t* kv_start, int* kv_len, int kv_capacity,
+                    long kv_token_stride, long kv_head_stride,
+                    const int* path_nodes, const int* accept_len, int path_cap,
+                    int window, float lo, float hi, int d_floor, int d_cap,
+                    int* hist, int* count, const int* d_max_in, int* d_max_out, float* avg_out, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * sage_lm_head_topk -- sage_entropy_topk on logits that are never stored: row r of the
  * logits is hidden[r, :] . weight[v, :] over v < vocab (the target's output projection,
  * whose softmax is the distribution of Eq. 1 and whose argmax is the greedy token of

@@ -7,18 +7,16 @@
 
 namespace {
 
-// One workgroup per (path slot j, sequence b): copies the K row and the V row of node path[j] (Hkv heads x d
-// elements each) to cache position kv_len[b] + j in 16-byte pieces.
-__global__ __launch_bounds__(256) void commit_path_kernel(
+// The workgroup copies the K row and the V row of node path[j] of sequence b (Hkv heads x d elements each) to cache
+// position len_b + j in 16-byte pieces.
+__device__ __forceinline__ void commit_row(
     const unsigned char* __restrict__ Kt, const unsigned char* __restrict__ Vt, unsigned char* __restrict__ Kc,
-    unsigned char* __restrict__ Vc, int esz, int Hkv, int d, const int64_t* __restrict__ kv_start,
-    const int* __restrict__ kv_len, int kv_capacity, long kv_token_stride, long kv_head_stride,
-    const int* __restrict__ path_nodes, const int* __restrict__ accept_len, int path_cap) {
-    const int j = blockIdx.x, b = blockIdx.y;
-    const int tau = accept_len[b];
+    unsigned char* __restrict__ Vc, int esz, int Hkv, int d, const int64_t* __restrict__ kv_start, int len_b,
+    int kv_capacity, long kv_token_stride, long kv_head_stride, const int* __restrict__ path_nodes, int tau, int path_cap,
+    int j, int b) {
     if (j > tau || j >= path_cap) return;
     const int node = path_nodes[static_cast<long>(b) * path_cap + j];
-    const long pos = static_cast<long>(kv_len[b]) + j;
+    const long pos = static_cast<long>(len_b) + j;
     if (node < 0 || node >= SAGE_MAX_NODES || pos >= kv_capacity) return;      // never read or write out of range
     const int pieces = d * esz / 16;                                           // 16-byte pieces of one head's row
     const long src_row = (static_cast<long>(b) * SAGE_MAX_NODES + node) * Hkv * d * esz;
@@ -32,23 +30,35 @@ __global__ __launch_bounds__(256) void commit_path_kernel(
     }
 }
 
+// One workgroup per (path slot j, sequence b).
+__global__ __launch_bounds__(256) void commit_path_kernel(
+    const unsigned char* __restrict__ Kt, const unsigned char* __restrict__ Vt, unsigned char* __restrict__ Kc,
+    unsigned char* __restrict__ Vc, int esz, int Hkv, int d, const int64_t* __restrict__ kv_start,
+    const int* __restrict__ kv_len, int kv_capacity, long kv_token_stride, long kv_head_stride,
+    const int* __restrict__ path_nodes, const int* __restrict__ accept_len, int path_cap) {
+    const int b = blockIdx.y;
+    commit_row(Kt, Vt, Kc, Vc, esz, Hkv, d, kv_start, kv_len[b], kv_capacity, kv_token_stride, kv_head_stride, path_nodes,
+               accept_len[b], path_cap, blockIdx.x, b);
+}
+
+__device__ __forceinline__ int advanced_len(int len_b, int tau, int kv_capacity) {
+    const long n = static_cast<long>(len_b) + tau + 1;                        // the root and the tau accepted tokens
+    return n > kv_capacity ? kv_capacity : static_cast<int>(n);
+}
+
 __global__ void advance_kv_len_kernel(int* __restrict__ kv_len, const int* __restrict__ accept_len, int B, int kv_capacity) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
-    const long n = static_cast<long>(kv_len[b]) + accept_len[b] + 1;          // the root and the tau accepted tokens
-    kv_len[b] = n > kv_capacity ? kv_capacity : static_cast<int>(n);
+    kv_len[b] = advanced_len(kv_len[b], accept_len[b], kv_capacity);
 }
 
-// One wave per sequence: lane i holds window slot i.
-__global__ __launch_bounds__(64) void update_history_kernel(const int* __restrict__ accept_len, int window, float lo, float hi,
-                                                            int d_floor, int d_cap, int* __restrict__ hist,
-                                                            int* __restrict__ count, int* __restrict__ d_max,
-                                                            float* __restrict__ avg_out) {
-    const int b = blockIdx.x, lane = threadIdx.x;
+// One wave for sequence b: lane i holds window slot i.  The new depth limit goes to d_max_out (which may be d_max_in).
+__device__ __forceinline__ void history_wave(int b, int lane, int tau, int window, float lo, float hi, int d_floor, int d_cap,
+                                             int* __restrict__ hist, int* __restrict__ count, const int* d_max_in,
+                                             int* d_max_out, float* __restrict__ avg_out) {
     int* h = hist + static_cast<long>(b) * window;
     const int cnt = count[b];
     const int slot = cnt % window;
-    const int tau = accept_len[b];
     const int n = min(cnt + 1, window);
     int v = 0;
     if (lane < n) v = (lane == slot) ? tau : h[lane];
@@ -59,11 +69,38 @@ __global__ __launch_bounds__(64) void update_history_kernel(const int* __restric
         count[b] = cnt + 1;
         const float fs = static_cast<float>(sum), fn = static_cast<float>(n);
         if (avg_out) avg_out[b] = __fdiv_rn(fs, fn);
-        int dm = d_max[b];
+        int dm = d_max_in[b];
         if (fs < __fmul_rn(lo, fn)) dm -= 1;                                   // strictly below the lower threshold
         else if (fs > __fmul_rn(hi, fn)) dm += 1;                              // strictly above the upper one
-        d_max[b] = min(max(dm, d_floor), d_cap);
+        d_max_out[b] = min(max(dm, d_floor), d_cap);
     }
+}
+
+__global__ __launch_bounds__(64) void update_history_kernel(const int* __restrict__ accept_len, int window, float lo, float hi,
+                                                            int d_floor, int d_cap, int* __restrict__ hist,
+                                                            int* __restrict__ count, int* d_max, float* __restrict__ avg_out) {
+    history_wave(blockIdx.x, threadIdx.x, accept_len[blockIdx.x], window, lo, hi, d_floor, d_cap, hist, count, d_max, d_max,
+                 avg_out);
+}
+
+// sage_close_step: one workgroup per sequence does what the three kernels above do, in their order: every path row is
+// copied against the old length (read once, before anything is written), then thread 0 advances the length and wave 0
+// updates the history.
+__global__ __launch_bounds__(256) void close_step_kernel(
+    const unsigned char* __restrict__ Kt, const unsigned char* __restrict__ Vt, unsigned char* __restrict__ Kc,
+    unsigned char* __restrict__ Vc, int esz, int Hkv, int d, const int64_t* __restrict__ kv_start, int* kv_len,
+    int kv_capacity, long kv_token_stride, long kv_head_stride, const int* __restrict__ path_nodes,
+    const int* __restrict__ accept_len, int path_cap, int window, float lo, float hi, int d_floor, int d_cap,
+    int* __restrict__ hist, int* __restrict__ count, const int* d_max_in, int* d_max_out, float* __restrict__ avg_out) {
+    const int b = blockIdx.x;
+    const int tau = accept_len[b];
+    const int len_b = kv_len[b];
+    for (int j = 0; j <= tau && j < path_cap; ++j)
+        commit_row(Kt, Vt, Kc, Vc, esz, Hkv, d, kv_start, len_b, kv_capacity, kv_token_stride, kv_head_stride, path_nodes, tau,
+                   path_cap, j, b);
+    __syncthreads();                                                           // every thread has read the old length
+    if (threadIdx.x == 0) kv_len[b] = advanced_len(len_b, tau, kv_capacity);
+    if (threadIdx.x < 64) history_wave(b, threadIdx.x, tau, window, lo, hi, d_floor, d_cap, hist, count, d_max_in, d_max_out, avg_out);
 }
 
 }  // namespace
@@ -106,5 +143,32 @@ extern "C" int sage_update_history(const int* accept_len, int B, int window, flo
     if (B == 0) return SAGE_OK;
     hipLaunchKernelGGL(update_history_kernel, dim3(B), dim3(64), 0, sage::as_stream(stream), accept_len, window, lo, hi,
                        d_floor, d_cap, hist, count, d_max, avg_out);
+    return sage::launch_status();
+}
+
+extern "C" int sage_close_step(const void* Kt, const void* Vt, void* Kc, void* Vc, int dtype, int B, int Hkv, int d,
+                               const int64_t* kv_start, int* kv_len, int kv_capacity, long kv_token_stride,
+                               long kv_head_stride, const int* path_nodes, const int* accept_len, int path_cap, int window,
+                               float lo, float hi, int d_floor, int d_cap, int* hist, int* count, const int* d_max_in,
+                               int* d_max_out, float* avg_out, void* stream) {
+    if (!Kt || !Vt || !Kc || !Vc || !kv_start || !kv_len || !path_nodes || !accept_len) return SAGE_INVALID_ARG;
+    if (!hist || !count || !d_max_in || !d_max_out) return SAGE_INVALID_ARG;
+    if (dtype != SAGE_F32 && dtype != SAGE_BF16) return SAGE_INVALID_ARG;
+    if (B < 0 || Hkv < 1 || d < 1 || path_cap < 1 || kv_capacity < 0) return SAGE_INVALID_ARG;
+    if (kv_head_stride < d || kv_token_stride < d) return SAGE_INVALID_ARG;
+    const int esz = dtype == SAGE_F32 ? 4 : 2;
+    if ((static_cast<long>(d) * esz) % 16 != 0 || (kv_token_stride * esz) % 16 != 0 || (kv_head_stride * esz) % 16 != 0)
+        return SAGE_INVALID_ARG;
+    if (!sage::aligned(Kt, 16) || !sage::aligned(Vt, 16) || !sage::aligned(Kc, 16) || !sage::aligned(Vc, 16))
+        return SAGE_INVALID_ARG;
+    if (window < 1 || window > 64 || d_floor < 1 || d_floor > d_cap || d_cap > SAGE_MAX_DEPTH || !(lo <= hi))
+        return SAGE_INVALID_ARG;
+    if (B > 65535 || path_cap > SAGE_MAX_NODES) return SAGE_UNSUPPORTED;
+    if (B == 0) return SAGE_OK;
+    hipLaunchKernelGGL(close_step_kernel, dim3(B), dim3(256), 0, sage::as_stream(stream),
+                       static_cast<const unsigned char*>(Kt), static_cast<const unsigned char*>(Vt),
+                       static_cast<unsigned char*>(Kc), static_cast<unsigned char*>(Vc), esz, Hkv, d, kv_start, kv_len,
+                       kv_capacity, kv_token_stride, kv_head_stride, path_nodes, accept_len, path_cap, window, lo, hi, d_floor,
+                       d_cap, hist, count, d_max_in, d_max_out, avg_out);
     return sage::launch_status();
 }

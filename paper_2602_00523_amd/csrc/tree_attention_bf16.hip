@@ -4,7 +4,8 @@
 // Formulation.  All query rows that share a KV head (node i, head-in-group hg -> row m = i*G + hg, up to 512
 // rows) are processed together so each K/V byte is fetched from HBM once.  Everything is computed transposed:
 //   S^T = K Q^T   (tokens x rows):  A operand = K rows as stored in the cache (16-byte LDS reads),
-//                                   B operand = Q rows held in registers for the whole kernel;
+//                                   B operand = Q rows, brought in through LDS once and held in registers
+//                                   for the whole kernel;
 //   O^T = V^T P^T (dims x rows):    A operand = V^T, read from row-major V in LDS with the transposing
 //                                   64-bit LDS read of gfx950, B operand = P^T.
 // In the 32x32 MFMA accumulator layout a lane owns ONE query row (column lane%32) and 16 tokens of it, so the
@@ -16,17 +17,19 @@
 // uses the same reference maximum for numerator and denominator, so the result is unchanged.
 //
 // Data movement.  K/V tiles of 64 tokens go from global memory straight into LDS (16-byte LDS-direct loads, no
-// staging registers; issued through inline assembly, see lds_direct_load16) through a 4-stage ring, three tiles ahead of the MFMAs.  A wave-level load writes 1 KB of
-// contiguous LDS; it carries four tokens that are 16 apart, and the 1 KB groups are padded so that consecutive
-// tokens are staggered across the banks (conflict-free reads with compile-time offsets, see the layout constants).
-// Every stage is its own LDS object, so every stage address is a compile-time constant.
+// staging registers; issued through inline assembly, see lds_direct_load16) through a 4-stage ring, three tiles
+// ahead of the MFMAs.  A wave-level load writes 1 KB of contiguous LDS; it carries four tokens that are 16 apart,
+// and the 1 KB groups are padded so that consecutive tokens are staggered across the banks (conflict-free reads
+// with compile-time offsets, see the layout constants).  Every stage is its own LDS object, so every stage address
+// is a compile-time constant.  The ancestor masks and the Q rows take the same road ahead of the first tiles, so
+// that no load of the kernel returns into a register and every wait on the vector-memory counter is a counted one.
 //
 // Decomposition (decided on the device from n_nodes/kv_len, so no host round trip): a workgroup of 8 waves
 // owns (sequence, KV head, group of up to 4 column tiles = 128 query rows, KV split); with 2..64 sequences the
-// splits are equal ranges of one list of all sequences' tiles, so ragged lengths leave no CU idle (see the kernel).  Waves w and w+4 share
-// column tile w and each takes one 32-token half of every tile; the halves are combined through LDS at the end.
-// Workgroups of one KV head are congruent modulo the KV-head count, which with 8 KV heads pins a head to one
-// XCD and its L2: the column groups of a large tree re-read K/V from that L2, not from HBM.  Each workgroup
+// splits are equal ranges of one list of all sequences' tiles, so ragged lengths leave no CU idle (see the
+// kernel).  Waves w and w+4 share column tile w and each takes one 32-token half of every tile; the halves are
+// combined through LDS at the end.  The KV head is the fastest grid index, so in launch order the workgroups of one
+// KV head are congruent modulo the KV-head count, which with 8 KV heads pins a head to one XCD and its L2: the column groups of a large tree re-read K/V from that L2, not from HBM.  Each workgroup
 // writes an un-normalised partial (max, sum, O^T); a second kernel merges the splits in a fixed order
 // (deterministic, no float atomics) and writes bf16.
 #include <type_traits>

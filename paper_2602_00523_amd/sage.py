@@ -59,6 +59,9 @@ def lib():
         L.sage_update_history.restype = _ci
         L.sage_update_history.argtypes = [_vp, _ci, _ci, _cf, _cf, _ci, _ci, _vp, _vp, _vp, _vp, _vp]
         L.sage_lm_head_topk_workspace_bytes.restype = _sz
+        L.sage_close_step.restype = _ci
+        L.sage_close_step.argtypes = [_vp, _vp, _vp, _vp, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _cl, _cl, _vp, _vp, _ci, _ci, _cf, _cf,
+                                      _ci, _ci, _vp, _vp, _vp, _vp, _vp, _vp]
         L.sage_entropy_topk_slices.restype = _ci
         L.sage_entropy_topk_slices.argtypes = [_vp, _ci, _ci, _ci, _cl, _ci, _vp, _ci, _vp, _sz, _vp]
         L.sage_build_tree_from_slices.restype = _ci
@@ -200,7 +203,16 @@ def _args_verify_accept_from_slices(slices, vocab, token, parent, depth, anc_mas
             _stream(stream)]
 
 
-_MARSHAL = {"sage_entropy_topk_slices": _args_entropy_topk_slices,
+def _args_close_step(Kt, Vt, Kc, Vc, kv_start, kv_len, kv_capacity, kv_token_stride, kv_head_stride, path_nodes, accept_len,
+                     hist, count, d_max_in, d_max_out, lo, hi, d_floor, d_cap, avg_out=None, stream=None):
+    B, _, Hkv, d = Kt.shape
+    return [_ptr(Kt), _ptr(Vt), _ptr(Kc), _ptr(Vc), _dtype_code(Kt), B, Hkv, d, _ptr(kv_start), _ptr(kv_len), kv_capacity,
+            kv_token_stride, kv_head_stride, _ptr(path_nodes), _ptr(accept_len), path_nodes.shape[1], hist.shape[1], lo, hi,
+            d_floor, d_cap, _ptr(hist), _ptr(count), _ptr(d_max_in), _ptr(d_max_out), _ptr(avg_out), _stream(stream)]
+
+
+_MARSHAL = {"sage_close_step": _args_close_step,
+            "sage_entropy_topk_slices": _args_entropy_topk_slices,
             "sage_build_tree_from_slices": _args_build_tree_from_slices,
             "sage_verify_accept_from_slices": _args_verify_accept_from_slices,
             "sage_entropy_topk": _args_entropy_topk, "sage_build_tree": _args_build_tree,
@@ -235,6 +247,10 @@ def sage_advance_kv_len(*a, **kw):
 
 def sage_update_history(*a, **kw):
     _check("sage_update_history", lib().sage_update_history(*_args_update_history(*a, **kw)))
+
+
+def sage_close_step(*a, **kw):
+    _check("sage_close_step", lib().sage_close_step(*_args_close_step(*a, **kw)))
 
 
 def sage_lm_head_topk(*a, **kw):

@@ -173,3 +173,23 @@ def test_fused_calls_validate_on_the_host(lib):
     assert va(slices=null) == INVALID and va(tok=null) == INVALID and va(tgt=null) == INVALID
     assert va(cap=0) == INVALID and va(B=-1) == INVALID and va(vocab=0) == INVALID
     assert va(B=2000) == UNSUPPORTED and va(vocab=2_000_000) == UNSUPPORTED
+
+
+def test_close_step_validates_on_the_host(lib):
+    INVALID, UNSUPPORTED = 1, 2
+    vp, ci, cl, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_float
+    null, one = vp(0), vp(16)
+    lib.sage_close_step.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, vp, vp, ci, cl, cl, vp, vp, ci, ci, cf, cf, ci, ci, vp, vp, vp,
+                                    vp, vp, vp]
+    cs = lambda Kt=one, dtype=1, B=0, Hkv=8, d=128, lens=one, ts=1024, hs=128, cap=9, window=10, lo=2.0, hi=3.0, floor=3, top=8, \
+                hist=one, dm_in=one, dm_out=one: lib.sage_close_step(Kt, one, one, one, dtype, B, Hkv, d, one, lens, 4096, ts, hs,
+                                                                    one, one, cap, window, lo, hi, floor, top, hist, one, dm_in,
+                                                                    dm_out, null, null)
+    assert cs() == 0
+    assert cs(Kt=null) == INVALID and cs(lens=null) == INVALID and cs(hist=null) == INVALID
+    assert cs(dm_in=null) == INVALID and cs(dm_out=null) == INVALID
+    assert cs(dtype=4) == INVALID and cs(B=-1) == INVALID and cs(d=0) == INVALID and cs(cap=0) == INVALID
+    assert cs(ts=100) == INVALID and cs(hs=3) == INVALID and cs(d=60, ts=480, hs=60) == INVALID       # 120-byte rows
+    assert cs(window=0) == INVALID and cs(window=65) == INVALID and cs(lo=4.0) == INVALID
+    assert cs(floor=0) == INVALID and cs(floor=9) == INVALID and cs(top=40) == INVALID
+    assert cs(B=70000) == UNSUPPORTED and cs(cap=65) == UNSUPPORTED

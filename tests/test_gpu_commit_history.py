@@ -178,3 +178,48 @@ def test_closed_loop_steps(gu):
         gu.gpu_update_history(g4["accept_len"], hist_g, cnt_g, dm_g, 1.0, 2.0, 2, 5)
         np.testing.assert_array_equal(dm_g.cpu().numpy(), dm_o)
     assert (lens > np.array([70, 9])).all()
+
+
+@pytest.mark.parametrize("dtype,Hkv,d,two_limits", [("bf16", 8, 128, True), ("f32", 2, 64, False)])
+def test_close_step_equals_commit_advance_history(gu, dtype, Hkv, d, two_limits):
+    """sage_close_step over several steps against the oracle's commit, advance and history applied in that order: cache
+    bytes, lengths, window, counts, depth limits and averages, all exact; with two depth-limit arrays the input one is
+    left alone."""
+    import torch
+    from paper_2602_00523_amd import sage
+    g = np.random.default_rng(23)
+    B, cap, path_cap, window = 6, 80, 9, 10
+    lens = np.array([0, 30, 76, 71, 12, 55], np.int32)         # empty cache, room, overflow within a few steps
+    Kc = wl.gaussian(3, (B * cap, Hkv, d), dtype)
+    Vc = wl.gaussian(4, (B * cap, Hkv, d), dtype)
+    ts, hs = Hkv * d, d
+    start = np.arange(B, dtype=np.int64) * cap
+    Ko, Vo = Kc.copy(), Vc.copy()
+    hist_o = np.zeros((B, window), np.int32); cnt_o = np.zeros(B, np.int32); dm_o = np.full(B, 6, np.int32)
+    dev = dict(Kc=gu.to_dev(Kc), Vc=gu.to_dev(Vc), start=gu.to_dev(start), lens=gu.to_dev(lens.copy()),
+               hist=torch.zeros((B, window), device="cuda:0", dtype=torch.int32),
+               cnt=torch.zeros(B, device="cuda:0", dtype=torch.int32),
+               dm=[torch.full((B,), 6, device="cuda:0", dtype=torch.int32) for _ in range(2)],
+               avg=torch.zeros(B, device="cuda:0", dtype=torch.float32))
+    for t in range(7):
+        Kt = wl.gaussian(100 + t, (B, MAX_NODES, Hkv, d), dtype)
+        Vt = wl.gaussian(200 + t, (B, MAX_NODES, Hkv, d), dtype)
+        path_nodes, accept_len = _random_paths(g, B, path_cap)
+        oracle.commit_path(Kt, Vt, Ko, Vo, start, lens, cap, ts, hs, path_nodes, accept_len, Hkv, d)
+        lens = oracle.advance_kv_len(lens, accept_len, cap)
+        avg_o = oracle.update_history(accept_len, hist_o, cnt_o, dm_o, window, 2.0, 3.0, 3, 8)
+        d_in, d_out = (dev["dm"][t % 2], dev["dm"][(t + 1) % 2]) if two_limits else (dev["dm"][0], dev["dm"][0])
+        before = d_in.clone()
+        sage.sage_close_step(gu.to_dev(Kt), gu.to_dev(Vt), dev["Kc"], dev["Vc"], dev["start"], dev["lens"], cap, ts, hs,
+                             gu.to_dev(path_nodes), gu.to_dev(accept_len), dev["hist"], dev["cnt"], d_in, d_out, 2.0, 3.0, 3, 8,
+                             dev["avg"])
+        torch.cuda.synchronize()
+        assert (gu.to_host(dev["Kc"]) == Ko).all() and (gu.to_host(dev["Vc"]) == Vo).all(), t
+        np.testing.assert_array_equal(dev["lens"].cpu().numpy(), lens)
+        np.testing.assert_array_equal(dev["hist"].cpu().numpy(), hist_o)
+        np.testing.assert_array_equal(dev["cnt"].cpu().numpy(), cnt_o)
+        np.testing.assert_array_equal(d_out.cpu().numpy(), dm_o)
+        np.testing.assert_array_equal(dev["avg"].cpu().numpy(), avg_o)
+        if two_limits:
+            assert torch.equal(d_in, before)
+    assert lens.max() == cap and not (Ko == Kc).all()           # a sequence ran into its capacity; rows were written
