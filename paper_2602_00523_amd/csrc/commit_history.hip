@@ -62,8 +62,7 @@ __device__ __forceinline__ void history_wave(int b, int lane, int tau, int windo
     const int n = min(cnt + 1, window);
     int v = 0;
     if (lane < n) v = (lane == slot) ? tau : h[lane];
-    int sum = v;
-    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+    const int sum = static_cast<int>(sage::wave_sum_u32(static_cast<uint32_t>(v)));
     if (lane == 0) {
         h[slot] = tau;
         count[b] = cnt + 1;

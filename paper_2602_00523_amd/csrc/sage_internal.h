@@ -50,4 +50,54 @@ __device__ __forceinline__ void lds_direct_load4(const unsigned char* gptr, __at
 }
 #pragma clang diagnostic pop
 
+// ---- Wave-wide reductions, result in every lane: four rotations inside each row of 16 lanes, then the 16-lane and
+// 32-lane swaps combine the four rows.  About ten vector instructions and no LDS traffic, where the shuffle intrinsics
+// go through the LDS crossbar at a round trip per step.
+template <int CTRL> __device__ __forceinline__ uint32_t u_dpp(uint32_t v) {
+    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, false));
+}
+template <int CTRL> __device__ __forceinline__ float f_dpp(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+    v = max(v, u_dpp<0x128>(v));         // row_ror:8
+    v = max(v, u_dpp<0x124>(v));         // row_ror:4
+    v = max(v, u_dpp<0x122>(v));         // row_ror:2
+    v = max(v, u_dpp<0x121>(v));         // row_ror:1
+    auto a = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    v = max(a[0], a[1]);
+    a = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return max(a[0], a[1]);
+}
+__device__ __forceinline__ uint32_t wave_sum_u32(uint32_t v) {
+    v += u_dpp<0x128>(v); v += u_dpp<0x124>(v); v += u_dpp<0x122>(v); v += u_dpp<0x121>(v);
+    auto a = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    v = a[0] + a[1];
+    a = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return a[0] + a[1];
+}
+__device__ __forceinline__ float wave_sum(float v) {
+    v += f_dpp<0x128>(v); v += f_dpp<0x124>(v); v += f_dpp<0x122>(v); v += f_dpp<0x121>(v);
+    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(a[0]) + __uint_as_float(a[1]);
+}
+__device__ __forceinline__ float wave_max(float v) {
+    v = fmaxf(v, f_dpp<0x128>(v)); v = fmaxf(v, f_dpp<0x124>(v)); v = fmaxf(v, f_dpp<0x122>(v)); v = fmaxf(v, f_dpp<0x121>(v));
+    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+}
+// Lane `lane` (wave-uniform) of a value, through a scalar register.
+__device__ __forceinline__ float lane_value(float v, int lane) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+__device__ __forceinline__ uint64_t lane_value(uint64_t v, int lane) {
+    const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(static_cast<uint32_t>(v)), lane));
+    const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(static_cast<uint32_t>(v >> 32)), lane));
+    return (static_cast<uint64_t>(hi) << 32) | lo;
+}
+
 }  // namespace sage

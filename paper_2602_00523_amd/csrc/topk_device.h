@@ -11,22 +11,12 @@ constexpr int MERGE_THREADS = 256;
 constexpr int MERGE_LDS_KEYS = 6144;     // lists are staged in LDS when they fit (48 KB)
 constexpr int MAX_OWN = 16;              // lists per lane in the second pass: up to 1024 slices = 1M logits
 
-// Wave-wide maximum, result in every lane: four rotations inside each row of 16 lanes, then the 16-lane and
-// 32-lane swaps combine the four rows.  A key is reduced in two passes: the value code first, then the index
-// code among the lanes that hold the winning value.
-template <int CTRL> __device__ __forceinline__ uint32_t u_dpp(uint32_t v) {
-    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xF, 0xF, false));
-}
-__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
-    v = max(v, u_dpp<0x128>(v));         // row_ror:8
-    v = max(v, u_dpp<0x124>(v));         // row_ror:4
-    v = max(v, u_dpp<0x122>(v));         // row_ror:2
-    v = max(v, u_dpp<0x121>(v));         // row_ror:1
-    auto a = __builtin_amdgcn_permlane16_swap(v, v, false, false);
-    v = max(a[0], a[1]);
-    a = __builtin_amdgcn_permlane32_swap(v, v, false, false);
-    return max(a[0], a[1]);
-}
+// The wave-wide reductions of sage_internal.h, under this namespace's names.
+using sage::wave_max;
+using sage::wave_max_u32;
+using sage::wave_sum;
+
+// A key is reduced in two passes: the value code first, then the index code among the lanes that hold the winning value.
 __device__ __forceinline__ Key wave_max_key(Key k) {
     const uint32_t hi = wave_max_u32(k.hi);
     const uint64_t holders = __ballot(k.hi == hi);
@@ -37,24 +27,6 @@ __device__ __forceinline__ Key wave_max_key(Key k) {
         lo = wave_max_u32(k.hi == hi ? k.lo : 0u);
     return Key{hi, lo};
 }
-template <int CTRL> __device__ __forceinline__ float f_dpp(float v) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
-}
-__device__ __forceinline__ float wave_sum(float v) {
-    v += f_dpp<0x128>(v); v += f_dpp<0x124>(v); v += f_dpp<0x122>(v); v += f_dpp<0x121>(v);
-    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    v = __uint_as_float(a[0]) + __uint_as_float(a[1]);
-    a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    return __uint_as_float(a[0]) + __uint_as_float(a[1]);
-}
-__device__ __forceinline__ float wave_max(float v) {
-    v = fmaxf(v, f_dpp<0x128>(v)); v = fmaxf(v, f_dpp<0x124>(v)); v = fmaxf(v, f_dpp<0x122>(v)); v = fmaxf(v, f_dpp<0x121>(v));
-    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
-    a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-    return fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
-}
-
 __device__ __forceinline__ bool row_is_valid(int row, const int* n_valid, int rows_per_group) {
     if (!n_valid) return true;
     return (row % rows_per_group) < n_valid[row / rows_per_group];

@@ -106,10 +106,7 @@ struct BatchShape {
     int n, L, tiles, col_groups, start_lo, start_hi;         // per lane (sequence)
     int total, q;                                            // wave-uniform
 };
-__device__ __forceinline__ int wave_sum_i32(int v) {
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
-    return v;
-}
+__device__ __forceinline__ int wave_sum_i32(int v) { return static_cast<int>(sage::wave_sum_u32(static_cast<uint32_t>(v))); }
 __device__ __forceinline__ BatchShape make_batch_shape(const Params& prm, int lane) {
     BatchShape bs;
     bs.n = 1; bs.L = 0; bs.tiles = 0; bs.col_groups = 0; bs.start_lo = 0; bs.start_hi = 0;
@@ -626,19 +623,16 @@ __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const i
                 asm("" : "+s"(next));                         // one scalar add per split, in place: left alone the compiler
                 ps = reinterpret_cast<global_bytes>(next);   // builds 32 pointers with 64-bit multiplies ahead of the loop
             }
-            float m_blk = ms;
-            for (int off = 32; off > 0; off >>= 1) m_blk = fmaxf(m_blk, __shfl_xor(m_blk, off));
+            const float m_blk = sage::wave_max(ms);
             const float m_new = fmaxf(m_all, m_blk);
             const float keep = (m_all == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_all - m_new) * c);
             const float w = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((ms - m_new) * c);
-            float l_blk = w * ls;
-            for (int off = 32; off > 0; off >>= 1) l_blk += __shfl_xor(l_blk, off);
-            l_all = l_all * keep + l_blk;
+            l_all = l_all * keep + sage::wave_sum(w * ls);
             o.x *= keep; o.y *= keep;
             m_all = m_new;
 #pragma unroll
             for (int s = 0; s < MAXS; ++s) {
-                const float ws = __shfl(w, s);
+                const float ws = sage::lane_value(w, s);        // split s's weight, through a scalar register
                 o.x += ws * v[s].x; o.y += ws * v[s].y;
             }
         }

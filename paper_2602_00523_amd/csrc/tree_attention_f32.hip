@@ -14,10 +14,7 @@ namespace {
 constexpr int THREADS = 256;
 
 __device__ __forceinline__ float block_reduce(float v, float* s_red, bool is_max) {
-    for (int off = 32; off > 0; off >>= 1) {
-        const float o = __shfl_xor(v, off);
-        v = is_max ? fmaxf(v, o) : v + o;
-    }
+    v = is_max ? sage::wave_max(v) : sage::wave_sum(v);
     __syncthreads();                         // s_red may still be read from a previous reduction
     if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = v;
     __syncthreads();

@@ -38,11 +38,11 @@ __device__ __forceinline__ void verify_accept_wave(int b, int i, int n, int par,
     const bool accepted = valid && ((am & ~matched) == 0) && ((am >> i) & 1);
 
     // max over (depth, then lowest index); the root (depth 0) is always accepted
-    int key = accepted ? (dep * SAGE_MAX_NODES + (SAGE_MAX_NODES - 1 - i)) : -1;
-    for (int off = 32; off > 0; off >>= 1) key = max(key, __shfl_xor(key, off));
-    const int best = SAGE_MAX_NODES - 1 - (key % SAGE_MAX_NODES);
+    const int own_key = accepted ? (dep * SAGE_MAX_NODES + (SAGE_MAX_NODES - 1 - i)) : -1;
+    const int key = static_cast<int>(sage::wave_max_u32(static_cast<uint32_t>(own_key + 1))) - 1;   // the root makes it >= 0
+    const int best = __builtin_amdgcn_readfirstlane(SAGE_MAX_NODES - 1 - (key % SAGE_MAX_NODES));
     const int tau = key / SAGE_MAX_NODES;
-    const uint64_t path_mask = __shfl(am, best);
+    const uint64_t path_mask = sage::lane_value(am, best);
 
     sh.slot_node[i] = -1;
     sh.slot_token[i] = -1;
