@@ -594,10 +594,9 @@ __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const i
     auto merge_row = [&](int b, int node, int hg, const float* first_row, unsigned stride_b, int nsplit_v) __attribute__((always_inline)) {
         // wave-uniform by construction; said to the compiler, which cannot see it through the lane exchanges of a batch
         const uintptr_t first_v = reinterpret_cast<uintptr_t>(first_row);
-        typedef const __attribute__((address_space(1))) unsigned char* global_bytes;    // rebuilt from integers: say "global"
-        global_bytes first = reinterpret_cast<global_bytes>(
+        const uintptr_t first =
             (static_cast<uintptr_t>(static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(first_v >> 32)))) << 32) |
-            static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(first_v))));   // (the builtin returns int)
+            static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(first_v)));   // (the builtin returns int)
         stride_b = __builtin_amdgcn_readfirstlane(stride_b);
         const int nsplit = __builtin_amdgcn_readfirstlane(nsplit_v);
         float2 o = make_float2(0.f, 0.f);
@@ -605,24 +604,27 @@ __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const i
         for (int s0 = 0; s0 < nsplit; s0 += MAXS) {           // MAXS splits at a time
             const int cnt = min(MAXS, nsplit - s0);
             float ms = -INFINITY, ls = 0.f;
-            global_bytes ps = first + static_cast<size_t>(s0) * stride_b;   // uniform: partial s0 of this row
-            if (lane < cnt) {
-                const f32x2 pair = *reinterpret_cast<const __attribute__((address_space(1))) f32x2*>(
-                    ps + (static_cast<unsigned>(lane) * stride_b + D * 4u));
-                ms = pair[0];
-                ls = pair[1];
+            // The row's partials of this pass as one buffer: uniform base (partial s0), 32-bit offsets, and a size that ends
+            // with the row's extent in its last split, so that a load for a split past the last one is answered with zeros
+            // by the bounds check instead of by memory.  One add and one load instruction per split.
+            typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+            const __amdgpu_buffer_rsrc_t rows = __builtin_amdgcn_make_buffer_rsrc(
+                reinterpret_cast<unsigned char*>(first + static_cast<size_t>(s0) * stride_b), 0,
+                static_cast<int>(static_cast<unsigned>(cnt - 1) * stride_b + PART_FLOATS * 4u), 0x00020000);
+            {
+                const u32x2 pair = __builtin_amdgcn_raw_buffer_load_b64(rows, static_cast<unsigned>(lane) * stride_b + D * 4u, 0, 0);
+                ms = lane < cnt ? __uint_as_float(pair[0]) : -INFINITY;
+                ls = lane < cnt ? __uint_as_float(pair[1]) : 0.f;
             }
             float2 v[MAXS];
-            const unsigned lane_off = 8u * lane;
-#pragma unroll
+            unsigned off = 8u * lane;                        // the whole offset goes through the per-lane operand: that one is
+#pragma unroll                                               // bounds-checked, the scalar offset operand is not
             for (int s = 0; s < MAXS; ++s) {
-                f32x2 x = {0.f, 0.f};
-                if (s < cnt) x = *reinterpret_cast<const __attribute__((address_space(1))) f32x2*>(ps + lane_off);
-                v[s] = make_float2(x[0], x[1]);
-                uintptr_t next = reinterpret_cast<uintptr_t>(ps) + stride_b;
-                asm("" : "+s"(next));                         // one scalar add per split, in place: left alone the compiler
-                ps = reinterpret_cast<global_bytes>(next);   // builds 32 pointers with 64-bit multiplies ahead of the loop
+                const u32x2 x = __builtin_amdgcn_raw_buffer_load_b64(rows, off, 0, 0);
+                v[s] = make_float2(__uint_as_float(x[0]), __uint_as_float(x[1]));
+                off += stride_b;
             }
+            __builtin_amdgcn_sched_barrier(0);               // every load is out before the first wait: one round trip
             const float m_blk = sage::wave_max(ms);
             const float m_new = fmaxf(m_all, m_blk);
             const float keep = (m_all == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_all - m_new) * c);
