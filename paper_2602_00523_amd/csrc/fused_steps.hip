@@ -41,12 +41,12 @@ __global__ __launch_bounds__(MERGE_THREADS) void plan_kernel(int k, int nunits, 
 constexpr int ACCEPT_WAVES = 16;
 constexpr int ROWS_PER_WAVE = SAGE_MAX_NODES / ACCEPT_WAVES;
 template <int OWN>
-__global__ __launch_bounds__(64 * ACCEPT_WAVES) void accept_kernel(int nunits, const UnitStats* __restrict__ stats,
+__global__ __launch_bounds__(64 * ACCEPT_WAVES) void accept_kernel(const int* __restrict__ n_nodes, int nunits,
+                                                                   const UnitStats* __restrict__ stats,
                                                                    const uint64_t* __restrict__ keys,
                                                                    const int* __restrict__ token, const int* __restrict__ parent,
                                                                    const int* __restrict__ depth,
-                                                                   const uint64_t* __restrict__ anc_mask,
-                                                                   const int* __restrict__ n_nodes, int path_cap,
+                                                                   const uint64_t* __restrict__ anc_mask, int path_cap,
                                                                    float* __restrict__ entropy, int* __restrict__ target_argmax,
                                                                    int* __restrict__ accept_len, int* __restrict__ best_node,
                                                                    int* __restrict__ path_nodes, int* __restrict__ out_tokens) {
@@ -168,11 +168,11 @@ extern "C" int sage_verify_accept_from_slices(void* slices, int vocab, const int
     if (B == 0) return SAGE_OK;
     hipStream_t s = sage::as_stream(stream);
     if (nunits <= 256)
-        hipLaunchKernelGGL(accept_kernel<4>, dim3(B), dim3(64 * ACCEPT_WAVES), 0, s, nunits, stats, keys, token, parent, depth,
-                           anc_mask, n_nodes, path_cap, entropy, target_argmax, accept_len, best_node, path_nodes, out_tokens);
+        hipLaunchKernelGGL(accept_kernel<4>, dim3(B), dim3(64 * ACCEPT_WAVES), 0, s, n_nodes, nunits, stats, keys, token, parent,
+                           depth, anc_mask, path_cap, entropy, target_argmax, accept_len, best_node, path_nodes, out_tokens);
     else
-        hipLaunchKernelGGL(accept_kernel<MAX_OWN>, dim3(B), dim3(64 * ACCEPT_WAVES), 0, s, nunits, stats, keys, token, parent,
-                           depth, anc_mask, n_nodes, path_cap, entropy, target_argmax, accept_len, best_node, path_nodes,
+        hipLaunchKernelGGL(accept_kernel<MAX_OWN>, dim3(B), dim3(64 * ACCEPT_WAVES), 0, s, n_nodes, nunits, stats, keys, token,
+                           parent, depth, anc_mask, path_cap, entropy, target_argmax, accept_len, best_node, path_nodes,
                            out_tokens);
     return sage::launch_status();
 }
