@@ -732,6 +732,53 @@ def draft_side_attention(launches=40):
         byts = 2.0 * 2 * L * Hkv * d + n * (2.0 * 2 * Hkv * d + 2.0 * 2 * Hq * d)
         out.append(dict(heads=f"{Hq}/{Hkv}", kv_len=L, nodes=n, avg_us=avg_ms * 1e3, min_us=min(t) * 1e3,
                         algorithmic_bytes=byts, hbm_GBps=byts / (avg_ms * 1e-3) / 1e9))
+
+    # Level-by-level growth (Alg. 1 Phase 1: the draft model extends the tree by one level per forward pass): the same
+    # call once per level on the level-ordered tree, call l with the nodes of levels 0..l.  One drafting pass = all levels.
+    L, n = 2560, 25
+    par = [-1] + [int(rng.integers(max(0, v - 6), v)) for v in range(1, n)]
+    dep = [0] * n
+    for v in range(1, n):
+        dep[v] = dep[par[v]] + 1
+    order = sorted(range(n), key=lambda v: (dep[v], v))          # level order: parents stay ahead of their children
+    new_of_old = {o: i for i, o in enumerate(order)}
+    par_l = [-1 if par[o] < 0 else new_of_old[par[o]] for o in order]
+    dep_l = [dep[o] for o in order]
+    mask = np.zeros((1, MAX_NODES), np.uint64)
+    for v in range(n):
+        u, bits = v, 0
+        while u >= 0:
+            bits |= 1 << u
+            u = par_l[u]
+        mask[0, v] = bits
+    maskd = torch.from_numpy(mask.view(np.int64)).to(dev)
+    counts = [sum(1 for x in dep_l if x <= lvl) for lvl in range(max(dep_l) + 1)]
+    nns = [torch.full((1,), c, device=dev, dtype=torch.int32) for c in counts]
+    nbuf = 16
+    Kc = [rn(L, Hkv, d) for _ in range(nbuf)]
+    Vc = [rn(L, Hkv, d) for _ in range(nbuf)]
+    Q, Kt, Vt = rn(1, MAX_NODES, Hq, d), rn(1, MAX_NODES, Hkv, d), rn(1, MAX_NODES, Hkv, d)
+    O = torch.zeros_like(Q)
+    kv_start = torch.zeros(1, device=dev, dtype=torch.int64)
+    kv_len = torch.full((1,), L, device=dev, dtype=torch.int32)
+    ws = torch.empty(sage.sage_tree_attention_workspace_bytes(sage.BF16, 1, Hq, Hkv, d, L), device=dev, dtype=torch.uint8)
+    passes = [[sage.prepare("sage_tree_attention", Q, Kc[i], Vc[i], Kt, Vt, O, kv_start, kv_len, L, Hkv * d, d, maskd, nn,
+                            1.0 / math.sqrt(d), ws) for nn in nns] for i in range(nbuf)]
+    for calls in passes:
+        for c in calls:
+            c()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * launches)]
+    for i in range(launches):
+        ev[2 * i].record()
+        for c in passes[i % nbuf]:
+            c()
+        ev[2 * i + 1].record()
+    torch.cuda.synchronize()
+    t = [ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(launches)]
+    out.append(dict(heads=f"{Hq}/{Hkv}", kv_len=L, growth="level by level", nodes_after_each_level=counts,
+                    calls_per_pass=len(counts), avg_us_per_pass=sum(t) / len(t) * 1e3, min_us_per_pass=min(t) * 1e3,
+                    avg_us_per_call=sum(t) / len(t) * 1e3 / len(counts)))
     return out
 
 

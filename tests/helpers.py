@@ -70,3 +70,13 @@ def star_parents(n: int) -> np.ndarray:
     p = np.zeros(n, np.int32)
     p[0] = -1
     return p
+
+
+def level_order(par: np.ndarray) -> np.ndarray:
+    """The same tree renumbered level by level (depth first, then old index), as a model that drafts one level per
+    forward pass numbers it: parents of the new tree, every parent still before its children."""
+    dep = depth_by_walk(par)
+    order = np.lexsort((np.arange(len(par)), dep))         # old index of new node i
+    new_of_old = np.empty(len(par), np.int64)
+    new_of_old[order] = np.arange(len(par))
+    return np.array([-1 if par[o] < 0 else new_of_old[par[o]] for o in order], np.int32)

@@ -222,6 +222,30 @@ def test_attention_bf16_other_group_sizes(gu, Hq, Hkv):
     run_attention_case(gu, 90 + Hq, "bf16", 2, Hq, Hkv, 128, [333, 70], sizes=[64, 11])
 
 
+@pytest.mark.parametrize("Hq,Hkv,L,n", [(28, 4, 1638, 25), (64, 8, 300, 64)])
+def test_attention_level_by_level_growth(gu, Hq, Hkv, L, n):
+    """A tree drafted one level per forward pass (the draft side of Alg. 1 Phase 1): call l sees the nodes of levels
+    0..l, a prefix of the level-ordered tree, and the rows of level l must come out as in the oracle's single pass over
+    the whole tree, because a node attends only to the cache and its ancestors."""
+    from helpers import depth_by_walk, level_order
+    g = wl.rng(7000 + n)
+    par = level_order(random_parents(g, n, chain_bias=0.3))
+    dep = depth_by_walk(par)
+    assert (np.diff(dep) >= 0).all() and dep.max() >= 3
+    _, _, mask, nn = pad_tree(par)
+    inp = wl.attention_inputs(7100 + n, 1, Hq, Hkv, 128, [L], "bf16")
+    ref = oracle.tree_attention(inp["Q"], inp["Kc"], inp["Vc"], inp["Kt"], inp["Vt"], inp["kv_start"], inp["kv_len"],
+                                inp["kv_token_stride"], inp["kv_head_stride"], mask, nn, Hq, Hkv, 128)
+    for level in range(int(dep.max()) + 1):
+        upto = np.array([int((dep <= level).sum())], np.int32)
+        got, _ = gu.gpu_tree_attention(inp, mask, upto, Hq, Hkv, 128, fill=7.0)
+        rows = np.nonzero(dep == level)[0]
+        g_l, r_l = got[0, rows], ref[0, rows]
+        err = np.abs(g_l - r_l).max(-1) / np.maximum(np.abs(r_l).max(-1), 1e-300)
+        assert err.max() <= TOL["bf16"], (level, float(err.max()))
+        assert (got[0, int(upto[0]):] == 7.0).all()             # nodes of deeper levels are not there yet
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_attention_bf16_random_configurations(gu, seed):
     """Random head counts (any group size up to 16), batch sizes, ragged lengths around tile and split boundaries,
