@@ -530,12 +530,12 @@ def closed_loop(name="c2", steps=512):
                             for s in range(w.slots)])
             c["a1t"].append([sg.prepare("sage_entropy_topk_slices", w.target[s], 1, w.ws1t, t["n_nodes"], MAX_NODES,
                                         stream=stream) for s in range(w.slots)])
-            c["a4"].append(sg.prepare("sage_verify_accept_from_slices", w.ws1t, V, t["node_token"], t["parent"], t["depth"],
-                                      t["anc_mask"], t["n_nodes"], w.path_cap, w.tH, w.tgt_idx, w.acc_len, w.best, w.path,
-                                      w.out_tok, stream=stream))
-        c["close"] = [[sg.prepare("sage_close_step", w.Kt[s], w.Vt[s], Kc, Vc, kv_start, kv_len, cap, Hkv * d, d, w.path, w.acc_len,
-                                  hist, count, d_max[cur], d_max[cur ^ 1], lo, hi, w.tree_prm["d_min"], w.tree_prm["d_max"],
-                                  stream=stream) for s in range(w.slots)] for cur in range(2)]
+            # acceptance, commit, advance and history in one launch
+            c["a4"].append([sg.prepare("sage_verify_accept_close_from_slices", w.ws1t, V, t["node_token"], t["parent"], t["depth"],
+                                       t["anc_mask"], t["n_nodes"], w.path_cap, w.tH, w.tgt_idx, w.acc_len, w.best, w.path,
+                                       w.out_tok, w.Kt[s], w.Vt[s], Kc, Vc, kv_start, kv_len, cap, Hkv * d, d, hist, count,
+                                       d_max[cur], d_max[cur ^ 1], lo, hi, w.tree_prm["d_min"], w.tree_prm["d_max"],
+                                       stream=stream) for s in range(w.slots)])
         return c
 
     state = dict(cur=0, step=0)
@@ -544,8 +544,7 @@ def closed_loop(name="c2", steps=512):
         s, cur = state["step"] % w.slots, state["cur"]
         main = torch.cuda.current_stream()
         plan_stream.wait_stream(main)                         # fork: the plan uses the depth limit of the previous step
-        c["a3"][cur][s](); c["a1t"][cur][s](); c["a4"][cur]()
-        c["close"][cur][s]()                                  # commit, advance, history in one launch
+        c["a3"][cur][s](); c["a1t"][cur][s](); c["a4"][cur][s]()
         acc_sum.add_(w.acc_len)
         c["a1"][s](); c["a2"][cur]()                          # plan branch, enqueued after the verification branch
         main.wait_stream(plan_stream)                         # join: the next step verifies the tree planned here
@@ -591,8 +590,8 @@ def closed_loop(name="c2", steps=512):
     verified = all(torch.equal(a, b) for a, b in zip(want, got))
     out = dict(workload=name, steps=steps, steps_per_s=steps / wall, ms_per_step=wall * 1e3 / steps,
                calls_per_step="entropy_topk_slices, build_tree_from_slices (per-sequence depth), tree_attention, "
-                              "entropy_topk_slices (k=1), verify_accept_from_slices, close_step (commit, advance, history); "
-                              "the first two on a second stream beside the rest",
+                              "entropy_topk_slices (k=1), verify_accept_close_from_slices (acceptance, commit, advance, "
+                              "history); the first two on a second stream beside the rest",
                kv_len_start=[int(x) for x in w.kv_lens], kv_len_end=[int(x) for x in kv_len.cpu().numpy()],
                mean_accept_len=float(acc_sum.sum().item()) / (steps * B),
                d_max_end=[int(x) for x in d_max[state["cur"]].cpu().numpy()],

@@ -281,6 +281,21 @@ int sage_verify_accept_from_slices(void* slices, int vocab, const int* token, co
                                    float* entropy, int* target_argmax, int* accept_len, int* best_node,
                                    int* path_nodes, int* out_tokens, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * sage_verify_accept_close_from_slices -- sage_verify_accept_from_slices followed by
+ * sage_close_step (one layer) in one launch: the workgroup that has found a sequence's
+ * accepted path (Sec. 2.2) appends that path's K/V rows to the cache, advances the length and
+ * updates the acceptance history (Alg. 1 Phase 3, Sec. 3.3) while the path is still on chip.
+ * Arguments, semantics, results and errors: those of the two calls, in their order.
+ */
+int sage_verify_accept_close_from_slices(
+    void* slices, int vocab, const int* token, const int* parent, const int* depth, const uint64_t* anc_mask,
+    const int* n_nodes, int B, int path_cap, float* entropy, int* target_argmax, int* accept_len, int* best_node,
+    int* path_nodes, int* out_tokens,
+    const void* Kt, const void* Vt, void* Kc, void* Vc, int dtype, int Hkv, int d, const int64_t* kv_start, int* kv_len,
+    int kv_capacity, long kv_token_stride, long kv_head_stride, int window, float lo, float hi, int d_floor, int d_cap,
+    int* hist, int* count, const int* d_max_in, int* d_max_out, float* avg_out, void* stream);
+
 /* Library build identification (host): returns a static string naming the target architecture. */
 const char* sage_build_info(void);
 

@@ -3,32 +3,11 @@
 // sage_update_history: adaptive history tracking (Sec. 3.3; window and thresholds of Sec. 5 "Implementation
 // details"): a sliding window of acceptance lengths steers the maximum tree depth of every sequence.
 // All three are byte/integer work of a few KB per step: one small kernel each, no workspace.
-#include "sage_internal.h"
+#include "commit_device.h"
+
+using namespace sage::closing;
 
 namespace {
-
-// The workgroup copies the K row and the V row of node path[j] of sequence b (Hkv heads x d elements each) to cache
-// position len_b + j in 16-byte pieces.
-__device__ __forceinline__ void commit_row(
-    const unsigned char* __restrict__ Kt, const unsigned char* __restrict__ Vt, unsigned char* __restrict__ Kc,
-    unsigned char* __restrict__ Vc, int esz, int Hkv, int d, const int64_t* __restrict__ kv_start, int len_b,
-    int kv_capacity, long kv_token_stride, long kv_head_stride, const int* __restrict__ path_nodes, int tau, int path_cap,
-    int j, int b) {
-    if (j > tau || j >= path_cap) return;
-    const int node = path_nodes[static_cast<long>(b) * path_cap + j];
-    const long pos = static_cast<long>(len_b) + j;
-    if (node < 0 || node >= SAGE_MAX_NODES || pos >= kv_capacity) return;      // never read or write out of range
-    const int pieces = d * esz / 16;                                           // 16-byte pieces of one head's row
-    const long src_row = (static_cast<long>(b) * SAGE_MAX_NODES + node) * Hkv * d * esz;
-    const long dst_tok = (kv_start[b] + pos) * kv_token_stride * esz;
-    for (int t = threadIdx.x; t < Hkv * pieces; t += blockDim.x) {
-        const int g = t / pieces, c = t % pieces;
-        const long src = src_row + (static_cast<long>(g) * d * esz) + c * 16;
-        const long dst = dst_tok + static_cast<long>(g) * kv_head_stride * esz + c * 16;
-        *reinterpret_cast<uint4*>(Kc + dst) = *reinterpret_cast<const uint4*>(Kt + src);
-        *reinterpret_cast<uint4*>(Vc + dst) = *reinterpret_cast<const uint4*>(Vt + src);
-    }
-}
 
 // One workgroup per (path slot j, sequence b).
 __global__ __launch_bounds__(256) void commit_path_kernel(
@@ -36,43 +15,16 @@ __global__ __launch_bounds__(256) void commit_path_kernel(
     unsigned char* __restrict__ Vc, int esz, int Hkv, int d, const int64_t* __restrict__ kv_start,
     const int* __restrict__ kv_len, int kv_capacity, long kv_token_stride, long kv_head_stride,
     const int* __restrict__ path_nodes, const int* __restrict__ accept_len, int path_cap) {
-    const int b = blockIdx.y;
-    commit_row(Kt, Vt, Kc, Vc, esz, Hkv, d, kv_start, kv_len[b], kv_capacity, kv_token_stride, kv_head_stride, path_nodes,
-               accept_len[b], path_cap, blockIdx.x, b);
-}
-
-__device__ __forceinline__ int advanced_len(int len_b, int tau, int kv_capacity) {
-    const long n = static_cast<long>(len_b) + tau + 1;                        // the root and the tau accepted tokens
-    return n > kv_capacity ? kv_capacity : static_cast<int>(n);
+    const int j = blockIdx.x, b = blockIdx.y;
+    if (j > accept_len[b] || j >= path_cap) return;
+    commit_row(Kt, Vt, Kc, Vc, esz, Hkv, d, kv_start, kv_len[b], kv_capacity, kv_token_stride, kv_head_stride,
+               path_nodes[static_cast<long>(b) * path_cap + j], j, b);
 }
 
 __global__ void advance_kv_len_kernel(int* __restrict__ kv_len, const int* __restrict__ accept_len, int B, int kv_capacity) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
     kv_len[b] = advanced_len(kv_len[b], accept_len[b], kv_capacity);
-}
-
-// One wave for sequence b: lane i holds window slot i.  The new depth limit goes to d_max_out (which may be d_max_in).
-__device__ __forceinline__ void history_wave(int b, int lane, int tau, int window, float lo, float hi, int d_floor, int d_cap,
-                                             int* __restrict__ hist, int* __restrict__ count, const int* d_max_in,
-                                             int* d_max_out, float* __restrict__ avg_out) {
-    int* h = hist + static_cast<long>(b) * window;
-    const int cnt = count[b];
-    const int slot = cnt % window;
-    const int n = min(cnt + 1, window);
-    int v = 0;
-    if (lane < n) v = (lane == slot) ? tau : h[lane];
-    const int sum = static_cast<int>(sage::wave_sum_u32(static_cast<uint32_t>(v)));
-    if (lane == 0) {
-        h[slot] = tau;
-        count[b] = cnt + 1;
-        const float fs = static_cast<float>(sum), fn = static_cast<float>(n);
-        if (avg_out) avg_out[b] = __fdiv_rn(fs, fn);
-        int dm = d_max_in[b];
-        if (fs < __fmul_rn(lo, fn)) dm -= 1;                                   // strictly below the lower threshold
-        else if (fs > __fmul_rn(hi, fn)) dm += 1;                              // strictly above the upper one
-        d_max_out[b] = min(max(dm, d_floor), d_cap);
-    }
 }
 
 __global__ __launch_bounds__(64) void update_history_kernel(const int* __restrict__ accept_len, int window, float lo, float hi,
@@ -95,8 +47,8 @@ __global__ __launch_bounds__(256) void close_step_kernel(
     const int tau = accept_len[b];
     const int len_b = kv_len[b];
     for (int j = 0; j <= tau && j < path_cap; ++j)
-        commit_row(Kt, Vt, Kc, Vc, esz, Hkv, d, kv_start, len_b, kv_capacity, kv_token_stride, kv_head_stride, path_nodes, tau,
-                   path_cap, j, b);
+        commit_row(Kt, Vt, Kc, Vc, esz, Hkv, d, kv_start, len_b, kv_capacity, kv_token_stride, kv_head_stride,
+                   path_nodes[static_cast<long>(b) * path_cap + j], j, b);
     __syncthreads();                                                           // every thread has read the old length
     if (threadIdx.x == 0) kv_len[b] = advanced_len(len_b, tau, kv_capacity);
     if (threadIdx.x < 64) history_wave(b, threadIdx.x, tau, window, lo, hi, d_floor, d_cap, hist, count, d_max_in, d_max_out, avg_out);

@@ -8,6 +8,7 @@
 // (topk_device.h, build_tree_device.h, verify_accept_device.h), so their outputs are bit-identical to the unfused
 // sequence sage_entropy_topk -> sage_build_tree / sage_verify_accept.
 #include "build_tree_device.h"
+#include "commit_device.h"
 #include "topk_device.h"
 #include "verify_accept_device.h"
 
@@ -40,7 +41,15 @@ __global__ __launch_bounds__(MERGE_THREADS) void plan_kernel(int k, int nunits, 
 // meet in LDS and wave 0 runs the acceptance rule on them.
 constexpr int ACCEPT_WAVES = 16;
 constexpr int ROWS_PER_WAVE = SAGE_MAX_NODES / ACCEPT_WAVES;
-template <int OWN>
+// What closes the step, for the kernel instantiated with CLOSE (sage_verify_accept_close_from_slices).
+struct CloseArgs {
+    const unsigned char* Kt; const unsigned char* Vt; unsigned char* Kc; unsigned char* Vc;
+    const int64_t* kv_start; int* kv_len; int* hist; int* count; const int* d_max_in; int* d_max_out; float* avg_out;
+    long kv_token_stride, kv_head_stride;
+    int esz, Hkv, d, kv_capacity, window, d_floor, d_cap;
+    float lo, hi;
+};
+template <int OWN, bool CLOSE>
 __global__ __launch_bounds__(64 * ACCEPT_WAVES) void accept_kernel(const int* __restrict__ n_nodes, int nunits,
                                                                    const UnitStats* __restrict__ stats,
                                                                    const uint64_t* __restrict__ keys,
@@ -49,8 +58,10 @@ __global__ __launch_bounds__(64 * ACCEPT_WAVES) void accept_kernel(const int* __
                                                                    const uint64_t* __restrict__ anc_mask, int path_cap,
                                                                    float* __restrict__ entropy, int* __restrict__ target_argmax,
                                                                    int* __restrict__ accept_len, int* __restrict__ best_node,
-                                                                   int* __restrict__ path_nodes, int* __restrict__ out_tokens) {
+                                                                   int* __restrict__ path_nodes, int* __restrict__ out_tokens,
+                                                                   CloseArgs cl) {
     __shared__ int s_tgt[SAGE_MAX_NODES];
+    __shared__ int s_tau;
     __shared__ sage::accept::AcceptShared sh;
     const int b = blockIdx.x;
     const int lane = threadIdx.x & 63;
@@ -110,11 +121,28 @@ __global__ __launch_bounds__(64 * ACCEPT_WAVES) void accept_kernel(const int* __
         }
     }
     __syncthreads();
-    if (wave != 0) return;
-    const int tgt = lane < n ? s_tgt[lane] : 0;
-    const int tgt_par = (lane < n && par >= 0 && par < n) ? s_tgt[par] : 0;
-    sage::accept::verify_accept_wave(b, lane, n, par, tok, dep, am, tgt, tgt_par, path_cap, sh, accept_len, best_node, path_nodes,
-                                     out_tokens);
+    if (wave != 0 && !CLOSE) return;
+    if (wave == 0) {
+        const int tgt = lane < n ? s_tgt[lane] : 0;
+        const int tgt_par = (lane < n && par >= 0 && par < n) ? s_tgt[par] : 0;
+        const int tau = sage::accept::verify_accept_wave(b, lane, n, par, tok, dep, am, tgt, tgt_par, path_cap, sh, accept_len,
+                                                         best_node, path_nodes, out_tokens);
+        if (CLOSE && lane == 0) s_tau = tau;
+    }
+    if (!CLOSE) return;
+    // ---- the accepted path joins the cache, the length advances, the history moves the depth limit: what
+    //      sage_close_step does, here with the path still in LDS and all 16 waves copying
+    __syncthreads();
+    const int tau = s_tau;
+    const int len_b = cl.kv_len[b];
+    for (int j = 0; j <= tau && j < path_cap; ++j)
+        sage::closing::commit_row(cl.Kt, cl.Vt, cl.Kc, cl.Vc, cl.esz, cl.Hkv, cl.d, cl.kv_start, len_b, cl.kv_capacity,
+                                  cl.kv_token_stride, cl.kv_head_stride, sh.slot_node[j], j, b);
+    __syncthreads();                                 // every thread has read the old length
+    if (threadIdx.x == 0) cl.kv_len[b] = sage::closing::advanced_len(len_b, tau, cl.kv_capacity);
+    if (wave == 1)
+        sage::closing::history_wave(b, lane, tau, cl.window, cl.lo, cl.hi, cl.d_floor, cl.d_cap, cl.hist, cl.count, cl.d_max_in,
+                                    cl.d_max_out, cl.avg_out);
 }
 
 }  // namespace
@@ -168,11 +196,58 @@ extern "C" int sage_verify_accept_from_slices(void* slices, int vocab, const int
     if (B == 0) return SAGE_OK;
     hipStream_t s = sage::as_stream(stream);
     if (nunits <= 256)
-        hipLaunchKernelGGL(accept_kernel<4>, dim3(B), dim3(64 * ACCEPT_WAVES), 0, s, n_nodes, nunits, stats, keys, token, parent,
-                           depth, anc_mask, path_cap, entropy, target_argmax, accept_len, best_node, path_nodes, out_tokens);
+        hipLaunchKernelGGL((accept_kernel<4, false>), dim3(B), dim3(64 * ACCEPT_WAVES), 0, s, n_nodes, nunits, stats, keys, token,
+                           parent, depth, anc_mask, path_cap, entropy, target_argmax, accept_len, best_node, path_nodes, out_tokens,
+                           CloseArgs{});
     else
-        hipLaunchKernelGGL(accept_kernel<MAX_OWN>, dim3(B), dim3(64 * ACCEPT_WAVES), 0, s, n_nodes, nunits, stats, keys, token,
-                           parent, depth, anc_mask, path_cap, entropy, target_argmax, accept_len, best_node, path_nodes,
-                           out_tokens);
+        hipLaunchKernelGGL((accept_kernel<MAX_OWN, false>), dim3(B), dim3(64 * ACCEPT_WAVES), 0, s, n_nodes, nunits, stats, keys,
+                           token, parent, depth, anc_mask, path_cap, entropy, target_argmax, accept_len, best_node, path_nodes,
+                           out_tokens, CloseArgs{});
+    return sage::launch_status();
+}
+
+extern "C" int sage_verify_accept_close_from_slices(
+    void* slices, int vocab, const int* token, const int* parent, const int* depth, const uint64_t* anc_mask, const int* n_nodes,
+    int B, int path_cap, float* entropy, int* target_argmax, int* accept_len, int* best_node, int* path_nodes, int* out_tokens,
+    const void* Kt, const void* Vt, void* Kc, void* Vc, int dtype, int Hkv, int d, const int64_t* kv_start, int* kv_len,
+    int kv_capacity, long kv_token_stride, long kv_head_stride, int window, float lo, float hi, int d_floor, int d_cap, int* hist,
+    int* count, const int* d_max_in, int* d_max_out, float* avg_out, void* stream) {
+    if (!slices || !token || !parent || !depth || !anc_mask || !n_nodes || !target_argmax || !accept_len || !best_node ||
+        !path_nodes || !out_tokens)
+        return SAGE_INVALID_ARG;
+    if (!Kt || !Vt || !Kc || !Vc || !kv_start || !kv_len || !hist || !count || !d_max_in || !d_max_out) return SAGE_INVALID_ARG;
+    if (B < 0 || vocab < 1 || path_cap < 1 || Hkv < 1 || d < 1 || kv_capacity < 0) return SAGE_INVALID_ARG;
+    if (dtype != SAGE_F32 && dtype != SAGE_BF16) return SAGE_INVALID_ARG;
+    if (kv_head_stride < d || kv_token_stride < d) return SAGE_INVALID_ARG;
+    const int esz = dtype == SAGE_F32 ? 4 : 2;
+    if ((static_cast<long>(d) * esz) % 16 != 0 || (kv_token_stride * esz) % 16 != 0 || (kv_head_stride * esz) % 16 != 0)
+        return SAGE_INVALID_ARG;
+    if (!sage::aligned(slices, 16) || !sage::aligned(Kt, 16) || !sage::aligned(Vt, 16) || !sage::aligned(Kc, 16) ||
+        !sage::aligned(Vc, 16))
+        return SAGE_INVALID_ARG;
+    if (window < 1 || window > 64 || d_floor < 1 || d_floor > d_cap || d_cap > SAGE_MAX_DEPTH || !(lo <= hi))
+        return SAGE_INVALID_ARG;
+    if (static_cast<long>(B) * SAGE_MAX_NODES > 65535 || path_cap > SAGE_MAX_NODES) return SAGE_UNSUPPORTED;
+    UnitStats* stats;
+    uint64_t* keys;
+    int nunits;
+    sage::topk_workspace_layout(B * SAGE_MAX_NODES, vocab, slices, &stats, &keys, &nunits);
+    if (nunits > sage::topk_max_units()) return SAGE_UNSUPPORTED;
+    if (B == 0) return SAGE_OK;
+    CloseArgs cl;
+    cl.Kt = static_cast<const unsigned char*>(Kt); cl.Vt = static_cast<const unsigned char*>(Vt);
+    cl.Kc = static_cast<unsigned char*>(Kc); cl.Vc = static_cast<unsigned char*>(Vc);
+    cl.kv_start = kv_start; cl.kv_len = kv_len; cl.hist = hist; cl.count = count; cl.d_max_in = d_max_in; cl.d_max_out = d_max_out;
+    cl.avg_out = avg_out; cl.kv_token_stride = kv_token_stride; cl.kv_head_stride = kv_head_stride;
+    cl.esz = esz; cl.Hkv = Hkv; cl.d = d; cl.kv_capacity = kv_capacity; cl.window = window; cl.d_floor = d_floor; cl.d_cap = d_cap;
+    cl.lo = lo; cl.hi = hi;
+    hipStream_t s = sage::as_stream(stream);
+    if (nunits <= 256)
+        hipLaunchKernelGGL((accept_kernel<4, true>), dim3(B), dim3(64 * ACCEPT_WAVES), 0, s, n_nodes, nunits, stats, keys, token,
+                           parent, depth, anc_mask, path_cap, entropy, target_argmax, accept_len, best_node, path_nodes, out_tokens, cl);
+    else
+        hipLaunchKernelGGL((accept_kernel<MAX_OWN, true>), dim3(B), dim3(64 * ACCEPT_WAVES), 0, s, n_nodes, nunits, stats, keys,
+                           token, parent, depth, anc_mask, path_cap, entropy, target_argmax, accept_len, best_node, path_nodes,
+                           out_tokens, cl);
     return sage::launch_status();
 }

@@ -27,7 +27,8 @@ __device__ __forceinline__ void wave_lds_sync() {
 
 // Lane i holds node i's fields (par, tok, dep, am; anything for i >= n) and tgt = the target's greedy token at node i;
 // tgt_of_parent = the target's greedy token at node i's parent (anything when the parent is out of range).
-__device__ __forceinline__ void verify_accept_wave(int b, int i, int n, int par, int tok, int dep, uint64_t am, int tgt,
+// Returns tau (wave-uniform); the path nodes stay in sh.slot_node[0..tau].
+__device__ __forceinline__ int verify_accept_wave(int b, int i, int n, int par, int tok, int dep, uint64_t am, int tgt,
                                                    int tgt_of_parent, int path_cap, AcceptShared& sh,
                                                    int* __restrict__ accept_len, int* __restrict__ best_node,
                                                    int* __restrict__ path_nodes, int* __restrict__ out_tokens) {
@@ -64,6 +65,7 @@ __device__ __forceinline__ void verify_accept_wave(int b, int i, int n, int par,
         accept_len[b] = tau;
         best_node[b] = best;
     }
+    return tau;
 }
 
 }  // namespace accept

@@ -59,6 +59,10 @@ def lib():
         L.sage_update_history.restype = _ci
         L.sage_update_history.argtypes = [_vp, _ci, _ci, _cf, _cf, _ci, _ci, _vp, _vp, _vp, _vp, _vp]
         L.sage_lm_head_topk_workspace_bytes.restype = _sz
+        L.sage_verify_accept_close_from_slices.restype = _ci
+        L.sage_verify_accept_close_from_slices.argtypes = (
+            [_vp, _ci, _vp, _vp, _vp, _vp, _vp, _ci, _ci] + [_vp] * 6 + [_vp, _vp, _vp, _vp, _ci, _ci, _ci, _vp, _vp, _ci, _cl, _cl,
+                                                                       _ci, _cf, _cf, _ci, _ci, _vp, _vp, _vp, _vp, _vp, _vp])
         L.sage_close_step.restype = _ci
         L.sage_close_step.argtypes = [_vp, _vp, _vp, _vp, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _cl, _cl, _vp, _vp, _ci, _ci, _cf, _cf,
                                       _ci, _ci, _vp, _vp, _vp, _vp, _vp, _vp]
@@ -211,7 +215,21 @@ def _args_close_step(Kt, Vt, Kc, Vc, kv_start, kv_len, kv_capacity, kv_token_str
             d_floor, d_cap, _ptr(hist), _ptr(count), _ptr(d_max_in), _ptr(d_max_out), _ptr(avg_out), _stream(stream)]
 
 
+def _args_verify_accept_close_from_slices(slices, vocab, token, parent, depth, anc_mask, n_nodes, path_cap, entropy, target_argmax,
+                                          accept_len, best_node, path_nodes, out_tokens, Kt, Vt, Kc, Vc, kv_start, kv_len,
+                                          kv_capacity, kv_token_stride, kv_head_stride, hist, count, d_max_in, d_max_out, lo, hi,
+                                          d_floor, d_cap, avg_out=None, stream=None):
+    B = n_nodes.shape[0]
+    _, _, Hkv, d = Kt.shape
+    return [_ptr(slices), vocab, _ptr(token), _ptr(parent), _ptr(depth), _ptr(anc_mask), _ptr(n_nodes), B, path_cap,
+            _ptr(entropy), _ptr(target_argmax), _ptr(accept_len), _ptr(best_node), _ptr(path_nodes), _ptr(out_tokens),
+            _ptr(Kt), _ptr(Vt), _ptr(Kc), _ptr(Vc), _dtype_code(Kt), Hkv, d, _ptr(kv_start), _ptr(kv_len), kv_capacity,
+            kv_token_stride, kv_head_stride, hist.shape[1], lo, hi, d_floor, d_cap, _ptr(hist), _ptr(count), _ptr(d_max_in),
+            _ptr(d_max_out), _ptr(avg_out), _stream(stream)]
+
+
 _MARSHAL = {"sage_close_step": _args_close_step,
+            "sage_verify_accept_close_from_slices": _args_verify_accept_close_from_slices,
             "sage_entropy_topk_slices": _args_entropy_topk_slices,
             "sage_build_tree_from_slices": _args_build_tree_from_slices,
             "sage_verify_accept_from_slices": _args_verify_accept_from_slices,
@@ -247,6 +265,11 @@ def sage_advance_kv_len(*a, **kw):
 
 def sage_update_history(*a, **kw):
     _check("sage_update_history", lib().sage_update_history(*_args_update_history(*a, **kw)))
+
+
+def sage_verify_accept_close_from_slices(*a, **kw):
+    _check("sage_verify_accept_close_from_slices",
+           lib().sage_verify_accept_close_from_slices(*_args_verify_accept_close_from_slices(*a, **kw)))
 
 
 def sage_close_step(*a, **kw):

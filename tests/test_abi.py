@@ -193,3 +193,23 @@ def test_close_step_validates_on_the_host(lib):
     assert cs(window=0) == INVALID and cs(window=65) == INVALID and cs(lo=4.0) == INVALID
     assert cs(floor=0) == INVALID and cs(floor=9) == INVALID and cs(top=40) == INVALID
     assert cs(B=70000) == UNSUPPORTED and cs(cap=65) == UNSUPPORTED
+
+
+def test_accept_close_validates_on_the_host(lib):
+    INVALID, UNSUPPORTED = 1, 2
+    vp, ci, cl, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_float
+    null, one = vp(0), vp(16)
+    lib.sage_verify_accept_close_from_slices.argtypes = ([vp, ci, vp, vp, vp, vp, vp, ci, ci] + [vp] * 6 +
+                                                         [vp, vp, vp, vp, ci, ci, ci, vp, vp, ci, cl, cl, ci, cf, cf, ci, ci] +
+                                                         [vp] * 6)
+    ac = lambda slices=one, vocab=152064, tok=one, B=0, cap=9, tgt=one, Kt=one, dtype=1, d=128, lens=one, ts=1024, hs=128, \
+                window=10, lo=2.0, floor=3, top=8, dm=one: lib.sage_verify_accept_close_from_slices(
+        slices, vocab, tok, one, one, one, one, B, cap, null, tgt, one, one, one, one, Kt, one, one, one, dtype, 8, d, one, lens,
+        4096, ts, hs, window, lo, 3.0, floor, top, one, one, dm, one, null, null)
+    assert ac() == 0
+    assert ac(slices=null) == INVALID and ac(tok=null) == INVALID and ac(tgt=null) == INVALID
+    assert ac(Kt=null) == INVALID and ac(lens=null) == INVALID and ac(dm=null) == INVALID
+    assert ac(cap=0) == INVALID and ac(B=-1) == INVALID and ac(vocab=0) == INVALID and ac(dtype=9) == INVALID
+    assert ac(ts=100) == INVALID and ac(d=60, ts=480, hs=60) == INVALID
+    assert ac(window=0) == INVALID and ac(lo=4.0) == INVALID and ac(floor=0) == INVALID and ac(top=40) == INVALID
+    assert ac(B=2000) == UNSUPPORTED and ac(cap=65) == UNSUPPORTED and ac(vocab=2_000_000) == UNSUPPORTED

@@ -223,3 +223,95 @@ def test_close_step_equals_commit_advance_history(gu, dtype, Hkv, d, two_limits)
         if two_limits:
             assert torch.equal(d_in, before)
     assert lens.max() == cap and not (Ko == Kc).all()           # a sequence ran into its capacity; rows were written
+
+
+@pytest.mark.parametrize("vocab,dtype", [(152064, "bf16"), (5000, "f32")])
+def test_accept_and_close_in_one_launch(gu, vocab, dtype):
+    """sage_verify_accept_close_from_slices over several steps against sage_verify_accept_from_slices + sage_close_step
+    on a second copy of the state (bit for bit) and against the oracle's acceptance, commit, advance and history."""
+    import torch
+    from paper_2602_00523_amd import sage
+    g = np.random.default_rng(31)
+    B, Hkv, d, cap, path_cap, window = 3, 2, 64, 120, 24, 10
+    rows = B * MAX_NODES
+    lens = np.array([5, 60, 101], np.int32)
+    Kc0 = wl.gaussian(3, (B * cap, Hkv, d), dtype); Vc0 = wl.gaussian(4, (B * cap, Hkv, d), dtype)
+    ts, hs = Hkv * d, d
+    start = np.arange(B, dtype=np.int64) * cap
+    Ko, Vo = Kc0.copy(), Vc0.copy()
+    hist_o = np.zeros((B, window), np.int32); cnt_o = np.zeros(B, np.int32); dm_o = np.full(B, 6, np.int32)
+
+    def state():
+        return dict(Kc=gu.to_dev(Kc0), Vc=gu.to_dev(Vc0), lens=gu.to_dev(lens.copy()),
+                    hist=torch.zeros((B, window), device="cuda:0", dtype=torch.int32),
+                    cnt=torch.zeros(B, device="cuda:0", dtype=torch.int32),
+                    dm=torch.full((B,), 6, device="cuda:0", dtype=torch.int32),
+                    avg=torch.zeros(B, device="cuda:0", dtype=torch.float32))
+    one, two = state(), state()
+    startd = gu.to_dev(start)
+    ws = torch.empty(sage.sage_entropy_topk_workspace_bytes(rows, vocab, 1), device="cuda:0", dtype=torch.uint8)
+    lens_o = lens.copy()
+    for t in range(5):
+        parent = np.full((B, MAX_NODES), -7, np.int32); depth = np.full((B, MAX_NODES), -7, np.int32)
+        mask = np.zeros((B, MAX_NODES), np.uint64); nn = np.zeros(B, np.int32); pars = []
+        for b in range(B):
+            n = int(g.integers(1, path_cap))                   # fewer nodes than path slots: no path is ever cut
+            par = random_parents(g, n, chain_bias=0.7)
+            p, dd, m, _ = pad_tree(par)
+            parent[b], depth[b], mask[b], nn[b] = p[0], dd[0], m[0], n
+            pars.append(par)
+        x = wl.to_storage(g.standard_normal((rows, vocab), dtype=np.float32) * 3.0, dtype)
+        o1 = oracle.entropy_topk(x, 1, nn, MAX_NODES)
+        tgt = o1["topk_idx"][:, 0].reshape(B, MAX_NODES)
+        tok = g.integers(0, vocab, (B, MAX_NODES)).astype(np.int32)
+        for b in range(B):
+            for v in range(1, int(nn[b])):
+                if g.random() < 0.85:
+                    tok[b, v] = tgt[b, pars[b][v]]
+        Kt = wl.gaussian(100 + t, (B, MAX_NODES, Hkv, d), dtype); Vt = wl.gaussian(200 + t, (B, MAX_NODES, Hkv, d), dtype)
+        # oracle
+        o4 = oracle.verify_accept(tok, np.where(tgt < 0, 0, tgt), parent, depth, nn, path_cap)
+        oracle.commit_path(Kt, Vt, Ko, Vo, start, lens_o, cap, ts, hs, o4["path_nodes"], o4["accept_len"], Hkv, d)
+        lens_o = oracle.advance_kv_len(lens_o, o4["accept_len"], cap)
+        avg_o = oracle.update_history(o4["accept_len"], hist_o, cnt_o, dm_o, window, 2.0, 3.0, 3, 8)
+        # device: fused on `one`, two calls on `two`
+        xd = gu.to_dev(x)
+        dev_in = [gu.to_dev(np.ascontiguousarray(a, np.int32)) for a in (tok, parent, depth)]
+        maskd, nnd = gu.to_dev(mask), gu.to_dev(nn)
+        Ktd, Vtd = gu.to_dev(Kt), gu.to_dev(Vt)
+        outs = []
+        for st, fused in ((one, True), (two, False)):
+            out = dict(entropy=torch.full((rows,), float("nan"), device="cuda:0"),
+                       tgt=torch.full((rows,), -1, device="cuda:0", dtype=torch.int32),
+                       acc=torch.full((B,), -9, device="cuda:0", dtype=torch.int32),
+                       best=torch.full((B,), -9, device="cuda:0", dtype=torch.int32),
+                       path=torch.full((B, path_cap), -9, device="cuda:0", dtype=torch.int32),
+                       toks=torch.full((B, path_cap), -9, device="cuda:0", dtype=torch.int32))
+            sage.sage_entropy_topk_slices(xd, 1, ws, nnd, MAX_NODES)
+            if fused:
+                sage.sage_verify_accept_close_from_slices(ws, vocab, dev_in[0], dev_in[1], dev_in[2], maskd, nnd, path_cap,
+                                                          out["entropy"], out["tgt"], out["acc"], out["best"], out["path"],
+                                                          out["toks"], Ktd, Vtd, st["Kc"], st["Vc"], startd, st["lens"], cap, ts,
+                                                          hs, st["hist"], st["cnt"], st["dm"], st["dm"], 2.0, 3.0, 3, 8, st["avg"])
+            else:
+                sage.sage_verify_accept_from_slices(ws, vocab, dev_in[0], dev_in[1], dev_in[2], maskd, nnd, path_cap,
+                                                    out["entropy"], out["tgt"], out["acc"], out["best"], out["path"], out["toks"])
+                sage.sage_close_step(Ktd, Vtd, st["Kc"], st["Vc"], startd, st["lens"], cap, ts, hs, out["path"], out["acc"],
+                                     st["hist"], st["cnt"], st["dm"], st["dm"], 2.0, 3.0, 3, 8, st["avg"])
+            torch.cuda.synchronize()
+            outs.append(out)
+        for key in outs[0]:
+            a, b2 = outs[0][key], outs[1][key]
+            assert torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a,
+                               b2.view(torch.int32) if b2.dtype == torch.float32 else b2), key
+        for key in one:
+            assert torch.equal(one[key].view(torch.int16) if one[key].dtype == torch.bfloat16 else one[key],
+                               two[key].view(torch.int16) if two[key].dtype == torch.bfloat16 else two[key]), key
+        np.testing.assert_array_equal(outs[0]["acc"].cpu().numpy(), o4["accept_len"])
+        np.testing.assert_array_equal(outs[0]["path"].cpu().numpy(), o4["path_nodes"])
+        assert (gu.to_host(one["Kc"]) == Ko).all() and (gu.to_host(one["Vc"]) == Vo).all()
+        np.testing.assert_array_equal(one["lens"].cpu().numpy(), lens_o)
+        np.testing.assert_array_equal(one["hist"].cpu().numpy(), hist_o)
+        np.testing.assert_array_equal(one["dm"].cpu().numpy(), dm_o)
+        np.testing.assert_array_equal(one["avg"].cpu().numpy(), avg_o)
+    assert cnt_o.max() >= 3                                     # enough steps really ran
