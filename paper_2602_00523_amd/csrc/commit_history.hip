@@ -2,7 +2,8 @@
 // keys and values are appended to the KV cache and the sequence length advances.
 // sage_update_history: adaptive history tracking (Sec. 3.3; window and thresholds of Sec. 5 "Implementation
 // details"): a sliding window of acceptance lengths steers the maximum tree depth of every sequence.
-// All three are byte/integer work of a few KB per step: one small kernel each, no workspace.
+// All three are byte/integer work of a few KB per step: one small kernel each, no workspace; sage_close_step does the
+// three in one launch.
 #include "commit_device.h"
 
 using namespace sage::closing;

@@ -7,6 +7,8 @@
 // Both read the workspace that sage_entropy_topk_slices filled and run exactly the device code of the separate calls
 // (topk_device.h, build_tree_device.h, verify_accept_device.h), so their outputs are bit-identical to the unfused
 // sequence sage_entropy_topk -> sage_build_tree / sage_verify_accept.
+//   sage_verify_accept_close_from_slices = the latter followed, in the same launch, by what closes the step (Alg. 1
+// Phase 3, Sec. 3.3: path commit, length advance, history update; the device code of commit_device.h).
 #include "build_tree_device.h"
 #include "commit_device.h"
 #include "topk_device.h"
