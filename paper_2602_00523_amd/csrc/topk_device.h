@@ -61,6 +61,7 @@ __device__ __forceinline__ void combine_unit_stats(const UnitStats (&u)[OWN], in
 template <int OWN> struct MergeShared {
     uint64_t keys[MERGE_LDS_KEYS];
     UnitStats stats[64 * OWN];
+    float row_m, row_Z;                  // the row's maximum and sum, from the wave that combines the statistics
 };
 
 // Short form of candidate `pos` of list `unit`: 16-bit value code, then the candidate's place among all lists, inverted.
@@ -122,16 +123,26 @@ __device__ __forceinline__ bool merge_row(int row, int k, int nunits, const Unit
         }
     }
     const bool use_short = __syncthreads_and(all_bf16) != 0 && short_possible;
-    if (tid >= 64) return false;                     // wave 0 finishes the row
-    const int lane = tid;
-
-    UnitStats mine_stats[OWN];
+    // Two serial chains that do not depend on each other run side by side: wave 1 combines the slice statistics (and
+    // stores the row's entropy), wave 0 selects the k winners; they meet before Eq. 7-9, which wave 0 evaluates.
+    const int lane = tid & 63;
+    if (tid >= 64) {
+        if (tid < 128) {
+            UnitStats mine_stats[OWN];
 #pragma unroll
-    for (int i = 0; i < OWN; ++i)
-        mine_stats[i] = lane + 64 * i < nunits ? s_stats[lane + 64 * i] : UnitStats{-INFINITY, 0.f, 0.f, 0.f};
-    float m, Z, Tm;
-    combine_unit_stats<OWN>(mine_stats, lane, nunits, m, Z, Tm);
-    if (lane == 0 && entropy) entropy[row] = logf(Z) + Tm / Z;
+            for (int i = 0; i < OWN; ++i)
+                mine_stats[i] = lane + 64 * i < nunits ? s_stats[lane + 64 * i] : UnitStats{-INFINITY, 0.f, 0.f, 0.f};
+            float m, Z, Tm;
+            combine_unit_stats<OWN>(mine_stats, lane, nunits, m, Z, Tm);
+            if (lane == 0) {
+                sh.row_m = m;
+                sh.row_Z = Z;
+                if (entropy) entropy[row] = logf(Z) + Tm / Z;
+            }
+        }
+        __syncthreads();
+        return false;                                // wave 0 finishes the row
+    }
 
     Key mine = Key{0, 0};                            // lane j keeps winner j
     if (use_short) {
@@ -196,6 +207,8 @@ __device__ __forceinline__ bool merge_row(int row, int k, int nunits, const Unit
         }
     }
 
+    __syncthreads();                                 // the statistics are combined
+    const float m = sh.row_m, Z = sh.row_Z;
     const bool have = lane < k;
     const float x = have ? key_value(mine) : -INFINITY;
     const float p = have ? expf(x - m) / Z : 0.f;
