@@ -29,9 +29,10 @@
 // splits are equal ranges of one list of all sequences' tiles, so ragged lengths leave no CU idle (see the
 // kernel).  Waves w and w+4 share column tile w and each takes one 32-token half of every tile; the halves are
 // combined through LDS at the end.  The KV head is the fastest grid index, so in launch order the workgroups of one
-// KV head are congruent modulo the KV-head count, which with 8 KV heads pins a head to one XCD and its L2: the column groups of a large tree re-read K/V from that L2, not from HBM.  Each workgroup
-// writes an un-normalised partial (max, sum, O^T); a second kernel merges the splits in a fixed order
-// (deterministic, no float atomics) and writes bf16.
+// KV head are congruent modulo the KV-head count, which with 8 KV heads pins a head to one XCD and its L2: the column
+// groups of a large tree re-read K/V from that L2, not from HBM.  Each workgroup writes an un-normalised partial
+// (max, sum, O^T); a second kernel merges the splits in a fixed order (deterministic, no float atomics) and writes
+// bf16.
 #include <type_traits>
 
 #include "sage_internal.h"
