@@ -56,7 +56,10 @@ def test_entropy_topk_toy_rows(gu):
 
 
 @pytest.mark.parametrize("vocab,k,dtype", [(152064, 10, "bf16"), (152064, 16, "bf16"), (152064, 1, "bf16"),
-                                           (4099, 5, "f32"), (1000, 64, "f32"), (70001, 3, "bf16")])
+                                           (4099, 5, "f32"), (1000, 64, "f32"), (70001, 3, "bf16"),
+                                           (300000, 32, "bf16"),      # candidate lists too long for the second pass's LDS
+                                           (1048576, 64, "f32"),      # the largest vocabulary and k the call takes
+                                           (1048576, 1, "bf16")])
 def test_entropy_topk_shapes(gu, vocab, k, dtype):
     rows = 6
     stride = (vocab + 15) // 16 * 16
