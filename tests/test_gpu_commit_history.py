@@ -225,7 +225,8 @@ def test_close_step_equals_commit_advance_history(gu, dtype, Hkv, d, two_limits)
     assert lens.max() == cap and not (Ko == Kc).all()           # a sequence ran into its capacity; rows were written
 
 
-@pytest.mark.parametrize("vocab,dtype", [(152064, "bf16"), (5000, "f32")])
+@pytest.mark.parametrize("vocab,dtype", [(152064, "bf16"), (5000, "f32"),
+                                         (300000, "bf16")])        # more than 256 slices per row
 def test_accept_and_close_in_one_launch(gu, vocab, dtype):
     """sage_verify_accept_close_from_slices over several steps against sage_verify_accept_from_slices + sage_close_step
     on a second copy of the state (bit for bit) and against the oracle's acceptance, commit, advance and history."""
