@@ -80,3 +80,60 @@ def level_order(par: np.ndarray) -> np.ndarray:
     new_of_old = np.empty(len(par), np.int64)
     new_of_old[order] = np.arange(len(par))
     return np.array([-1 if par[o] < 0 else new_of_old[par[o]] for o in order], np.int32)
+
+
+def relayout_cache(inp: dict, layout: str) -> dict:
+    """The packed cache [tokens, Hkv, d] of an attention input set (a dict as workloads.attention_inputs returns it)
+    stored another way, same values: 'head_major' = [Hkv, tokens, d]; 'padded' = [tokens, Hkv, d + 8] with unrelated
+    values in the padding; 'shifted' = the packed layout moved 29 tokens into a larger buffer (kv_start grows by 29);
+    'reversed' = sequences stored in reverse order with gaps between them.  Returns a copy of inp with Kc, Vc,
+    kv_start and the strides replaced."""
+    out = dict(inp)
+    Kc, Vc = inp["Kc"], inp["Vc"]
+    T, Hkv, d = Kc.shape
+    junk = np.random.default_rng(1234)
+
+    def noise(shape):
+        return (junk.integers(0, 2 ** 14, size=shape)).astype(Kc.dtype) if Kc.dtype == np.uint16 else \
+            junk.standard_normal(shape).astype(Kc.dtype)
+    if layout == "head_major":
+        out["Kc"], out["Vc"] = (np.ascontiguousarray(a.transpose(1, 0, 2)) for a in (Kc, Vc))
+        out["kv_token_stride"], out["kv_head_stride"] = d, T * d
+    elif layout == "padded":
+        bufs = []
+        for a in (Kc, Vc):
+            b = noise((T, Hkv, d + 8))
+            b[:, :, :d] = a
+            bufs.append(b)
+        out["Kc"], out["Vc"] = bufs
+        out["kv_token_stride"], out["kv_head_stride"] = Hkv * (d + 8), d + 8
+    elif layout == "shifted":
+        bufs = []
+        for a in (Kc, Vc):
+            b = noise((T + 40, Hkv, d))
+            b[29:29 + T] = a
+            bufs.append(b)
+        out["Kc"], out["Vc"] = bufs
+        out["kv_start"] = np.asarray(inp["kv_start"], np.int64) + 29
+    elif layout == "reversed":
+        lens = np.asarray(inp["kv_len"], np.int64)
+        starts = np.asarray(inp["kv_start"], np.int64)
+        new_start = np.zeros_like(starts)
+        at = 5
+        for b in range(len(lens) - 1, -1, -1):
+            new_start[b] = at
+            at += int(lens[b]) + 3
+        bufs = []
+        for a in (Kc, Vc):
+            buf = noise((at + 1, Hkv, d))
+            for b in range(len(lens)):
+                buf[new_start[b]:new_start[b] + lens[b]] = a[starts[b]:starts[b] + lens[b]]
+            bufs.append(buf)
+        out["Kc"], out["Vc"] = bufs
+        out["kv_start"] = new_start
+    else:
+        raise ValueError(layout)
+    return out
+
+
+CACHE_LAYOUTS = ("head_major", "padded", "shifted", "reversed")

@@ -225,6 +225,22 @@ def test_attention_bf16_other_group_sizes(gu, Hq, Hkv):
     run_attention_case(gu, 90 + Hq, "bf16", 2, Hq, Hkv, 128, [333, 70], sizes=[64, 11])
 
 
+@pytest.mark.parametrize("layout", ["head_major", "padded", "shifted", "reversed"])
+@pytest.mark.parametrize("dtype,Hq,Hkv,d", [("bf16", 64, 8, 128), ("bf16", 28, 4, 128), ("f32", 4, 2, 64)])
+def test_attention_cache_layouts(gu, layout, dtype, Hq, Hkv, d):
+    """The cache stored head-major, with padded rows, shifted, or with the sequences in another order: the kernels get
+    the re-laid-out buffers and strides, the reference is the oracle on the packed layout."""
+    from helpers import relayout_cache
+    B, lens, sizes = 3, [300, 0, 1000], [20, 5, 64]
+    g = wl.rng(500 + Hq)
+    inp = wl.attention_inputs(600 + Hq, B, Hq, Hkv, d, lens, dtype)
+    mask, nn = tree_batch(g, B, sizes)
+    ref = oracle.tree_attention(inp["Q"], inp["Kc"], inp["Vc"], inp["Kt"], inp["Vt"], inp["kv_start"], inp["kv_len"],
+                                inp["kv_token_stride"], inp["kv_head_stride"], mask, nn, Hq, Hkv, d)
+    got, _ = gu.gpu_tree_attention(relayout_cache(inp, layout), mask, nn, Hq, Hkv, d)
+    gu.assert_attention_close(got, ref, nn, TOL[dtype])
+
+
 @pytest.mark.parametrize("Hq,Hkv,L,n", [(28, 4, 1638, 25), (64, 8, 300, 64)])
 def test_attention_level_by_level_growth(gu, Hq, Hkv, L, n):
     """A tree drafted one level per forward pass (the draft side of Alg. 1 Phase 1): call l sees the nodes of levels

@@ -148,3 +148,26 @@ def test_cache_permutation_invariance_and_kv_start():
     inp3["Kc"], inp3["Vc"] = np.roll(inp["Kc"], 13, 0), np.roll(inp["Vc"], 13, 0)
     inp3["kv_start"] = np.array([13], np.int64)
     np.testing.assert_array_equal(run_oracle(inp3, mask, nn, Hq, Hkv, d)[0, :n], O[0, :n])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_cache_layouts_give_the_same_bits(dtype):
+    """The cache is addressed as (kv_start[b] + j) * token_stride + g * head_stride + c and nothing else: the same
+    values stored head-major, with padded rows, shifted, or with the sequences in another order and gaps between them
+    give bit-identical results (and values outside the addressed rows are never read: they differ between layouts)."""
+    from helpers import CACHE_LAYOUTS, relayout_cache
+    B, Hq, Hkv, d = 3, 4, 2, 16
+    inp = wl.attention_inputs(77, B, Hq, Hkv, d, [37, 0, 90], dtype)
+    g = wl.rng(78)
+    mask = np.zeros((B, MAX_NODES), np.uint64)
+    nn = np.zeros(B, np.int32)
+    for b, n in enumerate([9, 4, 17]):
+        _, _, m, _ = pad_tree(random_parents(g, n, chain_bias=0.5))
+        mask[b], nn[b] = m[0], n
+    ref = run_oracle(inp, mask, nn, Hq, Hkv, d)
+    for layout in CACHE_LAYOUTS:
+        alt = relayout_cache(inp, layout)
+        assert alt["Kc"].shape != inp["Kc"].shape or layout == "head_major"
+        got = run_oracle(alt, mask, nn, Hq, Hkv, d)
+        for b in range(B):
+            np.testing.assert_array_equal(got[b, :nn[b]], ref[b, :nn[b]], err_msg=layout)
