@@ -296,6 +296,35 @@ int sage_verify_accept_close_from_slices(
     int kv_capacity, long kv_token_stride, long kv_head_stride, int window, float lo, float hi, int d_floor, int d_cap,
     int* hist, int* count, const int* d_max_in, int* d_max_out, float* avg_out, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * sage_tree_attention_with_plan -- sage_tree_attention and sage_build_tree_from_slices in one
+ * launch.  With the lookahead of Sec. 3.2 the tree planned at a step (Sec. 3.1-3.2, from the
+ * step's draft distribution) is the one verified at the NEXT step, so the planning of a step
+ * and its verification attention (Alg. 1 Phase 2) touch disjoint data; here the planning
+ * workgroups (one per sequence) ride in the attention launch beside the workgroups that
+ * stream the cache, which removes planning's launch from the step's chain of dependent
+ * launches.  Results of both halves are bit-identical to the two separate calls.
+ *
+ * Arguments: those of sage_tree_attention (through workspace_bytes), then those of
+ * sage_build_tree_from_slices without its B (one draft row per sequence of the attention
+ * batch: `slices` filled by sage_entropy_topk_slices with rows = B); the planned tree goes to
+ * next_n_nodes / next_parent / next_depth / next_rank / next_anc_mask (/ next_cum_prob,
+ * next_node_token, nullable), which must not be the arrays the attention reads (n_nodes,
+ * anc_mask).  bf16 with at most 256 slices per draft row and at most 2048 candidates per row
+ * in `slices` (vocab 152064 with k = 10: 149 slices, 1490 candidates): one launch (plus the
+ * split merge of the attention); otherwise (fp32, longer lists) the two calls are enqueued
+ * one after the other with the same results.
+ * Errors: those of the two calls, checked before anything is enqueued; INVALID_ARG when the
+ * planned tree's arrays alias the verified tree's.
+ */
+int sage_tree_attention_with_plan(
+    const void* Q, const void* Kc, const void* Vc, const void* Kt, const void* Vt, void* O, int dtype, int B, int Hq, int Hkv,
+    int d, const int64_t* kv_start, const int* kv_len, int max_kv_len, long kv_token_stride, long kv_head_stride,
+    const uint64_t* anc_mask, const int* n_nodes, float scale, void* workspace, size_t workspace_bytes,
+    void* slices, int vocab, int k, const sage_tree_params* params, const int* d_max_seq, float* entropy, int* topk_idx,
+    float* topk_prob, float* topk_renorm, float* topk_entropy, float* alpha, int* next_n_nodes, int* next_parent,
+    int* next_depth, int* next_rank, uint64_t* next_anc_mask, float* next_cum_prob, int* next_node_token, void* stream);
+
 /* Library build identification (host): returns a static string naming the target architecture. */
 const char* sage_build_info(void);
 

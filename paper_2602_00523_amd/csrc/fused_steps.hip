@@ -9,9 +9,8 @@
 // sequence sage_entropy_topk -> sage_build_tree / sage_verify_accept.
 //   sage_verify_accept_close_from_slices = the latter followed, in the same launch, by what closes the step (Alg. 1
 // Phase 3, Sec. 3.3: path commit, length advance, history update; the device code of commit_device.h).
-#include "build_tree_device.h"
 #include "commit_device.h"
-#include "topk_device.h"
+#include "plan_device.h"
 #include "verify_accept_device.h"
 
 using namespace sage::topk;
@@ -30,12 +29,10 @@ __global__ __launch_bounds__(MERGE_THREADS) void plan_kernel(int k, int nunits, 
                                                              int* __restrict__ rank, uint64_t* __restrict__ anc_mask,
                                                              float* __restrict__ cum_prob, int* __restrict__ node_token) {
     __shared__ MergeShared<OWN> sh;
-    const int b = blockIdx.x;
-    MergedRow r;
-    if (!merge_row<OWN>(b, k, nunits, stats, keys, sh, entropy, topk_idx, topk_prob, topk_renorm, topk_entropy, alpha, r)) return;
-    const int lane = threadIdx.x;
-    sage::tree::build_tree_wave(b, lane, lane < k ? r.q : 0.0f, lane < k ? r.idx : -1, r.alpha, k, prm, d_max_seq, n_nodes, parent,
-                                depth, rank, anc_mask, cum_prob, node_token);
+    const sage::PlanArgs pl{k,        nunits,      stats,        keys,  entropy, topk_idx,  topk_prob, topk_renorm, topk_entropy,
+                            alpha,    prm,         d_max_seq,    n_nodes, parent, depth,    rank,      anc_mask,    cum_prob,
+                            node_token};
+    sage::plan_sequence<OWN, MERGE_THREADS>(blockIdx.x, pl, sh);
 }
 
 // One workgroup of 16 waves per sequence.  Wave w finishes the k = 1 reduction of the target rows of nodes w, w+16, ...
@@ -149,35 +146,55 @@ __global__ __launch_bounds__(64 * ACCEPT_WAVES) void accept_kernel(const int* __
 
 }  // namespace
 
-extern "C" int sage_build_tree_from_slices(void* slices, int vocab, int B, int k, const sage_tree_params* params,
-                                           const int* d_max_seq, float* entropy, int* topk_idx, float* topk_prob,
-                                           float* topk_renorm, float* topk_entropy, float* alpha, int* n_nodes, int* parent,
-                                           int* depth, int* rank, uint64_t* anc_mask, float* cum_prob, int* node_token,
-                                           void* stream) {
+// Argument checks of sage_build_tree_from_slices; fills what its kernel takes.  Shared with the attention call that
+// carries the planning along (tree_attention.hip).
+namespace sage {
+int plan_args_from_slices(void* slices, int vocab, int B, int k, const sage_tree_params* params, const int* d_max_seq,
+                          float* entropy, int* topk_idx, float* topk_prob, float* topk_renorm, float* topk_entropy,
+                          float* alpha, int* n_nodes, int* parent, int* depth, int* rank, uint64_t* anc_mask, float* cum_prob,
+                          int* node_token, PlanArgs* out) {
     if (!slices || !params || !topk_idx || !n_nodes || !parent || !depth || !rank || !anc_mask) return SAGE_INVALID_ARG;
     const sage_tree_params p = *params;
     if (B < 0 || vocab < 1 || k != p.k || k < 1 || k > SAGE_MAX_TOPK || k > vocab) return SAGE_INVALID_ARG;
     if (p.n_max < 1 || p.n_max > SAGE_MAX_NODES) return SAGE_INVALID_ARG;
     if (p.d_min < 1 || p.d_min > p.d_max || p.d_max > SAGE_MAX_DEPTH) return SAGE_INVALID_ARG;
     if (p.w_min < 1 || p.w_min > p.w_max || p.w_max > k) return SAGE_INVALID_ARG;
-    if (!sage::aligned(slices, 16)) return SAGE_INVALID_ARG;
+    if (!aligned(slices, 16)) return SAGE_INVALID_ARG;
     if (B > 65535) return SAGE_UNSUPPORTED;
     UnitStats* stats;
     uint64_t* keys;
     int nunits;
-    sage::topk_workspace_layout(B, vocab, slices, &stats, &keys, &nunits);
-    if (nunits > sage::topk_max_units()) return SAGE_UNSUPPORTED;
-    if (B == 0) return SAGE_OK;
-    hipStream_t s = sage::as_stream(stream);
-    if (nunits <= 256)
-        hipLaunchKernelGGL(plan_kernel<4>, dim3(B), dim3(MERGE_THREADS), 0, s, k, nunits, stats, keys, entropy, topk_idx, topk_prob,
-                           topk_renorm, topk_entropy, alpha, p, d_max_seq, n_nodes, parent, depth, rank, anc_mask, cum_prob,
-                           node_token);
+    topk_workspace_layout(B, vocab, slices, &stats, &keys, &nunits);
+    if (nunits > topk_max_units()) return SAGE_UNSUPPORTED;
+    *out = PlanArgs{k,     nunits, stats,     keys,   entropy, topk_idx, topk_prob, topk_renorm, topk_entropy,
+                    alpha, p,      d_max_seq, n_nodes, parent, depth,    rank,      anc_mask,    cum_prob,
+                    node_token};
+    return SAGE_OK;
+}
+
+int launch_plan(const PlanArgs& a, int B, hipStream_t s) {
+    if (a.nunits <= 256)
+        hipLaunchKernelGGL(plan_kernel<4>, dim3(B), dim3(MERGE_THREADS), 0, s, a.k, a.nunits, a.stats, a.keys, a.entropy, a.topk_idx,
+                           a.topk_prob, a.topk_renorm, a.topk_entropy, a.alpha, a.prm, a.d_max_seq, a.n_nodes, a.parent, a.depth,
+                           a.rank, a.anc_mask, a.cum_prob, a.node_token);
     else
-        hipLaunchKernelGGL(plan_kernel<MAX_OWN>, dim3(B), dim3(MERGE_THREADS), 0, s, k, nunits, stats, keys, entropy, topk_idx,
-                           topk_prob, topk_renorm, topk_entropy, alpha, p, d_max_seq, n_nodes, parent, depth, rank, anc_mask,
-                           cum_prob, node_token);
-    return sage::launch_status();
+        hipLaunchKernelGGL(plan_kernel<MAX_OWN>, dim3(B), dim3(MERGE_THREADS), 0, s, a.k, a.nunits, a.stats, a.keys, a.entropy,
+                           a.topk_idx, a.topk_prob, a.topk_renorm, a.topk_entropy, a.alpha, a.prm, a.d_max_seq, a.n_nodes, a.parent,
+                           a.depth, a.rank, a.anc_mask, a.cum_prob, a.node_token);
+    return launch_status();
+}
+}  // namespace sage
+
+extern "C" int sage_build_tree_from_slices(void* slices, int vocab, int B, int k, const sage_tree_params* params,
+                                           const int* d_max_seq, float* entropy, int* topk_idx, float* topk_prob,
+                                           float* topk_renorm, float* topk_entropy, float* alpha, int* n_nodes, int* parent,
+                                           int* depth, int* rank, uint64_t* anc_mask, float* cum_prob, int* node_token,
+                                           void* stream) {
+    sage::PlanArgs a;
+    const int rc = sage::plan_args_from_slices(slices, vocab, B, k, params, d_max_seq, entropy, topk_idx, topk_prob, topk_renorm,
+                                               topk_entropy, alpha, n_nodes, parent, depth, rank, anc_mask, cum_prob, node_token, &a);
+    if (rc != SAGE_OK || B == 0) return rc;
+    return sage::launch_plan(a, B, sage::as_stream(stream));
 }
 
 extern "C" int sage_verify_accept_from_slices(void* slices, int vocab, const int* token, const int* parent, const int* depth,

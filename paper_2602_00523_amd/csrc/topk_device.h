@@ -57,8 +57,10 @@ __device__ __forceinline__ void combine_unit_stats(const UnitStats (&u)[OWN], in
     Tm = wave_sum(Tm);
 }
 
-// LDS of one merging workgroup.
+// LDS of one merging workgroup.  merge_row takes any type with these members (keys, stats, row_m, row_Z; LDS_KEYS =
+// how many keys fit), so a kernel with LDS of its own can lend some of it instead.
 template <int OWN> struct MergeShared {
+    static constexpr int LDS_KEYS = MERGE_LDS_KEYS;
     uint64_t keys[MERGE_LDS_KEYS];
     UnitStats stats[64 * OWN];
     float row_m, row_Z;                  // the row's maximum and sum, from the wave that combines the statistics
@@ -83,25 +85,25 @@ struct MergedRow {
     float p, q, alpha;
 };
 
-// Second pass for one row, called by all MERGE_THREADS threads of a workgroup: combine the slice statistics, k-way
-// merge of the per-slice sorted key lists, Eq. 7-9.  OWN = lists per lane (lane owns lists lane, lane+64, ...); the
-// head of every owned list stays in registers and only the lane whose list wins a round fetches its next entry.
-// Writes the row's outputs (null pointers are skipped) and returns true in wave 0, whose lanes receive `out`; the other
-// waves only help staging and return false.
-template <int OWN>
+// Second pass for one row, called by all WG_THREADS threads of a workgroup (at least two waves): combine the slice
+// statistics, k-way merge of the per-slice sorted key lists, Eq. 7-9.  OWN = lists per lane (lane owns lists lane,
+// lane+64, ...); the head of every owned list stays in registers and only the lane whose list wins a round fetches its
+// next entry.  Writes the row's outputs (null pointers are skipped) and returns true in wave 0, whose lanes receive
+// `out`; the other waves only help staging and return false.  Every thread passes the same two workgroup barriers.
+template <int OWN, int WG_THREADS = MERGE_THREADS, class Shared>
 __device__ __forceinline__ bool merge_row(int row, int k, int nunits, const UnitStats* __restrict__ stats,
-                                          const uint64_t* __restrict__ keys, MergeShared<OWN>& sh, float* __restrict__ entropy,
+                                          const uint64_t* __restrict__ keys, Shared& sh, float* __restrict__ entropy,
                                           int* __restrict__ topk_idx, float* __restrict__ topk_prob,
                                           float* __restrict__ topk_renorm, float* __restrict__ topk_entropy,
                                           float* __restrict__ alpha, MergedRow& out) {
-    constexpr int THREADS = MERGE_THREADS;
+    constexpr int THREADS = WG_THREADS;
     uint64_t* s_keys = sh.keys;
     UnitStats* s_stats = sh.stats;
     const int tid = threadIdx.x;
     const UnitStats* st = stats + static_cast<long>(row) * nunits;
     const uint64_t* kk = keys + static_cast<long>(row) * nunits * k;
     const int total = nunits * k;
-    const bool in_lds = total <= MERGE_LDS_KEYS;
+    const bool in_lds = total <= Shared::LDS_KEYS;
     // ---- the whole workgroup stages statistics and lists in LDS, eight independent loads per thread at a time; while
     //      doing so it finds out whether the short form of the keys may be used for the selection rounds
     const bool short_possible = in_lds && k <= SHORT_MAX_K && nunits * SHORT_MAX_K < 0x10000;

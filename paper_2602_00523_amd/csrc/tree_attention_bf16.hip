@@ -35,6 +35,7 @@
 // bf16.
 #include <type_traits>
 
+#include "plan_device.h"
 #include "sage_internal.h"
 
 namespace {
@@ -160,10 +161,9 @@ __device__ __forceinline__ float cross_half_sum(float v) {
 // (the library is built with kernel-argument preloading), so the first thing a workgroup does, fetching its sequence's
 // length and node count, does not wait for a fetch of the argument block first.
 template <bool BATCH>
-__global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const int* __restrict__ kv_len_arg,
-                                                                      const int* __restrict__ n_nodes_arg,
-                                                                      const int64_t* __restrict__ kv_start_arg, int nslot_arg,
-                                                                      int min_tps_arg, int G_arg, const Params prm) {
+__device__ __forceinline__ void attention_workgroup(const int* __restrict__ kv_len_arg, const int* __restrict__ n_nodes_arg,
+                                                    const int64_t* __restrict__ kv_start_arg, int nslot_arg, int min_tps_arg,
+                                                    int G_arg, const Params& prm) {
     // one LDS object per stage and operand (see header)
     __shared__ __align__(1024) unsigned char sK0[K_STAGE_B];
     __shared__ __align__(1024) unsigned char sK1[K_STAGE_B];
@@ -566,6 +566,50 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const int*
 #undef SV
 }
 
+template <bool BATCH>
+__global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const int* __restrict__ kv_len_arg,
+                                                                      const int* __restrict__ n_nodes_arg,
+                                                                      const int64_t* __restrict__ kv_start_arg, int nslot_arg,
+                                                                      int min_tps_arg, int G_arg, const Params prm) {
+    attention_workgroup<BATCH>(kv_len_arg, n_nodes_arg, kv_start_arg, nslot_arg, min_tps_arg, G_arg, prm);
+}
+
+// The same launch carrying the planning of the next tree along (sage_tree_attention_with_plan): the grid has extra
+// slabs of workgroups past the attention's own (blockIdx.y >= first_plan_slab), one workgroup of which per sequence runs
+// sage_build_tree_from_slices' work for that sequence, with LDS of its own, while the attention workgroups stream the
+// cache.  The two halves share nothing: the tree being planned is the next step's, not the one whose mask the
+// attention reads.  A step is a chain of dependent launches and planning is two of them; inside this launch it costs
+// no launch and, as long as it is shorter than the attention, no time.
+constexpr int PLAN_LDS_KEYS = 2048;
+constexpr int PLAN_OWN = 4;              // slices per lane: up to 256 slices per draft row
+struct LentMergeShared {
+    static constexpr int LDS_KEYS = PLAN_LDS_KEYS;
+    uint64_t* keys;
+    sage::topk::UnitStats* stats;
+    float& row_m;
+    float& row_Z;
+};
+template <bool BATCH>
+__global__ __launch_bounds__(THREADS) void tree_attention_plan_kernel(const int* __restrict__ kv_len_arg,
+                                                                      const int* __restrict__ n_nodes_arg,
+                                                                      const int64_t* __restrict__ kv_start_arg, int nslot_arg,
+                                                                      int min_tps_arg, int G_arg, int first_plan_slab,
+                                                                      const Params prm, const sage::PlanArgs pl) {
+    if (static_cast<int>(blockIdx.y) >= first_plan_slab) {  // workgroup-uniform
+        __shared__ uint64_t p_keys[PLAN_LDS_KEYS];
+        __shared__ sage::topk::UnitStats p_stats[64 * PLAN_OWN];
+        __shared__ float p_row[2];
+        // one sequence per launch slot: the slab's first workgroup of sequence blockIdx.z; batches: slab workgroups in turn
+        const int b = BATCH ? (static_cast<int>(blockIdx.y) - first_plan_slab) * static_cast<int>(gridDim.x) + static_cast<int>(blockIdx.x)
+                            : (blockIdx.x == 0 ? static_cast<int>(blockIdx.z) : prm.B);
+        if (b >= prm.B) return;
+        LentMergeShared sh{p_keys, p_stats, p_row[0], p_row[1]};
+        sage::plan_sequence<PLAN_OWN, THREADS>(b, pl, sh);
+        return;
+    }
+    attention_workgroup<BATCH>(kv_len_arg, n_nodes_arg, kv_start_arg, nslot_arg, min_tps_arg, G_arg, prm);
+}
+
 // Merge the splits of one (sequence, node, query head) in split order and write bf16.  One wave per row:
 // lane = split for the (max, sum) pairs and their weights, lane = pair of output dims for the accumulation.
 // Every partial of the row is requested before the first one is used, so the merge costs one memory round trip.
@@ -733,10 +777,17 @@ size_t attention_bf16_workspace_bytes(int B, int Hkv, int G, int max_kv_len) {
     return (sh.batch ? static_cast<size_t>(1) : static_cast<size_t>(B)) * Hkv * sh.nslot * per_slot;
 }
 
+// Whether the attention launch can carry this planning along: the lists of a draft row must fit the LDS the planning
+// workgroup has, and a lane holds at most PLAN_OWN slices.
+bool attention_bf16_can_carry_plan(const PlanArgs& pl) {
+    return pl.nunits <= 64 * PLAN_OWN && pl.nunits * pl.k <= PLAN_LDS_KEYS;
+}
+
+// plan == nullptr: the attention alone.  Otherwise the caller has checked attention_bf16_can_carry_plan(*plan).
 int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const void* Kt, const void* Vt, void* O, int B,
                         int Hq, int Hkv, int d, const int64_t* kv_start, const int* kv_len, int max_kv_len,
                         long kv_token_stride, long kv_head_stride, const uint64_t* anc_mask, const int* n_nodes,
-                        float scale, void* workspace, size_t workspace_bytes, hipStream_t stream) {
+                        float scale, void* workspace, size_t workspace_bytes, hipStream_t stream, const PlanArgs* plan) {
     const int G = Hq / Hkv;
     if (d != D || G < 1 || G > 16) return SAGE_UNSUPPORTED;   // 64 nodes x 16 heads per KV head = 8 groups of 128 rows
     if ((kv_token_stride % 8) != 0 || (kv_head_stride % 8) != 0) return SAGE_INVALID_ARG;
@@ -759,13 +810,28 @@ int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const voi
     p.scale_log2e = scale * 1.4426950408889634f;
 
     p.nrange = sh.nrange;
-    const dim3 grid(Hkv, sh.batch ? p.nrange : p.nslot, sh.batch ? 1 : B), block(THREADS);
-    if (sh.batch)
-        hipLaunchKernelGGL(tree_attention_bf16_kernel<true>, grid, block, 0, stream, kv_len, n_nodes, kv_start, p.nslot,
-                           p.min_tiles_per_split, G, p);
-    else
-        hipLaunchKernelGGL(tree_attention_bf16_kernel<false>, grid, block, 0, stream, kv_len, n_nodes, kv_start, p.nslot,
-                           p.min_tiles_per_split, G, p);
+    const int own_slabs = sh.batch ? p.nrange : p.nslot;
+    const dim3 block(THREADS);
+    if (plan) {
+        // planning workgroups in slabs of their own past the attention's: one slab whose first workgroup of every
+        // sequence plans (one sequence per launch slot), or as many slabs as B workgroups need (batches)
+        const int plan_slabs = sh.batch ? (B + Hkv - 1) / Hkv : 1;
+        const dim3 grid(Hkv, own_slabs + plan_slabs, sh.batch ? 1 : B);
+        if (sh.batch)
+            hipLaunchKernelGGL(tree_attention_plan_kernel<true>, grid, block, 0, stream, kv_len, n_nodes, kv_start, p.nslot,
+                               p.min_tiles_per_split, G, own_slabs, p, *plan);
+        else
+            hipLaunchKernelGGL(tree_attention_plan_kernel<false>, grid, block, 0, stream, kv_len, n_nodes, kv_start, p.nslot,
+                               p.min_tiles_per_split, G, own_slabs, p, *plan);
+    } else {
+        const dim3 grid(Hkv, own_slabs, sh.batch ? 1 : B);
+        if (sh.batch)
+            hipLaunchKernelGGL(tree_attention_bf16_kernel<true>, grid, block, 0, stream, kv_len, n_nodes, kv_start, p.nslot,
+                               p.min_tiles_per_split, G, p);
+        else
+            hipLaunchKernelGGL(tree_attention_bf16_kernel<false>, grid, block, 0, stream, kv_len, n_nodes, kv_start, p.nslot,
+                               p.min_tiles_per_split, G, p);
+    }
     if (hipGetLastError() != hipSuccess) return SAGE_LAUNCH_FAILED;
     const int mrows = sh.batch ? MERGE_ROWS_BATCH : MERGE_ROWS_SINGLE;
     const int row_blocks = (SAGE_MAX_NODES * G + mrows - 1) / mrows;

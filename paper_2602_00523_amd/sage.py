@@ -50,6 +50,10 @@ def lib():
         L.sage_tree_attention.restype = _ci
         L.sage_tree_attention.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _cl, _cl,
                                           _vp, _vp, _cf, _vp, _sz, _vp]
+        L.sage_tree_attention_with_plan.restype = _ci
+        L.sage_tree_attention_with_plan.argtypes = (
+            [_vp, _vp, _vp, _vp, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _cl, _cl, _vp, _vp, _cf, _vp, _sz]
+            + [_vp, _ci, _ci, ctypes.POINTER(TreeParams)] + [_vp] * 15)
         L.sage_verify_accept.restype = _ci
         L.sage_verify_accept.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _ci, _ci, _vp, _vp, _vp, _vp, _vp]
         L.sage_commit_path.restype = _ci
@@ -150,6 +154,19 @@ def _args_tree_attention(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_
             _ptr(workspace), _nbytes(workspace), _stream(stream)]
 
 
+def _args_tree_attention_with_plan(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_token_stride, kv_head_stride, anc_mask,
+                                   n_nodes, scale, workspace, slices, vocab, params: TreeParams, entropy, topk_idx, topk_prob,
+                                   topk_renorm, topk_entropy, alpha, next_n_nodes, next_parent, next_depth, next_rank,
+                                   next_anc_mask, next_cum_prob=None, next_node_token=None, stream=None, d_max_seq=None):
+    att = _args_tree_attention(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_token_stride, kv_head_stride, anc_mask,
+                               n_nodes, scale, workspace, stream)
+    plan = _args_build_tree_from_slices(slices, vocab, params, entropy, topk_idx, topk_prob, topk_renorm, topk_entropy, alpha,
+                                        next_n_nodes, next_parent, next_depth, next_rank, next_anc_mask, next_cum_prob,
+                                        next_node_token, stream, d_max_seq)
+    assert plan[2] == att[7], "one draft row per sequence"
+    return att[:-1] + plan[:2] + plan[3:]              # the batch size travels once
+
+
 def _args_verify_accept(token, target_argmax, parent, depth, anc_mask, n_nodes, path_cap, accept_len, best_node,
                         path_nodes, out_tokens, stream=None):
     B = n_nodes.shape[0]
@@ -229,6 +246,7 @@ def _args_verify_accept_close_from_slices(slices, vocab, token, parent, depth, a
 
 
 _MARSHAL = {"sage_close_step": _args_close_step,
+            "sage_tree_attention_with_plan": _args_tree_attention_with_plan,
             "sage_verify_accept_close_from_slices": _args_verify_accept_close_from_slices,
             "sage_entropy_topk_slices": _args_entropy_topk_slices,
             "sage_build_tree_from_slices": _args_build_tree_from_slices,
@@ -249,6 +267,10 @@ def sage_build_tree(*a, **kw):
 
 def sage_tree_attention(*a, **kw):
     _check("sage_tree_attention", lib().sage_tree_attention(*_args_tree_attention(*a, **kw)))
+
+
+def sage_tree_attention_with_plan(*a, **kw):
+    _check("sage_tree_attention_with_plan", lib().sage_tree_attention_with_plan(*_args_tree_attention_with_plan(*a, **kw)))
 
 
 def sage_verify_accept(*a, **kw):

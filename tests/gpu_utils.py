@@ -177,6 +177,42 @@ def gpu_plan_from_slices(logits_np, k, prm: dict, d_max_seq_np=None):
     return r1, r2
 
 
+def gpu_attention_with_plan(inp: dict, anc_mask_np, n_nodes_np, Hq, Hkv, d, logits_np, k, prm: dict, d_max_seq_np=None):
+    """sage_entropy_topk_slices + sage_tree_attention_with_plan: O (raw tensor bits as numpy) and the outputs of the planning
+    half, laid out as gpu_plan_from_slices returns them."""
+    Q, Kc, Vc, Kt, Vt = (to_dev(inp[key]) for key in ("Q", "Kc", "Vc", "Kt", "Vt"))
+    B = Q.shape[0]
+    O = torch.zeros_like(Q)
+    kv_start, kv_len = to_dev(np.asarray(inp["kv_start"], np.int64)), to_dev(np.asarray(inp["kv_len"], np.int32))
+    mask, nn = to_dev(np.ascontiguousarray(anc_mask_np, np.uint64)), to_dev(np.asarray(n_nodes_np, np.int32))
+    max_len = int(np.max(inp["kv_len"])) if B else 0
+    code = sage.F32 if Q.dtype == torch.float32 else sage.BF16
+    ws3 = torch.empty(sage.sage_tree_attention_workspace_bytes(code, B, Hq, Hkv, d, max_len), device=DEV, dtype=torch.uint8)
+    x = to_dev(logits_np)
+    assert x.shape[0] == B
+    vocab = x.shape[1]
+    f = lambda *s: torch.full(s, float("nan"), device=DEV, dtype=torch.float32)
+    i32 = lambda fill: torch.full((B, MAX_NODES), fill, device=DEV, dtype=torch.int32)
+    a1 = dict(entropy=f(B), topk_idx=torch.full((B, k), -1, device=DEV, dtype=torch.int32), topk_prob=f(B, k),
+              topk_renorm=f(B, k), topk_entropy=f(B), alpha=f(B))
+    a2 = dict(n_nodes=torch.zeros(B, device=DEV, dtype=torch.int32), parent=i32(-2), depth=i32(-2), rank=i32(-2),
+              anc_mask=torch.zeros((B, MAX_NODES), device=DEV, dtype=torch.int64),
+              cum_prob=torch.full((B, MAX_NODES), float("nan"), device=DEV, dtype=torch.float32), node_token=i32(-2))
+    ws1 = torch.empty(sage.sage_entropy_topk_workspace_bytes(B, vocab, k), device=DEV, dtype=torch.uint8)
+    dm = None if d_max_seq_np is None else to_dev(np.ascontiguousarray(d_max_seq_np, np.int32))
+    sage.sage_entropy_topk_slices(x, k, ws1)
+    sage.sage_tree_attention_with_plan(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_len, inp["kv_token_stride"],
+                                       inp["kv_head_stride"], mask, nn, 1.0 / float(np.sqrt(d)), ws3, ws1, vocab,
+                                       sage.tree_params(**prm), a1["entropy"], a1["topk_idx"], a1["topk_prob"], a1["topk_renorm"],
+                                       a1["topk_entropy"], a1["alpha"], a2["n_nodes"], a2["parent"], a2["depth"], a2["rank"],
+                                       a2["anc_mask"], a2["cum_prob"], a2["node_token"], d_max_seq=dm)
+    torch.cuda.synchronize()
+    r1 = {key: v.cpu().numpy() for key, v in a1.items()}
+    r2 = {key: v.cpu().numpy() for key, v in a2.items()}
+    r2["anc_mask"] = r2["anc_mask"].view(np.uint64)
+    return to_host(O), r1, r2
+
+
 def gpu_accept_from_slices(target_logits_np, token, parent, depth, anc_mask, n_nodes, path_cap):
     """sage_entropy_topk_slices (k = 1, rows grouped by sequence) + sage_verify_accept_from_slices."""
     x = to_dev(target_logits_np)

@@ -213,3 +213,29 @@ def test_accept_close_validates_on_the_host(lib):
     assert ac(ts=100) == INVALID and ac(d=60, ts=480, hs=60) == INVALID
     assert ac(window=0) == INVALID and ac(lo=4.0) == INVALID and ac(floor=0) == INVALID and ac(top=40) == INVALID
     assert ac(B=2000) == UNSUPPORTED and ac(cap=65) == UNSUPPORTED and ac(vocab=2_000_000) == UNSUPPORTED
+
+
+def test_attention_with_plan_validates_on_the_host(lib):
+    """Both halves' checks run before anything is enqueued; B = 0 is a valid no-op."""
+    INVALID, UNSUPPORTED = 1, 2
+    vp, ci, cl, cf, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_float, ctypes.c_size_t
+    null, one, two = vp(0), vp(16), vp(32)
+
+    class P(ctypes.Structure):
+        _fields_ = [(n, ctypes.c_int) for n in ("d_min", "d_max", "w_min", "w_max", "k", "n_max")]
+    lib.sage_tree_attention_with_plan.argtypes = ([vp] * 6 + [ci] * 5 + [vp, vp, ci, cl, cl, vp, vp, cf, vp, sz] +
+                                                  [vp, ci, ci, ctypes.POINTER(P)] + [vp] * 15)
+
+    def call(Q=one, dtype=1, B=0, Hq=64, Hkv=8, d=128, lens=one, ts=1024, hs=128, mask=one, nn=one, scale=0.088, ws=one,
+             slices=one, vocab=152064, k=10, prm=(3, 8, 2, 10, 10, 64), idx=one, next_nn=two, next_mask=two, next_par=two):
+        return lib.sage_tree_attention_with_plan(Q, one, one, one, one, one, dtype, B, Hq, Hkv, d, one, lens, 4096, ts, hs, mask,
+                                                 nn, scale, ws, 1 << 20, slices, vocab, k, ctypes.byref(P(*prm)), null, null, idx,
+                                                 null, null, null, null, next_nn, next_par, two, two, next_mask, null, null, null)
+    assert call() == 0
+    assert call(Q=null) == INVALID and call(lens=null) == INVALID and call(mask=null) == INVALID and call(nn=null) == INVALID
+    assert call(Hq=60) == INVALID and call(scale=0.0) == INVALID and call(dtype=7) == INVALID and call(hs=3) == INVALID
+    assert call(slices=null) == INVALID and call(idx=null) == INVALID and call(next_par=null) == INVALID
+    assert call(k=9) == INVALID and call(prm=(3, 40, 2, 10, 10, 64)) == INVALID and call(prm=(3, 8, 2, 10, 10, 65)) == INVALID
+    assert call(next_nn=one) == INVALID and call(next_mask=one) == INVALID      # the planned tree aliases the verified one
+    assert call(ws=null) == INVALID and call(ws=null, dtype=0) == 0             # fp32 needs no workspace
+    assert call(vocab=2_000_000) == UNSUPPORTED and call(B=70000) == UNSUPPORTED

@@ -104,3 +104,50 @@ def test_accept_from_slices_equals_separate_calls_and_oracle(gu, vocab, dtype, B
     for key in ("accept_len", "best_node", "path_nodes", "out_tokens"):
         np.testing.assert_array_equal(f[key], o4[key], err_msg=key)
     assert o4["accept_len"].max() >= 3
+
+
+@pytest.mark.parametrize("name,dtype,B,Hq,Hkv,d,lens,sizes,vocab,k,ldtype,prm", [
+    # the benchmark's shape: one sequence, planning in the slab past the attention's 32 slots
+    ("c2", "bf16", 1, 64, 8, 128, [4096], [13], 152064, 10, "bf16", wl.CONFIGS["c2"]["tree"]),
+    # a ragged batch: ranges of one tile list, planning workgroups of all sequences in one slab
+    ("batch", "bf16", 5, 64, 8, 128, [700, 0, 3000, 64, 1500], [8, 64, 1, 30, 47], 152064, 16, "bf16", wl.CONFIGS["c3"]["tree"]),
+    # more sequences than KV heads: several planning slabs, the last one partly empty
+    ("slabs", "bf16", 11, 28, 4, 128, [300] * 11, [5] * 11, 4100, 8, "f32", wl.CONFIGS["toy"]["tree"]),
+    # more sequences than the batched decomposition takes: one launch slot per sequence
+    ("many", "bf16", 70, 8, 2, 128, [90] * 70, [3] * 70, 2000, 4, "f32", dict(d_min=1, d_max=5, w_min=1, w_max=4, k=4, n_max=20)),
+    # candidate lists too long for the planning workgroup: two launches, same results
+    ("long", "bf16", 2, 64, 8, 128, [500, 200], [20, 9], 300000, 20, "bf16", dict(d_min=2, d_max=12, w_min=2, w_max=20, k=20, n_max=64)),
+    # fp32 attention: two launches, same results
+    ("toy", "f32", 2, 4, 1, 64, [256, 100], [16, 7], 1024, 8, "f32", wl.CONFIGS["toy"]["tree"]),
+])
+def test_attention_with_plan_equals_separate_calls_and_oracle(gu, name, dtype, B, Hq, Hkv, d, lens, sizes, vocab, k, ldtype, prm):
+    """sage_tree_attention_with_plan against sage_tree_attention and sage_build_tree_from_slices on the same inputs (every
+    output bit for bit) and against the oracle (attention to the tolerance of its dtype, top-k indices and tree exact)."""
+    from test_gpu_parity import TOL, tree_batch
+    g = wl.rng(len(name) * 1000 + B)
+    inp = wl.attention_inputs(4000 + B, B, Hq, Hkv, d, lens, dtype, pad_tokens=2)
+    mask, nn = tree_batch(g, B, sizes)
+    scales = g.uniform(0.3, 9.0, size=(B, 1)).astype(np.float32)
+    x = wl.to_storage(g.standard_normal((B, vocab), dtype=np.float32) * scales, ldtype)
+    dms = g.integers(prm["d_min"], prm["d_max"] + 1, size=B).astype(np.int32)
+    for d_max_seq in (None, dms):
+        O, a1, a2 = gu.gpu_attention_with_plan(inp, mask, nn, Hq, Hkv, d, x, k, prm, d_max_seq)
+        _, raw = gu.gpu_tree_attention(inp, mask, nn, Hq, Hkv, d)
+        same_bits(O, gu.to_host(raw), "O")
+        s1, s2 = gu.gpu_plan_from_slices(x, k, prm, d_max_seq)
+        for key in s1:
+            same_bits(a1[key], s1[key], key)
+        for key in s2:
+            same_bits(a2[key], s2[key], key)
+        ref = oracle.tree_attention(inp["Q"], inp["Kc"], inp["Vc"], inp["Kt"], inp["Vt"], inp["kv_start"], inp["kv_len"],
+                                    inp["kv_token_stride"], inp["kv_head_stride"], mask, nn, Hq, Hkv, d)
+        gu.assert_attention_close(gu.widen(O), ref, nn, TOL[dtype])
+        o1 = oracle.entropy_topk(x, k)
+        np.testing.assert_array_equal(a1["topk_idx"], o1["topk_idx"])
+        assert (np.abs(a1["alpha"] - o1["alpha"]) <= 1e-5).all()
+        o2 = oracle.build_tree(a1["topk_renorm"], a1["alpha"], prm, a1["topk_idx"], d_max_seq)
+        np.testing.assert_array_equal(a2["n_nodes"], o2["n_nodes"])
+        for key in ("parent", "depth", "rank", "anc_mask", "node_token"):
+            for b in range(B):
+                n = int(o2["n_nodes"][b])
+                np.testing.assert_array_equal(a2[key][b, :n], o2[key][b, :n], err_msg=f"{key}[{b}]")
