@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="c2", choices=["toy", "c2", "c3", "c4", "c5"])
     ap.add_argument("--slots", type=int, default=None, help="number of rotating input sets")
+    ap.add_argument("--no-carry", action="store_true",
+                    help="time the two-stream schedule instead of planning carried in the attention launch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the long-KV attention, closed-loop and output-projection measurements")
@@ -59,7 +61,7 @@ def parse():
 class Workload:
     """Device-resident synthetic inputs of one configuration plus every output/scratch buffer of a step."""
 
-    def __init__(self, name: str, slots: int | None, fused: bool = True, overlap: bool = False):
+    def __init__(self, name: str, slots: int | None, fused: bool = True, overlap: bool = False, carry: bool = False):
         import numpy as np
         import torch
         from paper_2602_00523_amd import sage, workloads as wl
@@ -164,6 +166,10 @@ class Workload:
         # that fork at the start of a step and join at its end.
         self.overlap = overlap
         self.plan_stream = torch.cuda.Stream() if overlap else None
+        # The other way to take planning off the step's chain of launches: its second half (merge + tree rule) rides in
+        # the launch of the first layer's attention (sage_tree_attention_with_plan), everything on one stream.
+        self.carry = carry
+        assert not (carry and (overlap or not fused))
         self.verify_first = True                     # enqueue the verification branch first (measured 2 % faster)
         self._prepare()
         torch.cuda.synchronize()
@@ -180,9 +186,17 @@ class Workload:
         else:
             self.c_a1 = [sg.prepare("sage_entropy_topk", self.draft[s], self.k, self.H, self.idx, self.prob, self.renorm,
                                     self.Hk, self.alpha, self.ws1, stream=pstream) for s in range(self.slots)]
-        self.c_a2, self.c_a3, self.c_a1t, self.c_a4 = [], [], [], []
+        self.c_a2, self.c_a3, self.c_a1t, self.c_a4, self.c_a3p = [], [], [], [], []
         for cur in range(2):
             t, nxt = self.tree[cur], self.tree[cur ^ 1]
+            if self.carry:
+                self.c_a3p.append([sg.prepare("sage_tree_attention_with_plan", self.Q[s], self.Kc[s % self.kv_slots][0],
+                                              self.Vc[s % self.kv_slots][0], self.Kt[s], self.Vt[s], self.O, self.kv_start,
+                                              self.kv_len, self.max_len, self.Hkv * self.d, self.d, t["anc_mask"], t["n_nodes"],
+                                              self.scale, self.ws3, self.ws1, V, self.prm, self.H, self.idx, self.prob,
+                                              self.renorm, self.Hk, self.alpha, nxt["n_nodes"], nxt["parent"], nxt["depth"],
+                                              nxt["rank"], nxt["anc_mask"], None, nxt["node_token"], stream=stream)
+                                   for s in range(self.slots)])
             if self.fused:
                 self.c_a2.append(sg.prepare("sage_build_tree_from_slices", self.ws1, V, self.prm, self.H, self.idx, self.prob,
                                             self.renorm, self.Hk, self.alpha, nxt["n_nodes"], nxt["parent"], nxt["depth"],
@@ -225,6 +239,16 @@ class Workload:
         if self.overlap:                             # fork: the plan branch starts where the main stream stands
             main = self.torch.cuda.current_stream()
             self.plan_stream.wait_stream(main)
+        if self.carry and events is None:
+            self.c_a1[s]()
+            self.c_a3p[cur][s]()                     # first layer's attention with the planning inside its launch
+            for call in self.c_a3[cur][s][1:]:
+                call()
+            self.c_a1t[cur][s]()
+            self.c_a4[cur]()
+            self.cur ^= 1
+            self.step_no += 1
+            return
         if not (self.overlap and self.verify_first):
             self.c_a1[s]()
             self.c_a2[cur]()
@@ -480,14 +504,17 @@ def long_kv_attention(names, launches=48):
     return out
 
 
-def closed_loop(name="c2", steps=512):
+def closed_loop(name="c2", steps=512, carry=True):
     """The step with its loop closed on the device: after acceptance the path's K/V rows are committed to the
     cache, the sequence length advances and the acceptance history adapts the maximum depth that the next tree may
     reach (Alg. 1 Phase 3; Sec. 3.3 adaptive history tracking).  One input-set cycle is captured as a HIP graph whose
     replays carry the state (cache, lengths, history, trees) forward; the final state of `steps` replayed steps is
-    checked against the same number of eager steps from the same start.  The top-k calls are the fused ones."""
+    checked against the same number of eager steps from the same start.  The top-k calls are the fused ones.  With `carry`
+    (bf16 workloads) the planning rides in the attention launch and everything runs on one stream; without it, planning
+    runs on a second stream beside the verification."""
     import torch
     w = Workload(name, None)
+    carry = carry and w.dtype == torch.bfloat16
     sg, dev = w.sage, "cuda:0"
     B, Hkv, d = w.B, w.Hkv, w.d
     cycle = w.slots if w.slots % 2 == 0 else 2 * w.slots
@@ -518,10 +545,16 @@ def closed_loop(name="c2", steps=512):
 
     def prep(stream):
         V = w.cfg["vocab"]
-        c = dict(a1=[sg.prepare("sage_entropy_topk_slices", w.draft[s], w.k, w.ws1, stream=plan_stream) for s in range(w.slots)],
-                 a2=[], a3=[], a1t=[], a4=[], commit=[])
+        c = dict(a1=[sg.prepare("sage_entropy_topk_slices", w.draft[s], w.k, w.ws1, stream=stream if carry else plan_stream)
+                     for s in range(w.slots)], a2=[], a3=[], a1t=[], a4=[], commit=[], a3p=[])
         for cur in range(2):
             t, nxt = w.tree[cur], w.tree[cur ^ 1]
+            if carry:
+                c["a3p"].append([sg.prepare("sage_tree_attention_with_plan", w.Q[s], Kc, Vc, w.Kt[s], w.Vt[s], w.O, kv_start,
+                                            kv_len, cap, Hkv * d, d, t["anc_mask"], t["n_nodes"], w.scale, ws3, w.ws1, V, w.prm,
+                                            w.H, w.idx, w.prob, w.renorm, w.Hk, w.alpha, nxt["n_nodes"], nxt["parent"],
+                                            nxt["depth"], nxt["rank"], nxt["anc_mask"], None, nxt["node_token"], stream=stream,
+                                            d_max_seq=d_max[cur]) for s in range(w.slots)])
             c["a2"].append(sg.prepare("sage_build_tree_from_slices", w.ws1, V, w.prm, w.H, w.idx, w.prob, w.renorm, w.Hk, w.alpha,
                                       nxt["n_nodes"], nxt["parent"], nxt["depth"], nxt["rank"], nxt["anc_mask"], None,
                                       nxt["node_token"], stream=plan_stream, d_max_seq=d_max[cur]))
@@ -542,6 +575,12 @@ def closed_loop(name="c2", steps=512):
 
     def step(c):
         s, cur = state["step"] % w.slots, state["cur"]
+        if carry:                                             # one stream: the plan (depth limit of the previous step) rides
+            c["a1"][s](); c["a3p"][cur][s](); c["a1t"][cur][s](); c["a4"][cur][s]()        # in the attention launch
+            acc_sum.add_(w.acc_len)
+            state["cur"] ^= 1
+            state["step"] += 1
+            return
         main = torch.cuda.current_stream()
         plan_stream.wait_stream(main)                         # fork: the plan uses the depth limit of the previous step
         c["a3"][cur][s](); c["a1t"][cur][s](); c["a4"][cur][s]()
@@ -589,9 +628,11 @@ def closed_loop(name="c2", steps=512):
     got = snapshot_state()
     verified = all(torch.equal(a, b) for a, b in zip(want, got))
     out = dict(workload=name, steps=steps, steps_per_s=steps / wall, ms_per_step=wall * 1e3 / steps,
-               calls_per_step="entropy_topk_slices, build_tree_from_slices (per-sequence depth), tree_attention, "
-                              "entropy_topk_slices (k=1), verify_accept_close_from_slices (acceptance, commit, advance, "
-                              "history); the first two on a second stream beside the rest",
+               calls_per_step=("entropy_topk_slices, tree_attention_with_plan (per-sequence depth), entropy_topk_slices (k=1), "
+                               "verify_accept_close_from_slices (acceptance, commit, advance, history); one stream") if carry else
+                              ("entropy_topk_slices, build_tree_from_slices (per-sequence depth), tree_attention, "
+                               "entropy_topk_slices (k=1), verify_accept_close_from_slices (acceptance, commit, advance, "
+                               "history); the first two on a second stream beside the rest"),
                kv_len_start=[int(x) for x in w.kv_lens], kv_len_end=[int(x) for x in kv_len.cpu().numpy()],
                mean_accept_len=float(acc_sum.sum().item()) / (steps * B),
                d_max_end=[int(x) for x in d_max[state["cur"]].cpu().numpy()],
@@ -823,6 +864,7 @@ def main():
     if not same_state(w, sep_state, sep_step_no):
         print("bench.py: the fused calls and the separate calls ended in different states", file=sys.stderr)
         sys.exit(4)
+    two_wall = carry_wall = None
     if args.no_overlap:
         wall, graphed = one_wall, not args.eager
     else:
@@ -836,6 +878,18 @@ def main():
             sys.exit(4)
         w.overlap = False                            # the measurement passes below run on one stream
         w._prepare(None)
+        two_wall, carry_wall = wall, None
+        if w.dtype == torch.bfloat16 and not args.no_carry:
+            # bf16 workloads: planning's second half inside the first layer's attention launch, one stream
+            wc = Workload(args.workload, args.slots, fused=True, carry=True)
+            carry_wall, carry_graphed = time_steps(wc, steps, warmup, not args.eager)
+            torch.cuda.synchronize()
+            if not same_state(wc, sep_state, sep_step_no):
+                print("bench.py: the step with planning carried in the attention launch ended in a different state", file=sys.stderr)
+                sys.exit(4)
+            del wc
+            torch.cuda.empty_cache()
+            wall, graphed = carry_wall, carry_graphed
     att_ms, n_log, eager_wall = time_attention_launches(w, min(steps, 2000))
     ms_per_step = wall * 1e3 / steps
     eager_att_us = sum(att_ms) / len(att_ms) * 1e3
@@ -866,12 +920,20 @@ def main():
             "kv_len": [int(x) for x in w.kv_lens], "layers": w.layers, "batch": w.B, "input_sets": w.slots,
             "mean_tree_nodes": mean_nodes, "tree_params": w.tree_prm,
             "launch_mode": "HIP graph replay of whole input-set cycles" if graphed else "eager launches",
-            "calls_per_step": "sage_entropy_topk_slices, sage_build_tree_from_slices, sage_tree_attention x layers, "
-                              "sage_entropy_topk_slices, sage_verify_accept_from_slices (final state equal, bit for bit, "
-                              "to the same steps through the five separate calls)",
-            "streams": ("planning (a1, a2) and verification (a3, a1', a4) of a step on two streams, forked and joined every step: "
+            "calls_per_step": ("sage_entropy_topk_slices, sage_tree_attention_with_plan (first layer; sage_tree_attention for "
+                               "the others), sage_entropy_topk_slices, sage_verify_accept_from_slices (final state equal, bit "
+                               "for bit, to the same steps through the five separate calls)") if carry_wall is not None else
+                              ("sage_entropy_topk_slices, sage_build_tree_from_slices, sage_tree_attention x layers, "
+                               "sage_entropy_topk_slices, sage_verify_accept_from_slices (final state equal, bit for bit, "
+                               "to the same steps through the five separate calls)"),
+            "streams": ("one stream; the merge + tree rule of the planning (a1, a2) ride in the launch of the attention (a3): the "
+                        "tree planned in a step is verified in the next one (Sec. 3.2 lookahead), so the two are independent")
+                       if carry_wall is not None else
+                       ("planning (a1, a2) and verification (a3, a1', a4) of a step on two streams, forked and joined every step: "
                         "the tree planned in a step is verified in the next one (Sec. 3.2 lookahead)") if not args.no_overlap
                        else "one stream",
+            "two_streams_steps_per_s": None if two_wall is None else steps / two_wall,
+            "two_streams_ms_per_step": None if two_wall is None else two_wall * 1e3 / steps,
             "one_stream_steps_per_s": steps / one_wall, "one_stream_ms_per_step": one_wall * 1e3 / steps,
             "separate_calls_steps_per_s": steps / sep_wall, "separate_calls_ms_per_step": sep_wall * 1e3 / steps,
             "eager_ms_per_step": eager_wall * 1e3 / len(n_log) * w.layers / w.layers},

@@ -310,8 +310,8 @@ int sage_verify_accept_close_from_slices(
  * batch: `slices` filled by sage_entropy_topk_slices with rows = B); the planned tree goes to
  * next_n_nodes / next_parent / next_depth / next_rank / next_anc_mask (/ next_cum_prob,
  * next_node_token, nullable), which must not be the arrays the attention reads (n_nodes,
- * anc_mask).  bf16 with at most 256 slices per draft row and at most 2048 candidates per row
- * in `slices` (vocab 152064 with k = 10: 149 slices, 1490 candidates): one launch (plus the
+ * anc_mask).  bf16 with at most 256 slices per draft row and at most 2432 candidates per row
+ * in `slices` (vocab 152064 with k = 16: 149 slices, 2384 candidates): one launch (plus the
  * split merge of the attention); otherwise (fp32, longer lists) the two calls are enqueued
  * one after the other with the same results.
  * Errors: those of the two calls, checked before anything is enqueued; INVALID_ARG when the

@@ -580,7 +580,7 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const int*
 // cache.  The two halves share nothing: the tree being planned is the next step's, not the one whose mask the
 // attention reads.  A step is a chain of dependent launches and planning is two of them; inside this launch it costs
 // no launch and, as long as it is shorter than the attention, no time.
-constexpr int PLAN_LDS_KEYS = 2048;
+constexpr int PLAN_LDS_KEYS = 2432;     // what the 160 KB of a CU leave beside the attention's stages (k = 16 at 152064 tokens: 2384)
 constexpr int PLAN_OWN = 4;              // slices per lane: up to 256 slices per draft row
 struct LentMergeShared {
     static constexpr int LDS_KEYS = PLAN_LDS_KEYS;

@@ -1,5 +1,6 @@
-"""Whole steps of the default benchmark workload, executed exactly as bench.py times them (fused calls, planning and
-verification on two streams, one HIP graph per cycle of input sets), checked against the CPU oracle call by call.
+"""Whole steps of the benchmark workloads, executed exactly as bench.py times them (fused calls; planning carried in the
+attention launch, or on a second stream beside verification; one HIP graph per cycle of input sets), checked against
+the CPU oracle call by call.
 
 bench.capture_cycle itself proves graph replay == eager execution bit for bit; this test adds that every eager step of
 that configuration equals the oracle on the same device inputs: top-k indices, trees, greedy tokens and acceptance
@@ -19,13 +20,16 @@ def close(a, b, tol=1e-5):
     return (np.abs(a - b) <= tol * np.maximum(np.abs(b), 1.0)).all()
 
 
-@pytest.mark.parametrize("name,slots", [("c2", 4), ("toy", 6), ("c4", 2)])
-def test_steps_in_the_timed_configuration_match_the_oracle(name, slots):
+@pytest.mark.parametrize("name,slots,schedule", [("c2", 4, "carried"), ("c4", 2, "carried"), ("toy", 6, "carried"),
+                                                 ("c2", 4, "two streams"), ("toy", 6, "two streams"), ("c4", 2, "two streams")])
+def test_steps_in_the_timed_configuration_match_the_oracle(name, slots, schedule):
     import torch
     import bench
     import gpu_utils as gu
 
-    w = bench.Workload(name, slots, fused=True, overlap=True)
+    # "carried": planning inside the attention launch (what bench.py times for bf16 workloads; the fp32 Toy takes the
+    # call's two-launch path); "two streams": planning beside verification on a second stream
+    w = bench.Workload(name, slots, fused=True, overlap=schedule == "two streams", carry=schedule == "carried")
     for _ in range(3):                                   # leave the start-up tree behind
         w.step()
     graph, cycle = bench.capture_cycle(w)
