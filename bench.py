@@ -889,7 +889,10 @@ def main():
                 sys.exit(4)
             del wc
             torch.cuda.empty_cache()
-            wall, graphed = carry_wall, carry_graphed
+            # the timed configuration is the faster of the two (carrying wins unless the attention's own workgroups fill
+            # every CU, where the planning workgroup has to queue behind one of them); the other one is reported beside it
+            if carry_wall < two_wall:
+                wall, graphed = carry_wall, carry_graphed
     att_ms, n_log, eager_wall = time_attention_launches(w, min(steps, 2000))
     ms_per_step = wall * 1e3 / steps
     eager_att_us = sum(att_ms) / len(att_ms) * 1e3
@@ -906,6 +909,7 @@ def main():
     achieved = per_launch_bytes / (att_avg_ms * 1e-3) / 1e9
     mean_nodes = float(sum(n.sum() for n in n_log) / len(n_log))
 
+    carried = carry_wall is not None and wall == carry_wall
     result = {
         "metric": "tree-verify steps/sec + attention HBM GB/s (% of peak), 72B shape, 1 MI355X",
         "value": steps / wall, "unit": "steps/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
@@ -922,18 +926,20 @@ def main():
             "launch_mode": "HIP graph replay of whole input-set cycles" if graphed else "eager launches",
             "calls_per_step": ("sage_entropy_topk_slices, sage_tree_attention_with_plan (first layer; sage_tree_attention for "
                                "the others), sage_entropy_topk_slices, sage_verify_accept_from_slices (final state equal, bit "
-                               "for bit, to the same steps through the five separate calls)") if carry_wall is not None else
+                               "for bit, to the same steps through the five separate calls)") if carried else
                               ("sage_entropy_topk_slices, sage_build_tree_from_slices, sage_tree_attention x layers, "
                                "sage_entropy_topk_slices, sage_verify_accept_from_slices (final state equal, bit for bit, "
                                "to the same steps through the five separate calls)"),
             "streams": ("one stream; the merge + tree rule of the planning (a1, a2) ride in the launch of the attention (a3): the "
                         "tree planned in a step is verified in the next one (Sec. 3.2 lookahead), so the two are independent")
-                       if carry_wall is not None else
+                       if carried else
                        ("planning (a1, a2) and verification (a3, a1', a4) of a step on two streams, forked and joined every step: "
                         "the tree planned in a step is verified in the next one (Sec. 3.2 lookahead)") if not args.no_overlap
                        else "one stream",
             "two_streams_steps_per_s": None if two_wall is None else steps / two_wall,
             "two_streams_ms_per_step": None if two_wall is None else two_wall * 1e3 / steps,
+            "plan_in_attention_launch_steps_per_s": None if carry_wall is None else steps / carry_wall,
+            "plan_in_attention_launch_ms_per_step": None if carry_wall is None else carry_wall * 1e3 / steps,
             "one_stream_steps_per_s": steps / one_wall, "one_stream_ms_per_step": one_wall * 1e3 / steps,
             "separate_calls_steps_per_s": steps / sep_wall, "separate_calls_ms_per_step": sep_wall * 1e3 / steps,
             "eager_ms_per_step": eager_wall * 1e3 / len(n_log) * w.layers / w.layers},
