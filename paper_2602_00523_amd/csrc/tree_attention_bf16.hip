@@ -163,7 +163,7 @@ __device__ __forceinline__ float cross_half_sum(float v) {
 template <bool BATCH>
 __device__ __forceinline__ void attention_workgroup(const int* __restrict__ kv_len_arg, const int* __restrict__ n_nodes_arg,
                                                     const int64_t* __restrict__ kv_start_arg, int nslot_arg, int min_tps_arg,
-                                                    int G_arg, const Params& prm) {
+                                                    int G_arg, const Params& prm, const int first_slab) {
     // one LDS object per stage and operand (see header)
     __shared__ __align__(1024) unsigned char sK0[K_STAGE_B];
     __shared__ __align__(1024) unsigned char sK1[K_STAGE_B];
@@ -186,7 +186,7 @@ __device__ __forceinline__ void attention_workgroup(const int* __restrict__ kv_l
     // grid = (KV head, slot or range, sequence): the KV head is the fastest index of the launch order, and no index
     // costs a division
     const int g = blockIdx.x;
-    const int id = blockIdx.y;
+    const int id = static_cast<int>(blockIdx.y) - first_slab;   // slabs before first_slab belong to somebody else
     const int inv_G = (65536 + G_arg - 1) / G_arg;           // (m * inv_G) >> 16 == m / G for the rows of a KV head
 
     // One pass over tiles [t_begin, t_end) of sequence b for column group cg; the un-normalised partial goes to out_base.
@@ -571,15 +571,18 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const int*
                                                                       const int* __restrict__ n_nodes_arg,
                                                                       const int64_t* __restrict__ kv_start_arg, int nslot_arg,
                                                                       int min_tps_arg, int G_arg, const Params prm) {
-    attention_workgroup<BATCH>(kv_len_arg, n_nodes_arg, kv_start_arg, nslot_arg, min_tps_arg, G_arg, prm);
+    attention_workgroup<BATCH>(kv_len_arg, n_nodes_arg, kv_start_arg, nslot_arg, min_tps_arg, G_arg, prm, 0);
 }
 
 // The same launch carrying the planning of the next tree along (sage_tree_attention_with_plan): the grid has extra
-// slabs of workgroups past the attention's own (blockIdx.y >= first_plan_slab), one workgroup of which per sequence runs
+// slabs of workgroups ahead of the attention's own (blockIdx.y < plan_slabs), one workgroup of which per sequence runs
 // sage_build_tree_from_slices' work for that sequence, with LDS of its own, while the attention workgroups stream the
 // cache.  The two halves share nothing: the tree being planned is the next step's, not the one whose mask the
 // attention reads.  A step is a chain of dependent launches and planning is two of them; inside this launch it costs
-// no launch and, as long as it is shorter than the attention, no time.
+// no launch and, as long as it is shorter than the attention, no time.  The planning slabs come first in launch order:
+// when the attention's own workgroups fill every CU, the one that has to wait for a free CU is then the attention's
+// last (a sequence's final split, seldom a full one), and it waits for the short planning workgroup, not the other
+// way round.
 constexpr int PLAN_LDS_KEYS = 2432;     // what the 160 KB of a CU leave beside the attention's stages (k = 16 at 152064 tokens: 2384)
 constexpr int PLAN_OWN = 4;              // slices per lane: up to 256 slices per draft row
 struct LentMergeShared {
@@ -593,21 +596,21 @@ template <bool BATCH>
 __global__ __launch_bounds__(THREADS) void tree_attention_plan_kernel(const int* __restrict__ kv_len_arg,
                                                                       const int* __restrict__ n_nodes_arg,
                                                                       const int64_t* __restrict__ kv_start_arg, int nslot_arg,
-                                                                      int min_tps_arg, int G_arg, int first_plan_slab,
+                                                                      int min_tps_arg, int G_arg, int plan_slabs,
                                                                       const Params prm, const sage::PlanArgs pl) {
-    if (static_cast<int>(blockIdx.y) >= first_plan_slab) {  // workgroup-uniform
+    if (static_cast<int>(blockIdx.y) < plan_slabs) {        // workgroup-uniform
         __shared__ uint64_t p_keys[PLAN_LDS_KEYS];
         __shared__ sage::topk::UnitStats p_stats[64 * PLAN_OWN];
         __shared__ float p_row[2];
         // one sequence per launch slot: the slab's first workgroup of sequence blockIdx.z; batches: slab workgroups in turn
-        const int b = BATCH ? (static_cast<int>(blockIdx.y) - first_plan_slab) * static_cast<int>(gridDim.x) + static_cast<int>(blockIdx.x)
+        const int b = BATCH ? static_cast<int>(blockIdx.y * gridDim.x + blockIdx.x)
                             : (blockIdx.x == 0 ? static_cast<int>(blockIdx.z) : prm.B);
         if (b >= prm.B) return;
         LentMergeShared sh{p_keys, p_stats, p_row[0], p_row[1]};
         sage::plan_sequence<PLAN_OWN, THREADS>(b, pl, sh);
         return;
     }
-    attention_workgroup<BATCH>(kv_len_arg, n_nodes_arg, kv_start_arg, nslot_arg, min_tps_arg, G_arg, prm);
+    attention_workgroup<BATCH>(kv_len_arg, n_nodes_arg, kv_start_arg, nslot_arg, min_tps_arg, G_arg, prm, plan_slabs);
 }
 
 // Merge the splits of one (sequence, node, query head) in split order and write bf16.  One wave per row:
@@ -813,16 +816,16 @@ int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const voi
     const int own_slabs = sh.batch ? p.nrange : p.nslot;
     const dim3 block(THREADS);
     if (plan) {
-        // planning workgroups in slabs of their own past the attention's: one slab whose first workgroup of every
+        // planning workgroups in slabs of their own ahead of the attention's: one slab whose first workgroup of every
         // sequence plans (one sequence per launch slot), or as many slabs as B workgroups need (batches)
         const int plan_slabs = sh.batch ? (B + Hkv - 1) / Hkv : 1;
-        const dim3 grid(Hkv, own_slabs + plan_slabs, sh.batch ? 1 : B);
+        const dim3 grid(Hkv, plan_slabs + own_slabs, sh.batch ? 1 : B);
         if (sh.batch)
             hipLaunchKernelGGL(tree_attention_plan_kernel<true>, grid, block, 0, stream, kv_len, n_nodes, kv_start, p.nslot,
-                               p.min_tiles_per_split, G, own_slabs, p, *plan);
+                               p.min_tiles_per_split, G, plan_slabs, p, *plan);
         else
             hipLaunchKernelGGL(tree_attention_plan_kernel<false>, grid, block, 0, stream, kv_len, n_nodes, kv_start, p.nslot,
-                               p.min_tiles_per_split, G, own_slabs, p, *plan);
+                               p.min_tiles_per_split, G, plan_slabs, p, *plan);
     } else {
         const dim3 grid(Hkv, own_slabs, sh.batch ? 1 : B);
         if (sh.batch)
