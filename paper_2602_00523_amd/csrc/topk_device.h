@@ -58,7 +58,7 @@ __device__ __forceinline__ void combine_unit_stats(const UnitStats (&u)[OWN], in
 }
 
 // LDS of one merging workgroup.  merge_row takes any type with these members (keys, stats, row_m, row_Z; LDS_KEYS =
-// how many keys fit), so a kernel with LDS of its own can lend some of it instead.
+// how many keys fit), so a kernel with another LDS budget can bring a smaller one.
 template <int OWN> struct MergeShared {
     static constexpr int LDS_KEYS = MERGE_LDS_KEYS;
     uint64_t keys[MERGE_LDS_KEYS];

@@ -585,7 +585,7 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const int*
 // way round.
 constexpr int PLAN_LDS_KEYS = 2432;     // what the 160 KB of a CU leave beside the attention's stages (k = 16 at 152064 tokens: 2384)
 constexpr int PLAN_OWN = 4;              // slices per lane: up to 256 slices per draft row
-struct LentMergeShared {
+struct PlanShared {
     static constexpr int LDS_KEYS = PLAN_LDS_KEYS;
     uint64_t* keys;
     sage::topk::UnitStats* stats;
@@ -606,7 +606,7 @@ __global__ __launch_bounds__(THREADS) void tree_attention_plan_kernel(const int*
         const int b = BATCH ? static_cast<int>(blockIdx.y * gridDim.x + blockIdx.x)
                             : (blockIdx.x == 0 ? static_cast<int>(blockIdx.z) : prm.B);
         if (b >= prm.B) return;
-        LentMergeShared sh{p_keys, p_stats, p_row[0], p_row[1]};
+        PlanShared sh{p_keys, p_stats, p_row[0], p_row[1]};
         sage::plan_sequence<PLAN_OWN, THREADS>(b, pl, sh);
         return;
     }
