@@ -197,9 +197,13 @@ __device__ __forceinline__ void attention_workgroup(const int* __restrict__ kv_l
     // ---- wave roles: waves w and w+4 share column tile w; each takes one 32-token half of every tile
     const int group_rows = min(ROWS_PER_WG, seq_rows - cg * ROWS_PER_WG);
     const int group_ct = (group_rows + 31) / 32;             // 1..4 column tiles in this group
-    const int ct = wave & 3;
-    const int sub_lo = wave >> 2;
-    const bool wave_active = ct < group_ct;
+    // Waves w and w + 4 run on the same SIMD.  With three or four column tiles every SIMD gets one tile's two halves; with
+    // one or two (trees of up to 64 / G nodes) the four (tile, half) units go to waves 0..3, one per SIMD, instead of
+    // two each on SIMDs 0 and 1, which halves the time of a tile step.  Which wave computes a unit changes no result.
+    const bool narrow = group_ct <= 2;
+    const int ct = narrow ? (wave & 1) : (wave & 3);
+    const int sub_lo = narrow ? ((wave >> 1) & 1) : (wave >> 2);
+    const bool wave_active = ct < group_ct && (!narrow || wave < 4);
 
     // ---- this lane's query row
     const int m_local = ct * 32 + r32;                       // row within the group
