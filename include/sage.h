@@ -325,6 +325,29 @@ int sage_tree_attention_with_plan(
     float* topk_prob, float* topk_renorm, float* topk_entropy, float* alpha, int* next_n_nodes, int* next_parent,
     int* next_depth, int* next_rank, uint64_t* next_anc_mask, float* next_cum_prob, int* next_node_token, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * sage_tree_attention_static -- sage_tree_attention for callers that cannot allocate: code
+ * under HIP graph capture, serving loops and harnesses that must not call hipMalloc (or any
+ * allocating routine) and so cannot provide a workspace sized per call.  Arguments, results
+ * (bit-identical) and errors are those of sage_tree_attention without its workspace pair: the
+ * split partials live in a device array inside the library,
+ * sage_tree_attention_static_scratch_bytes() = 40 MiB per GPU the library runs on, held until
+ * the process ends.  The call allocates and frees nothing.
+ * Limit: a call whose sage_tree_attention_workspace_bytes(...) exceeds that size returns
+ * SAGE_WORKSPACE_TOO_SMALL and enqueues nothing (72B shape: one sequence of any length fits;
+ * a batch of 8 fits; a batch of 16 does not).  fp32 calls use no scratch at all.
+ * All calls on one GPU share the one array: two calls may not overlap in time on a GPU
+ * (different streams without ordering, or two host threads), or their partials race.  Calls
+ * ordered on one stream are safe; nothing needs clearing between calls.
+ * Further error: LAUNCH_FAILED when the array's device address cannot be obtained.
+ */
+size_t sage_tree_attention_static_scratch_bytes(void);
+int sage_tree_attention_static(const void* Q, const void* Kc, const void* Vc, const void* Kt, const void* Vt, void* O,
+                               int dtype, int B, int Hq, int Hkv, int d,
+                               const int64_t* kv_start, const int* kv_len, int max_kv_len,
+                               long kv_token_stride, long kv_head_stride,
+                               const uint64_t* anc_mask, const int* n_nodes, float scale, void* stream);
+
 /* Library build identification (host): returns a static string naming the target architecture. */
 const char* sage_build_info(void);
 

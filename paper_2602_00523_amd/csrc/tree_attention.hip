@@ -1,6 +1,8 @@
 // sage_tree_attention entry point: argument checks and dispatch to the fp32 FMA kernel or the bf16 MFMA kernel.
 // Operation: attention of the verify pass under the tree mask (Sec. 2.2; Alg. 1 Phase 2).
 // sage_tree_attention_with_plan: the same, with the planning of the next tree (Sec. 3.1-3.2) riding in the launch.
+#include <mutex>
+
 #include "plan_device.h"
 #include "sage_internal.h"
 
@@ -51,6 +53,59 @@ extern "C" int sage_tree_attention(const void* Q, const void* Kc, const void* Vc
     if (!workspace) return SAGE_INVALID_ARG;
     return sage::tree_attention_bf16(Q, Kc, Vc, Kt, Vt, O, B, Hq, Hkv, d, kv_start, kv_len, max_kv_len, kv_token_stride,
                                      kv_head_stride, anc_mask, n_nodes, scale, workspace, workspace_bytes, s, nullptr);
+}
+
+// ---- sage_tree_attention_static: the same call for callers that cannot hand over a workspace they allocated
+// (code under graph capture, serving loops that must not call the allocator).  The split partials go to a
+// file-scope device array instead.  In host code the array's name only stands for the symbol: its device address
+// is looked up once per device and every use below goes through that address.
+#define SAGE_STATIC_SCRATCH_BYTES (40u << 20)
+static __device__ __align__(256) unsigned char scratch[SAGE_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_lock;
+void* scratch_ptr[MAX_DEVICES];          // per device: every GPU holds its own copy of the array at its own address
+
+// Device address of `scratch` on the current device (looked up on the first call there); nullptr on failure.
+void* scratch_of_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> hold(scratch_lock);
+    if (!scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        scratch_ptr[dev] = p;
+    }
+    return scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" size_t sage_tree_attention_static_scratch_bytes(void) { return SAGE_STATIC_SCRATCH_BYTES; }
+
+extern "C" int sage_tree_attention_static(const void* Q, const void* Kc, const void* Vc, const void* Kt, const void* Vt, void* O,
+                                          int dtype, int B, int Hq, int Hkv, int d, const int64_t* kv_start,
+                                          const int* kv_len, int max_kv_len, long kv_token_stride, long kv_head_stride,
+                                          const uint64_t* anc_mask, const int* n_nodes, float scale, void* stream) {
+    const int rc = check_attention_args(Q, Kc, Vc, Kt, Vt, O, dtype, B, Hq, Hkv, d, kv_start, kv_len, max_kv_len, kv_token_stride,
+                                        kv_head_stride, anc_mask, n_nodes, scale);
+    if (rc != SAGE_OK || B == 0) return rc;
+    hipStream_t s = sage::as_stream(stream);
+    if (dtype == SAGE_F32)               // no scratch in this path
+        return sage::tree_attention_f32(Q, Kc, Vc, Kt, Vt, O, B, Hq, Hkv, d, kv_start, kv_len, kv_token_stride,
+                                        kv_head_stride, anc_mask, n_nodes, scale, s);
+    // sizes whose partials do not fit the array are refused, nothing is enqueued
+    if (sage_tree_attention_workspace_bytes(dtype, B, Hq, Hkv, d, max_kv_len) > SAGE_STATIC_SCRATCH_BYTES)
+        return SAGE_WORKSPACE_TOO_SMALL;
+    void* ws = scratch_of_current_device();
+    if (!ws) return SAGE_LAUNCH_FAILED;
+    // Every partial slot the merge reads is written by the main kernel of the same call first, so nothing of an earlier
+    // call's contents has to be cleared.
+    return sage::tree_attention_bf16(Q, Kc, Vc, Kt, Vt, O, B, Hq, Hkv, d, kv_start, kv_len, max_kv_len, kv_token_stride,
+                                     kv_head_stride, anc_mask, n_nodes, scale, ws, SAGE_STATIC_SCRATCH_BYTES, s, nullptr);
 }
 
 extern "C" int sage_tree_attention_with_plan(

@@ -50,6 +50,11 @@ def lib():
         L.sage_tree_attention.restype = _ci
         L.sage_tree_attention.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _cl, _cl,
                                           _vp, _vp, _cf, _vp, _sz, _vp]
+        L.sage_tree_attention_static_scratch_bytes.restype = _sz
+        L.sage_tree_attention_static_scratch_bytes.argtypes = []
+        L.sage_tree_attention_static.restype = _ci
+        L.sage_tree_attention_static.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _cl, _cl,
+                                                 _vp, _vp, _cf, _vp]
         L.sage_tree_attention_with_plan.restype = _ci
         L.sage_tree_attention_with_plan.argtypes = (
             [_vp, _vp, _vp, _vp, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _cl, _cl, _vp, _vp, _cf, _vp, _sz]
@@ -154,6 +159,13 @@ def _args_tree_attention(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_
             _ptr(workspace), _nbytes(workspace), _stream(stream)]
 
 
+def _args_tree_attention_static(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_token_stride, kv_head_stride, anc_mask,
+                                n_nodes, scale, stream=None):
+    att = _args_tree_attention(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_token_stride, kv_head_stride, anc_mask,
+                               n_nodes, scale, None, stream)
+    return att[:-3] + att[-1:]                         # no workspace pair
+
+
 def _args_tree_attention_with_plan(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_token_stride, kv_head_stride, anc_mask,
                                    n_nodes, scale, workspace, slices, vocab, params: TreeParams, entropy, topk_idx, topk_prob,
                                    topk_renorm, topk_entropy, alpha, next_n_nodes, next_parent, next_depth, next_rank,
@@ -252,7 +264,8 @@ _MARSHAL = {"sage_close_step": _args_close_step,
             "sage_build_tree_from_slices": _args_build_tree_from_slices,
             "sage_verify_accept_from_slices": _args_verify_accept_from_slices,
             "sage_entropy_topk": _args_entropy_topk, "sage_build_tree": _args_build_tree,
-            "sage_tree_attention": _args_tree_attention, "sage_verify_accept": _args_verify_accept,
+            "sage_tree_attention": _args_tree_attention, "sage_tree_attention_static": _args_tree_attention_static,
+            "sage_verify_accept": _args_verify_accept,
             "sage_commit_path": _args_commit_path, "sage_advance_kv_len": _args_advance_kv_len,
             "sage_update_history": _args_update_history, "sage_lm_head_topk": _args_lm_head_topk}
 
@@ -267,6 +280,14 @@ def sage_build_tree(*a, **kw):
 
 def sage_tree_attention(*a, **kw):
     _check("sage_tree_attention", lib().sage_tree_attention(*_args_tree_attention(*a, **kw)))
+
+
+def sage_tree_attention_static(*a, **kw):
+    _check("sage_tree_attention_static", lib().sage_tree_attention_static(*_args_tree_attention_static(*a, **kw)))
+
+
+def sage_tree_attention_static_scratch_bytes() -> int:
+    return int(lib().sage_tree_attention_static_scratch_bytes())
 
 
 def sage_tree_attention_with_plan(*a, **kw):

@@ -1,0 +1,97 @@
+"""sage_tree_attention_static (the entry point for callers that cannot allocate) against sage_tree_attention:
+same kernels, partials in the library's own device array instead of a caller workspace, so the outputs must be
+identical bit for bit.  Two calls in a row share the array, the second with a smaller input (the first call's
+partials are still lying in it); a batch exercises the batched decomposition; sizes past the array are refused.
+"""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2602_00523_amd import sage
+from paper_2602_00523_amd import workloads as wl
+
+import gpu_utils as gu
+from helpers import pad_tree, random_parents
+
+pytestmark = pytest.mark.gpu
+Hq, Hkv, d = 64, 8, 128
+
+
+def _case(seed, kv_lens, n_nodes):
+    B = len(kv_lens)
+    inp = wl.attention_inputs(seed, B, Hq, Hkv, d, kv_lens, "bf16")
+    rng = np.random.default_rng(seed)
+    mask = np.zeros((B, 64), np.uint64)
+    for b in range(B):
+        mask[b] = pad_tree(random_parents(rng, n_nodes[b], 0.4))[2][0]
+    dev = {k: gu.to_dev(inp[k]) for k in ("Q", "Kc", "Vc", "Kt", "Vt")}
+    dev["kv_start"] = gu.to_dev(np.asarray(inp["kv_start"], np.int64))
+    dev["kv_len"] = gu.to_dev(np.asarray(inp["kv_len"], np.int32))
+    dev["mask"] = gu.to_dev(mask)
+    dev["nn"] = gu.to_dev(np.asarray(n_nodes, np.int32))
+    dev["max_len"] = int(max(kv_lens))
+    dev["ts"], dev["hs"] = inp["kv_token_stride"], inp["kv_head_stride"]
+    return dev
+
+
+def _with_workspace(c):
+    O = torch.full_like(c["Q"], 7.0)
+    B = c["Q"].shape[0]
+    ws = torch.empty(sage.sage_tree_attention_workspace_bytes(sage.BF16, B, Hq, Hkv, d, c["max_len"]), device=gu.DEV,
+                     dtype=torch.uint8)
+    sage.sage_tree_attention(c["Q"], c["Kc"], c["Vc"], c["Kt"], c["Vt"], O, c["kv_start"], c["kv_len"], c["max_len"], c["ts"],
+                             c["hs"], c["mask"], c["nn"], 1.0 / np.sqrt(d), ws)
+    return O
+
+
+def _static(c):
+    O = torch.full_like(c["Q"], 7.0)
+    sage.sage_tree_attention_static(c["Q"], c["Kc"], c["Vc"], c["Kt"], c["Vt"], O, c["kv_start"], c["kv_len"], c["max_len"],
+                                    c["ts"], c["hs"], c["mask"], c["nn"], 1.0 / np.sqrt(d))
+    return O
+
+
+def test_static_scratch_matches_workspace_call_twice_in_a_row():
+    big = _case(11, [9000], [40])
+    small = _case(12, [700], [9])
+    batch = _case(13, [3000, 1200, 2100], [30, 5, 17])
+    refs = [_with_workspace(c) for c in (big, small, batch)]
+    torch.cuda.synchronize()
+    # all static calls are enqueued before anything is read back: the second and third find the earlier partials in place
+    outs = [_static(c) for c in (big, small, batch)]
+    outs.append(_static(small))
+    torch.cuda.synchronize()
+    for got, ref in zip(outs, refs + [refs[1]]):
+        assert torch.equal(got.view(torch.int16), ref.view(torch.int16))
+    # live rows were written, rows of nodes past n_nodes kept the fill
+    assert float(outs[1][0, 9:].float().min()) == 7.0 and float(outs[1][0, :9].float().abs().max()) != 7.0
+
+
+def test_static_scratch_limit_and_fp32():
+    L = sage.lib()
+    limit = sage.sage_tree_attention_static_scratch_bytes()
+    assert limit == 40 << 20
+    assert sage.sage_tree_attention_workspace_bytes(sage.BF16, 8, Hq, Hkv, d, 12288) <= limit
+    too_many = 16
+    assert sage.sage_tree_attention_workspace_bytes(sage.BF16, too_many, Hq, Hkv, d, 12288) > limit
+    c = _case(14, [300] * too_many, [3] * too_many)
+    with pytest.raises(sage.SageError) as e:
+        _static(c)
+    assert e.value.code == 3
+    # fp32 goes through without scratch and equals the workspace call
+    inp = wl.attention_inputs(15, 1, 4, 1, 64, [256], "f32")
+    mask = pad_tree(random_parents(np.random.default_rng(15), 12, 0.3))[2]
+    t = {k: gu.to_dev(inp[k]) for k in ("Q", "Kc", "Vc", "Kt", "Vt")}
+    st, ln = gu.to_dev(np.asarray(inp["kv_start"], np.int64)), gu.to_dev(np.asarray(inp["kv_len"], np.int32))
+    m, nn = gu.to_dev(mask), gu.to_dev(np.asarray([12], np.int32))
+    O1, O2 = torch.zeros_like(t["Q"]), torch.zeros_like(t["Q"])
+    ws = torch.empty(256, device=gu.DEV, dtype=torch.uint8)
+    sage.sage_tree_attention(t["Q"], t["Kc"], t["Vc"], t["Kt"], t["Vt"], O1, st, ln, 256, inp["kv_token_stride"],
+                             inp["kv_head_stride"], m, nn, 0.125, ws)
+    sage.sage_tree_attention_static(t["Q"], t["Kc"], t["Vc"], t["Kt"], t["Vt"], O2, st, ln, 256, inp["kv_token_stride"],
+                                    inp["kv_head_stride"], m, nn, 0.125)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O2)
+    assert isinstance(L.sage_tree_attention_static, ctypes._CFuncPtr)
