@@ -310,7 +310,7 @@ int sage_verify_accept_close_from_slices(
  * batch: `slices` filled by sage_entropy_topk_slices with rows = B); the planned tree goes to
  * next_n_nodes / next_parent / next_depth / next_rank / next_anc_mask (/ next_cum_prob,
  * next_node_token, nullable), which must not be the arrays the attention reads (n_nodes,
- * anc_mask).  bf16 with at most 256 slices per draft row and at most 2432 candidates per row
+ * anc_mask).  bf16 with at most 256 slices per draft row and at most 2400 candidates per row
  * in `slices` (vocab 152064 with k = 16: 149 slices, 2384 candidates): one launch (plus the
  * split merge of the attention); otherwise (fp32, longer lists) the two calls are enqueued
  * one after the other with the same results.
@@ -335,7 +335,7 @@ int sage_tree_attention_with_plan(
  * the process ends.  The call allocates and frees nothing.
  * Limit: a call whose sage_tree_attention_workspace_bytes(...) exceeds that size returns
  * SAGE_WORKSPACE_TOO_SMALL and enqueues nothing (72B shape: one sequence of any length fits;
- * a batch of 8 fits; a batch of 16 does not).  fp32 calls use no scratch at all.
+ * a batch of 16 fits; a batch of 24 does not).  fp32 calls use no scratch at all.
  * All calls on one GPU share the one array: two calls may not overlap in time on a GPU
  * (different streams without ordering, or two host threads), or their partials race.  Calls
  * ordered on one stream are safe; nothing needs clearing between calls.

@@ -40,6 +40,20 @@ __device__ __forceinline__ void lds_direct_load16(const unsigned char* gptr, __a
                  : "v"(gptr), "s"(m0v)
                  : "m0", "memory");
 }
+// The same load with the address split into a wave-uniform base (scalar register pair) and a 32-bit per-lane byte
+// offset: a stream whose per-lane offsets repeat from tile to tile then advances with scalar arithmetic only.
+__device__ __forceinline__ void lds_direct_load16(const unsigned char* sbase, unsigned voff,
+                                                  __attribute__((address_space(3))) unsigned char* lds) {
+    const unsigned m0v = static_cast<unsigned>(reinterpret_cast<uintptr_t>(lds));
+    // the base is uniform by contract; said to the compiler, which otherwise may hand the asm a vector register pair
+    const uintptr_t bv = reinterpret_cast<uintptr_t>(sbase);
+    const uintptr_t base = (static_cast<uintptr_t>(static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(bv >> 32)))) << 32) |
+                           static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(bv)));
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(voff), "s"(base), "s"(m0v)
+                 : "m0", "memory");
+}
 // The 4-byte form: lane l lands at lds + 4 l.
 __device__ __forceinline__ void lds_direct_load4(const unsigned char* gptr, __attribute__((address_space(3))) unsigned char* lds) {
     const unsigned m0v = static_cast<unsigned>(reinterpret_cast<uintptr_t>(lds));

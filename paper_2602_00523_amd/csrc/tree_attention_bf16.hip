@@ -2,19 +2,30 @@
 // verify pass (Sec. 2.2 tree mask; Alg. 1 Phase 2) against a long KV cache plus the tree's own keys.
 //
 // Formulation.  All query rows that share a KV head (node i, head-in-group hg -> row m = i*G + hg, up to 512
-// rows) are processed together so each K/V byte is fetched from HBM once.  Everything is computed transposed:
+// rows at G = 8) are processed together so each K/V byte is fetched from HBM once.  Everything is computed transposed:
 //   S^T = K Q^T   (tokens x rows):  A operand = K rows as stored in the cache (16-byte LDS reads),
 //                                   B operand = Q rows, brought in through LDS once and held in registers
 //                                   for the whole kernel;
 //   O^T = V^T P^T (dims x rows):    A operand = V^T, read from row-major V in LDS with the transposing
 //                                   64-bit LDS read of gfx950, B operand = P^T.
-// In the 32x32 MFMA accumulator layout a lane owns ONE query row (column lane%32) and 16 tokens of it, so the
-// softmax max/sum are in-register reductions plus one cross-half lane swap, the rescale factor is a per-lane
-// scalar, and the accumulator registers of S^T are, as they stand, the B operand of the PV product (the token
-// order inside a 16-token k-block is whatever the accumulator layout says; the V^T reads follow that order).
-// The running maximum is only raised when a score exceeds it by more than 2^8 in the exp2 domain, so the
-// accumulator is rescaled a handful of times per kernel instead of once per tile; the final normalisation
-// uses the same reference maximum for numerator and denominator, so the result is unchanged.
+// In the 32x32 MFMA accumulator layout a lane owns ONE query row (column lane%32) and 16 tokens of it per 32-token
+// half tile, so the softmax sums are in-register, the rescale factor is a per-lane scalar, and the accumulator
+// registers of S^T are, as they stand, the B operand of the PV product (the token order inside a 16-token k-block
+// is whatever the accumulator layout says; the V^T reads follow that order).
+//
+// Decomposition (decided on the device from n_nodes/kv_len, so no host round trip): a workgroup of 8 waves owns
+// (sequence, KV head, group of up to 8 column tiles = 256 query rows, KV split); wave w owns column tile w (32 query
+// rows) and processes whole 64-token tiles for it, so nothing is shared between waves but the K/V stages, and a wave's
+// partial result is complete for its rows.  What bounds this kernel is how many bytes per second ONE compute unit can
+// pull in (about 24-32 GB/s when the data comes from HBM, the latency of a miss times what a CU can keep in flight;
+// every workgroup that shares a tile through L2 still waits out the first one's miss), not the matrix pipe: so a tile
+// that has been brought into LDS must serve as many query rows as registers allow, and a tree of up to 32 nodes (G = 8)
+// is one group.  With 2..64 sequences the splits are equal ranges of one list of all sequences' tiles, so ragged lengths
+// leave no CU idle (see the kernel).  The KV head is the fastest grid index, so in launch order the workgroups of one KV
+// head are congruent modulo the KV-head count, which with 8 KV heads pins a head to one XCD and its L2: the two groups
+// of a 64-node tree re-read K/V from that L2, not from HBM.  Each workgroup writes an un-normalised partial (max, sum
+// in fp32, O^T in bf16); a second kernel merges the splits in a fixed order (deterministic, no float atomics) and
+// writes bf16.
 //
 // Data movement.  K/V tiles of 64 tokens go from global memory straight into LDS (16-byte LDS-direct loads, no
 // staging registers; issued through inline assembly, see lds_direct_load16) through a 4-stage ring, three tiles
@@ -22,17 +33,13 @@
 // and the 1 KB groups are padded so that consecutive tokens are staggered across the banks (conflict-free reads
 // with compile-time offsets, see the layout constants).  Every stage is its own LDS object, so every stage address
 // is a compile-time constant.  The ancestor masks and the Q rows take the same road ahead of the first tiles, so
-// that no load of the kernel returns into a register and every wait on the vector-memory counter is a counted one.
+// that no load of the kernel returns into a register and every wait on the vector-memory counter is a counted one
+// (which is also why these kernels must not spill: the build checks that they use no scratch memory).
 //
-// Decomposition (decided on the device from n_nodes/kv_len, so no host round trip): a workgroup of 8 waves
-// owns (sequence, KV head, group of up to 4 column tiles = 128 query rows, KV split); with 2..64 sequences the
-// splits are equal ranges of one list of all sequences' tiles, so ragged lengths leave no CU idle (see the
-// kernel).  Waves w and w+4 share column tile w and each takes one 32-token half of every tile; the halves are
-// combined through LDS at the end.  The KV head is the fastest grid index, so in launch order the workgroups of one
-// KV head are congruent modulo the KV-head count, which with 8 KV heads pins a head to one XCD and its L2: the column
-// groups of a large tree re-read K/V from that L2, not from HBM.  Each workgroup writes an un-normalised partial
-// (max, sum, O^T); a second kernel merges the splits in a fixed order (deterministic, no float atomics) and writes
-// bf16.
+// Softmax.  The reference maximum of a row is only moved by rebase(): the usual tile costs no maximum at all.
+// Probabilities are exp2 of the scaled differences to the reference, rounded to bf16 (the B operand of PV); their sum,
+// taken over the rounded values with a two-element dot product, doubles as the overflow check.  The final
+// normalisation uses the same reference for numerator and denominator, so the result does not depend on it.
 #include <type_traits>
 
 #include "plan_device.h"
@@ -44,6 +51,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef __attribute__((address_space(3))) unsigned char lds_byte;
 #define LDS_AS __attribute__((address_space(3)))
@@ -51,7 +59,7 @@ typedef __attribute__((address_space(3))) unsigned char lds_byte;
 constexpr int D = 128;                  // head_dim
 constexpr int TILE = 64;                // tokens per LDS stage
 constexpr int THREADS = 512;
-constexpr int CT_PER_WG = 4;            // column tiles (of 32 query rows) per workgroup
+constexpr int CT_PER_WG = 8;            // column tiles (of 32 query rows) per workgroup: one per wave
 constexpr int ROWS_PER_WG = CT_PER_WG * 32;
 constexpr int ROW_B = 256;              // bytes of one token row (128 bf16)
 // LDS stage layout: token t of a tile sits at (t % 16) * GROUP + (t / 16) * ROW_B, where a group is the 1 KB that
@@ -60,20 +68,23 @@ constexpr int ROW_B = 256;              // bytes of one token row (128 bf16)
 // 64 bytes for V (read 4 consecutive tokens x 64 bytes at a time).  All per-fragment offsets are compile-time.
 constexpr int K_GROUP = 4 * ROW_B + 16;
 constexpr int V_GROUP = 4 * ROW_B + 64;
-constexpr int EPI_ROW_F = 132;            // floats per parked row in the epilogue (130 used; 132 keeps 16-byte stores conflict-free)
-constexpr int K_STAGE_B = 32 * EPI_ROW_F * 4;   // 16 * K_GROUP for the ring, rounded up to hold an epilogue block
+constexpr int K_STAGE_B = 16 * K_GROUP;
 constexpr int V_STAGE_B = 16 * V_GROUP;
-static_assert(K_STAGE_B >= 16 * K_GROUP && V_STAGE_B >= 32 * EPI_ROW_F * 4, "stage buffers double as epilogue blocks");
 constexpr int STAGES = 4;
 constexpr int LOADS_PER_TILE = 2 * TILE * ROW_B / (THREADS * 16);   // LDS-direct loads per thread per tile (K and V)
-constexpr int PART_FLOATS = D + 2;      // per query row: O^T[128], then max, sum
-constexpr float RESCALE_THRESHOLD = 8.0f;   // raise the reference maximum only past 2^8
+// A partial: per query row O^T[128] in bf16, then max and sum in fp32.
+constexpr int PART_ROW_B = D * 2 + 16;   // (8 bytes of padding keep the rows 16-byte aligned)
+constexpr int PART_SLOT_B = ROWS_PER_WG * PART_ROW_B;
+constexpr int EPI_ROW_B = PART_ROW_B;    // a parked row of the epilogue has the layout of a partial row
+static_assert(32 * EPI_ROW_B <= K_STAGE_B && 32 * EPI_ROW_B <= V_STAGE_B, "a stage buffer holds a wave's epilogue block");
+constexpr float RAISE_MIN = 4.0f;       // rebase() raises a row's reference maximum only past 2^4 ...
+constexpr float REBASE_SUM = 512.0f;    // ... which bounds a lane's 32 probabilities of a tile by this sum afterwards
 
 struct Params {
     const uint16_t* Q; const uint16_t* Kc; const uint16_t* Vc; const uint16_t* Kt; const uint16_t* Vt;
     uint16_t* O;
     const int64_t* kv_start; const int* kv_len; const uint64_t* anc_mask; const int* n_nodes;
-    float* part;                         // [B][Hkv][nslot][ROWS_PER_WG][PART_FLOATS]; batched launches: [Hkv][nslot][..][..]
+    unsigned char* part;                 // [B][Hkv][nslot] slots of PART_SLOT_B bytes; batched launches: [Hkv][nslot]
     long kv_token_stride, kv_head_stride;
     int B, Hq, Hkv, G, nslot, min_tiles_per_split;
     int nrange;                          // batched launches: ranges (workgroups) per KV head
@@ -177,11 +188,7 @@ __device__ __forceinline__ void attention_workgroup(const int* __restrict__ kv_l
 #define SK(i) ((i) == 0 ? sK0 : (i) == 1 ? sK1 : (i) == 2 ? sK2 : sK3)
 #define SV(i) ((i) == 0 ? sV0 : (i) == 1 ? sV1 : (i) == 2 ? sV2 : sV3)
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, so LDS stage addresses stay scalar
-    const int r32 = lane & 31;           // MFMA row (A) / column (B, C) owned by this lane
-    const int half = lane >> 5;
+    const int lane = threadIdx.x & 63;   // (run_segment derives its own copies)
 
     // grid = (KV head, slot or range, sequence): the KV head is the fastest index of the launch order, and no index
     // costs a division
@@ -190,26 +197,43 @@ __device__ __forceinline__ void attention_workgroup(const int* __restrict__ kv_l
     const int inv_G = (65536 + G_arg - 1) / G_arg;           // (m * inv_G) >> 16 == m / G for the rows of a KV head
 
     // One pass over tiles [t_begin, t_end) of sequence b for column group cg; the un-normalised partial goes to out_base.
-    auto run_segment = [&](const int b, const int L, const int seq_n, const int seq_rows, const int cg, const int t_begin,
-                           const int t_end, const int tree_tile, const long kv_start_b, float* const out_base)
+    auto run_segment = [&](const int b_v, const int L_v, const int seq_n_v, const int seq_rows_v, const int cg_v, const int t_begin_v,
+                           const int t_end_v, const int tree_tile_v, const long kv_start_v, unsigned char* const out_base_v)
                            __attribute__((always_inline)) {
+    // every argument is wave-uniform; said to the compiler (the batched walk derives them through lane reads), so that
+    // everything computed from them stays in scalar registers
+    auto uni = [](int v) __attribute__((always_inline)) { return __builtin_amdgcn_readfirstlane(v); };
+    auto uni64 = [&](uint64_t v) __attribute__((always_inline)) {
+        return (static_cast<uint64_t>(static_cast<uint32_t>(uni(static_cast<int>(v >> 32)))) << 32) |
+               static_cast<uint32_t>(uni(static_cast<int>(static_cast<uint32_t>(v))));
+    };
+    const int b = uni(b_v), L = uni(L_v), seq_n = uni(seq_n_v), seq_rows = uni(seq_rows_v), cg = uni(cg_v);
+    const int t_begin = uni(t_begin_v), t_end = uni(t_end_v), tree_tile = uni(tree_tile_v);
+    const long kv_start_b = static_cast<long>(uni64(static_cast<uint64_t>(kv_start_v)));
+    unsigned char* const out_base = reinterpret_cast<unsigned char*>(uni64(reinterpret_cast<uint64_t>(out_base_v)));
     if (BATCH) __syncthreads();                              // the previous segment's epilogue has left the stage buffers
-    // ---- wave roles: waves w and w+4 share column tile w; each takes one 32-token half of every tile
+    // A batched workgroup calls this in a loop.  Everything below that depends only on the thread index would be
+    // loop-invariant, and the compiler hoists all of it out of the loop and keeps it alive across the whole pass (some
+    // fifty registers more than the pass itself needs, which does not fit).  The thread index is therefore made opaque
+    // per pass, and its derived values are recomputed (a handful of instructions).
+    int tid = static_cast<int>(threadIdx.x);
+    if (BATCH) asm volatile("" : "+v"(tid));
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, so LDS stage addresses stay scalar
+    const int r32 = lane & 31;           // MFMA row (A) / column (B, C) owned by this lane
+    const int half = lane >> 5;
+    // ---- wave roles: wave w owns column tile w of the group (32 query rows) and processes whole tiles for it; with up
+    // to four column tiles every computing wave has a SIMD to itself
     const int group_rows = min(ROWS_PER_WG, seq_rows - cg * ROWS_PER_WG);
-    const int group_ct = (group_rows + 31) / 32;             // 1..4 column tiles in this group
-    // Waves w and w + 4 run on the same SIMD.  With three or four column tiles every SIMD gets one tile's two halves; with
-    // one or two (trees of up to 64 / G nodes) the four (tile, half) units go to waves 0..3, one per SIMD, instead of
-    // two each on SIMDs 0 and 1, which halves the time of a tile step.  Which wave computes a unit changes no result.
-    const bool narrow = group_ct <= 2;
-    const int ct = narrow ? (wave & 1) : (wave & 3);
-    const int sub_lo = narrow ? ((wave >> 1) & 1) : (wave >> 2);
-    const bool wave_active = ct < group_ct && (!narrow || wave < 4);
+    const int group_ct = (group_rows + 31) / 32;             // 1..8 column tiles in this group
+    const bool wide = group_ct > 4;                          // Q needs two stages of the ring on its way in
+    const bool wave_active = wave < group_ct;
+    const int m_local = wave * 32 + r32;                     // this lane's query row within the group
 
-    // ---- this lane's query row
-    const int m_local = ct * 32 + r32;                       // row within the group
     // ---- loader: instruction i of wave w copies tokens r, r+16, r+32, r+48 (r = 2w + i) of K and of V, 1 KB of
-    //      LDS each: lane l fills chunk l%16 of token r + 16 (l/16).  Addresses are a wave-uniform tile base plus a
-    //      32-bit per-lane offset that is the same for every full tile, so a tile costs no address arithmetic.
+    //      LDS each: lane l fills chunk l%16 of token r + 16 (l/16).  Addresses are a wave-uniform tile base in scalar
+    //      registers plus a 32-bit per-lane offset that is the same for every full tile, so a tile costs no vector
+    //      address arithmetic.
     const int ld_tok = (lane >> 4) * 16 + wave * 2;          // token within the tile for i = 0 (i = 1: the next one)
     const unsigned ld_chunk_b = (lane & 15) * 16;
     const unsigned char* k_cache = reinterpret_cast<const unsigned char*>(
@@ -234,17 +258,17 @@ __device__ __forceinline__ void attention_workgroup(const int* __restrict__ kv_l
             // Nothing left to fetch, but every step issues the same number of loads, so the wait for a tile is one fixed
             // count on every path.  Four loads of one valid 16-byte piece (served by L2) into the free stage.
             const unsigned char* any = reinterpret_cast<const unsigned char*>(prm.Q);
-            sage::lds_direct_load16(any, k_dst);
-            sage::lds_direct_load16(any, v_dst);
-            sage::lds_direct_load16(any, k_dst + K_GROUP);
-            sage::lds_direct_load16(any, v_dst + V_GROUP);
+            sage::lds_direct_load16(any, 0u, k_dst);
+            sage::lds_direct_load16(any, 0u, v_dst);
+            sage::lds_direct_load16(any, 0u, k_dst + K_GROUP);
+            sage::lds_direct_load16(any, 0u, v_dst + V_GROUP);
         } else if (!is_tree && tile * TILE + TILE <= L) {    // full cache tile
             const unsigned char* kb = k_cache + static_cast<long>(tile) * TILE * cache_row_b;
             const unsigned char* vb = v_cache + static_cast<long>(tile) * TILE * cache_row_b;
-            sage::lds_direct_load16(kb + ld_off0, k_dst);
-            sage::lds_direct_load16(vb + ld_off0, v_dst);
-            sage::lds_direct_load16(kb + ld_off1, k_dst + K_GROUP);
-            sage::lds_direct_load16(vb + ld_off1, v_dst + V_GROUP);
+            sage::lds_direct_load16(kb, ld_off0, k_dst);
+            sage::lds_direct_load16(vb, ld_off0, v_dst);
+            sage::lds_direct_load16(kb, ld_off1, k_dst + K_GROUP);
+            sage::lds_direct_load16(vb, ld_off1, v_dst + V_GROUP);
         } else {                                             // ragged tail or the tree's keys: rows past the end are
             const unsigned char* kb = is_tree ? k_tree : k_cache + static_cast<long>(tile) * TILE * cache_row_b;   // masked later,
             const unsigned char* vb = is_tree ? v_tree : v_cache + static_cast<long>(tile) * TILE * cache_row_b;   // reads stay in range
@@ -252,69 +276,88 @@ __device__ __forceinline__ void attention_workgroup(const int* __restrict__ kv_l
             const int last = is_tree ? seq_n - 1 : L - 1 - tile * TILE;
             const unsigned o0 = static_cast<unsigned>(min(ld_tok, last)) * row_b + ld_chunk_b;
             const unsigned o1 = static_cast<unsigned>(min(ld_tok + 1, last)) * row_b + ld_chunk_b;
-            sage::lds_direct_load16(kb + o0, k_dst);
-            sage::lds_direct_load16(vb + o0, v_dst);
-            sage::lds_direct_load16(kb + o1, k_dst + K_GROUP);
-            sage::lds_direct_load16(vb + o1, v_dst + V_GROUP);
+            sage::lds_direct_load16(kb, o0, k_dst);
+            sage::lds_direct_load16(vb, o0, v_dst);
+            sage::lds_direct_load16(kb, o1, k_dst + K_GROUP);
+            sage::lds_direct_load16(vb, o1, v_dst + V_GROUP);
         }
     };
     // Everything the prologue needs from memory goes straight into LDS, requested back to back in this order: the rows'
-    // ancestor masks, the Q rows (into the ring's fourth stage, idle until the first tile step refills it), the first
-    // three K/V tiles.  No load returns into a register, so the compiler never waits on the vector-memory counter here
-    // and the only waits are the counted ones: loads complete in order, so masks and Q have landed once no more than the
-    // tile loads are outstanding, and the first tile is processed while the second and third are still arriving.
+    // ancestor masks, the Q rows (into the ring's last stage, idle until the first tile step refills it; a group of more
+    // than four column tiles also borrows the third stage, whose tile is then requested one step later), the first
+    // tiles.  No load returns into a register, so the compiler never waits on the vector-memory counter here and the
+    // only waits are the counted ones: loads complete in order, so masks and Q have landed once no more than the tile
+    // loads are outstanding, and the first tile is processed while the following ones are still arriving.
     // Rows past the group's last one repeat that row (their results are never written).
     auto row_of = [&](int local) __attribute__((always_inline)) {      // row `local` of this group -> (node, head in group)
         const int mm = min(cg * ROWS_PER_WG + local, seq_rows - 1);
-        const int nd = (mm * inv_G) >> 16;                               // exact for mm < 512, G <= 16
+        const int nd = (mm * inv_G) >> 16;                               // exact for mm < 64 G, G <= 16
         return make_int2(nd, mm - nd * prm.G);
     };
     {
-        // wave w (and w + 4 again: every wave issues the same number of loads) brings both words of the masks of rows
-        // 32 (w % 4) + lane / 2
-        const int2 r = row_of((wave & 3) * 32 + (lane >> 1));
+        // wave w brings both words of the masks of its rows 32 w + lane / 2
+        const int2 r = row_of(wave * 32 + (lane >> 1));
         sage::lds_direct_load4(
             reinterpret_cast<const unsigned char*>(prm.anc_mask + static_cast<long>(b) * SAGE_MAX_NODES + r.x) + (lane & 1) * 4,
-            (LDS_AS unsigned char*)(&s_mask[(wave & 3) * 32]));
+            (LDS_AS unsigned char*)(&s_mask[wave * 32]));
     }
-    // Q rows as two blocks of 64 in the layout of a K tile (K buffer) and of a V tile (V buffer) of stage 3: row q of a
-    // block sits at (q % 16) * GROUP + (q / 16) * ROW_B.
-#pragma unroll
-    for (int blk = 0; blk < 2; ++blk)
+    // Q rows as blocks of 64 in the layout of a K tile (K buffer) and of a V tile (V buffer): row q of a block sits at
+    // (q % 16) * GROUP + (q / 16) * ROW_B.  Blocks 0, 1 -> stage 3; blocks 2, 3 (wide groups only) -> stage 2.
+    auto issue_q = [&](auto blkc) __attribute__((always_inline)) {
+        constexpr int BLK = decltype(blkc)::value;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            const int2 r = row_of(blk * 64 + wave * 2 + i + 16 * (lane >> 4));
+            const int2 r = row_of(BLK * 64 + wave * 2 + i + 16 * (lane >> 4));
             const unsigned char* src = reinterpret_cast<const unsigned char*>(
                 prm.Q + ((static_cast<long>(b) * SAGE_MAX_NODES + r.x) * prm.Hq + g * prm.G + r.y) * D) + ld_chunk_b;
-            if (blk == 0) sage::lds_direct_load16(src, (LDS_AS unsigned char*)(&sK3[(wave * 2 + i) * K_GROUP]));
-            else sage::lds_direct_load16(src, (LDS_AS unsigned char*)(&sV3[(wave * 2 + i) * V_GROUP]));
+            unsigned char* buf = BLK == 0 ? sK3 : BLK == 1 ? sV3 : BLK == 2 ? sK2 : sV2;
+            const int group_b = (BLK & 1) ? V_GROUP : K_GROUP;
+            sage::lds_direct_load16(src, (LDS_AS unsigned char*)(&buf[(wave * 2 + i) * group_b]));
         }
-    issue_loads(t_begin, std::integral_constant<int, 0>{});
-    issue_loads(t_begin + 1, std::integral_constant<int, 1>{});
-    issue_loads(t_begin + 2, std::integral_constant<int, 2>{});
-    wait_vm<3 * LOADS_PER_TILE>();                           // this thread's mask and Q loads have landed
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>;
+    using I4 = std::integral_constant<int, 4>;
+    issue_q(I0{});
+    issue_q(I1{});
+    if (wide) {
+        issue_q(I2{});
+        issue_q(I3{});
+    }
+    issue_loads(t_begin, I0{});
+    issue_loads(t_begin + 1, I1{});
+    if (wide) {
+        wait_vm<2 * LOADS_PER_TILE>();                       // this thread's mask and Q loads have landed
+    } else {
+        issue_loads(t_begin + 2, I2{});
+        wait_vm<3 * LOADS_PER_TILE>();
+    }
     stage_barrier();                                         // ... everyone's have
     bf16x8 qf[8];                                            // this lane's query row: the B operand of every score MFMA
     {
-        const int q = (ct & 1) * 32 + r32;                   // row within its block of 64
-        const lds_byte* qb = (ct >> 1) ? (const lds_byte*)sV3 + (q & 15) * V_GROUP : (const lds_byte*)sK3 + (q & 15) * K_GROUP;
-        qb += (q >> 4) * ROW_B + half * 16;
+        const int q = (wave & 1) * 32 + r32;                 // row within its block of 64
+        const int blk = wave >> 1;
+        const lds_byte* qb = blk == 0 ? (const lds_byte*)sK3 : blk == 1 ? (const lds_byte*)sV3 : blk == 2 ? (const lds_byte*)sK2
+                                                                                                       : (const lds_byte*)sV2;
+        qb += (q & 15) * ((blk & 1) ? V_GROUP : K_GROUP) + (q >> 4) * ROW_B + half * 16;
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) qf[kk] = __builtin_bit_cast(bf16x8, *(const LDS_AS uint4*)(qb + kk * 32));
     }
     __builtin_amdgcn_s_waitcnt(0xc07f);                      // lgkmcnt(0): Q is in registers before this wave reaches the
-                                                             // first step's barrier, after which stage 3 is refilled
+                                                             // barrier after which its stages are refilled
 
-    // ---- per-lane LDS read offsets (this wave's 32-token half starts sub_lo * 2 * ROW_B into every group).
-    // K fragment kk: token r32 of the half, chunk 2kk + half -> k_lane + 32 kk.
-    const int k_lane = (r32 & 15) * K_GROUP + (r32 >> 4) * ROW_B + half * 16 + sub_lo * 2 * ROW_B;
-    // V^T fragment (dt, j, u): the 16-lane group q = lane/16 reads tokens 16j + 8u + 4(q/2) + s/4 of the half and dims
-    // dt*32 + 16(q%2) + 4(s%4) .. +3  (s = lane%16); after the transposing read lane s holds dim dt*32+16(q%2)+s.
-    // Offset: v_lane + j * ROW_B + u * 8 * V_GROUP + dt * 64.
+    // ---- per-lane LDS read offsets.  K fragment (sub, kk): token r32 of 32-token half `sub`, chunk 2kk + half
+    //      -> k_lane + sub * 2 * ROW_B + 32 kk.
+    const int k_lane = (r32 & 15) * K_GROUP + (r32 >> 4) * ROW_B + half * 16;
+    // V^T fragment (dt, jj, u): k-block jj (16 tokens); the 16-lane group q = lane/16 reads tokens 16jj + 8u + 4(q/2) + s/4
+    // and dims dt*32 + 16(q%2) + 4(s%4) .. +3  (s = lane%16); after the transposing read lane s holds dim dt*32+16(q%2)+s.
+    // Offset: v_lane + jj * ROW_B + u * 8 * V_GROUP + dt * 64.
     int v_lane;
     {
         const int q = lane >> 4, s16 = lane & 15;
-        v_lane = (4 * (q >> 1) + (s16 >> 2)) * V_GROUP + (2 * (q & 1) + ((s16 & 3) >> 1)) * 16 + 8 * (s16 & 1) + sub_lo * 2 * ROW_B;
+        v_lane = (4 * (q >> 1) + (s16 >> 2)) * V_GROUP + (2 * (q & 1) + ((s16 & 3) >> 1)) * 16 + 8 * (s16 & 1);
     }
 
     f32x16 acc[4];                                           // O^T: 4 tiles of 32 dims x this lane's query row
@@ -323,196 +366,205 @@ __device__ __forceinline__ void attention_workgroup(const int* __restrict__ kv_l
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[dt][i] = 0.f;
     float m_ref = -INFINITY;                                 // reference maximum of raw (unscaled) scores
+    float neg_mc = 0.f;                                      // -m_ref * c, 0 while there is no reference yet
     float l_run = 0.f;                                       // this lane's share of the running sum
     const float c = prm.scale_log2e;
-    f32x16 sc;                                               // scores of this wave's 32-token half tile
-    bf16x8 pf[2];                                            // P^T of that half tile, the B operand of PV
+    f32x16 sc[2];                                            // scores of the tile's two 32-token halves
+    bf16x8 pf[4];                                            // P^T of the tile's four 16-token k-blocks, the B operand of PV
+    bf16x8 ka[8], va[2][4];                                  // K fragments of a half tile; V^T fragments of two dim tiles
 
-    // A tile step of a wave: scores (S^T = K Q^T, MFMA), softmax (VALU), PV (MFMA).  The LDS reads of a phase are
-    // issued in batches ahead of the arithmetic that hides their latency; the scheduling fences keep the compiler
-    // from sinking them back next to their uses, where every MFMA group would wait out a full LDS round trip.
-    auto read_k = [&](const lds_byte* kb, bf16x8 (&a)[8], auto firstc) __attribute__((always_inline)) {
+    // The pieces of a tile step: scores (S^T = K Q^T, MFMA), softmax (VALU), PV (MFMA).  The LDS reads of a piece are
+    // issued in batches ahead of the arithmetic that hides their latency; the scheduling fences keep the compiler from
+    // sinking them back next to their uses, where every MFMA group would wait out a full LDS round trip.
+    auto read_k = [&](const lds_byte* kb, auto subc, auto firstc) __attribute__((always_inline)) {
+        constexpr int SUB = decltype(subc)::value;
         constexpr int FIRST = decltype(firstc)::value;        // dims FIRST*16 .. FIRST*16 + 63
 #pragma unroll
-        for (int kk = FIRST; kk < FIRST + 4; ++kk) a[kk] = __builtin_bit_cast(bf16x8, *(const LDS_AS uint4*)(kb + k_lane + kk * 32));
+        for (int kk = FIRST; kk < FIRST + 4; ++kk)
+            ka[kk] = __builtin_bit_cast(bf16x8, *(const LDS_AS uint4*)(kb + k_lane + SUB * 2 * ROW_B + kk * 32));
     };
-    auto read_v = [&](const lds_byte* vb, bf16x8 (&v)[4][2], auto dt0c) __attribute__((always_inline)) {
-        constexpr int DT0 = decltype(dt0c)::value;            // dims DT0*32 .. DT0*32 + 63
+    auto read_v = [&](const lds_byte* vb, auto dt0c) __attribute__((always_inline)) {
+        constexpr int DT0 = decltype(dt0c)::value;            // dims DT0*32 .. DT0*32 + 63, all four k-blocks
 #pragma unroll
         for (int dt = DT0; dt < DT0 + 2; ++dt)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const lds_byte* p0 = vb + v_lane + j * ROW_B + dt * 64;
+            for (int jj = 0; jj < 4; ++jj) {
+                const lds_byte* p0 = vb + v_lane + jj * ROW_B + dt * 64;
                 const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)p0);
                 const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((LDS_AS bf16x4*)(p0 + 8 * V_GROUP));
-                v[dt][j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                va[dt - DT0][jj] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             }
     };
-    auto score_mfma = [&](const bf16x8 (&a)[8], auto firstc) __attribute__((always_inline)) {
+    auto score_mfma = [&](auto subc, auto firstc) __attribute__((always_inline)) {
+        constexpr int SUB = decltype(subc)::value;
         constexpr int FIRST = decltype(firstc)::value;
         if (FIRST == 0) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) sc[i] = 0.f;
+            for (int i = 0; i < 16; ++i) sc[SUB][i] = 0.f;
         }
 #pragma unroll
-        for (int kk = FIRST; kk < FIRST + 4; ++kk) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[kk], qf[kk], sc, 0, 0, 0);
+        for (int kk = FIRST; kk < FIRST + 4; ++kk) sc[SUB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk], qf[kk], sc[SUB], 0, 0, 0);
     };
     // admit keys: cache positions below kv_len; tree nodes in this row's ancestor-or-self mask
-    auto score_mask = [&](uint32_t adm) __attribute__((always_inline)) {
+    auto score_mask = [&](int tile) __attribute__((always_inline)) {
+        const bool is_tree = (tile == tree_tile);
+        if (!(is_tree || tile * TILE + TILE > L)) return;
+        uint64_t admit;
+        if (is_tree) {
+            admit = s_mask[m_local];
+        } else {
+            const int left = L - tile * TILE;                // 1..63 valid tokens
+            admit = (1ull << left) - 1ull;
+        }
+        // token of accumulator register i of half `sub`: 32 sub + 8 (i/4) + 4 half + i%4
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
-            if (!((adm >> (8 * (i >> 2) + (i & 3))) & 1u)) sc[i] = -INFINITY;
+        for (int sub = 0; sub < 2; ++sub) {
+            const uint32_t adm = static_cast<uint32_t>(admit >> (4 * half + 32 * sub));
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if (!((adm >> (8 * (i >> 2) + (i & 3))) & 1u)) sc[sub][i] = -INFINITY;
+        }
     };
-    // online softmax for this lane's query row, lazily rescaled: sc -> pf
-    auto softmax_phase = [&]() __attribute__((always_inline)) {
-        float tmax = sc[0];
+    // probabilities of k-block JJ: sc[JJ / 2][8 (JJ % 2) .. + 7] -> pf[JJ]; returns sum + the block's rounded probabilities
+    auto probs = [&](auto jjc, float sum) __attribute__((always_inline)) {
+        constexpr int JJ = decltype(jjc)::value;
+        const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
+        bf16x8 frag;
 #pragma unroll
-        for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, sc[i]);
+        for (int e = 0; e < 8; e += 2) {
+            const f32x2 pp = {__builtin_amdgcn_exp2f(fmaf(sc[JJ >> 1][8 * (JJ & 1) + e], c, neg_mc)),
+                              __builtin_amdgcn_exp2f(fmaf(sc[JJ >> 1][8 * (JJ & 1) + e + 1], c, neg_mc))};
+            const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
+            frag[e] = pb[0];
+            frag[e + 1] = pb[1];
+            sum = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, sum, false);
+        }
+        pf[JJ] = frag;
+        return sum;
+    };
+    auto all_probs = [&]() __attribute__((always_inline)) { return probs(I3{}, probs(I2{}, probs(I1{}, probs(I0{}, 0.f)))); };
+    // Move the reference maximum of the rows that need it to the row maximum of the current tile (both 32-lane halves of
+    // a row decide alike) and rescale what has been accumulated so far.
+    auto rebase = [&]() __attribute__((always_inline)) {
+        float tmax = fmaxf(sc[0][0], sc[1][0]);
+#pragma unroll
+        for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, fmaxf(sc[0][i], sc[1][i]));
         tmax = cross_half_max(tmax);
-        const bool raise = (tmax - m_ref) * c > RESCALE_THRESHOLD;     // also true for the first admitted key
+        const bool raise = (m_ref == -INFINITY) ? (tmax > -INFINITY) : ((tmax - m_ref) * c > RAISE_MIN);
         if (__any(raise)) {
             const float m_new = raise ? tmax : m_ref;
-            const float corr = (m_ref == -INFINITY) ? (raise ? 0.f : 1.f) : __builtin_amdgcn_exp2f((m_ref - m_new) * c);
+            const float corr = !raise ? 1.f : (m_ref == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m_ref - m_new) * c);
             m_ref = m_new;
+            neg_mc = -m_ref * c;                             // raise implies a finite maximum
+            if (!raise && m_ref == -INFINITY) neg_mc = 0.f;
             l_run *= corr;
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[dt][i] *= corr;
         }
-        const float neg_mc = (m_ref == -INFINITY) ? 0.f : -m_ref * c;
-        float psum = 0.f;
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            bf16x8 frag;
-#pragma unroll
-            for (int e = 0; e < 8; e += 2) {
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[8 * j + e], c, neg_mc));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[8 * j + e + 1], c, neg_mc));
-                psum += p0 + p1;
-                const f32x2 pp = {p0, p1};
-                const bf16x2 pb = __builtin_convertvector(pp, bf16x2);
-                frag[e] = pb[0];
-                frag[e + 1] = pb[1];
-            }
-            pf[j] = frag;
-        }
-        l_run += psum;
     };
-    // O^T += V^T P^T for 64 dims (two k-blocks of 16 tokens)
-    auto pv_mfma = [&](const bf16x8 (&v)[4][2], auto dt0c) __attribute__((always_inline)) {
+    // Back to rebase() when a lane's sum says its probabilities may have overflowed, or when a lane has no reference yet:
+    // the pass's first tile, or every key so far was masked for its half of the row.
+    auto overflow = [&](float sum) __attribute__((always_inline)) {
+        return __any(!(sum <= REBASE_SUM) || m_ref == -INFINITY) != 0;
+    };
+    // O^T += V^T P^T for the 64 dims whose fragments are in va (four k-blocks of 16 tokens)
+    auto pv_mfma = [&](auto dt0c) __attribute__((always_inline)) {
         constexpr int DT0 = decltype(dt0c)::value;
 #pragma unroll
-        for (int dt = DT0; dt < DT0 + 2; ++dt)
+        for (int jj = 0; jj < 4; ++jj)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v[dt][j], pf[j], acc[dt], 0, 0, 0);
+            for (int dt = DT0; dt < DT0 + 2; ++dt)
+                acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[dt - DT0][jj], pf[jj], acc[dt], 0, 0, 0);
     };
-    using I0 = std::integral_constant<int, 0>;
-    using I2 = std::integral_constant<int, 2>;
-    using I4 = std::integral_constant<int, 4>;
 #define FENCE() __builtin_amdgcn_sched_barrier(0)
 
-    auto process = [&](int tile, auto stc) __attribute__((always_inline)) {
+    auto process = [&](int tile, int first, auto stc) __attribute__((always_inline)) {
         constexpr int ST = decltype(stc)::value;
-        wait_vm<2 * LOADS_PER_TILE>();                       // this thread's part of `tile` has landed (two tiles may fly)
-        stage_barrier();                                     // ... everyone's has, and the stage read last step is free
+        if (first && wide) {
+            wait_vm<1 * LOADS_PER_TILE>();                   // (the third tile is not on its way yet)
+            stage_barrier();                                 // tile 0 has landed; everyone has read Q out of stages 2, 3
+            issue_loads(tile + 2, std::integral_constant<int, (ST + 2) % STAGES>{});
+        } else {
+            wait_vm<2 * LOADS_PER_TILE>();                   // this thread's part of `tile` has landed (two tiles may fly)
+            stage_barrier();                                 // ... everyone's has, and the stage read last step is free
+        }
         issue_loads(tile + 3, std::integral_constant<int, (ST + 3) % STAGES>{});
         if (!wave_active) return;
 
-        const bool is_tree = (tile == tree_tile);
-        const bool masked = is_tree || tile * TILE + TILE > L;
-        uint32_t adm = ~0u;
-        if (masked) {
-            uint64_t admit;
-            if (is_tree) {
-                admit = s_mask[m_local];
-            } else {
-                const int left = L - tile * TILE;            // 1..63 valid tokens
-                admit = (1ull << left) - 1ull;
-            }
-            // token of accumulator register i: 32 sub + 8 (i/4) + 4 half + i%4
-            adm = static_cast<uint32_t>(admit >> (4 * half + 32 * sub_lo));
-        }
         const lds_byte* kst = (const lds_byte*)(SK(ST));
         const lds_byte* vst = (const lds_byte*)(SV(ST));
-        bf16x8 ka[8], va[4][2];
-        read_k(kst, ka, I0{});
-        read_k(kst, ka, I4{});
+        read_k(kst, I0{}, I0{});
+        read_k(kst, I0{}, I4{});
         FENCE();
-        score_mfma(ka, I0{});
+        score_mfma(I0{}, I0{});
         FENCE();
-        read_v(vst, va, I0{});                               // V reads go out between the score MFMAs and land
+        read_k(kst, I1{}, I0{});                             // the second half's fragments follow the first's through the
+        FENCE();                                             // same registers, one batch of four behind the MFMAs
+        score_mfma(I0{}, I4{});
+        FENCE();
+        read_k(kst, I1{}, I4{});
+        FENCE();
+        score_mfma(I1{}, I0{});
+        FENCE();
+        read_v(vst, I0{});                                   // V reads go out between the score MFMAs and land
         FENCE();                                             // during the softmax
-        score_mfma(ka, I4{});
+        score_mfma(I1{}, I4{});
         FENCE();
-        read_v(vst, va, I2{});
+        score_mask(tile);
+        float sum = all_probs();
+        if (overflow(sum)) {
+            rebase();
+            sum = all_probs();
+        }
+        l_run += sum;
+        pv_mfma(I0{});
         FENCE();
-        if (masked) score_mask(adm);
-        softmax_phase();
-        pv_mfma(va, I0{});
-        pv_mfma(va, I2{});
+        read_v(vst, I2{});
+        FENCE();
+        pv_mfma(I2{});
     };
     for (int tile = t_begin; tile < t_end; tile += STAGES) {    // no path reaches a step without the steps before it
-        process(tile, std::integral_constant<int, 0>{});
+        process(tile, tile == t_begin, I0{});
         if (tile + 1 >= t_end) break;
-        process(tile + 1, std::integral_constant<int, 1>{});
+        process(tile + 1, 0, I1{});
         if (tile + 2 >= t_end) break;
-        process(tile + 2, std::integral_constant<int, 2>{});
+        process(tile + 2, 0, I2{});
         if (tile + 3 >= t_end) break;
-        process(tile + 3, std::integral_constant<int, 3>{});
+        process(tile + 3, 0, I3{});
     }
 #undef FENCE
 
     const float l_tot = cross_half_sum(l_run);
     wait_vm<0>();                                            // the placeholder loads of the last steps have landed too
 
-    // ---- epilogue: every wave parks its block (O^T, max, sum) in the stage buffer of its (column tile, token half)
-    // as [32 rows][EPI_ROW_F floats]; then the whole workgroup combines the two halves of each row and writes the
-    // un-normalised partial of this split row by row (512 contiguous bytes per row), for the second kernel to merge.
+    // ---- epilogue: a wave's block (O^T in bf16, max, sum) is complete for its 32 rows.  It goes through the wave's own
+    // piece of a stage buffer as [32 rows][EPI_ROW_B bytes], transposed on the way: written 8 bytes (4 dims) at a time from
+    // the accumulator layout, read back and stored to the partial in row order, for the second kernel to merge.
     __syncthreads();                                         // all stages are idle now
     if (wave_active) {
-        float* blk = reinterpret_cast<float*>(sub_lo ? SV(ct) : SK(ct)) + r32 * EPI_ROW_F;
+        unsigned char* blk = wave < 4 ? SK(wave) : SV(wave - 4);
+        unsigned char* mine = blk + r32 * EPI_ROW_B;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                *reinterpret_cast<float4*>(blk + dt * 32 + 8 * q + 4 * half) =
-                    make_float4(acc[dt][4 * q], acc[dt][4 * q + 1], acc[dt][4 * q + 2], acc[dt][4 * q + 3]);
-        if (half == 0) { blk[D] = m_ref; blk[D + 1] = l_tot; }
-    }
-    __syncthreads();
-    {
-        // thread -> 16-byte chunk tid % 32 of rows tid / 32, + 16, ...: every row's LDS reads are requested before the first
-        // one is used, so the pass costs one LDS round trip, not one per row
-        constexpr int PASSES = ROWS_PER_WG * 32 / THREADS;
-        const int ch = tid & 31;
-        float4 x[PASSES], y[PASSES];
-        float2 ml0[PASSES], ml1[PASSES];
-#pragma unroll
-        for (int i = 0; i < PASSES; ++i) {
-            const int row = (tid >> 5) + i * (THREADS / 32);
-            if (row < group_rows) {
-                const float* b0 = reinterpret_cast<const float*>(SK(row >> 5)) + (row & 31) * EPI_ROW_F;
-                const float* b1 = reinterpret_cast<const float*>(SV(row >> 5)) + (row & 31) * EPI_ROW_F;
-                ml0[i] = *reinterpret_cast<const float2*>(b0 + D);
-                ml1[i] = *reinterpret_cast<const float2*>(b1 + D);
-                x[i] = *reinterpret_cast<const float4*>(b0 + ch * 4);
-                y[i] = *reinterpret_cast<const float4*>(b1 + ch * 4);
+            for (int q = 0; q < 4; ++q) {
+                const f32x4 v = {acc[dt][4 * q], acc[dt][4 * q + 1], acc[dt][4 * q + 2], acc[dt][4 * q + 3]};
+                *reinterpret_cast<bf16x4*>(mine + (dt * 32 + 8 * q + 4 * half) * 2) = __builtin_convertvector(v, bf16x4);
             }
-        }
+        if (half == 0) *reinterpret_cast<float2*>(mine + D * 2) = make_float2(m_ref, l_tot);
+        // (a wave's LDS operations complete in order, and the reads below wait for them: no barrier inside a wave)
+        const int rows_here = min(32, group_rows - wave * 32);
+        unsigned char* out = out_base + static_cast<long>(wave) * 32 * PART_ROW_B;
+        // parked rows and partial rows have the same pitch, so the wave's block goes out as one contiguous copy of
+        // rows_here * 17 chunks of 16 bytes (16 of O^T, one of max and sum), 64 chunks per store instruction
+        const int last_chunk = rows_here * (PART_ROW_B / 16);
 #pragma unroll
-        for (int i = 0; i < PASSES; ++i) {
-            const int row = (tid >> 5) + i * (THREADS / 32);
-            if (row < group_rows) {
-                const float m0 = ml0[i].x, l0 = ml0[i].y, m1 = ml1[i].x, l1 = ml1[i].y;
-                const float m_new = fmaxf(m0, m1);
-                const float w0 = (m0 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m0 - m_new) * c);
-                const float w1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((m1 - m_new) * c);
-                float* out = out_base + row * PART_FLOATS;
-                *reinterpret_cast<float4*>(out + ch * 4) = make_float4(x[i].x * w0 + y[i].x * w1, x[i].y * w0 + y[i].y * w1,
-                                                                       x[i].z * w0 + y[i].z * w1, x[i].w * w0 + y[i].w * w1);
-                if (ch == 0) { out[D] = m_new; out[D + 1] = l0 * w0 + l1 * w1; }
-            }
+        for (int i = 0; i < 9; ++i) {
+            const int ch = lane + 64 * i;
+            if (ch < last_chunk)
+                *reinterpret_cast<uint4*>(out + ch * 16) = *reinterpret_cast<const uint4*>(blk + ch * 16);
         }
     }
     };   // run_segment
@@ -538,7 +590,7 @@ __device__ __forceinline__ void attention_workgroup(const int* __restrict__ kv_l
         const int t_begin = split * sp.tiles_per_split;
         const int t_end = min(sp.tiles, t_begin + sp.tiles_per_split);
         run_segment(b, L, sp.n, sp.rows, cg, t_begin, t_end, sp.tiles - 1, start_b,
-                    prm.part + ((static_cast<long>(b) * prm.Hkv + g) * prm.nslot + slot) * ROWS_PER_WG * PART_FLOATS);
+                    prm.part + ((static_cast<long>(b) * prm.Hkv + g) * prm.nslot + slot) * PART_SLOT_B);
     } else {
         const BatchShape bs = make_batch_shape(prm, lane);  // lane b holds sequence b
         const int r0 = id * bs.q;                            // this workgroup's range of the tile list
@@ -559,7 +611,7 @@ __device__ __forceinline__ void attention_workgroup(const int* __restrict__ kv_l
                     const int lo = max(r0, tile0), hi = min(r1, tile0 + tiles_b);
                     if (lo < hi)
                         run_segment(b, L_b, n_b, n_b * prm.G, cg, lo - tile0, hi - tile0, tiles_b - 1, start_b,
-                                    prm.part + (static_cast<long>(g) * prm.nslot + id + groups_before + cg) * ROWS_PER_WG * PART_FLOATS);
+                                    prm.part + (static_cast<long>(g) * prm.nslot + id + groups_before + cg) * PART_SLOT_B);
                 }
             }
             first += seg_len * cgs_b;
@@ -587,7 +639,7 @@ __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const int*
 // when the attention's own workgroups fill every CU, the one that has to wait for a free CU is then the attention's
 // last (a sequence's final split, seldom a full one), and it waits for the short planning workgroup, not the other
 // way round.
-constexpr int PLAN_LDS_KEYS = 2432;     // what the 160 KB of a CU leave beside the attention's stages (k = 16 at 152064 tokens: 2384)
+constexpr int PLAN_LDS_KEYS = 2400;     // what the 160 KB of a CU leave beside the attention's stages (k = 16 at 152064 tokens: 2384)
 constexpr int PLAN_OWN = 4;              // slices per lane: up to 256 slices per draft row
 struct PlanShared {
     static constexpr int LDS_KEYS = PLAN_LDS_KEYS;
@@ -621,7 +673,7 @@ __global__ __launch_bounds__(THREADS) void tree_attention_plan_kernel(const int*
 // lane = split for the (max, sum) pairs and their weights, lane = pair of output dims for the accumulation.
 // Every partial of the row is requested before the first one is used, so the merge costs one memory round trip.
 // ROWS = rows (waves) per workgroup.  MAXS = splits handled per pass (one per lane for the (max, sum) pairs, one
-// register pair each for the accumulation); the host picks the smallest instantiation that covers the launch's slot
+// register each for the accumulation); the host picks the smallest instantiation that covers the launch's slot
 // count, which keeps the register count, and with it the number of resident waves, in proportion to the work.
 constexpr int MERGE_ROWS_SINGLE = 4;     // one sequence: many small workgroups spread best over the CUs
 constexpr int MERGE_ROWS_BATCH = 4;      // (16 rows per workgroup measured 6 % slower on the ragged batch of 8)
@@ -632,7 +684,7 @@ __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const i
                                                                          const int* __restrict__ n_nodes_arg, int nslot_arg,
                                                                          int min_tps_arg, int G_arg, int phases_arg,
                                                                          const Params prm) {
-    static_assert(MAXS <= 32, "one split per lane, one register pair per split");
+    static_assert(MAXS <= 32, "one split per lane, one register per split");
     // As in the main kernel, a KV head's blocks are congruent modulo the KV-head count, so with 8 KV heads they run on
     // the XCD whose L2 still holds that head's partials.  Rows of a KV head are numbered as there: node * G + head-in-group.
     const int lane = threadIdx.x & 63;
@@ -643,7 +695,7 @@ __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const i
     // one row: `first_row` = the row in the first of its nsplit partials, stride_b = bytes to the next one.  Addresses are
     // the uniform row pointer plus 32-bit offsets (a launch's partials span far less than 4 GB from any row), which
     // keeps the address arithmetic of up to 32 loads per lane off the critical path of this latency-bound kernel.
-    auto merge_row = [&](int b, int node, int hg, const float* first_row, unsigned stride_b, int nsplit_v) __attribute__((always_inline)) {
+    auto merge_row = [&](int b, int node, int hg, const unsigned char* first_row, unsigned stride_b, int nsplit_v) __attribute__((always_inline)) {
         // wave-uniform by construction; said to the compiler, which cannot see it through the lane exchanges of a batch
         const uintptr_t first_v = reinterpret_cast<uintptr_t>(first_row);
         const uintptr_t first =
@@ -662,18 +714,17 @@ __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const i
             typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
             const __amdgpu_buffer_rsrc_t rows = __builtin_amdgcn_make_buffer_rsrc(
                 reinterpret_cast<unsigned char*>(first + static_cast<size_t>(s0) * stride_b), 0,
-                static_cast<int>(static_cast<unsigned>(cnt - 1) * stride_b + PART_FLOATS * 4u), 0x00020000);
+                static_cast<int>(static_cast<unsigned>(cnt - 1) * stride_b + PART_ROW_B), 0x00020000);
             {
-                const u32x2 pair = __builtin_amdgcn_raw_buffer_load_b64(rows, static_cast<unsigned>(lane) * stride_b + D * 4u, 0, 0);
+                const u32x2 pair = __builtin_amdgcn_raw_buffer_load_b64(rows, static_cast<unsigned>(lane) * stride_b + D * 2u, 0, 0);
                 ms = lane < cnt ? __uint_as_float(pair[0]) : -INFINITY;
                 ls = lane < cnt ? __uint_as_float(pair[1]) : 0.f;
             }
-            float2 v[MAXS];
-            unsigned off = 8u * lane;                        // the whole offset goes through the per-lane operand: that one is
+            unsigned v[MAXS];                                // two bf16 output dims of split s
+            unsigned off = 4u * lane;                        // the whole offset goes through the per-lane operand: that one is
 #pragma unroll                                               // bounds-checked, the scalar offset operand is not
             for (int s = 0; s < MAXS; ++s) {
-                const u32x2 x = __builtin_amdgcn_raw_buffer_load_b64(rows, off, 0, 0);
-                v[s] = make_float2(__uint_as_float(x[0]), __uint_as_float(x[1]));
+                v[s] = __builtin_amdgcn_raw_buffer_load_b32(rows, off, 0, 0);
                 off += stride_b;
             }
             __builtin_amdgcn_sched_barrier(0);               // every load is out before the first wait: one round trip
@@ -687,7 +738,8 @@ __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const i
 #pragma unroll
             for (int s = 0; s < MAXS; ++s) {
                 const float ws = sage::lane_value(w, s);        // split s's weight, through a scalar register
-                o.x += ws * v[s].x; o.y += ws * v[s].y;
+                o.x += ws * __uint_as_float(v[s] << 16);
+                o.y += ws * __uint_as_float(v[s] & 0xFFFF0000u);
             }
         }
         const float inv = 1.0f / l_all;
@@ -708,10 +760,10 @@ __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const i
         const int L = len_b > 0 ? len_b : 0;
         const Split sp = make_split(n_b, L, G_arg, nslot_arg, min_tps_arg);
         if (sp.col_groups > nslot_arg) return;
-        const float* base = prm.part + ((static_cast<long>(b) * prm.Hkv + g) * prm.nslot) * ROWS_PER_WG * PART_FLOATS;
+        const unsigned char* base = prm.part + ((static_cast<long>(b) * prm.Hkv + g) * prm.nslot) * PART_SLOT_B;
         for (int m = phase * ROWS + wave; m < sp.rows; m += phases * ROWS)
-            merge_row(b, m / prm.G, m % prm.G, base + (static_cast<long>(m / ROWS_PER_WG) * ROWS_PER_WG + m % ROWS_PER_WG) * PART_FLOATS,
-                      static_cast<unsigned>(sp.col_groups) * (ROWS_PER_WG * PART_FLOATS * 4u), sp.nsplit);
+            merge_row(b, m / prm.G, m % prm.G, base + (static_cast<long>(m / ROWS_PER_WG) * ROWS_PER_WG + m % ROWS_PER_WG) * PART_ROW_B,
+                      static_cast<unsigned>(sp.col_groups) * static_cast<unsigned>(PART_SLOT_B), sp.nsplit);
     } else {
         const BatchShape bs = make_batch_shape(prm, lane);
         const int live = __builtin_amdgcn_readlane(bs.n, b) * prm.G;
@@ -723,8 +775,8 @@ __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const i
             const int u0 = before + cg * (tiles_b + SEG_COST_TILES) + SEG_COST_TILES;   // first tile of segment (b, cg)
             const int s_first = u0 / bs.q;
             merge_row(b, m / prm.G, m % prm.G,
-                      prm.part + ((static_cast<long>(g) * prm.nslot + s_first + groups_before + cg) * ROWS_PER_WG + m % ROWS_PER_WG) * PART_FLOATS,
-                      ROWS_PER_WG * PART_FLOATS * 4u, (u0 + tiles_b - 1) / bs.q - s_first + 1);
+                      prm.part + (static_cast<long>(g) * prm.nslot + s_first + groups_before + cg) * PART_SLOT_B + (m % ROWS_PER_WG) * PART_ROW_B,
+                      static_cast<unsigned>(PART_SLOT_B), (u0 + tiles_b - 1) / bs.q - s_first + 1);
         }
     }
 }
@@ -780,8 +832,7 @@ LaunchShape attention_bf16_shape(int B, int Hkv, int G, int max_kv_len) {
 
 size_t attention_bf16_workspace_bytes(int B, int Hkv, int G, int max_kv_len) {
     const LaunchShape sh = attention_bf16_shape(B, Hkv, G, max_kv_len);
-    const size_t per_slot = static_cast<size_t>(ROWS_PER_WG) * PART_FLOATS * sizeof(float);
-    return (sh.batch ? static_cast<size_t>(1) : static_cast<size_t>(B)) * Hkv * sh.nslot * per_slot;
+    return (sh.batch ? static_cast<size_t>(1) : static_cast<size_t>(B)) * Hkv * sh.nslot * static_cast<size_t>(PART_SLOT_B);
 }
 
 // Whether the attention launch can carry this planning along: the lists of a draft row must fit the LDS the planning
@@ -808,7 +859,7 @@ int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const voi
     p.Q = static_cast<const uint16_t*>(Q); p.Kc = static_cast<const uint16_t*>(Kc); p.Vc = static_cast<const uint16_t*>(Vc);
     p.Kt = static_cast<const uint16_t*>(Kt); p.Vt = static_cast<const uint16_t*>(Vt); p.O = static_cast<uint16_t*>(O);
     p.kv_start = kv_start; p.kv_len = kv_len; p.anc_mask = anc_mask; p.n_nodes = n_nodes;
-    p.part = static_cast<float*>(workspace);
+    p.part = static_cast<unsigned char*>(workspace);
     p.kv_token_stride = kv_token_stride; p.kv_head_stride = kv_head_stride;
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.G = G;
     const LaunchShape sh = attention_bf16_shape(B, Hkv, G, max_kv_len);

@@ -74,7 +74,7 @@ def test_static_scratch_limit_and_fp32():
     limit = sage.sage_tree_attention_static_scratch_bytes()
     assert limit == 40 << 20
     assert sage.sage_tree_attention_workspace_bytes(sage.BF16, 8, Hq, Hkv, d, 12288) <= limit
-    too_many = 16
+    too_many = 24
     assert sage.sage_tree_attention_workspace_bytes(sage.BF16, too_many, Hq, Hkv, d, 12288) > limit
     c = _case(14, [300] * too_many, [3] * too_many)
     with pytest.raises(sage.SageError) as e:
