@@ -23,7 +23,9 @@
  *   - Per-sequence tree arrays have a fixed stride of SAGE_MAX_NODES entries; entries at or
  *     beyond n_nodes[b] are neither read nor written.  Node 0 is the root (the last
  *     committed token); nodes are in creation order (depth-first, pre-order), so
- *     parent[v] < v.
+ *     parent[v] < v.  A tree always has its root: every call that takes n_nodes treats a
+ *     value below 1 as 1 and a value above SAGE_MAX_NODES as SAGE_MAX_NODES.  (Row groups of
+ *     sage_entropy_topk are a different thing: n_valid[g] = 0 processes no row of group g.)
  *   - Return value: SAGE_OK, or an error code; on error nothing has been enqueued.
  *   - Logits must be finite or -inf (NaN / +inf give unspecified values, never a fault).
  */

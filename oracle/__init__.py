@@ -20,13 +20,25 @@ MAX_NODES = 64
 F32, BF16 = 0, 1
 
 
-def build(force: bool = False) -> str:
-    """Compile the oracle with the host C compiler (no HIP, no contraction)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+_LIB_SAN = os.path.join(_HERE, "libsage_oracle_san.so")
+SANITIZE = os.environ.get("SAGE_ORACLE_SANITIZE", "") not in ("", "0")
+
+
+def build(force: bool = False, sanitize: bool | None = None) -> str:
+    """Compile the oracle with the host C compiler (no HIP, no contraction).
+
+    With sanitize (or SAGE_ORACLE_SANITIZE=1 in the environment) the library is built with AddressSanitizer and
+    UndefinedBehaviorSanitizer, any report fatal; the process that loads it must have the ASan runtime preloaded
+    (tests/test_oracle_sanitized.py runs the oracle's own tests that way)."""
+    sanitize = SANITIZE if sanitize is None else sanitize
+    out = _LIB_SAN if sanitize else _LIB
+    if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
+        flags = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer"] \
+            if sanitize else ["-O2"]
         subprocess.check_call(
-            ["gcc", "-O2", "-std=c99", "-fopenmp", "-ffp-contract=off", "-fno-fast-math", "-shared", "-fPIC",
-             "-o", _LIB, _SRC, "-lm"])
-    return _LIB
+            ["gcc", *flags, "-std=c99", "-fopenmp", "-ffp-contract=off", "-fno-fast-math", "-shared", "-fPIC",
+             "-o", out, _SRC, "-lm"])
+    return out
 
 
 _lib = None

@@ -35,7 +35,7 @@ __global__ __launch_bounds__(THREADS) void tree_attention_f32_kernel(
 
     const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     int n = n_nodes[b];
-    n = n > SAGE_MAX_NODES ? SAGE_MAX_NODES : n;
+    n = n < 1 ? 1 : (n > SAGE_MAX_NODES ? SAGE_MAX_NODES : n);   // a tree always has its root
     if (i >= n) return;
     const int tid = threadIdx.x;
     const int g = h / (Hq / Hkv);

@@ -1,6 +1,7 @@
-// The acceptance rule of sage_verify_accept as a wave-level device function (Sec. 2.2 "longest prefix matching the
-// target's predictions"; Sec. 3.3 Phase 2 "all draft tokens along the path match"; Def. 4.1), shared by the kernel that
-// runs it on its own (verify_accept.hip) and by the kernel that first finishes the target's argmax (fused_steps.hip).
+// The acceptance rule of sage_verify_accept as a wave-level device function: the prefix-AND of the per-node match bits
+// along every root-to-node path, deepest fully matched node wins (Sec. 2.2; Sec. 3.3 Phase 2; Def. 4.1), shared by the
+// kernel that runs it on its own (verify_accept.hip) and by the kernel that first finishes the target's argmax
+// (fused_steps.hip).
 //
 // One wave64 per sequence, lane i = tree node i.  The per-node match bits are gathered with one ballot;
 // node i is accepted iff its ancestor-or-self mask has no unmatched bit, so the prefix-AND along every

@@ -95,15 +95,15 @@ def ragged_kv_lens(seed: int, B: int, lo: int, hi: int) -> np.ndarray:
     return rng(seed).integers(lo, hi + 1, size=B).astype(np.int32)
 
 
-# Mean full-vocabulary entropy (nats) of softmax(beta * z), z ~ N(0,1)^152064 stored as bf16, measured once over
-# six seeds; used only to steer the logit scale toward a requested entropy.  Individual rows scatter around it
-# (the low end depends on the gap between the two largest draws), which is fine: the table shapes inputs, the
-# kernels report what the entropy actually is.
+# Mean full-vocabulary entropy (nats) of softmax(beta * z), z ~ N(0,1)^152064 stored as bf16, over six seeds, as
+# printed by tests/golden/make_entropy_scale_table.py; used only to steer the logit scale toward a requested entropy.
+# Individual rows scatter around it (the low end depends on the gap between the two largest draws), which is fine:
+# the table shapes inputs, the kernels report what the entropy actually is.
 _ENTROPY_TO_SCALE_152064 = [
-    (11.81, 0.5), (11.43, 1.0), (10.81, 1.5), (9.94, 2.0), (8.83, 2.5), (7.54, 3.0), (6.85, 3.25), (6.18, 3.5),
-    (5.54, 3.75), (4.95, 4.0), (4.37, 4.25), (3.92, 4.5), (3.48, 4.75), (3.12, 5.0), (2.53, 5.5), (2.06, 6.0),
-    (1.73, 6.5), (1.47, 7.0), (1.09, 8.0), (0.86, 9.0), (0.70, 10.0), (0.48, 12.0), (0.36, 14.0), (0.27, 17.0),
-    (0.22, 20.0), (0.17, 25.0), (0.14, 30.0), (0.05, 60.0),
+    (11.81, 0.5), (11.43, 1.0), (10.81, 1.5), (9.94, 2.0), (8.83, 2.5), (7.56, 3.0), (6.91, 3.25), (6.28, 3.5),
+    (5.70, 3.75), (5.19, 4.0), (4.71, 4.25), (4.30, 4.5), (3.94, 4.75), (3.61, 5.0), (3.10, 5.5), (2.67, 6.0),
+    (2.37, 6.5), (2.09, 7.0), (1.69, 8.0), (1.41, 9.0), (1.19, 10.0), (0.89, 12.0), (0.70, 14.0), (0.48, 17.0),
+    (0.37, 20.0), (0.24, 25.0), (0.19, 30.0), (0.13, 60.0),
 ]
 
 

@@ -215,6 +215,12 @@ def test_paper_hyperparameters_fixture():
     for name in ("c2", "c4", "c5"):
         assert wl.CONFIGS[name]["tree"] == gold["tree"]
     assert gold["alpha_init"] == 0.5
+    # Thm. 4.4 prints its confidence threshold for k = 10, eps = 0.05 as about 0.56: (k - 2 + 4 eps k) / (2 (k - 1))
+    k, eps = gold["tree"]["k"], 0.05
+    assert abs((k - 2 + 4 * eps * k) / (2 * (k - 1)) - gold["thm_4_4_threshold_k10_eps005"]) < 5e-3
+    # the confidence of Alg. 1's initial state lies below it, the peaked end point above
+    peaked = oracle.entropy_topk(np.array([[50.0] + [0.0] * 63], F), k)
+    assert gold["alpha_init"] < gold["thm_4_4_threshold_k10_eps005"] < float(peaked["alpha"][0])
 
 
 def test_node_token_is_the_candidate_of_the_nodes_rank():
