@@ -7,8 +7,10 @@ A step is one pass of the whole path over one batch of synthetic input:
   a3  sage_tree_attention once per layer, on the tree built one step ago
   a1' sage_entropy_topk   k = 1 over the per-node target logits         -> the target's greedy token per node
   a4  sage_verify_accept
-All inputs are resident in HBM before the timed region; input sets rotate so that consecutive steps do not find
-their KV cache or logits in L2 / Infinity Cache.  Prints ONE JSON line.
+All inputs are resident in HBM before the timed region; logits and query/tree inputs cycle through one input set per
+step of the configuration, the KV cache through enough sets that consecutive steps do not find it in L2 / Infinity
+Cache.  The timed region is a HIP graph of the requested steps, replayed until at least a few milliseconds have been
+timed; every graph is first checked bit for bit against eager execution of the same steps.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -26,14 +28,27 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
 MAX_NODES = 64
-# HBM bytes of one attention launch (main kernel + split merge) from rocprofv3 FETCH_SIZE/WRITE_SIZE runs, scaled by
-# the counters' readings for a 64 MiB copy (profiles/tree_attention_c2_hbm_traffic.md); workloads not profiled: null.
-MEASURED_TRAFFIC_BYTES = {"c2": 35.5e6}
+MIN_TIMED_MS = 5.0              # the timed region is stretched to at least this by replaying the captured steps
+# HBM bytes of one sage_tree_attention call (main kernel + split merge) per workload, from the rocprofv3 FETCH_SIZE /
+# WRITE_SIZE runs summarised under profiles/ (scaled by the counters' readings for a 64 MiB copy); the summaries state
+# the command, the tree sizes and the split count they were taken at.  Workloads not profiled: null.
+MEASURED_TRAFFIC_BYTES = {}
+try:
+    with open(os.path.join(ROOT, "profiles", "tree_attention_hbm_traffic.json")) as _f:
+        MEASURED_TRAFFIC_BYTES = {k: float(v["bytes_per_call"]) for k, v in json.load(_f).items() if not k.startswith("_")}
+except (OSError, ValueError, KeyError):
+    pass
 
 # Trees of the 80-layer configuration are asked to have 64 nodes every step.  With the paper's own parameters the
 # rule never grows a tree that large, so that workload plants a geometric top-64 distribution (ratio 1/2) in the
 # draft row and builds with a wide/deep parameter set, for which the rule saturates the 64-node cap.
 C5_TREE = dict(d_min=31, d_max=31, w_min=16, w_max=16, k=64, n_max=64)
+WORKLOAD_TEXT = {
+    "toy": "Toy fp32, 4/1 heads d64, KV 256, vocab 1024",
+    "c2": "one layer at the 72B shape (64/8 heads, d128, bf16), KV 4096, vocab 152064, adaptive tree <= 64 nodes, batch 1",
+    "c3": "72B shape (64/8 heads, d128, bf16), one layer, video-length KV 16384, 256 steps of AR(1) entropy-driven trees, vocab 152064, batch 1",
+    "c4": "72B shape, batch 8, ragged KV 2048..12288, ragged trees, vocab 152064",
+    "c5": "80-layer attention stack at the 72B shape, KV 32768 per layer, 64-node tree, vocab 152064"}
 
 
 def parse():
@@ -41,17 +56,18 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c2", choices=["toy", "c2", "c3", "c4", "c5"])
-    ap.add_argument("--slots", type=int, default=None, help="number of rotating input sets")
-    ap.add_argument("--no-carry", action="store_true",
-                    help="time the two-stream schedule instead of planning carried in the attention launch")
+    ap.add_argument("--workload", default="c3", choices=["toy", "c2", "c3", "c4", "c5"],
+                    help="the workload `value` and `roofline` are measured on (default: the long-KV single-layer configuration)")
+    ap.add_argument("--slots", type=int, default=None, help="number of input sets (default: the configuration's step count)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
-                    help="skip the long-KV attention, closed-loop and output-projection measurements")
-    ap.add_argument("--only", default=None, choices=["long_kv", "closed_loop", "lm_head", "entropy_topk", "draft_side"],
-                    help="run one of the extra measurements alone and print its JSON (for profiling it)")
+                    help="skip the other workloads and the closed-loop, output-projection, top-k and draft-side measurements")
+    ap.add_argument("--all-schedules", action="store_true",
+                    help="also time the headline workload with planning on a second stream and as launches of its own")
+    ap.add_argument("--only", default=None, choices=["attention", "closed_loop", "lm_head", "entropy_topk", "draft_side"],
+                    help="run one measurement alone and print its JSON (for profiling it); `attention` = graph replays of the "
+                         "sage_tree_attention calls of --workload")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
-    ap.add_argument("--no-overlap", action="store_true", help="time the single-stream step instead of the overlapped one")
     ap.add_argument("--eager", action="store_true", help="time the steps eagerly instead of as HIP-graph replays")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run plain 64 MiB device copies, the known-size reference for rocprofv3 FETCH_SIZE/WRITE_SIZE")
@@ -61,7 +77,8 @@ def parse():
 class Workload:
     """Device-resident synthetic inputs of one configuration plus every output/scratch buffer of a step."""
 
-    def __init__(self, name: str, slots: int | None, fused: bool = True, overlap: bool = False, carry: bool = False):
+    def __init__(self, name: str, slots: int | None = None, fused: bool = True, overlap: bool = False, carry: bool = False,
+                 layers: int | None = None, keep_layer_outputs: bool = False):
         import numpy as np
         import torch
         from paper_2602_00523_amd import sage, workloads as wl
@@ -71,7 +88,8 @@ class Workload:
         dev = "cuda:0"
         self.dtype = torch.float32 if cfg["dtype"] == "f32" else torch.bfloat16
         B, Hq, Hkv, d, V = cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["d"], cfg["vocab"]
-        self.B, self.Hq, self.Hkv, self.d, self.V, self.layers = B, Hq, Hkv, d, V, cfg["layers"]
+        self.B, self.Hq, self.Hkv, self.d, self.V = B, Hq, Hkv, d, V
+        self.layers = cfg["layers"] if layers is None else layers
         self.tree_prm = dict(C5_TREE) if name == "c5" else dict(cfg["tree"])
         self.k = self.tree_prm["k"]
         if isinstance(cfg["kv_len"], tuple):
@@ -83,11 +101,14 @@ class Workload:
         esz = 4 if cfg["dtype"] == "f32" else 2
         kv_bytes = 2 * total * Hkv * d * esz * self.layers
         logit_bytes = (B * MAX_NODES + B) * V * esz
-        if slots is None:                       # rotate through > 512 MB of KV and of logits, bounded to ~6 GB
-            slots = max(2, min(32, math.ceil(600e6 / max(kv_bytes, 1))))
-            slots = max(1, min(slots, int(6e9 // (kv_bytes + logit_bytes))))
-        self.kv_slots = 1 if self.layers > 1 else slots
-        self.slots = max(slots, 4) if self.layers > 1 else slots
+        # One input set (draft row, per-node target rows, Q, tree K/V) per step of the configuration, so that the tree
+        # sequence is the configuration's own (c3: all 256 steps of its AR(1) entropy process); the KV cache rotates
+        # through its own, smaller number of sets: more than 512 MB in total, so that no step finds its cache on chip
+        # (a multi-layer stack already walks through that much within a step).
+        if slots is None:
+            slots = max(2, min(cfg["steps"], int(12e9 // max(logit_bytes, 1))))
+        self.slots = slots
+        self.kv_slots = 1 if kv_bytes > 600e6 else max(1, min(slots, math.ceil(600e6 / max(kv_bytes, 1))))
         gen = torch.Generator(device=dev)
         gen.manual_seed(wl.seed_for(name))
 
@@ -147,6 +168,8 @@ class Workload:
                           node_token=i32(B, MAX_NODES) - 1) for _ in range(2)]
         self.prm = sage.tree_params(**self.tree_prm)
         self.O = torch.zeros(B, MAX_NODES, Hq, d, device=dev, dtype=self.dtype)
+        # tests keep every layer's output; the benchmark, like a model, lets each layer overwrite the last one's
+        self.O_layers = [torch.zeros_like(self.O) for _ in range(self.layers)] if keep_layer_outputs else None
         code = sage.F32 if self.dtype == torch.float32 else sage.BF16
         self.ws3 = torch.empty(sage.sage_tree_attention_workspace_bytes(code, B, Hq, Hkv, d, self.max_len), device=dev,
                                dtype=torch.uint8)
@@ -191,7 +214,8 @@ class Workload:
             t, nxt = self.tree[cur], self.tree[cur ^ 1]
             if self.carry:
                 self.c_a3p.append([sg.prepare("sage_tree_attention_with_plan", self.Q[s], self.Kc[s % self.kv_slots][0],
-                                              self.Vc[s % self.kv_slots][0], self.Kt[s], self.Vt[s], self.O, self.kv_start,
+                                              self.Vc[s % self.kv_slots][0], self.Kt[s], self.Vt[s],
+                                              self.O if self.O_layers is None else self.O_layers[0], self.kv_start,
                                               self.kv_len, self.max_len, self.Hkv * self.d, self.d, t["anc_mask"], t["n_nodes"],
                                               self.scale, self.ws3, self.ws1, V, self.prm, self.H, self.idx, self.prob,
                                               self.renorm, self.Hk, self.alpha, nxt["n_nodes"], nxt["parent"], nxt["depth"],
@@ -206,7 +230,8 @@ class Workload:
                                             nxt["parent"], nxt["depth"], nxt["rank"], nxt["anc_mask"], None, self.idx,
                                             nxt["node_token"], stream=pstream))
             self.c_a3.append([[sg.prepare("sage_tree_attention", self.Q[s], self.Kc[s % self.kv_slots][layer],
-                                          self.Vc[s % self.kv_slots][layer], self.Kt[s], self.Vt[s], self.O, self.kv_start,
+                                          self.Vc[s % self.kv_slots][layer], self.Kt[s], self.Vt[s],
+                                          self.O if self.O_layers is None else self.O_layers[layer], self.kv_start,
                                           self.kv_len, self.max_len, self.Hkv * self.d, self.d, t["anc_mask"], t["n_nodes"],
                                           self.scale, self.ws3, stream=stream) for layer in range(self.layers)]
                               for s in range(self.slots)])
@@ -233,13 +258,13 @@ class Workload:
     def attention(self, s, layer):
         self.c_a3[self.cur][s][layer]()
 
-    def step(self, events=None):
+    def step(self):
         s = self.step_no % self.slots
         cur = self.cur
         if self.overlap:                             # fork: the plan branch starts where the main stream stands
             main = self.torch.cuda.current_stream()
             self.plan_stream.wait_stream(main)
-        if self.carry and events is None:
+        if self.carry:
             self.c_a1[s]()
             self.c_a3p[cur][s]()                     # first layer's attention with the planning inside its launch
             for call in self.c_a3[cur][s][1:]:
@@ -252,17 +277,8 @@ class Workload:
         if not (self.overlap and self.verify_first):
             self.c_a1[s]()
             self.c_a2[cur]()
-        if events is None:
-            for call in self.c_a3[cur][s]:
-                call()
-        else:
-            for call in self.c_a3[cur][s]:
-                e0, e1 = events[self.ev_used], events[self.ev_used + 1]
-                self.ev_used += 2
-                self.pad_dst.copy_(self.pad_src)      # keeps the queue busy so the start event is not reached early
-                e0.record()
-                call()
-                e1.record()
+        for call in self.c_a3[cur][s]:
+            call()
         self.c_a1t[cur][s]()
         self.c_a4[cur]()
         if self.overlap and self.verify_first:       # the plan branch is enqueued after the verification branch
@@ -285,35 +301,52 @@ class Workload:
 
 
 def snapshot(w: Workload):
-    t = w.tree[w.cur]
-    return [x.clone() for x in (w.O, w.acc_len, w.best, w.path, w.out_tok, w.tgt_idx, w.alpha, t["n_nodes"], t["parent"],
-                                t["anc_mask"], t["node_token"])]
+    """What a step leaves behind, with everything the calls do not write blanked out: output rows of nodes past the
+    verified tree's size and entries of the planned tree past its size keep whatever an earlier step left there,
+    which depends on the steps before and is no part of the state."""
+    torch = w.torch
+    planned, verified = w.tree[w.cur], w.tree[w.cur ^ 1]      # planned by the last step / verified by it
+    node = torch.arange(MAX_NODES, device=w.O.device)[None, :]
+    live_v = node < verified["n_nodes"][:, None]
+    live_p = node < planned["n_nodes"][:, None]
+    outs = w.O_layers if w.O_layers is not None else [w.O]
+    state = [torch.where(live_v[:, :, None, None], o, torch.zeros_like(o)) for o in outs]
+    state.append(torch.where(live_v.reshape(-1, 1), w.tgt_idx, torch.full_like(w.tgt_idx, -1)))
+    state += [x.clone() for x in (w.acc_len, w.best, w.path, w.out_tok, w.alpha, planned["n_nodes"])]
+    state += [torch.where(live_p, planned[k], torch.zeros_like(planned[k])) for k in ("parent", "anc_mask", "node_token")]
+    return state
 
 
-def capture_cycle(w: Workload):
-    """Record one full cycle over the input sets as a HIP graph and check its replays against eager execution.
+def capture_steps(w: Workload, length: int):
+    """Record the next `length` steps (an even number: the two tree buffers swap roles every step) as a HIP graph and
+    check its replays against eager execution.
 
-    A cycle returns the step state (tree buffers, input-set index) to where it started, so every replay computes
-    what an eager cycle computes; that is checked bit for bit on three replays with eager cycles in between.
-    Returns (graph, steps_per_replay) or (None, 0) when capture is unavailable or a replay disagrees.
+    The graph bakes in which input sets and tree buffers its steps use, so every replay runs the same `length` steps
+    again, each starting from the tree the previous pass planned last; an eager pass over the same steps does exactly
+    the same, and three replays, with eager passes in between, must each land in the eager pass's state bit for bit.
+    Returns the graph, or None when capture is unavailable or a replay disagrees.
     """
     torch = w.torch
-    cycle = w.slots if w.slots % 2 == 0 else 2 * w.slots
-    while w.step_no % cycle:                      # align to a cycle boundary
-        w.step()
+    assert length % 2 == 0
+    start = (w.step_no, w.cur)
+
+    def eager_pass():
+        w.step_no, w.cur = start
+        for _ in range(length):
+            w.step()
+
     torch.cuda.synchronize()
     try:
         side = torch.cuda.Stream()
         w._prepare(side)
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
-            for _ in range(cycle):
-                w.step()
+            eager_pass()                                  # (recorded, not executed)
         w._prepare(None)
         torch.cuda.synchronize()
+        eager_pass()
         for _ in range(3):
-            for _ in range(cycle):
-                w.step()
+            eager_pass()
             torch.cuda.synchronize()
             want = snapshot(w)
             graph.replay()
@@ -321,75 +354,72 @@ def capture_cycle(w: Workload):
             got = snapshot(w)
             if not all(torch.equal(a, b) for a, b in zip(want, got)):
                 print("bench.py: graph replay differs from eager execution; timing eagerly", file=sys.stderr)
-                return None, 0
-        return graph, cycle
+                return None
+        return graph
     except Exception as ex:  # capture unsupported on this stack: time eagerly
         print(f"bench.py: graph capture unavailable ({type(ex).__name__}); timing eagerly", file=sys.stderr)
         w._prepare(None)
-        return None, 0
+        w.step_no, w.cur = start
+        return None
 
 
-def time_steps(w: Workload, steps: int, warmup: int, use_graph: bool):
-    """Timed region: exactly `steps` steps, as graph replays of whole cycles (plus an eager remainder) or eagerly."""
+def capture_cycle(w: Workload):
+    """capture_steps over one whole cycle of the input sets, from a cycle boundary.  Returns (graph, steps per replay)
+    or (None, 0)."""
+    cycle = w.slots if w.slots % 2 == 0 else 2 * w.slots
+    while w.step_no % cycle:
+        w.step()
+    graph = capture_steps(w, cycle)
+    return (graph, cycle) if graph is not None else (None, 0)
+
+
+def time_steps(w: Workload, steps: int, warmup: int, use_graph: bool = True, min_ms: float = MIN_TIMED_MS):
+    """The timed region.  `steps` consecutive steps are captured as one HIP graph (2 * steps when steps is odd, whole
+    input-set cycles when steps exceeds a cycle) and the graph is replayed as often as it takes to time at least
+    `steps` steps and at least `min_ms` milliseconds.  Returns a dict with the wall time, the number of steps actually
+    timed and how they were launched; nothing is labelled a replay that was not one."""
     torch = w.torch
     for _ in range(warmup):
         w.step()
+    if w.step_no % 2:
+        w.step()
     torch.cuda.synchronize()
-    graph, cycle = capture_cycle(w) if use_graph else (None, 0)
+    cycle = w.slots if w.slots % 2 == 0 else 2 * w.slots
+    if steps >= cycle:
+        while w.step_no % cycle:
+            w.step()
+        length = cycle
+    else:
+        length = steps if steps % 2 == 0 else 2 * steps
+    graph = capture_steps(w, length) if use_graph else None
+    torch.cuda.synchronize()
+    if graph is None:
+        n = max(steps, 1)
+        t0 = time.perf_counter()
+        for _ in range(n):
+            w.step()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return dict(wall_s=wall, timed_steps=n, replays=0, steps_per_replay=0, eager_steps=n, launch_mode="eager launches")
+    t0 = time.perf_counter()                                    # one untimed-looking probe that is timed on its own
+    graph.replay()
+    torch.cuda.synchronize()
+    probe = max(time.perf_counter() - t0, 1e-6)
+    replays = max(math.ceil(steps / length), math.ceil(min_ms * 1e-3 / probe))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    done = 0
-    if graph is not None:
-        while done + cycle <= steps:
-            graph.replay()
-            done += cycle
-            w.step_no += cycle
-    while done < steps:
-        w.step()
-        done += 1
+    for _ in range(replays):
+        graph.replay()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    return wall, graph is not None
+    return dict(wall_s=wall, timed_steps=replays * length, replays=replays, steps_per_replay=length, eager_steps=0,
+                launch_mode=f"HIP graph replay: {replays} replays of a graph of {length} consecutive steps")
 
 
-def time_attention_launches(w: Workload, steps: int):
-    """Eager measurement pass over `steps` steps with HIP events around every sage_tree_attention call.
-
-    Launching from Python is slower than these kernels run, so an idle queue would let the start event fire before
-    the kernel is even submitted; a 64 MiB device copy is queued ahead of every start event, which keeps the GPU
-    busy while the host enqueues event, kernels and event (and leaves the caches cold for the attention launch).
-    """
+def planned_trees(w: Workload):
+    """The tree every input set is verified with in the step sequence (the one planned from the previous set), as
+    (mask, count, host sizes) per input set; planning is replayed untimed."""
     torch = w.torch
-    w.pad_src = torch.empty(64 << 20, device="cuda:0", dtype=torch.uint8)
-    w.pad_dst = torch.empty_like(w.pad_src)
-    first = w.step_no
-    events = [torch.cuda.Event(enable_timing=True) for _ in range(2 * steps * w.layers)]
-    w.ev_used = 0
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        w.step(events)
-    torch.cuda.synchronize()
-    eager_wall = time.perf_counter() - t0
-    att_ms = [events[i].elapsed_time(events[i + 1]) for i in range(0, w.ev_used, 2)]
-    # tree sizes seen by those launches: the tree verified at step t was planned at step t-1 from input set
-    # (t-1) % slots; replay that planning (untimed) to read the node counts back
-    sizes, n_log = {}, []
-    for s in range(w.slots):
-        w.draft_confidence(s)
-        w.plan_next_tree()
-        torch.cuda.synchronize()
-        sizes[s] = w.tree[w.cur ^ 1]["n_nodes"].cpu().numpy().copy()
-    for t in range(first, first + steps):
-        n_log.append(sizes[(t - 1) % w.slots])
-    return att_ms, n_log, eager_wall
-
-
-def time_attention_graph(w: Workload, target_launches: int = 2000):
-    """The attention launches of one input-set cycle alone, as a HIP graph: every input set with the tree that the step
-    sequence verifies on it (the one planned from the previous set), replayed between two HIP events on the capture
-    stream.  This is how the launches run inside the timed region (graph replay, no host gaps, rotating K/V buffers),
-    and it is what the per-kernel durations of a rocprofv3 trace add up to.  Returns (us per launch, tree sizes)."""
-    torch, sg = w.torch, w.sage
     masks, counts, sizes = [], [], []
     for s in range(w.slots):
         w.draft_confidence((s - 1) % w.slots)
@@ -399,10 +429,22 @@ def time_attention_graph(w: Workload, target_launches: int = 2000):
         masks.append(t["anc_mask"].clone())
         counts.append(t["n_nodes"].clone())
         sizes.append(t["n_nodes"].cpu().numpy().copy())
+    return masks, counts, sizes
+
+
+def time_attention_graph(w: Workload, min_ms: float = 20.0, max_sets: int = 64):
+    """The sage_tree_attention calls of the step sequence alone, as a HIP graph: input sets in order (at most
+    `max_sets` of them), each with the tree that the sequence verifies on it and with the K/V set its step uses,
+    every layer; replayed between two HIP events on the capture stream until `min_ms` have been timed.  This is how
+    the launches run inside the timed region (graph replay, no host gaps, rotating K/V), and what the per-kernel
+    durations of a rocprofv3 trace add up to.  Returns (us per call, tree sizes of the calls)."""
+    torch, sg = w.torch, w.sage
+    masks, counts, sizes = planned_trees(w)
+    sets = list(range(min(w.slots, max_sets)))
     side = torch.cuda.Stream()
     calls = [sg.prepare("sage_tree_attention", w.Q[s], w.Kc[s % w.kv_slots][layer], w.Vc[s % w.kv_slots][layer], w.Kt[s],
                         w.Vt[s], w.O, w.kv_start, w.kv_len, w.max_len, w.Hkv * w.d, w.d, masks[s], counts[s], w.scale,
-                        w.ws3, stream=side) for s in range(w.slots) for layer in range(w.layers)]
+                        w.ws3, stream=side) for s in sets for layer in range(w.layers)]
     try:
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
@@ -410,17 +452,54 @@ def time_attention_graph(w: Workload, target_launches: int = 2000):
                 c()
     except Exception:
         return None, sizes
-    reps = max(3, target_launches // len(calls))
     with torch.cuda.stream(side):
         graph.replay()
         side.synchronize()
+        t0 = time.perf_counter()
+        graph.replay()
+        side.synchronize()
+        reps = max(2, math.ceil(min_ms * 1e-3 / max(time.perf_counter() - t0, 1e-6)))
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(side)
         for _ in range(reps):
             graph.replay()
         e1.record(side)
     torch.cuda.synchronize()
-    return e0.elapsed_time(e1) * 1e3 / (reps * len(calls)), sizes
+    return e0.elapsed_time(e1) * 1e3 / (reps * len(calls)), [sizes[s] for s in sets]
+
+
+def attention_roofline(w: Workload, name: str):
+    """Roofline entry of the sage_tree_attention call at workload `name` (measured live, see time_attention_graph)."""
+    us, sized = time_attention_graph(w)
+    if us is None:
+        return None
+    per_bytes = sum(w.attention_algorithmic_bytes(n) for n in sized) / len(sized)
+    per_flops = sum(w.attention_flops(n) for n in sized) / len(sized)
+    gbps = per_bytes / (us * 1e-6) / 1e9
+    tflops = per_flops / (us * 1e-6) / 1e12
+    nodes = [int(x) for n in sized for x in n]
+    hist = {}
+    for x in nodes:
+        key = f"{(x - 1) // 8 * 8 + 1}-{(x - 1) // 8 * 8 + 8}"
+        hist[key] = hist.get(key, 0) + 1
+    # a tree of N nodes has arithmetic intensity N * G flop per byte: past about 310 flop/B (39 nodes at G = 8) the
+    # matrix rate, not the HBM rate, is the binding roof
+    mfma_bound = per_flops / per_bytes > MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBPS * 1e9)
+    out = {"workload": name, "kernel": "sage_tree_attention (bf16 MFMA kernel + split merge, per layer call)",
+           "bound": "mfma" if mfma_bound else "hbm",
+           "achieved": tflops if mfma_bound else gbps, "peak": MFMA_BF16_PEAK_TFLOPS if mfma_bound else HBM_PEAK_GBPS,
+           "unit": "TFLOP/s" if mfma_bound else "GB/s",
+           "frac": (tflops / MFMA_BF16_PEAK_TFLOPS) if mfma_bound else gbps / HBM_PEAK_GBPS,
+           "traffic": MEASURED_TRAFFIC_BYTES.get(name), "avg_launch_us": us,
+           "algorithmic_bytes_per_launch": per_bytes, "hbm_GBps": gbps, "hbm_frac": gbps / HBM_PEAK_GBPS,
+           "mfma_TFLOPs": tflops, "mfma_frac": tflops / MFMA_BF16_PEAK_TFLOPS,
+           "mean_tree_nodes": sum(nodes) / len(nodes), "tree_size_histogram": dict(sorted(hist.items(), key=lambda kv: int(kv[0].split("-")[0]))),
+           "calls_timed_per_replay": len(sized) * w.layers,
+           "timing": ("HIP events around graph replays of the step sequence's sage_tree_attention calls alone (each input "
+                      "set with the tree the sequence verifies on it, K/V sets rotating as in the steps), per call")}
+    if w.dtype == w.torch.float32:
+        out.update(kernel="sage_tree_attention (fp32 FMA kernel)", note="launch-latency scale: 131 KB per call")
+    return out
 
 
 def cpu_baseline(w: Workload, budget_s: float):
@@ -466,44 +545,6 @@ def cpu_baseline(w: Workload, budget_s: float):
     return dict(value=n_steps / spent, unit="steps/s", cores=oracle.num_threads(), kind="oracle", sample=sample)
 
 
-def long_kv_attention(names, launches=48):
-    """Attention alone on the long-KV shapes: rotating input sets / layers, HIP events around every launch."""
-    out = []
-    for name in names:
-        import torch
-        w = Workload(name, None)
-        ms, nodes = [], []
-        events = [torch.cuda.Event(enable_timing=True) for _ in range(2 * (launches + 8))]
-        for it in range(launches + 8):
-            s = it % w.slots
-            w.draft_confidence(s)                 # plan the tree of this input set into the other buffer, switch to it
-            w.plan_next_tree()
-            w.cur ^= 1
-            if it >= 8:
-                nodes.append(w.tree[w.cur]["n_nodes"].cpu().numpy().copy())
-            torch.cuda.synchronize()
-            e0, e1 = events[2 * it], events[2 * it + 1]
-            e0.record()
-            w.attention(s, it % w.layers)
-            e1.record()
-            if it >= 8:
-                ms.append((e0, e1))
-        torch.cuda.synchronize()
-        t = [a.elapsed_time(b) for a, b in ms]
-        avg_ms = sum(t) / len(t)
-        bytes_avg = sum(w.attention_algorithmic_bytes(n) for n in nodes) / len(nodes)
-        flops_avg = sum(w.attention_flops(n) for n in nodes) / len(nodes)
-        out.append(dict(workload=name, kv_len=[int(x) for x in w.kv_lens] if w.B > 1 else int(w.max_len),
-                        mean_nodes=float(sum(n.sum() for n in nodes) / len(nodes)),
-                        avg_us=avg_ms * 1e3, min_us=min(t) * 1e3, hbm_GBps=bytes_avg / (avg_ms * 1e-3) / 1e9,
-                        hbm_frac=bytes_avg / (avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                        mfma_TFLOPs=flops_avg / (avg_ms * 1e-3) / 1e12,
-                        mfma_frac=flops_avg / (avg_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS))
-        del w
-        torch.cuda.empty_cache()
-    return out
-
-
 def closed_loop(name="c2", steps=512, carry=True):
     """The step with its loop closed on the device: after acceptance the path's K/V rows are committed to the
     cache, the sequence length advances and the acceptance history adapts the maximum depth that the next tree may
@@ -513,7 +554,7 @@ def closed_loop(name="c2", steps=512, carry=True):
     (bf16 workloads) the planning rides in the attention launch and everything runs on one stream; without it, planning
     runs on a second stream beside the verification."""
     import torch
-    w = Workload(name, None)
+    w = Workload(name, 32)
     carry = carry and w.dtype == torch.bfloat16
     sg, dev = w.sage, "cuda:0"
     B, Hkv, d = w.B, w.Hkv, w.d
@@ -822,6 +863,58 @@ def draft_side_attention(launches=40):
     return out
 
 
+def run_workload(name, steps, warmup, slots=None, eager=False, all_schedules=False, verify=True):
+    """Whole steps of one workload in its timed configuration plus the roofline of its attention call.  Returns
+    (entry for the JSON line, the Workload object, still alive for the CPU baseline)."""
+    import torch
+    bf16 = name != "toy"
+    # the reference state: the same number of steps modulo a cycle through the five separate calls, eagerly
+    w = Workload(name, slots, fused=True, carry=bf16, overlap=not bf16)
+    timing = time_steps(w, steps, warmup, not eager)
+    torch.cuda.synchronize()
+    ms = timing["wall_s"] * 1e3 / timing["timed_steps"]
+    entry = {"workload": name, "description": WORKLOAD_TEXT[name], "ms_per_step": ms, "steps_per_s": 1e3 / ms,
+             "launch_mode": timing["launch_mode"], "timed_steps": timing["timed_steps"], "replays": timing["replays"],
+             "steps_per_replay": timing["steps_per_replay"], "eager_steps": timing["eager_steps"],
+             "timed_region_ms": timing["wall_s"] * 1e3, "layers": w.layers, "batch": w.B, "input_sets": w.slots,
+             "kv_sets": w.kv_slots, "kv_len": [int(x) for x in w.kv_lens], "tree_params": w.tree_prm,
+             "schedule": ("one stream; sage_entropy_topk_slices, sage_tree_attention_with_plan (first layer; sage_tree_attention "
+                          "for the others), sage_entropy_topk_slices, sage_verify_accept_from_slices: the merge + tree rule of the "
+                          "planning ride in the attention launch (the tree planned in a step is verified in the next one, Sec. 3.2 "
+                          "lookahead)") if bf16 else
+                         ("two streams forked and joined every step: planning (sage_entropy_topk_slices, "
+                          "sage_build_tree_from_slices) beside verification (sage_tree_attention, sage_entropy_topk_slices, "
+                          "sage_verify_accept_from_slices)")}
+    if verify:
+        # the same step sequence through the five separate calls, eagerly, must end in the same state (bit for bit)
+        ref = Workload(name, slots, fused=False)
+        cycle = ref.slots if ref.slots % 2 == 0 else 2 * ref.slots
+        for _ in range(cycle + w.step_no % cycle):
+            ref.step()
+        torch.cuda.synchronize()
+        same = (ref.step_no - w.step_no) % cycle == 0 and all(torch.equal(a, b) for a, b in zip(snapshot(ref), snapshot(w)))
+        entry["state_equals_separate_calls"] = bool(same)
+        if not same:
+            print(f"bench.py: {name}: the timed schedule and the five separate calls ended in different states", file=sys.stderr)
+            sys.exit(4)
+        if all_schedules:
+            t = time_steps(ref, steps, warmup, not eager)
+            entry["separate_calls_ms_per_step"] = t["wall_s"] * 1e3 / t["timed_steps"]
+        del ref
+        torch.cuda.empty_cache()
+    if all_schedules:
+        for key, kw in (("one_stream_ms_per_step", dict(fused=True)), ("two_streams_ms_per_step", dict(fused=True, overlap=True))):
+            alt = Workload(name, slots, **kw)
+            t = time_steps(alt, steps, warmup, not eager)
+            entry[key] = t["wall_s"] * 1e3 / t["timed_steps"]
+            del alt
+            torch.cuda.empty_cache()
+    w.carry, w.overlap = False, False                    # the measurement passes below run on one stream
+    w._prepare(None)
+    entry["roofline"] = attention_roofline(w, name)
+    return entry, w
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -833,138 +926,65 @@ def main():
         sys.exit(3)
     from paper_2602_00523_amd import sage
     sage.lib()                                          # fail loudly if the HIP library is not built
-    if args.only:
-        if args.calibrate_copy:
-            src = torch.empty(64 << 20, device="cuda:0", dtype=torch.uint8).random_()
-            dst = torch.empty_like(src)
-            for _ in range(5):
-                dst.copy_(src)
-            torch.cuda.synchronize()
-            del src, dst
-        extra = {"long_kv": lambda: long_kv_attention(["c3", "c4", "c5"]), "closed_loop": lambda: closed_loop("c2"),
-                 "lm_head": lm_head_projection, "entropy_topk": entropy_topk_streams, "draft_side": draft_side_attention}[args.only]()
-        print(json.dumps({args.only: extra}))
-        return
-    defaults = {"toy": (2000, 50), "c2": (2000, 100), "c3": (1024, 64), "c4": (300, 20), "c5": (24, 3)}
-    steps = args.steps if args.steps is not None else defaults[args.workload][0]
-    warmup = args.warmup if args.warmup is not None else defaults[args.workload][1]
 
-    # the same steps through the five separate calls first (its final state is the reference for the other runs), then
-    # the fused calls on one stream, then the fused calls with planning and verification overlapped (the timed run)
-    def same_state(w, ref_state, ref_step_no):
-        return w.step_no == ref_step_no and all(torch.equal(a, b) for a, b in zip(snapshot(w), ref_state))
-
-    w = Workload(args.workload, args.slots, fused=False)
-    sep_wall, _ = time_steps(w, steps, warmup, not args.eager)
-    sep_state, sep_step_no = snapshot(w), w.step_no
-    del w
-    torch.cuda.empty_cache()
-    w = Workload(args.workload, args.slots, fused=True)
-    one_wall, _ = time_steps(w, steps, warmup, not args.eager)
-    if not same_state(w, sep_state, sep_step_no):
-        print("bench.py: the fused calls and the separate calls ended in different states", file=sys.stderr)
-        sys.exit(4)
-    two_wall = carry_wall = None
-    if args.no_overlap:
-        wall, graphed = one_wall, not args.eager
-    else:
-        del w
-        torch.cuda.empty_cache()
-        w = Workload(args.workload, args.slots, fused=True, overlap=True)
-        wall, graphed = time_steps(w, steps, warmup, not args.eager)
-        torch.cuda.synchronize()
-        if not same_state(w, sep_state, sep_step_no):
-            print("bench.py: overlapped planning and the single-stream step ended in different states", file=sys.stderr)
-            sys.exit(4)
-        w.overlap = False                            # the measurement passes below run on one stream
-        w._prepare(None)
-        two_wall, carry_wall = wall, None
-        if w.dtype == torch.bfloat16 and not args.no_carry:
-            # bf16 workloads: planning's second half inside the first layer's attention launch, one stream
-            wc = Workload(args.workload, args.slots, fused=True, carry=True)
-            carry_wall, carry_graphed = time_steps(wc, steps, warmup, not args.eager)
-            torch.cuda.synchronize()
-            if not same_state(wc, sep_state, sep_step_no):
-                print("bench.py: the step with planning carried in the attention launch ended in a different state", file=sys.stderr)
-                sys.exit(4)
-            del wc
-            torch.cuda.empty_cache()
-            # the timed configuration is the faster of the two (carrying wins unless the attention's own workgroups fill
-            # every CU, where the planning workgroup has to queue behind one of them); the other one is reported beside it
-            if carry_wall < two_wall:
-                wall, graphed = carry_wall, carry_graphed
-    att_ms, n_log, eager_wall = time_attention_launches(w, min(steps, 2000))
-    ms_per_step = wall * 1e3 / steps
-    eager_att_us = sum(att_ms) / len(att_ms) * 1e3
-    graph_att_us, cycle_sizes = time_attention_graph(w)
-    if graph_att_us is not None:                            # the launches as the timed region runs them
-        att_avg_ms, sized = graph_att_us * 1e-3, cycle_sizes
-        how = ("HIP events around graph replays of one input-set cycle's sage_tree_attention calls alone (each input set "
-               "with the tree the step sequence verifies on it), per launch")
-    else:
-        att_avg_ms, sized = eager_att_us * 1e-3, n_log
-        how = "HIP events around every sage_tree_attention call in an eager pass over the same steps, queue kept busy"
-    per_launch_bytes = sum(w.attention_algorithmic_bytes(n) for n in sized) / len(sized)
-    per_launch_flops = sum(w.attention_flops(n) for n in sized) / len(sized)
-    achieved = per_launch_bytes / (att_avg_ms * 1e-3) / 1e9
-    mean_nodes = float(sum(n.sum() for n in n_log) / len(n_log))
-
-    carried = carry_wall is not None and wall == carry_wall
-    result = {
-        "metric": "tree-verify steps/sec + attention HBM GB/s (% of peak), 72B shape, 1 MI355X",
-        "value": steps / wall, "unit": "steps/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": w.cfg["dtype"], "data": "synthetic",
-        "config": {"workload": f"{args.workload}: " + {
-            "toy": "Toy fp32, 4/1 heads d64, KV 256, vocab 1024",
-            "c2": "one layer at the 72B shape (64/8 heads, d128, bf16), KV 4096, vocab 152064, adaptive tree <= 64 nodes, batch 1",
-            "c3": "72B shape, KV 16384, AR(1) entropy-driven trees, vocab 152064, batch 1",
-            "c4": "72B shape, batch 8, ragged KV 2048..12288, ragged trees, vocab 152064",
-            "c5": "80-layer attention stack at the 72B shape, KV 32768 per layer, 64-node tree, vocab 152064"}[args.workload],
-            "kv_len": [int(x) for x in w.kv_lens], "layers": w.layers, "batch": w.B, "input_sets": w.slots,
-            "mean_tree_nodes": mean_nodes, "tree_params": w.tree_prm,
-            "launch_mode": "HIP graph replay of whole input-set cycles" if graphed else "eager launches",
-            "calls_per_step": ("sage_entropy_topk_slices, sage_tree_attention_with_plan (first layer; sage_tree_attention for "
-                               "the others), sage_entropy_topk_slices, sage_verify_accept_from_slices (final state equal, bit "
-                               "for bit, to the same steps through the five separate calls)") if carried else
-                              ("sage_entropy_topk_slices, sage_build_tree_from_slices, sage_tree_attention x layers, "
-                               "sage_entropy_topk_slices, sage_verify_accept_from_slices (final state equal, bit for bit, "
-                               "to the same steps through the five separate calls)"),
-            "streams": ("one stream; the merge + tree rule of the planning (a1, a2) ride in the launch of the attention (a3): the "
-                        "tree planned in a step is verified in the next one (Sec. 3.2 lookahead), so the two are independent")
-                       if carried else
-                       ("planning (a1, a2) and verification (a3, a1', a4) of a step on two streams, forked and joined every step: "
-                        "the tree planned in a step is verified in the next one (Sec. 3.2 lookahead)") if not args.no_overlap
-                       else "one stream",
-            "two_streams_steps_per_s": None if two_wall is None else steps / two_wall,
-            "two_streams_ms_per_step": None if two_wall is None else two_wall * 1e3 / steps,
-            "plan_in_attention_launch_steps_per_s": None if carry_wall is None else steps / carry_wall,
-            "plan_in_attention_launch_ms_per_step": None if carry_wall is None else carry_wall * 1e3 / steps,
-            "one_stream_steps_per_s": steps / one_wall, "one_stream_ms_per_step": one_wall * 1e3 / steps,
-            "separate_calls_steps_per_s": steps / sep_wall, "separate_calls_ms_per_step": sep_wall * 1e3 / steps,
-            "eager_ms_per_step": eager_wall * 1e3 / len(n_log) * w.layers / w.layers},
-        "roofline": {"bound": "hbm", "kernel": "sage_tree_attention (bf16 MFMA kernel + split merge, per layer launch)",
-                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS,
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload), "avg_launch_us": att_avg_ms * 1e3,
-                     "timing": how, "eager_launch_us": eager_att_us,
-                     "eager_timing": "HIP events around every sage_tree_attention call in an eager pass over the same steps (includes the event pair and host launch gaps)",
-                     "algorithmic_bytes_per_launch": per_launch_bytes,
-                     "mfma_TFLOPs": per_launch_flops / (att_avg_ms * 1e-3) / 1e12,
-                     "mfma_frac": per_launch_flops / (att_avg_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS},
-    }
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds)
-    if args.calibrate_copy:
+    def calibrate_copy():
         src = torch.empty(64 << 20, device="cuda:0", dtype=torch.uint8).random_()
         dst = torch.empty_like(src)
         for _ in range(5):
             dst.copy_(src)
         torch.cuda.synchronize()
-        del src, dst
+
+    if args.only:
+        if args.calibrate_copy:
+            calibrate_copy()
+        if args.only == "attention":
+            w = Workload(args.workload, args.slots)
+            extra = attention_roofline(w, args.workload)
+        else:
+            extra = {"closed_loop": lambda: closed_loop("c2"), "lm_head": lm_head_projection,
+                     "entropy_topk": entropy_topk_streams, "draft_side": draft_side_attention}[args.only]()
+        print(json.dumps({args.only: extra}))
+        return
+    defaults = {"toy": (2000, 50), "c2": (2000, 100), "c3": (1024, 64), "c4": (320, 16), "c5": (24, 4)}
+    steps = args.steps if args.steps is not None else defaults[args.workload][0]
+    warmup = args.warmup if args.warmup is not None else defaults[args.workload][1]
+
+    head, w = run_workload(args.workload, steps, warmup, args.slots, args.eager, args.all_schedules)
+    roof = dict(head["roofline"])
+    result = {
+        "metric": "tree-verify steps/sec + attention HBM GB/s (% of peak), 72B shape, 1 MI355X",
+        "value": head["steps_per_s"], "unit": "steps/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.cfg["dtype"], "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {WORKLOAD_TEXT[args.workload]}",
+                   **{k: head[k] for k in ("layers", "batch", "input_sets", "kv_sets", "kv_len", "tree_params", "launch_mode",
+                                           "timed_steps", "replays", "steps_per_replay", "eager_steps", "timed_region_ms",
+                                           "schedule", "state_equals_separate_calls")
+                      if k in head},
+                   **{k: head[k] for k in ("separate_calls_ms_per_step", "one_stream_ms_per_step", "two_streams_ms_per_step")
+                      if k in head},
+                   "mean_tree_nodes": roof["mean_tree_nodes"]},
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds)
+    if args.calibrate_copy:
+        calibrate_copy()
     del w
     torch.cuda.empty_cache()
-    if not args.no_extras and args.workload == "c2":
-        result["attention_long_kv"] = long_kv_attention(["c3", "c4", "c5"])
+    if not args.no_extras:
+        # every configuration, whole steps and the attention call's roofline, from this same run
+        by_workload = []
+        for name in ("toy", "c2", "c3", "c4", "c5"):
+            if name == args.workload:
+                by_workload.append({k: v for k, v in head.items()})
+                continue
+            k_steps, k_warm = defaults[name]
+            entry, wk = run_workload(name, min(k_steps, 512), min(k_warm, 32))
+            del wk
+            torch.cuda.empty_cache()
+            by_workload.append(entry)
+        result["by_workload"] = by_workload
         result["closed_loop"] = closed_loop("c2")
         result["lm_head_projection"] = lm_head_projection()
         result["entropy_topk_streams"] = entropy_topk_streams()
