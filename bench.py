@@ -30,14 +30,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 MFMA rate
 MAX_NODES = 64
 MIN_TIMED_MS = 5.0              # the timed region is stretched to at least this by replaying the captured steps
 # HBM bytes of one sage_tree_attention call (main kernel + split merge) per workload, from the rocprofv3 FETCH_SIZE /
-# WRITE_SIZE runs summarised under profiles/ (scaled by the counters' readings for a 64 MiB copy); the summaries state
-# the command, the tree sizes and the split count they were taken at.  Workloads not profiled: null.
-MEASURED_TRAFFIC_BYTES = {}
-try:
-    with open(os.path.join(ROOT, "profiles", "tree_attention_hbm_traffic.json")) as _f:
-        MEASURED_TRAFFIC_BYTES = {k: float(v["bytes_per_call"]) for k, v in json.load(_f).items() if not k.startswith("_")}
-except (OSError, ValueError, KeyError):
-    pass
+# WRITE_SIZE runs summarised in profiles/tree_attention_hbm_traffic_by_workload.md (scaled by the counters' readings
+# for a 64 MiB copy; the summary states the commands, the tree sizes and the split counts they were taken at).
+MEASURED_TRAFFIC_BYTES = {"c2": 26.84e6, "c3": 82.88e6, "c4": 265.10e6, "c5": 172.57e6}
 
 # Trees of the 80-layer configuration are asked to have 64 nodes every step.  With the paper's own parameters the
 # rule never grows a tree that large, so that workload plants a geometric top-64 distribution (ratio 1/2) in the
@@ -432,7 +427,7 @@ def planned_trees(w: Workload):
     return masks, counts, sizes
 
 
-def time_attention_graph(w: Workload, min_ms: float = 20.0, max_sets: int = 64):
+def time_attention_graph(w: Workload, min_ms: float = 20.0, max_sets: int = 64, eager: bool = False):
     """The sage_tree_attention calls of the step sequence alone, as a HIP graph: input sets in order (at most
     `max_sets` of them), each with the tree that the sequence verifies on it and with the K/V set its step uses,
     every layer; replayed between two HIP events on the capture stream until `min_ms` have been timed.  This is how
@@ -445,6 +440,19 @@ def time_attention_graph(w: Workload, min_ms: float = 20.0, max_sets: int = 64):
     calls = [sg.prepare("sage_tree_attention", w.Q[s], w.Kc[s % w.kv_slots][layer], w.Vc[s % w.kv_slots][layer], w.Kt[s],
                         w.Vt[s], w.O, w.kv_start, w.kv_len, w.max_len, w.Hkv * w.d, w.d, masks[s], counts[s], w.scale,
                         w.ws3, stream=side) for s in sets for layer in range(w.layers)]
+    if eager:                                                  # (counter collection wants plain dispatches)
+        with torch.cuda.stream(side):
+            for c in calls:
+                c()
+            side.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(side)
+            for _ in range(3):
+                for c in calls:
+                    c()
+            e1.record(side)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (3 * len(calls)), [sizes[s] for s in sets]
     try:
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
@@ -468,9 +476,9 @@ def time_attention_graph(w: Workload, min_ms: float = 20.0, max_sets: int = 64):
     return e0.elapsed_time(e1) * 1e3 / (reps * len(calls)), [sizes[s] for s in sets]
 
 
-def attention_roofline(w: Workload, name: str):
+def attention_roofline(w: Workload, name: str, eager: bool = False):
     """Roofline entry of the sage_tree_attention call at workload `name` (measured live, see time_attention_graph)."""
-    us, sized = time_attention_graph(w)
+    us, sized = time_attention_graph(w, eager=eager)
     if us is None:
         return None
     per_bytes = sum(w.attention_algorithmic_bytes(n) for n in sized) / len(sized)
@@ -939,7 +947,7 @@ def main():
             calibrate_copy()
         if args.only == "attention":
             w = Workload(args.workload, args.slots)
-            extra = attention_roofline(w, args.workload)
+            extra = attention_roofline(w, args.workload, eager=args.eager)
         else:
             extra = {"closed_loop": lambda: closed_loop("c2"), "lm_head": lm_head_projection,
                      "entropy_topk": entropy_topk_streams, "draft_side": draft_side_attention}[args.only]()
