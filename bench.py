@@ -691,39 +691,51 @@ def closed_loop(name="c2", steps=512, carry=True):
     return out
 
 
-def lm_head_projection(rows=64, dim=8192, vocab=152064, launches=12):
+def lm_head_projection(dim=8192, vocab=152064, launches=12):
     """The target's greedy token and softmax statistics taken straight from the output projection at the 72B shape
-    (sage_lm_head_topk): the [vocab, dim] weight matrix (2.5 GB) is streamed once, the 64 x vocab logits never exist
-    in memory.  Weights ~ N(0, 9/dim), hidden rows ~ N(0,1): logits ~ N(0, 9)."""
+    (sage_lm_head_topk): the [vocab, dim] weight matrix (2.5 GB) is streamed once, the rows x vocab logits never exist
+    in memory.  Weights ~ N(0, 9/dim), hidden rows ~ N(0,1): logits ~ N(0, 9).  Cases: the 64 node rows of one tree,
+    the 512 of a batch of eight with every row live (the contraction then bounds the call, not the weight stream),
+    and the same batch with tree sizes like c4's (about 160 live rows, packed into three blocks)."""
     import torch
     from paper_2602_00523_amd import sage
     dev = "cuda:0"
     g = torch.Generator(device=dev)
     g.manual_seed(523007)
     W = (torch.randn(vocab, dim, generator=g, device=dev, dtype=torch.float32) * (3.0 / math.sqrt(dim))).to(torch.bfloat16)
-    H = torch.randn(rows, dim, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
-    ent = torch.zeros(rows, device=dev)
-    idx = torch.zeros(rows, 1, device=dev, dtype=torch.int32)
-    ws = torch.empty(sage.sage_lm_head_topk_workspace_bytes(rows, vocab), device=dev, dtype=torch.uint8)
-    call = sage.prepare("sage_lm_head_topk", H, W, 1, ent, idx, None, None, None, None, ws)
-    for _ in range(3):
-        call()
-    torch.cuda.synchronize()
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * launches)]
-    for i in range(launches):
-        ev[2 * i].record()
-        call()
-        ev[2 * i + 1].record()
-    torch.cuda.synchronize()
-    t = [ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(launches)]
-    avg_ms = sum(t) / len(t)
-    byts = 2.0 * vocab * dim + 2.0 * rows * dim
-    ref = (H.float() @ W.float().T).argmax(1)
-    out = dict(rows=rows, dim=dim, vocab=vocab, avg_us=avg_ms * 1e3, min_us=min(t) * 1e3,
-               algorithmic_bytes=byts, hbm_GBps=byts / (avg_ms * 1e-3) / 1e9, hbm_frac=byts / (avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-               mfma_TFLOPs=2.0 * rows * dim * vocab / (avg_ms * 1e-3) / 1e12,
-               argmax_agrees_with_fp32_matmul=float((ref == idx[:, 0].long()).float().mean().item()))
-    del W, H
+    Wf = W.float()
+    out = []
+    for rows, n_valid in ((64, None), (512, None), (512, [12, 25, 9, 40, 16, 8, 30, 20])):
+        H = torch.randn(rows, dim, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        ent = torch.zeros(rows, device=dev)
+        idx = torch.zeros(rows, 1, device=dev, dtype=torch.int32)
+        ws = torch.empty(sage.sage_lm_head_topk_workspace_bytes(rows, vocab), device=dev, dtype=torch.uint8)
+        nv = None if n_valid is None else torch.tensor(n_valid, device=dev, dtype=torch.int32)
+        call = sage.prepare("sage_lm_head_topk", H, W, 1, ent, idx, None, None, None, None, ws, nv, 64)
+        for _ in range(3):
+            call()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * launches)]
+        for i in range(launches):
+            ev[2 * i].record()
+            call()
+            ev[2 * i + 1].record()
+        torch.cuda.synchronize()
+        t = [ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(launches)]
+        avg_s = sum(t) / len(t) * 1e-3
+        live = rows if n_valid is None else sum(n_valid)
+        alive = torch.ones(rows, dtype=torch.bool, device=dev) if n_valid is None else \
+            (torch.arange(rows, device=dev) % 64) < nv.repeat_interleave(64)
+        byts = 2.0 * vocab * dim + 2.0 * live * dim            # the weights once, whatever the number of rows
+        flops = 2.0 * live * dim * vocab
+        ref = (H.float() @ Wf.T).argmax(1)
+        out.append(dict(rows=rows, live_rows=live, dim=dim, vocab=vocab, avg_us=avg_s * 1e6, min_us=min(t) * 1e3,
+                        algorithmic_bytes=byts, hbm_GBps=byts / avg_s / 1e9, hbm_frac=byts / avg_s / 1e9 / HBM_PEAK_GBPS,
+                        mfma_TFLOPs=flops / avg_s / 1e12, mfma_frac=flops / avg_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                        bound="mfma" if flops / byts > MFMA_BF16_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBPS else "hbm",
+                        argmax_agrees_with_fp32_matmul=float((ref == idx[:, 0].long())[alive].float().mean().item())))
+        del H
+    del W, Wf
     torch.cuda.empty_cache()
     return out
 

@@ -1,7 +1,11 @@
 // sage_lm_head_topk: the target's greedy token and softmax statistics per row (Sec. 2.2 / Def. 4.1, Eq. 1) taken
 // straight from the output projection, logits = hidden . weight^T, so that the rows x vocabulary logits never
 // exist in memory.  HBM-bound: the weight matrix ([vocab, dim] bf16, 2.5 GB at the 72B shape) is streamed exactly
-// once per block of 64 rows; the hidden rows (1 MB) are read once per workgroup from L2.
+// once: with more than 64 live rows, the workgroups that push different blocks of 64 rows through the same weight
+// tiles are placed next to each other on one XCD, so that the first of them fetches a tile from HBM and the others
+// find it in that XCD's L2.  Rows that n_valid marks dead are left out before the blocks are formed (the live rows
+// of all groups are packed into dense blocks of 64), so a batch of partly filled trees costs its live rows only.
+// The hidden rows (1 MB per block) are read once per workgroup from L2.
 //
 // A workgroup of 4 waves owns T consecutive 64-row vocabulary tiles and keeps the logits of ALL of them in
 // registers (T accumulators of 32 x 32 per wave; with one wave per SIMD a wave has 512 registers).  The loop runs
@@ -46,6 +50,8 @@ struct Params {
     const unsigned char* hidden; const unsigned char* weight;
     long hidden_stride_b, weight_stride_b;
     int rows, dim, vocab, k, nunits, ntiles;
+    int row_blocks;                      // blocks of 64 (packed live) rows
+    const int* n_valid; int rows_per_group;
     UnitStats* stats; uint64_t* keys;    // [rows][nunits]
 };
 
@@ -90,6 +96,8 @@ __global__ __launch_bounds__(THREADS) void lm_head_kernel(const Params prm) {
     __shared__ __align__(16) unsigned char sH0[STAGE_B];    // the current hidden chunk (read into registers in step 0)
     __shared__ float s_part[TILE_R][4][3];                   // per hidden row: 4 partial (m, Z, T)
     __shared__ uint64_t s_key[TILE_R][4];
+    __shared__ int s_row[TILE_R];                            // hidden row behind each of this block's 64 slots, -1 = none
+    __shared__ int s_cnt[THREADS];
 #define SW(i) ((i) == 0 ? sW0 : (i) == 1 ? sW1 : (i) == 2 ? sW2 : (i) == 3 ? sW3 : (i) == 4 ? sW4 : (i) == 5 ? sW5 : (i) == 6 ? sW6 : sW7)
 
     const int tid = threadIdx.x;
@@ -97,8 +105,36 @@ __global__ __launch_bounds__(THREADS) void lm_head_kernel(const Params prm) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int r32 = lane & 31, half = lane >> 5;
     const int vt = wave & 1, rt = wave >> 1;
-    const int unit = blockIdx.x;
-    const int row0 = blockIdx.y * TILE_R;                    // first hidden row of this launch block
+    // Workgroup ids go round-robin over the 8 XCDs; the row blocks of one unit take consecutive places on one XCD, so
+    // they run side by side and share the unit's weight tiles through that XCD's L2.
+    const int slot = blockIdx.x >> 3;
+    const int unit = (slot / prm.row_blocks) * 8 + (blockIdx.x & 7);
+    const int rb = slot % prm.row_blocks;
+    if (unit >= prm.nunits) return;
+
+    // ---- the rows of this block: slot j of block rb is live row number 64 rb + j, counted over the groups in order
+    if (prm.n_valid == nullptr) {
+        if (tid < TILE_R) s_row[tid] = rb * TILE_R + tid < prm.rows ? rb * TILE_R + tid : -1;
+    } else {
+        const int groups = (prm.rows + prm.rows_per_group - 1) / prm.rows_per_group;
+        const int want = rb * TILE_R + tid;                  // (threads 64.. only help to load the counts)
+        int before = 0, found = -1;
+        for (int g0 = 0; g0 < groups; g0 += THREADS) {       // uniform trip count
+            const int g = g0 + tid;
+            s_cnt[tid] = g < groups ? max(0, min(prm.n_valid[g], min(prm.rows_per_group, prm.rows - g * prm.rows_per_group))) : 0;
+            __syncthreads();
+            const int here = min(THREADS, groups - g0);
+            for (int j = 0; j < here; ++j) {
+                const int c = s_cnt[j];
+                if (found < 0 && want < before + c) found = (g0 + j) * prm.rows_per_group + (want - before);
+                before += c;
+            }
+            __syncthreads();
+        }
+        if (tid < TILE_R) s_row[tid] = found;
+    }
+    __syncthreads();
+    if (s_row[0] < 0) return;                                // fewer live rows than this block starts at
     // this unit's tiles: an even share of the vocabulary, at most T; missing ones are phantom steps that re-read one
     // row (an L2 hit) and whose logits are masked, so that every unit runs the same step sequence
     const int tile_begin = static_cast<int>(static_cast<long>(unit) * prm.ntiles / prm.nunits);
@@ -109,16 +145,10 @@ __global__ __launch_bounds__(THREADS) void lm_head_kernel(const Params prm) {
 
     // ---- loader: instruction i of wave w copies rows r, r+16, r+32, r+48 (r = 4w + i) of a 64-row tile: lane l fills
     // chunk l%16 of row r + 16 (l/16).  Vocabulary rows past the end (the last unit's missing tiles, a partial last
-    // tile) and hidden rows past the end re-read the last valid row; their results are masked or never written.
+    // tile) re-read the last valid row; their results are masked.
     const int ld_row = (lane >> 4) * 16 + wave * 4;
     const unsigned ld_chunk_b = (lane & 15) * 16;
-    unsigned h_off[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int hr = min(row0 + ld_row + i, prm.rows - 1);
-        h_off[i] = static_cast<unsigned>(hr - row0) * static_cast<unsigned>(prm.hidden_stride_b) + ld_chunk_b;
-    }
-    const unsigned char* h_base = prm.hidden + static_cast<long>(row0) * prm.hidden_stride_b;
+    // (a slot without a row re-reads the block's first row)
     const unsigned char* w_base = prm.weight + static_cast<long>(tile_begin) * TILE_V * prm.weight_stride_b;
     const int rows_mine = v_end - tile_begin * TILE_V;       // vocabulary rows of this unit (>= 1)
     const int full_tiles = rows_mine / TILE_V;               // tiles that need no clamping
@@ -130,7 +160,8 @@ __global__ __launch_bounds__(THREADS) void lm_head_kernel(const Params prm) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         w_ptr[i] = w_base + static_cast<long>(ld_row + i) * prm.weight_stride_b + ld_chunk_b;
-        h_ptr[i] = h_base + h_off[i];
+        const int hr = s_row[ld_row + i] >= 0 ? s_row[ld_row + i] : s_row[0];
+        h_ptr[i] = prm.hidden + static_cast<long>(hr) * prm.hidden_stride_b + ld_chunk_b;
     }
 
     auto issue_w = [&](int kc, int t, auto stc) __attribute__((always_inline)) {
@@ -262,7 +293,7 @@ __global__ __launch_bounds__(THREADS) void lm_head_kernel(const Params prm) {
     s_part[hr][vt * 2 + half][2] = Tm;
     s_key[hr][vt * 2 + half] = key_pack(best);
     __syncthreads();
-    if (tid < TILE_R && row0 + tid < prm.rows) {
+    if (tid < TILE_R && s_row[tid] >= 0) {
         float m = -INFINITY;
         Key bk = Key{0, 0};
 #pragma unroll
@@ -281,7 +312,7 @@ __global__ __launch_bounds__(THREADS) void lm_head_kernel(const Params prm) {
                 t += sc * (s_part[tid][p][2] + s_part[tid][p][1] * dlt);
             }
         }
-        const long o = static_cast<long>(row0 + tid) * prm.nunits + unit;
+        const long o = static_cast<long>(s_row[tid]) * prm.nunits + unit;
         prm.stats[o] = UnitStats{m, z, t, 0.f};
         prm.keys[o] = key_pack(bk);
     }
@@ -324,8 +355,8 @@ extern "C" int sage_lm_head_topk(const void* hidden, const void* weight, int dty
     if ((hidden_stride % 8) != 0 || (weight_stride % 8) != 0 || !sage::aligned(hidden, 16) || !sage::aligned(weight, 16) ||
         !sage::aligned(workspace, 16))
         return SAGE_INVALID_ARG;
-    if (weight_stride > (1L << 24) || hidden_stride > (1L << 24)) return SAGE_UNSUPPORTED;   // 64 rows: 32-bit byte offsets
-    if (rows > 65535 * TILE_R) return SAGE_UNSUPPORTED;
+    if (weight_stride > (1L << 24) || hidden_stride > (1L << 24)) return SAGE_UNSUPPORTED;
+    if (rows > (1 << 20)) return SAGE_UNSUPPORTED;                                            // grid size
     if (workspace_bytes < sage_lm_head_topk_workspace_bytes(rows, vocab)) return SAGE_WORKSPACE_TOO_SMALL;
     if (rows == 0) return SAGE_OK;
     const Shape sh = launch_shape(vocab);
@@ -337,11 +368,13 @@ extern "C" int sage_lm_head_topk(const void* hidden, const void* weight, int dty
     p.hidden_stride_b = hidden_stride * 2;
     p.weight_stride_b = weight_stride * 2;
     p.rows = rows; p.dim = dim; p.vocab = vocab; p.k = k; p.nunits = sh.nunits; p.ntiles = sh.ntiles;
+    p.row_blocks = (rows + TILE_R - 1) / TILE_R;
+    p.n_valid = n_valid; p.rows_per_group = rows_per_group;
     p.stats = static_cast<UnitStats*>(workspace);
     p.keys = reinterpret_cast<uint64_t*>(static_cast<char*>(workspace) +
                                          align256(static_cast<size_t>(rows) * sh.nunits * sizeof(UnitStats)));
     hipStream_t s = sage::as_stream(stream);
-    const dim3 grid(sh.nunits, (rows + TILE_R - 1) / TILE_R);
+    const dim3 grid(((sh.nunits + 7) / 8) * 8 * p.row_blocks);
     if (sh.tiles_per_unit == 5) hipLaunchKernelGGL(lm_head_kernel<5>, grid, dim3(THREADS), 0, s, p);
     else hipLaunchKernelGGL(lm_head_kernel<10>, grid, dim3(THREADS), 0, s, p);
     if (hipGetLastError() != hipSuccess) return SAGE_LAUNCH_FAILED;
