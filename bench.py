@@ -177,7 +177,6 @@ class Workload:
         self.scale = 1.0 / math.sqrt(d)
         self.cur = 0
         self.step_no = 0
-        self.ev_used = 0
         self.fused = fused
         # Sec. 3.2 lookahead: the tree planned from this step's draft row is verified in the NEXT step, so planning
         # (a1 + a2) and verification (a3, a1', a4) of a step touch disjoint data; with `overlap` they run on two streams
@@ -835,7 +834,9 @@ def draft_side_attention(launches=40):
                         algorithmic_bytes=byts, hbm_GBps=byts / (avg_ms * 1e-3) / 1e9))
 
     # Level-by-level growth (Alg. 1 Phase 1: the draft model extends the tree by one level per forward pass): the same
-    # call once per level on the level-ordered tree, call l with the nodes of levels 0..l.  One drafting pass = all levels.
+    # call once per level on the level-ordered tree; call l sees the nodes of levels 0..l as keys and computes the rows
+    # of level l only (first_node).  One drafting pass = all levels; the passes over the rotating K/V buffers are one
+    # HIP graph, as a drafting loop would replay them.
     L, n = 2560, 25
     par = [-1] + [int(rng.integers(max(0, v - 6), v)) for v in range(1, n)]
     dep = [0] * n
@@ -855,31 +856,49 @@ def draft_side_attention(launches=40):
     maskd = torch.from_numpy(mask.view(np.int64)).to(dev)
     counts = [sum(1 for x in dep_l if x <= lvl) for lvl in range(max(dep_l) + 1)]
     nns = [torch.full((1,), c, device=dev, dtype=torch.int32) for c in counts]
+    firsts = [torch.full((1,), c, device=dev, dtype=torch.int32) for c in [0] + counts[:-1]]
     nbuf = 16
     Kc = [rn(L, Hkv, d) for _ in range(nbuf)]
     Vc = [rn(L, Hkv, d) for _ in range(nbuf)]
     Q, Kt, Vt = rn(1, MAX_NODES, Hq, d), rn(1, MAX_NODES, Hkv, d), rn(1, MAX_NODES, Hkv, d)
-    O = torch.zeros_like(Q)
     kv_start = torch.zeros(1, device=dev, dtype=torch.int64)
     kv_len = torch.full((1,), L, device=dev, dtype=torch.int32)
     ws = torch.empty(sage.sage_tree_attention_workspace_bytes(sage.BF16, 1, Hq, Hkv, d, L), device=dev, dtype=torch.uint8)
-    passes = [[sage.prepare("sage_tree_attention", Q, Kc[i], Vc[i], Kt, Vt, O, kv_start, kv_len, L, Hkv * d, d, maskd, nn,
-                            1.0 / math.sqrt(d), ws) for nn in nns] for i in range(nbuf)]
-    for calls in passes:
-        for c in calls:
-            c()
-    torch.cuda.synchronize()
-    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * launches)]
-    for i in range(launches):
-        ev[2 * i].record()
-        for c in passes[i % nbuf]:
-            c()
-        ev[2 * i + 1].record()
-    torch.cuda.synchronize()
-    t = [ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(launches)]
-    out.append(dict(heads=f"{Hq}/{Hkv}", kv_len=L, growth="level by level", nodes_after_each_level=counts,
-                    calls_per_pass=len(counts), avg_us_per_pass=sum(t) / len(t) * 1e3, min_us_per_pass=min(t) * 1e3,
-                    avg_us_per_call=sum(t) / len(t) * 1e3 / len(counts)))
+    side = torch.cuda.Stream()
+    for rows_only in (False, True):
+        O = torch.zeros_like(Q)
+        passes = [[sage.prepare("sage_tree_attention", Q, Kc[i], Vc[i], Kt, Vt, O, kv_start, kv_len, L, Hkv * d, d, maskd, nn,
+                                1.0 / math.sqrt(d), ws, stream=side, first_node=fn if rows_only else None)
+                   for nn, fn in zip(nns, firsts)] for i in range(nbuf)]
+        with torch.cuda.stream(side):
+            for calls in passes:
+                for c in calls:
+                    c()
+        torch.cuda.synchronize()
+        eager = O.clone()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for calls in passes:
+                for c in calls:
+                    c()
+        O.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        same = bool(torch.equal(O.view(torch.int16), eager.view(torch.int16)))
+        reps = 20
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(side):
+            e0.record(side)
+            for _ in range(reps):
+                graph.replay()
+            e1.record(side)
+        torch.cuda.synchronize()
+        us_pass = e0.elapsed_time(e1) * 1e3 / (reps * nbuf)
+        out.append(dict(heads=f"{Hq}/{Hkv}", kv_len=L, growth="level by level",
+                        rows_computed="the new level only (first_node)" if rows_only else "every node so far",
+                        nodes_after_each_level=counts, calls_per_pass=len(counts), launch_mode="HIP graph replay",
+                        replay_equals_eager=same, avg_us_per_pass=us_pass, avg_us_per_call=us_pass / len(counts)))
+        del graph, passes
     return out
 
 

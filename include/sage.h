@@ -134,6 +134,11 @@ int sage_build_tree(const float* topk_renorm, const float* alpha, const int* top
  * bf16: MFMA path, requires d == 128, Hq / Hkv <= 16, kv_token_stride <= 2^24 elements;
  * fp32: d <= 256, multiple of 4.
  * Accumulation is fp32; bf16 outputs are rounded to nearest even.
+ * first_node [B] i32 (device), nullable = all zero: only the rows of nodes first_node[b] <= i <
+ * n_nodes[b] are computed and written; earlier nodes still serve as keys and values through
+ * the masks.  This is the draft side of Alg. 1 Phase 1, where the tree grows by one level per
+ * forward pass and call l needs the rows of level l only (nodes in level order).  Values
+ * outside [0, n_nodes[b]) are clamped into that range.
  * workspace: sage_tree_attention_workspace_bytes(...) bytes, 256-byte aligned.
  * Errors: INVALID_ARG (null pointers, B < 0, Hq % Hkv != 0, strides, max_kv_len < 0),
  * UNSUPPORTED (shape outside the above), WORKSPACE_TOO_SMALL.
@@ -143,7 +148,7 @@ int sage_tree_attention(const void* Q, const void* Kc, const void* Vc, const voi
                         int dtype, int B, int Hq, int Hkv, int d,
                         const int64_t* kv_start, const int* kv_len, int max_kv_len,
                         long kv_token_stride, long kv_head_stride,
-                        const uint64_t* anc_mask, const int* n_nodes, float scale,
+                        const uint64_t* anc_mask, const int* n_nodes, const int* first_node, float scale,
                         void* workspace, size_t workspace_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------

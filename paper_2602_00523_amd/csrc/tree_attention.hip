@@ -8,10 +8,10 @@
 
 namespace sage {
 int tree_attention_f32(const void*, const void*, const void*, const void*, const void*, void*, int, int, int, int,
-                       const int64_t*, const int*, long, long, const uint64_t*, const int*, float, hipStream_t);
+                       const int64_t*, const int*, long, long, const uint64_t*, const int*, const int*, float, hipStream_t);
 int tree_attention_bf16(const void*, const void*, const void*, const void*, const void*, void*, int, int, int, int,
-                        const int64_t*, const int*, int, long, long, const uint64_t*, const int*, float, void*, size_t,
-                        hipStream_t, const PlanArgs*);
+                        const int64_t*, const int*, int, long, long, const uint64_t*, const int*, const int*, float, void*,
+                        size_t, hipStream_t, const PlanArgs*);
 bool attention_bf16_can_carry_plan(const PlanArgs&);
 size_t attention_bf16_workspace_bytes(int B, int Hkv, int G, int max_kv_len);
 int plan_args_from_slices(void*, int, int, int, const sage_tree_params*, const int*, float*, int*, float*, float*, float*, float*,
@@ -41,18 +41,18 @@ extern "C" size_t sage_tree_attention_workspace_bytes(int dtype, int B, int Hq, 
 extern "C" int sage_tree_attention(const void* Q, const void* Kc, const void* Vc, const void* Kt, const void* Vt, void* O,
                                    int dtype, int B, int Hq, int Hkv, int d, const int64_t* kv_start, const int* kv_len,
                                    int max_kv_len, long kv_token_stride, long kv_head_stride, const uint64_t* anc_mask,
-                                   const int* n_nodes, float scale, void* workspace, size_t workspace_bytes,
-                                   void* stream) {
+                                   const int* n_nodes, const int* first_node, float scale, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
     const int rc = check_attention_args(Q, Kc, Vc, Kt, Vt, O, dtype, B, Hq, Hkv, d, kv_start, kv_len, max_kv_len, kv_token_stride,
                                         kv_head_stride, anc_mask, n_nodes, scale);
     if (rc != SAGE_OK || B == 0) return rc;
     hipStream_t s = sage::as_stream(stream);
     if (dtype == SAGE_F32)
         return sage::tree_attention_f32(Q, Kc, Vc, Kt, Vt, O, B, Hq, Hkv, d, kv_start, kv_len, kv_token_stride,
-                                        kv_head_stride, anc_mask, n_nodes, scale, s);
+                                        kv_head_stride, anc_mask, n_nodes, first_node, scale, s);
     if (!workspace) return SAGE_INVALID_ARG;
     return sage::tree_attention_bf16(Q, Kc, Vc, Kt, Vt, O, B, Hq, Hkv, d, kv_start, kv_len, max_kv_len, kv_token_stride,
-                                     kv_head_stride, anc_mask, n_nodes, scale, workspace, workspace_bytes, s, nullptr);
+                                     kv_head_stride, anc_mask, n_nodes, first_node, scale, workspace, workspace_bytes, s, nullptr);
 }
 
 // ---- sage_tree_attention_static: the same call for callers that cannot hand over a workspace they allocated
@@ -96,7 +96,7 @@ extern "C" int sage_tree_attention_static(const void* Q, const void* Kc, const v
     hipStream_t s = sage::as_stream(stream);
     if (dtype == SAGE_F32)               // no scratch in this path
         return sage::tree_attention_f32(Q, Kc, Vc, Kt, Vt, O, B, Hq, Hkv, d, kv_start, kv_len, kv_token_stride,
-                                        kv_head_stride, anc_mask, n_nodes, scale, s);
+                                        kv_head_stride, anc_mask, n_nodes, nullptr, scale, s);
     // sizes whose partials do not fit the array are refused, nothing is enqueued
     if (sage_tree_attention_workspace_bytes(dtype, B, Hq, Hkv, d, max_kv_len) > SAGE_STATIC_SCRATCH_BYTES)
         return SAGE_WORKSPACE_TOO_SMALL;
@@ -105,7 +105,7 @@ extern "C" int sage_tree_attention_static(const void* Q, const void* Kc, const v
     // Every partial slot the merge reads is written by the main kernel of the same call first, so nothing of an earlier
     // call's contents has to be cleared.
     return sage::tree_attention_bf16(Q, Kc, Vc, Kt, Vt, O, B, Hq, Hkv, d, kv_start, kv_len, max_kv_len, kv_token_stride,
-                                     kv_head_stride, anc_mask, n_nodes, scale, ws, SAGE_STATIC_SCRATCH_BYTES, s, nullptr);
+                                     kv_head_stride, anc_mask, n_nodes, nullptr, scale, ws, SAGE_STATIC_SCRATCH_BYTES, s, nullptr);
 }
 
 extern "C" int sage_tree_attention_with_plan(
@@ -130,13 +130,13 @@ extern "C" int sage_tree_attention_with_plan(
     hipStream_t s = sage::as_stream(stream);
     if (dtype == SAGE_BF16 && sage::attention_bf16_can_carry_plan(pl))
         return sage::tree_attention_bf16(Q, Kc, Vc, Kt, Vt, O, B, Hq, Hkv, d, kv_start, kv_len, max_kv_len, kv_token_stride,
-                                         kv_head_stride, anc_mask, n_nodes, scale, workspace, workspace_bytes, s, &pl);
+                                         kv_head_stride, anc_mask, n_nodes, nullptr, scale, workspace, workspace_bytes, s, &pl);
     // fp32, or candidate lists too long for the planning workgroup's LDS: the two launches one after the other
     rc = dtype == SAGE_F32 ? sage::tree_attention_f32(Q, Kc, Vc, Kt, Vt, O, B, Hq, Hkv, d, kv_start, kv_len, kv_token_stride,
-                                                      kv_head_stride, anc_mask, n_nodes, scale, s)
+                                                      kv_head_stride, anc_mask, n_nodes, nullptr, scale, s)
                            : sage::tree_attention_bf16(Q, Kc, Vc, Kt, Vt, O, B, Hq, Hkv, d, kv_start, kv_len, max_kv_len,
-                                                       kv_token_stride, kv_head_stride, anc_mask, n_nodes, scale, workspace,
-                                                       workspace_bytes, s, nullptr);
+                                                       kv_token_stride, kv_head_stride, anc_mask, n_nodes, nullptr, scale,
+                                                       workspace, workspace_bytes, s, nullptr);
     if (rc != SAGE_OK) return rc;
     return sage::launch_plan(pl, B, s);
 }

@@ -84,6 +84,7 @@ struct Params {
     const uint16_t* Q; const uint16_t* Kc; const uint16_t* Vc; const uint16_t* Kt; const uint16_t* Vt;
     uint16_t* O;
     const int64_t* kv_start; const int* kv_len; const uint64_t* anc_mask; const int* n_nodes;
+    const int* first_node;               // nullable: rows are computed for nodes first_node[b] .. n_nodes[b] - 1 only
     unsigned char* part;                 // [B][Hkv][nslot] slots of PART_SLOT_B bytes; batched launches: [Hkv][nslot]
     long kv_token_stride, kv_head_stride;
     int B, Hq, Hkv, G, nslot, min_tiles_per_split;
@@ -94,12 +95,15 @@ struct Params {
 
 // How one (sequence, KV head) is cut into workgroups; evaluated identically by both kernels.
 struct Split {
-    int n, rows, col_groups, tiles, tiles_per_split, nsplit;
+    int n, first, rows, col_groups, tiles, tiles_per_split, nsplit;
 };
-__device__ __forceinline__ Split make_split(int n_nodes, int kv_len, int G, int nslot, int min_tps) {
+// the first node whose rows are computed: inside [0, n), so that a call always has a row
+__device__ __forceinline__ int clamp_first(int first, int n) { return first < 0 ? 0 : (first > n - 1 ? n - 1 : first); }
+__device__ __forceinline__ Split make_split(int n_nodes, int first_node, int kv_len, int G, int nslot, int min_tps) {
     Split s;
     s.n = n_nodes < 1 ? 1 : (n_nodes > SAGE_MAX_NODES ? SAGE_MAX_NODES : n_nodes);
-    s.rows = s.n * G;
+    s.first = clamp_first(first_node, s.n);
+    s.rows = (s.n - s.first) * G;
     s.col_groups = (s.rows + ROWS_PER_WG - 1) / ROWS_PER_WG;
     const int L = kv_len > 0 ? kv_len : 0;
     s.tiles = (L + TILE - 1) / TILE + 1;                    // cache tiles, then one tile holding the tree's keys
@@ -116,21 +120,22 @@ __device__ __forceinline__ Split make_split(int n_nodes, int kv_len, int G, int 
 // workgroup whose range starts several segments gets fewer tiles.  Evaluated identically by both kernels.
 constexpr int SEG_COST_TILES = 4;
 struct BatchShape {
-    int n, L, tiles, col_groups, start_lo, start_hi;         // per lane (sequence)
+    int n, first, L, tiles, col_groups, start_lo, start_hi;  // per lane (sequence)
     int total, q;                                            // wave-uniform
 };
 __device__ __forceinline__ int wave_sum_i32(int v) { return static_cast<int>(sage::wave_sum_u32(static_cast<uint32_t>(v))); }
 __device__ __forceinline__ BatchShape make_batch_shape(const Params& prm, int lane) {
     BatchShape bs;
-    bs.n = 1; bs.L = 0; bs.tiles = 0; bs.col_groups = 0; bs.start_lo = 0; bs.start_hi = 0;
+    bs.n = 1; bs.first = 0; bs.L = 0; bs.tiles = 0; bs.col_groups = 0; bs.start_lo = 0; bs.start_hi = 0;
     if (lane < prm.B) {
         const int nn = prm.n_nodes[lane];
         const int len = prm.kv_len[lane];
         const int64_t st = prm.kv_start[lane];
         bs.n = nn < 1 ? 1 : (nn > SAGE_MAX_NODES ? SAGE_MAX_NODES : nn);
+        bs.first = prm.first_node ? clamp_first(prm.first_node[lane], bs.n) : 0;
         bs.L = len > 0 ? len : 0;
         bs.tiles = (bs.L + TILE - 1) / TILE + 1;             // cache tiles, then one tile holding the tree's keys
-        bs.col_groups = (bs.n * prm.G + ROWS_PER_WG - 1) / ROWS_PER_WG;
+        bs.col_groups = ((bs.n - bs.first) * prm.G + ROWS_PER_WG - 1) / ROWS_PER_WG;
         bs.start_lo = static_cast<int>(static_cast<uint32_t>(st));
         bs.start_hi = static_cast<int>(st >> 32);
     }
@@ -173,6 +178,7 @@ __device__ __forceinline__ float cross_half_sum(float v) {
 // length and node count, does not wait for a fetch of the argument block first.
 template <bool BATCH>
 __device__ __forceinline__ void attention_workgroup(const int* __restrict__ kv_len_arg, const int* __restrict__ n_nodes_arg,
+                                                    const int* __restrict__ first_node_arg,
                                                     const int64_t* __restrict__ kv_start_arg, int nslot_arg, int min_tps_arg,
                                                     int G_arg, const Params& prm, const int first_slab) {
     // one LDS object per stage and operand (see header)
@@ -197,7 +203,8 @@ __device__ __forceinline__ void attention_workgroup(const int* __restrict__ kv_l
     const int inv_G = (65536 + G_arg - 1) / G_arg;           // (m * inv_G) >> 16 == m / G for the rows of a KV head
 
     // One pass over tiles [t_begin, t_end) of sequence b for column group cg; the un-normalised partial goes to out_base.
-    auto run_segment = [&](const int b_v, const int L_v, const int seq_n_v, const int seq_rows_v, const int cg_v, const int t_begin_v,
+    // (seq_rows rows, of nodes first_v .. seq_n - 1)
+    auto run_segment = [&](const int b_v, const int L_v, const int seq_n_v, const int first_v, const int seq_rows_v, const int cg_v, const int t_begin_v,
                            const int t_end_v, const int tree_tile_v, const long kv_start_v, unsigned char* const out_base_v)
                            __attribute__((always_inline)) {
     // every argument is wave-uniform; said to the compiler (the batched walk derives them through lane reads), so that
@@ -208,6 +215,7 @@ __device__ __forceinline__ void attention_workgroup(const int* __restrict__ kv_l
                static_cast<uint32_t>(uni(static_cast<int>(static_cast<uint32_t>(v))));
     };
     const int b = uni(b_v), L = uni(L_v), seq_n = uni(seq_n_v), seq_rows = uni(seq_rows_v), cg = uni(cg_v);
+    const int node0 = uni(first_v);
     const int t_begin = uni(t_begin_v), t_end = uni(t_end_v), tree_tile = uni(tree_tile_v);
     const long kv_start_b = static_cast<long>(uni64(static_cast<uint64_t>(kv_start_v)));
     unsigned char* const out_base = reinterpret_cast<unsigned char*>(uni64(reinterpret_cast<uint64_t>(out_base_v)));
@@ -292,7 +300,7 @@ __device__ __forceinline__ void attention_workgroup(const int* __restrict__ kv_l
     auto row_of = [&](int local) __attribute__((always_inline)) {      // row `local` of this group -> (node, head in group)
         const int mm = min(cg * ROWS_PER_WG + local, seq_rows - 1);
         const int nd = (mm * inv_G) >> 16;                               // exact for mm < 64 G, G <= 16
-        return make_int2(nd, mm - nd * prm.G);
+        return make_int2(node0 + nd, mm - nd * prm.G);
     };
     {
         // wave w brings both words of the masks of its rows 32 w + lane / 2
@@ -579,17 +587,18 @@ __device__ __forceinline__ void attention_workgroup(const int* __restrict__ kv_l
         const int64_t start_w = kv_start_arg[b];
         int start_lo = __builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(start_w)));
         int start_hi = __builtin_amdgcn_readfirstlane(static_cast<int>(start_w >> 32));
-        asm("" : "+s"(len_b), "+s"(n_b), "+s"(start_lo), "+s"(start_hi));
+        int f_b = first_node_arg ? __builtin_amdgcn_readfirstlane(first_node_arg[b]) : 0;   // (a uniform branch on an argument)
+        asm("" : "+s"(len_b), "+s"(n_b), "+s"(start_lo), "+s"(start_hi), "+s"(f_b));
         const long start_b = (static_cast<long>(start_hi) << 32) | static_cast<uint32_t>(start_lo);
         const int L = len_b > 0 ? len_b : 0;
-        const Split sp = make_split(n_b, L, G_arg, nslot_arg, min_tps_arg);
+        const Split sp = make_split(n_b, f_b, L, G_arg, nslot_arg, min_tps_arg);
         if (sp.col_groups > nslot_arg) return;              // host guarantees nslot >= the largest group count
         const int cg = slot % sp.col_groups;
         const int split = slot / sp.col_groups;
         if (split >= sp.nsplit) return;
         const int t_begin = split * sp.tiles_per_split;
         const int t_end = min(sp.tiles, t_begin + sp.tiles_per_split);
-        run_segment(b, L, sp.n, sp.rows, cg, t_begin, t_end, sp.tiles - 1, start_b,
+        run_segment(b, L, sp.n, sp.first, sp.rows, cg, t_begin, t_end, sp.tiles - 1, start_b,
                     prm.part + ((static_cast<long>(b) * prm.Hkv + g) * prm.nslot + slot) * PART_SLOT_B);
     } else {
         const BatchShape bs = make_batch_shape(prm, lane);  // lane b holds sequence b
@@ -603,6 +612,7 @@ __device__ __forceinline__ void attention_workgroup(const int* __restrict__ kv_l
             const int seg_len = tiles_b + SEG_COST_TILES;
             if (first + seg_len * cgs_b > r0) {
                 const int n_b = __builtin_amdgcn_readlane(bs.n, b);
+                const int f_b = __builtin_amdgcn_readlane(bs.first, b);
                 const int L_b = __builtin_amdgcn_readlane(bs.L, b);
                 const long start_b = (static_cast<long>(__builtin_amdgcn_readlane(bs.start_hi, b)) << 32) |
                                      static_cast<uint32_t>(__builtin_amdgcn_readlane(bs.start_lo, b));
@@ -610,7 +620,7 @@ __device__ __forceinline__ void attention_workgroup(const int* __restrict__ kv_l
                     const int tile0 = first + cg * seg_len + SEG_COST_TILES;      // position of the segment's first tile
                     const int lo = max(r0, tile0), hi = min(r1, tile0 + tiles_b);
                     if (lo < hi)
-                        run_segment(b, L_b, n_b, n_b * prm.G, cg, lo - tile0, hi - tile0, tiles_b - 1, start_b,
+                        run_segment(b, L_b, n_b, f_b, (n_b - f_b) * prm.G, cg, lo - tile0, hi - tile0, tiles_b - 1, start_b,
                                     prm.part + (static_cast<long>(g) * prm.nslot + id + groups_before + cg) * PART_SLOT_B);
                 }
             }
@@ -625,9 +635,10 @@ __device__ __forceinline__ void attention_workgroup(const int* __restrict__ kv_l
 template <bool BATCH>
 __global__ __launch_bounds__(THREADS) void tree_attention_bf16_kernel(const int* __restrict__ kv_len_arg,
                                                                       const int* __restrict__ n_nodes_arg,
+                                                                      const int* __restrict__ first_node_arg,
                                                                       const int64_t* __restrict__ kv_start_arg, int nslot_arg,
                                                                       int min_tps_arg, int G_arg, const Params prm) {
-    attention_workgroup<BATCH>(kv_len_arg, n_nodes_arg, kv_start_arg, nslot_arg, min_tps_arg, G_arg, prm, 0);
+    attention_workgroup<BATCH>(kv_len_arg, n_nodes_arg, first_node_arg, kv_start_arg, nslot_arg, min_tps_arg, G_arg, prm, 0);
 }
 
 // The same launch carrying the planning of the next tree along (sage_tree_attention_with_plan): the grid has extra
@@ -666,7 +677,7 @@ __global__ __launch_bounds__(THREADS) void tree_attention_plan_kernel(const int*
         sage::plan_sequence<PLAN_OWN, THREADS>(b, pl, sh);
         return;
     }
-    attention_workgroup<BATCH>(kv_len_arg, n_nodes_arg, kv_start_arg, nslot_arg, min_tps_arg, G_arg, prm, plan_slabs);
+    attention_workgroup<BATCH>(kv_len_arg, n_nodes_arg, nullptr, kv_start_arg, nslot_arg, min_tps_arg, G_arg, prm, plan_slabs);   // a verify pass: every node
 }
 
 // Merge the splits of one (sequence, node, query head) in split order and write bf16.  One wave per row:
@@ -756,17 +767,19 @@ __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const i
     if (!BATCH) {
         int len_b = __builtin_amdgcn_readfirstlane(kv_len_arg[b]);   // requested together, waited for once
         int n_b = __builtin_amdgcn_readfirstlane(n_nodes_arg[b]);
-        asm("" : "+s"(len_b), "+s"(n_b));
+        int f_b = prm.first_node ? __builtin_amdgcn_readfirstlane(prm.first_node[b]) : 0;
+        asm("" : "+s"(len_b), "+s"(n_b), "+s"(f_b));
         const int L = len_b > 0 ? len_b : 0;
-        const Split sp = make_split(n_b, L, G_arg, nslot_arg, min_tps_arg);
+        const Split sp = make_split(n_b, f_b, L, G_arg, nslot_arg, min_tps_arg);
         if (sp.col_groups > nslot_arg) return;
         const unsigned char* base = prm.part + ((static_cast<long>(b) * prm.Hkv + g) * prm.nslot) * PART_SLOT_B;
         for (int m = phase * ROWS + wave; m < sp.rows; m += phases * ROWS)
-            merge_row(b, m / prm.G, m % prm.G, base + (static_cast<long>(m / ROWS_PER_WG) * ROWS_PER_WG + m % ROWS_PER_WG) * PART_ROW_B,
+            merge_row(b, sp.first + m / prm.G, m % prm.G, base + (static_cast<long>(m / ROWS_PER_WG) * ROWS_PER_WG + m % ROWS_PER_WG) * PART_ROW_B,
                       static_cast<unsigned>(sp.col_groups) * static_cast<unsigned>(PART_SLOT_B), sp.nsplit);
     } else {
         const BatchShape bs = make_batch_shape(prm, lane);
-        const int live = __builtin_amdgcn_readlane(bs.n, b) * prm.G;
+        const int first_b = __builtin_amdgcn_readlane(bs.first, b);
+        const int live = (__builtin_amdgcn_readlane(bs.n, b) - first_b) * prm.G;
         const int tiles_b = __builtin_amdgcn_readlane(bs.tiles, b);
         const int before = wave_sum_i32(lane < b ? (bs.tiles + SEG_COST_TILES) * bs.col_groups : 0);
         const int groups_before = wave_sum_i32(lane < b ? bs.col_groups : 0);
@@ -774,7 +787,7 @@ __global__ __launch_bounds__(64 * ROWS) void tree_attention_merge_kernel(const i
             const int cg = m / ROWS_PER_WG;
             const int u0 = before + cg * (tiles_b + SEG_COST_TILES) + SEG_COST_TILES;   // first tile of segment (b, cg)
             const int s_first = u0 / bs.q;
-            merge_row(b, m / prm.G, m % prm.G,
+            merge_row(b, first_b + m / prm.G, m % prm.G,
                       prm.part + (static_cast<long>(g) * prm.nslot + s_first + groups_before + cg) * PART_SLOT_B + (m % ROWS_PER_WG) * PART_ROW_B,
                       static_cast<unsigned>(PART_SLOT_B), (u0 + tiles_b - 1) / bs.q - s_first + 1);
         }
@@ -845,7 +858,8 @@ bool attention_bf16_can_carry_plan(const PlanArgs& pl) {
 int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const void* Kt, const void* Vt, void* O, int B,
                         int Hq, int Hkv, int d, const int64_t* kv_start, const int* kv_len, int max_kv_len,
                         long kv_token_stride, long kv_head_stride, const uint64_t* anc_mask, const int* n_nodes,
-                        float scale, void* workspace, size_t workspace_bytes, hipStream_t stream, const PlanArgs* plan) {
+                        const int* first_node, float scale, void* workspace, size_t workspace_bytes, hipStream_t stream,
+                        const PlanArgs* plan) {
     const int G = Hq / Hkv;
     if (d != D || G < 1 || G > 16) return SAGE_UNSUPPORTED;   // 64 nodes x 16 heads per KV head = 8 groups of 128 rows
     if ((kv_token_stride % 8) != 0 || (kv_head_stride % 8) != 0) return SAGE_INVALID_ARG;
@@ -859,6 +873,7 @@ int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const voi
     p.Q = static_cast<const uint16_t*>(Q); p.Kc = static_cast<const uint16_t*>(Kc); p.Vc = static_cast<const uint16_t*>(Vc);
     p.Kt = static_cast<const uint16_t*>(Kt); p.Vt = static_cast<const uint16_t*>(Vt); p.O = static_cast<uint16_t*>(O);
     p.kv_start = kv_start; p.kv_len = kv_len; p.anc_mask = anc_mask; p.n_nodes = n_nodes;
+    p.first_node = plan ? nullptr : first_node;
     p.part = static_cast<unsigned char*>(workspace);
     p.kv_token_stride = kv_token_stride; p.kv_head_stride = kv_head_stride;
     p.B = B; p.Hq = Hq; p.Hkv = Hkv; p.G = G;
@@ -884,10 +899,10 @@ int tree_attention_bf16(const void* Q, const void* Kc, const void* Vc, const voi
     } else {
         const dim3 grid(Hkv, own_slabs, sh.batch ? 1 : B);
         if (sh.batch)
-            hipLaunchKernelGGL(tree_attention_bf16_kernel<true>, grid, block, 0, stream, kv_len, n_nodes, kv_start, p.nslot,
+            hipLaunchKernelGGL(tree_attention_bf16_kernel<true>, grid, block, 0, stream, kv_len, n_nodes, first_node, kv_start, p.nslot,
                                p.min_tiles_per_split, G, p);
         else
-            hipLaunchKernelGGL(tree_attention_bf16_kernel<false>, grid, block, 0, stream, kv_len, n_nodes, kv_start, p.nslot,
+            hipLaunchKernelGGL(tree_attention_bf16_kernel<false>, grid, block, 0, stream, kv_len, n_nodes, first_node, kv_start, p.nslot,
                                p.min_tiles_per_split, G, p);
     }
     if (hipGetLastError() != hipSuccess) return SAGE_LAUNCH_FAILED;

@@ -28,7 +28,7 @@ __global__ __launch_bounds__(THREADS) void tree_attention_f32_kernel(
     const float* __restrict__ Q, const float* __restrict__ Kc, const float* __restrict__ Vc,
     const float* __restrict__ Kt, const float* __restrict__ Vt, float* __restrict__ O, int Hq, int Hkv, int d,
     const int64_t* __restrict__ kv_start, const int* __restrict__ kv_len, long kv_token_stride, long kv_head_stride,
-    const uint64_t* __restrict__ anc_mask, const int* __restrict__ n_nodes, float scale) {
+    const uint64_t* __restrict__ anc_mask, const int* __restrict__ n_nodes, const int* __restrict__ first_node, float scale) {
     __shared__ float s_q[256];
     __shared__ float s_p[THREADS];
     __shared__ float s_red[THREADS / 64];
@@ -36,7 +36,9 @@ __global__ __launch_bounds__(THREADS) void tree_attention_f32_kernel(
     const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     int n = n_nodes[b];
     n = n < 1 ? 1 : (n > SAGE_MAX_NODES ? SAGE_MAX_NODES : n);   // a tree always has its root
-    if (i >= n) return;
+    int first = first_node ? first_node[b] : 0;             // rows of earlier nodes are not asked for
+    first = first < 0 ? 0 : (first > n - 1 ? n - 1 : first);
+    if (i >= n || i < first) return;
     const int tid = threadIdx.x;
     const int g = h / (Hq / Hkv);
     const int L = kv_len[b] > 0 ? kv_len[b] : 0;
@@ -122,15 +124,15 @@ namespace sage {
 
 int tree_attention_f32(const void* Q, const void* Kc, const void* Vc, const void* Kt, const void* Vt, void* O, int B,
                        int Hq, int Hkv, int d, const int64_t* kv_start, const int* kv_len, long kv_token_stride,
-                       long kv_head_stride, const uint64_t* anc_mask, const int* n_nodes, float scale,
-                       hipStream_t stream) {
+                       long kv_head_stride, const uint64_t* anc_mask, const int* n_nodes, const int* first_node,
+                       float scale, hipStream_t stream) {
     if (d < 4 || d > 256 || (d % 4) != 0) return SAGE_UNSUPPORTED;
     if ((kv_token_stride % 4) != 0 || (kv_head_stride % 4) != 0) return SAGE_INVALID_ARG;
     if (Hq > 65535 || B > 65535) return SAGE_UNSUPPORTED;
     hipLaunchKernelGGL(tree_attention_f32_kernel, dim3(SAGE_MAX_NODES, Hq, B), dim3(THREADS), 0, stream,
                        static_cast<const float*>(Q), static_cast<const float*>(Kc), static_cast<const float*>(Vc),
                        static_cast<const float*>(Kt), static_cast<const float*>(Vt), static_cast<float*>(O), Hq, Hkv, d,
-                       kv_start, kv_len, kv_token_stride, kv_head_stride, anc_mask, n_nodes, scale);
+                       kv_start, kv_len, kv_token_stride, kv_head_stride, anc_mask, n_nodes, first_node, scale);
     return launch_status();
 }
 

@@ -49,7 +49,7 @@ def lib():
         L.sage_tree_attention_workspace_bytes.argtypes = [_ci, _ci, _ci, _ci, _ci, _ci]
         L.sage_tree_attention.restype = _ci
         L.sage_tree_attention.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _ci, _ci, _ci, _ci, _ci, _vp, _vp, _ci, _cl, _cl,
-                                          _vp, _vp, _cf, _vp, _sz, _vp]
+                                          _vp, _vp, _vp, _cf, _vp, _sz, _vp]
         L.sage_tree_attention_static_scratch_bytes.restype = _sz
         L.sage_tree_attention_static_scratch_bytes.argtypes = []
         L.sage_tree_attention_static.restype = _ci
@@ -150,8 +150,9 @@ def _args_build_tree(topk_renorm, alpha, params: TreeParams, n_nodes, parent, de
             _ptr(parent), _ptr(depth), _ptr(rank), _ptr(anc_mask), _ptr(cum_prob), _ptr(node_token), _stream(stream)]
 
 
-def _args_tree_attention(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_token_stride, kv_head_stride, anc_mask,
-                         n_nodes, scale, workspace, stream=None):
+def _args_attention_common(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_token_stride, kv_head_stride, anc_mask,
+                           n_nodes, scale, workspace, stream):
+    """The argument list the three attention entry points share (without first_node, which only the plain call has)."""
     B, _, Hq, d = Q.shape
     Hkv = Kt.shape[2]
     return [_ptr(Q), _ptr(Kc), _ptr(Vc), _ptr(Kt), _ptr(Vt), _ptr(O), _dtype_code(Q), B, Hq, Hkv, d, _ptr(kv_start),
@@ -159,10 +160,17 @@ def _args_tree_attention(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_
             _ptr(workspace), _nbytes(workspace), _stream(stream)]
 
 
+def _args_tree_attention(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_token_stride, kv_head_stride, anc_mask,
+                         n_nodes, scale, workspace, stream=None, first_node=None):
+    att = _args_attention_common(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_token_stride, kv_head_stride, anc_mask,
+                                 n_nodes, scale, workspace, stream)
+    return att[:18] + [_ptr(first_node)] + att[18:]    # first_node follows n_nodes
+
+
 def _args_tree_attention_static(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_token_stride, kv_head_stride, anc_mask,
                                 n_nodes, scale, stream=None):
-    att = _args_tree_attention(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_token_stride, kv_head_stride, anc_mask,
-                               n_nodes, scale, None, stream)
+    att = _args_attention_common(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_token_stride, kv_head_stride, anc_mask,
+                                 n_nodes, scale, None, stream)
     return att[:-3] + att[-1:]                         # no workspace pair
 
 
@@ -170,8 +178,8 @@ def _args_tree_attention_with_plan(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_k
                                    n_nodes, scale, workspace, slices, vocab, params: TreeParams, entropy, topk_idx, topk_prob,
                                    topk_renorm, topk_entropy, alpha, next_n_nodes, next_parent, next_depth, next_rank,
                                    next_anc_mask, next_cum_prob=None, next_node_token=None, stream=None, d_max_seq=None):
-    att = _args_tree_attention(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_token_stride, kv_head_stride, anc_mask,
-                               n_nodes, scale, workspace, stream)
+    att = _args_attention_common(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_kv_len, kv_token_stride, kv_head_stride, anc_mask,
+                                 n_nodes, scale, workspace, stream)
     plan = _args_build_tree_from_slices(slices, vocab, params, entropy, topk_idx, topk_prob, topk_renorm, topk_entropy, alpha,
                                         next_n_nodes, next_parent, next_depth, next_rank, next_anc_mask, next_cum_prob,
                                         next_node_token, stream, d_max_seq)

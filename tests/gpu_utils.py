@@ -67,7 +67,7 @@ def gpu_build_tree(topk_renorm_np, alpha_np, prm: dict, topk_idx_np=None, d_max_
     return res
 
 
-def gpu_tree_attention(inp: dict, anc_mask_np, n_nodes_np, Hq, Hkv, d, scale=None, fill=None):
+def gpu_tree_attention(inp: dict, anc_mask_np, n_nodes_np, Hq, Hkv, d, scale=None, fill=None, first_node_np=None):
     """inp as produced by workloads.attention_inputs.  Returns O widened to fp64 ([B,64,Hq,d]) and the raw tensor."""
     Q, Kc, Vc, Kt, Vt = (to_dev(inp[k]) for k in ("Q", "Kc", "Vc", "Kt", "Vt"))
     B = Q.shape[0]
@@ -81,8 +81,9 @@ def gpu_tree_attention(inp: dict, anc_mask_np, n_nodes_np, Hq, Hkv, d, scale=Non
     ws = torch.empty(sage.sage_tree_attention_workspace_bytes(code, B, Hq, Hkv, d, max_len), device=DEV, dtype=torch.uint8)
     if scale is None:
         scale = 1.0 / float(np.sqrt(d))
+    first = None if first_node_np is None else to_dev(np.asarray(first_node_np, np.int32))
     sage.sage_tree_attention(Q, Kc, Vc, Kt, Vt, O, kv_start, kv_len, max_len, inp["kv_token_stride"],
-                             inp["kv_head_stride"], mask, nn, scale, ws)
+                             inp["kv_head_stride"], mask, nn, scale, ws, first_node=first)
     torch.cuda.synchronize()
     return widen(to_host(O)), O
 

@@ -82,9 +82,9 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
 
     lib.sage_tree_attention.argtypes = [ctypes.c_void_p] * 6 + [ctypes.c_int] * 5 + [ctypes.c_void_p, ctypes.c_void_p,
                                        ctypes.c_int, ctypes.c_long, ctypes.c_long, ctypes.c_void_p, ctypes.c_void_p,
-                                       ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+                                       ctypes.c_void_p, ctypes.c_float, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
     att = lambda **kw: [256] * 6 + [kw.get("dtype", 1), kw.get("B", 1), kw.get("Hq", 64), kw.get("Hkv", 8), kw.get("d", 128),
-                                    256, 256, kw.get("L", 4096), kw.get("ts", 1024), 128, 256, 256, kw.get("scale", 0.088),
+                                    256, 256, kw.get("L", 4096), kw.get("ts", 1024), 128, 256, 256, None, kw.get("scale", 0.088),
                                     kw.get("ws", 256), kw.get("wsb", 1 << 30), None]
     assert lib.sage_tree_attention(*att(Hq=63)) == INVALID
     assert lib.sage_tree_attention(*att(scale=0.0)) == INVALID

@@ -241,11 +241,13 @@ def test_attention_cache_layouts(gu, layout, dtype, Hq, Hkv, d):
     gu.assert_attention_close(got, ref, nn, TOL[dtype])
 
 
-@pytest.mark.parametrize("Hq,Hkv,L,n", [(28, 4, 1638, 25), (64, 8, 300, 64)])
-def test_attention_level_by_level_growth(gu, Hq, Hkv, L, n):
+@pytest.mark.parametrize("Hq,Hkv,L,n,rows_only", [(28, 4, 1638, 25, False), (64, 8, 300, 64, False),
+                                                   (28, 4, 1638, 25, True), (64, 8, 300, 64, True), (32, 2, 700, 64, True)])
+def test_attention_level_by_level_growth(gu, Hq, Hkv, L, n, rows_only):
     """A tree drafted one level per forward pass (the draft side of Alg. 1 Phase 1): call l sees the nodes of levels
     0..l, a prefix of the level-ordered tree, and the rows of level l must come out as in the oracle's single pass over
-    the whole tree, because a node attends only to the cache and its ancestors."""
+    the whole tree, because a node attends only to the cache and its ancestors.  With rows_only the call is also told
+    where level l starts (first_node) and must leave the rows of the levels before it alone."""
     from helpers import depth_by_walk, level_order
     g = wl.rng(7000 + n)
     par = level_order(random_parents(g, n, chain_bias=0.3))
@@ -257,12 +259,40 @@ def test_attention_level_by_level_growth(gu, Hq, Hkv, L, n):
                                 inp["kv_token_stride"], inp["kv_head_stride"], mask, nn, Hq, Hkv, 128)
     for level in range(int(dep.max()) + 1):
         upto = np.array([int((dep <= level).sum())], np.int32)
-        got, _ = gu.gpu_tree_attention(inp, mask, upto, Hq, Hkv, 128, fill=7.0)
+        first = np.array([int((dep < level).sum())], np.int32)
+        got, _ = gu.gpu_tree_attention(inp, mask, upto, Hq, Hkv, 128, fill=7.0, first_node_np=first if rows_only else None)
         rows = np.nonzero(dep == level)[0]
         g_l, r_l = got[0, rows], ref[0, rows]
         err = np.abs(g_l - r_l).max(-1) / np.maximum(np.abs(r_l).max(-1), 1e-300)
         assert err.max() <= TOL["bf16"], (level, float(err.max()))
         assert (got[0, int(upto[0]):] == 7.0).all()             # nodes of deeper levels are not there yet
+        if rows_only:
+            assert (got[0, :int(first[0])] == 7.0).all()        # and the levels before are not computed again
+
+
+@pytest.mark.parametrize("dtype,B,Hq,Hkv,d", [("bf16", 3, 32, 4, 128), ("bf16", 1, 64, 4, 128), ("f32", 2, 4, 2, 64)])
+def test_attention_first_node_batches_and_clamping(gu, dtype, B, Hq, Hkv, d):
+    """first_node per sequence: rows [first, n) equal the call without it bit for bit (the same keys, the same split
+    boundaries only if the row count leaves the decomposition alone, so compare to the oracle as well), rows outside
+    stay untouched; values outside [0, n) are clamped into it."""
+    g = wl.rng(7300 + B)
+    lens = [int(x) for x in g.integers(100, 1500, size=B)]
+    sizes = [64, 9, 33][:B]
+    masks = np.zeros((B, 64), np.uint64)
+    for b in range(B):
+        masks[b] = pad_tree(random_parents(g, sizes[b], 0.4))[2][0]
+    nn = np.array(sizes, np.int32)
+    inp = wl.attention_inputs(7400 + B, B, Hq, Hkv, d, lens, dtype)
+    ref = oracle.tree_attention(inp["Q"], inp["Kc"], inp["Vc"], inp["Kt"], inp["Vt"], inp["kv_start"], inp["kv_len"],
+                                inp["kv_token_stride"], inp["kv_head_stride"], masks, nn, Hq, Hkv, d)
+    for first in ([10, 8, 32][:B], [63, 0, 1][:B], [-5, 100, 33][:B]):
+        got, _ = gu.gpu_tree_attention(inp, masks, nn, Hq, Hkv, d, fill=7.0, first_node_np=np.array(first, np.int32))
+        for b in range(B):
+            f = min(max(first[b], 0), sizes[b] - 1)
+            assert (got[b, :f] == 7.0).all() and (got[b, sizes[b]:] == 7.0).all()
+            g_l, r_l = got[b, f:sizes[b]], ref[b, f:sizes[b]]
+            err = np.abs(g_l - r_l).max(-1) / np.maximum(np.abs(r_l).max(-1), 1e-300)
+            assert err.max() <= TOL[dtype], (first, b, float(err.max()))
 
 
 @pytest.mark.parametrize("seed", range(24))
