@@ -187,6 +187,12 @@ class Workload:
         # the launch of the first layer's attention (sage_tree_attention_with_plan), everything on one stream.
         self.carry = carry
         assert not (carry and (overlap or not fused))
+        # With carried planning, what is left of planning on the chain is the slice pass over the draft row.  It depends
+        # on nothing the verification produces, so inside a run of steps (run_steps) the pass for the NEXT step shares
+        # the launch of this step's target-row pass (sage_entropy_topk_slices_pair).  A run starts with the pass as a
+        # launch of its own and ends with a plain target-row pass, so a captured graph is self-contained.
+        self.pair = carry
+        self.slices_for = -1                         # step number whose draft slices the last pair launch produced
         self.verify_first = True                     # enqueue the verification branch first (measured 2 % faster)
         self._prepare()
         torch.cuda.synchronize()
@@ -203,7 +209,7 @@ class Workload:
         else:
             self.c_a1 = [sg.prepare("sage_entropy_topk", self.draft[s], self.k, self.H, self.idx, self.prob, self.renorm,
                                     self.Hk, self.alpha, self.ws1, stream=pstream) for s in range(self.slots)]
-        self.c_a2, self.c_a3, self.c_a1t, self.c_a4, self.c_a3p = [], [], [], [], []
+        self.c_a2, self.c_a3, self.c_a1t, self.c_a4, self.c_a3p, self.c_pair = [], [], [], [], [], []
         for cur in range(2):
             t, nxt = self.tree[cur], self.tree[cur ^ 1]
             if self.carry:
@@ -242,6 +248,10 @@ class Workload:
                 self.c_a4.append(sg.prepare("sage_verify_accept", t["node_token"], self.tgt_idx, t["parent"], t["depth"],
                                             t["anc_mask"], t["n_nodes"], self.path_cap, self.acc_len, self.best, self.path,
                                             self.out_tok, stream=stream))
+            if self.carry:
+                self.c_pair.append([sg.prepare("sage_entropy_topk_slices_pair", self.target[s], t["n_nodes"], MAX_NODES, self.ws1t,
+                                               self.draft[(s + 1) % self.slots], self.k, self.ws1, stream=stream)
+                                    for s in range(self.slots)])
 
     def draft_confidence(self, s):
         self.c_a1[s]()
@@ -252,18 +262,30 @@ class Workload:
     def attention(self, s, layer):
         self.c_a3[self.cur][s][layer]()
 
-    def step(self):
+    def run_steps(self, n: int):
+        """n consecutive steps; inside the run the draft row's slice pass of a step rides in the previous step's
+        target-row launch (carried planning only)."""
+        self.slices_for = -1
+        for i in range(n):
+            self.step(last=i == n - 1)
+
+    def step(self, last: bool = True):
         s = self.step_no % self.slots
         cur = self.cur
         if self.overlap:                             # fork: the plan branch starts where the main stream stands
             main = self.torch.cuda.current_stream()
             self.plan_stream.wait_stream(main)
         if self.carry:
-            self.c_a1[s]()
+            if not (self.pair and self.slices_for == self.step_no):
+                self.c_a1[s]()                       # (otherwise the previous step's pair launch has left the slices)
             self.c_a3p[cur][s]()                     # first layer's attention with the planning inside its launch
             for call in self.c_a3[cur][s][1:]:
                 call()
-            self.c_a1t[cur][s]()
+            if self.pair and not last:               # target rows of this step + draft row of the next in one launch
+                self.c_pair[cur][s]()
+                self.slices_for = self.step_no + 1
+            else:
+                self.c_a1t[cur][s]()
             self.c_a4[cur]()
             self.cur ^= 1
             self.step_no += 1
@@ -326,8 +348,7 @@ def capture_steps(w: Workload, length: int):
 
     def eager_pass():
         w.step_no, w.cur = start
-        for _ in range(length):
-            w.step()
+        w.run_steps(length)
 
     torch.cuda.synchronize()
     try:
@@ -390,8 +411,7 @@ def time_steps(w: Workload, steps: int, warmup: int, use_graph: bool = True, min
     if graph is None:
         n = max(steps, 1)
         t0 = time.perf_counter()
-        for _ in range(n):
-            w.step()
+        w.run_steps(n)
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
         return dict(wall_s=wall, timed_steps=n, replays=0, steps_per_replay=0, eager_steps=n, launch_mode="eager launches")
@@ -917,10 +937,11 @@ def run_workload(name, steps, warmup, slots=None, eager=False, all_schedules=Fal
              "steps_per_replay": timing["steps_per_replay"], "eager_steps": timing["eager_steps"],
              "timed_region_ms": timing["wall_s"] * 1e3, "layers": w.layers, "batch": w.B, "input_sets": w.slots,
              "kv_sets": w.kv_slots, "kv_len": [int(x) for x in w.kv_lens], "tree_params": w.tree_prm,
-             "schedule": ("one stream; sage_entropy_topk_slices, sage_tree_attention_with_plan (first layer; sage_tree_attention "
-                          "for the others), sage_entropy_topk_slices, sage_verify_accept_from_slices: the merge + tree rule of the "
-                          "planning ride in the attention launch (the tree planned in a step is verified in the next one, Sec. 3.2 "
-                          "lookahead)") if bf16 else
+             "schedule": ("one stream, three launches per step: sage_tree_attention_with_plan (first layer; sage_tree_attention for "
+                          "the others), sage_entropy_topk_slices_pair, sage_verify_accept_from_slices.  The merge + tree rule of "
+                          "the planning ride in the attention launch (the tree planned in a step is verified in the next one, "
+                          "Sec. 3.2 lookahead) and the slice pass over the NEXT step's draft row shares the launch of this step's "
+                          "target-row pass; the first step of a graph runs sage_entropy_topk_slices on its draft row itself") if bf16 else
                          ("two streams forked and joined every step: planning (sage_entropy_topk_slices, "
                           "sage_build_tree_from_slices) beside verification (sage_tree_attention, sage_entropy_topk_slices, "
                           "sage_verify_accept_from_slices)")}

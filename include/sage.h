@@ -274,10 +274,22 @@ int sage_lm_head_topk(const void* hidden, const void* weight, int dtype, int row
  * (required), entropy [B,64] (nullable; full-vocabulary entropy of each live target row) and
  * those of sage_verify_accept.  Rows of nodes >= n_nodes[b] are neither read nor written.
  * Errors as for the calls they replace; `slices` 16-byte aligned.
+ *
+ * sage_entropy_topk_slices_pair: two per-slice passes that do not depend on each other in ONE
+ * launch: job A = sage_entropy_topk_slices(logits_a, rows_a, k = 1, n_valid_a, rows_per_group_a)
+ * (the target rows of the trees being verified, Sec. 2.2) and job B = sage_entropy_topk_slices(
+ * logits_b, rows_b, k_b > 1, every row valid) (draft rows, Sec. 3.1; in a decoding loop those of
+ * the NEXT step, whose planning depends on nothing this step's verification produces).  Both
+ * workspaces end up exactly as after the two separate calls; same dtype and vocab for both.
+ * Errors: INVALID_ARG if n_valid_a is null or k_b < 2, otherwise those of the separate calls.
  */
 int sage_entropy_topk_slices(const void* logits, int dtype, int rows, int vocab, long row_stride, int k,
                              const int* n_valid, int rows_per_group, void* workspace, size_t workspace_bytes,
                              void* stream);
+int sage_entropy_topk_slices_pair(const void* logits_a, int rows_a, long row_stride_a, const int* n_valid_a,
+                                  int rows_per_group_a, void* workspace_a, size_t workspace_a_bytes,
+                                  const void* logits_b, int rows_b, long row_stride_b, int k_b, void* workspace_b,
+                                  size_t workspace_b_bytes, int dtype, int vocab, void* stream);
 int sage_build_tree_from_slices(void* slices, int vocab, int B, int k, const sage_tree_params* params,
                                 const int* d_max_seq, float* entropy, int* topk_idx, float* topk_prob,
                                 float* topk_renorm, float* topk_entropy, float* alpha, int* n_nodes, int* parent,

@@ -134,16 +134,14 @@ __global__ __launch_bounds__(THREADS) void slice_kernel(const T* __restrict__ lo
 // while the current one is reduced, so rows past n_valid cost no workgroup of their own.
 constexpr int ROW_PHASES = 16;
 template <typename T>
-__global__ __launch_bounds__(THREADS) void slice_rows_kernel(const T* __restrict__ logits, int vocab, long row_stride,
-                                                             const int* __restrict__ n_valid, int rows_per_group, int rows,
-                                                             int nunits, UnitStats* __restrict__ stats,
-                                                             uint64_t* __restrict__ keys) {
+__device__ __forceinline__ void slice_rows_block(const T* __restrict__ logits, int vocab, long row_stride,
+                                                 const int* __restrict__ n_valid, int rows_per_group, int rows, int nunits,
+                                                 UnitStats* __restrict__ stats, uint64_t* __restrict__ keys, int block_x,
+                                                 int phase, int phases, int group) {
     constexpr int NV = EPT / Loader<T>::VEC;
-    const int group = blockIdx.z;
-    const int phases = gridDim.y;
-    const int unit = blockIdx.x * WAVES + (threadIdx.x >> 6);
+    const int unit = block_x * WAVES + (threadIdx.x >> 6);
     const int n = min(n_valid[group], min(rows_per_group, rows - group * rows_per_group));   // the last group may be short
-    int r = blockIdx.y;
+    int r = phase;
     if (unit >= nunits || r >= n) return;
     const int lane = threadIdx.x & 63;
     const int base = unit * UNIT;
@@ -161,6 +159,14 @@ __global__ __launch_bounds__(THREADS) void slice_rows_kernel(const T* __restrict
         r = rn;
     }
 }
+template <typename T>
+__global__ __launch_bounds__(THREADS) void slice_rows_kernel(const T* __restrict__ logits, int vocab, long row_stride,
+                                                             const int* __restrict__ n_valid, int rows_per_group, int rows,
+                                                             int nunits, UnitStats* __restrict__ stats,
+                                                             uint64_t* __restrict__ keys) {
+    slice_rows_block<T>(logits, vocab, row_stride, n_valid, rows_per_group, rows, nunits, stats, keys, blockIdx.x, blockIdx.y,
+                        gridDim.y, blockIdx.z);
+}
 
 // Pass 1 for bf16 logits and 1 < k <= 16 (the draft row of a step; pure latency, so the serial selection rounds are
 // kept as short as they can be): the same decomposition as the generic kernel below, but the rounds run on ONE
@@ -168,14 +174,12 @@ __global__ __launch_bounds__(THREADS) void slice_rows_kernel(const T* __restrict
 // order (value descending, index ascending) inside a slice; 0 = no candidate.  Each wave selects the k best of its
 // 256 logits, wave 0 then selects the k best of the 4k survivors held one per lane.
 constexpr int FAST_MAX_K = 16;
-__global__ __launch_bounds__(THREADS) void slice_topk_bf16_kernel(const uint16_t* __restrict__ logits, int vocab, long row_stride,
-                                                                  int k, const int* __restrict__ n_valid, int rows_per_group,
-                                                                  int nunits, UnitStats* __restrict__ stats,
-                                                                  uint64_t* __restrict__ keys) {
+__device__ __forceinline__ void slice_topk_bf16_block(const uint16_t* __restrict__ logits, int vocab, long row_stride, int k,
+                                                      const int* __restrict__ n_valid, int rows_per_group, int nunits,
+                                                      UnitStats* __restrict__ stats, uint64_t* __restrict__ keys, int unit,
+                                                      int row) {
     __shared__ uint32_t s_list[WAVES * FAST_MAX_K];
     __shared__ float s_red[3][WAVES];
-    const int row = blockIdx.y;
-    const int unit = blockIdx.x;
     if (!row_is_valid(row, n_valid, rows_per_group)) return;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -252,17 +256,21 @@ __global__ __launch_bounds__(THREADS) void slice_topk_bf16_kernel(const uint16_t
         stats[static_cast<long>(row) * nunits + unit] = UnitStats{m, z, t, 0.f};
     }
 }
+__global__ __launch_bounds__(THREADS) void slice_topk_bf16_kernel(const uint16_t* __restrict__ logits, int vocab, long row_stride,
+                                                                  int k, const int* __restrict__ n_valid, int rows_per_group,
+                                                                  int nunits, UnitStats* __restrict__ stats,
+                                                                  uint64_t* __restrict__ keys) {
+    slice_topk_bf16_block(logits, vocab, row_stride, k, n_valid, rows_per_group, nunits, stats, keys, blockIdx.x, blockIdx.y);
+}
 
 // Pass 1 for k > 1 (few rows, latency matters more than bandwidth): one WORKGROUP per slice, 4 logits per lane.
 // Each wave extracts the k best of its 256 logits; wave 0 then merges the four sorted lists.
 template <typename T>
-__global__ __launch_bounds__(THREADS) void slice_topk_kernel(const T* __restrict__ logits, int vocab, long row_stride, int k,
-                                                             const int* __restrict__ n_valid, int rows_per_group, int nunits,
-                                                             UnitStats* __restrict__ stats, uint64_t* __restrict__ keys) {
+__device__ __forceinline__ void slice_topk_block(const T* __restrict__ logits, int vocab, long row_stride, int k,
+                                                 const int* __restrict__ n_valid, int rows_per_group, int nunits,
+                                                 UnitStats* __restrict__ stats, uint64_t* __restrict__ keys, int unit, int row) {
     __shared__ uint64_t s_list[WAVES][SAGE_MAX_TOPK];
     __shared__ float s_red[3][WAVES];
-    const int row = blockIdx.y;
-    const int unit = blockIdx.x;
     if (!row_is_valid(row, n_valid, rows_per_group)) return;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -347,6 +355,41 @@ __global__ __launch_bounds__(THREADS) void slice_topk_kernel(const T* __restrict
         stats[static_cast<long>(row) * nunits + unit] = UnitStats{m, z, t, 0.f};
     }
 }
+template <typename T>
+__global__ __launch_bounds__(THREADS) void slice_topk_kernel(const T* __restrict__ logits, int vocab, long row_stride, int k,
+                                                             const int* __restrict__ n_valid, int rows_per_group, int nunits,
+                                                             UnitStats* __restrict__ stats, uint64_t* __restrict__ keys) {
+    slice_topk_block<T>(logits, vocab, row_stride, k, n_valid, rows_per_group, nunits, stats, keys, blockIdx.x, blockIdx.y);
+}
+
+// Two first passes in one launch (sage_entropy_topk_slices_pair): the k = 1 pass over grouped rows (job A, the grid
+// of slice_rows_kernel) with the k > 1 pass over a few rows (job B) in slabs of workgroups ahead of it.  A step is a
+// chain of dependent launches, each a few microseconds whatever it computes; two passes that do not depend on each
+// other share one.  FAST: job B takes the 32-bit rounds (bf16, k <= 16).
+struct PairJob {
+    const void* logits; long row_stride; int rows, k, nunits;
+    UnitStats* stats; uint64_t* keys;
+};
+template <typename T, bool FAST>
+__global__ __launch_bounds__(THREADS) void slice_pair_kernel(const T* __restrict__ logits_a, int vocab, long row_stride_a,
+                                                             const int* __restrict__ n_valid_a, int rows_per_group_a,
+                                                             int rows_a, int nunits, UnitStats* __restrict__ stats_a,
+                                                             uint64_t* __restrict__ keys_a, int slabs_b, const PairJob b) {
+    if (static_cast<int>(blockIdx.z) < slabs_b) {            // workgroup-uniform
+        const int lin = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+        if (lin >= b.nunits * b.rows) return;
+        const int row = lin / b.nunits, unit = lin - row * b.nunits;
+        if constexpr (FAST)
+            slice_topk_bf16_block(static_cast<const uint16_t*>(b.logits), vocab, b.row_stride, b.k, nullptr, 1, b.nunits, b.stats,
+                                  b.keys, unit, row);
+        else
+            slice_topk_block<T>(static_cast<const T*>(b.logits), vocab, b.row_stride, b.k, nullptr, 1, b.nunits, b.stats, b.keys,
+                                unit, row);
+        return;
+    }
+    slice_rows_block<T>(logits_a, vocab, row_stride_a, n_valid_a, rows_per_group_a, rows_a, nunits, stats_a, keys_a, blockIdx.x,
+                        blockIdx.y, gridDim.y, static_cast<int>(blockIdx.z) - slabs_b);
+}
 
 // Pass 2 as a launch of its own: one workgroup per row (see merge_row).
 template <int OWN>
@@ -404,9 +447,9 @@ void topk_workspace_layout(int rows, int vocab, void* workspace, UnitStats** sta
 
 }  // namespace sage
 
-// Argument checks and the first pass, common to sage_entropy_topk and sage_entropy_topk_slices.
-static int run_first_pass(const void* logits, int dtype, int rows, int vocab, long row_stride, int k, const int* n_valid,
-                          int rows_per_group, void* workspace, size_t workspace_bytes, hipStream_t s) {
+// Argument checks of a first pass; SAGE_OK means it may be launched (rows == 0: there is nothing to launch).
+static int check_first_pass(const void* logits, int dtype, int rows, int vocab, long row_stride, int k, const int* n_valid,
+                            int rows_per_group, void* workspace, size_t workspace_bytes) {
     if (!logits || !workspace) return SAGE_INVALID_ARG;
     if (rows < 0 || vocab < 1 || k < 1 || k > SAGE_MAX_TOPK || k > vocab || row_stride < vocab) return SAGE_INVALID_ARG;
     if (dtype != SAGE_F32 && dtype != SAGE_BF16) return SAGE_INVALID_ARG;
@@ -418,8 +461,15 @@ static int run_first_pass(const void* logits, int dtype, int rows, int vocab, lo
     if (nunits > 64 * MAX_OWN) return SAGE_UNSUPPORTED;
     if (rows > 65535) return SAGE_UNSUPPORTED;
     if (workspace_bytes < sage_entropy_topk_workspace_bytes(rows, vocab, k)) return SAGE_WORKSPACE_TOO_SMALL;
-    if (rows == 0) return SAGE_OK;
+    return SAGE_OK;
+}
 
+// Argument checks and the first pass, common to sage_entropy_topk and sage_entropy_topk_slices.
+static int run_first_pass(const void* logits, int dtype, int rows, int vocab, long row_stride, int k, const int* n_valid,
+                          int rows_per_group, void* workspace, size_t workspace_bytes, hipStream_t s) {
+    const int rc = check_first_pass(logits, dtype, rows, vocab, row_stride, k, n_valid, rows_per_group, workspace, workspace_bytes);
+    if (rc != SAGE_OK || rows == 0) return rc;
+    const int nunits = num_units(vocab);
     UnitStats* stats = static_cast<UnitStats*>(workspace);
     uint64_t* keys = reinterpret_cast<uint64_t*>(static_cast<char*>(workspace) + stats_bytes(rows, vocab));
     if (k == 1 && !n_valid) {                        // many rows, one round: a wave per slice, 16 logits per lane
@@ -476,4 +526,47 @@ extern "C" int sage_entropy_topk_slices(const void* logits, int dtype, int rows,
                                         void* stream) {
     return run_first_pass(logits, dtype, rows, vocab, row_stride, k, n_valid, rows_per_group, workspace, workspace_bytes,
                           sage::as_stream(stream));
+}
+
+extern "C" int sage_entropy_topk_slices_pair(const void* logits_a, int rows_a, long row_stride_a, const int* n_valid_a,
+                                             int rows_per_group_a, void* workspace_a, size_t workspace_a_bytes,
+                                             const void* logits_b, int rows_b, long row_stride_b, int k_b, void* workspace_b,
+                                             size_t workspace_b_bytes, int dtype, int vocab, void* stream) {
+    if (!n_valid_a || k_b < 2) return SAGE_INVALID_ARG;      // job A is the grouped k = 1 pass, job B a k > 1 pass
+    int rc = check_first_pass(logits_a, dtype, rows_a, vocab, row_stride_a, 1, n_valid_a, rows_per_group_a, workspace_a,
+                              workspace_a_bytes);
+    if (rc != SAGE_OK) return rc;
+    rc = check_first_pass(logits_b, dtype, rows_b, vocab, row_stride_b, k_b, nullptr, 1, workspace_b, workspace_b_bytes);
+    if (rc != SAGE_OK) return rc;
+    hipStream_t s = sage::as_stream(stream);
+    if (rows_a == 0 || rows_b == 0) {                        // one job is empty: the other one's own launch
+        if (rows_a) return run_first_pass(logits_a, dtype, rows_a, vocab, row_stride_a, 1, n_valid_a, rows_per_group_a, workspace_a,
+                                          workspace_a_bytes, s);
+        return run_first_pass(logits_b, dtype, rows_b, vocab, row_stride_b, k_b, nullptr, 1, workspace_b, workspace_b_bytes, s);
+    }
+    const int nunits = num_units(vocab);
+    UnitStats* stats_a = static_cast<UnitStats*>(workspace_a);
+    uint64_t* keys_a = reinterpret_cast<uint64_t*>(static_cast<char*>(workspace_a) + stats_bytes(rows_a, vocab));
+    PairJob b;
+    b.logits = logits_b; b.row_stride = row_stride_b; b.rows = rows_b; b.k = k_b; b.nunits = nunits;
+    b.stats = static_cast<UnitStats*>(workspace_b);
+    b.keys = reinterpret_cast<uint64_t*>(static_cast<char*>(workspace_b) + stats_bytes(rows_b, vocab));
+    const int groups = (rows_a + rows_per_group_a - 1) / rows_per_group_a;
+    const int gx = (nunits + WAVES - 1) / WAVES, gy = rows_per_group_a < ROW_PHASES ? rows_per_group_a : ROW_PHASES;
+    const long blocks_b = static_cast<long>(nunits) * rows_b;
+    const long slabs_b = (blocks_b + static_cast<long>(gx) * gy - 1) / (static_cast<long>(gx) * gy);
+    if (slabs_b + groups > 65535) return SAGE_UNSUPPORTED;
+    const dim3 grid(gx, gy, static_cast<unsigned>(slabs_b + groups));
+    if (dtype == SAGE_F32)
+        hipLaunchKernelGGL((slice_pair_kernel<float, false>), grid, dim3(THREADS), 0, s, static_cast<const float*>(logits_a), vocab,
+                           row_stride_a, n_valid_a, rows_per_group_a, rows_a, nunits, stats_a, keys_a, static_cast<int>(slabs_b), b);
+    else if (k_b <= FAST_MAX_K)
+        hipLaunchKernelGGL((slice_pair_kernel<uint16_t, true>), grid, dim3(THREADS), 0, s, static_cast<const uint16_t*>(logits_a),
+                           vocab, row_stride_a, n_valid_a, rows_per_group_a, rows_a, nunits, stats_a, keys_a,
+                           static_cast<int>(slabs_b), b);
+    else
+        hipLaunchKernelGGL((slice_pair_kernel<uint16_t, false>), grid, dim3(THREADS), 0, s, static_cast<const uint16_t*>(logits_a),
+                           vocab, row_stride_a, n_valid_a, rows_per_group_a, rows_a, nunits, stats_a, keys_a,
+                           static_cast<int>(slabs_b), b);
+    return sage::launch_status();
 }

@@ -77,6 +77,8 @@ def lib():
                                       _ci, _ci, _vp, _vp, _vp, _vp, _vp, _vp]
         L.sage_entropy_topk_slices.restype = _ci
         L.sage_entropy_topk_slices.argtypes = [_vp, _ci, _ci, _ci, _cl, _ci, _vp, _ci, _vp, _sz, _vp]
+        L.sage_entropy_topk_slices_pair.restype = _ci
+        L.sage_entropy_topk_slices_pair.argtypes = [_vp, _ci, _cl, _vp, _ci, _vp, _sz, _vp, _ci, _cl, _ci, _vp, _sz, _ci, _ci, _vp]
         L.sage_build_tree_from_slices.restype = _ci
         L.sage_build_tree_from_slices.argtypes = [_vp, _ci, _ci, _ci, ctypes.POINTER(TreeParams)] + [_vp] * 15
         L.sage_verify_accept_from_slices.restype = _ci
@@ -227,6 +229,15 @@ def _args_entropy_topk_slices(logits, k, workspace, n_valid=None, rows_per_group
             _ptr(workspace), _nbytes(workspace), _stream(stream)]
 
 
+def _args_entropy_topk_slices_pair(logits_a, n_valid_a, rows_per_group_a, workspace_a, logits_b, k_b, workspace_b, stream=None):
+    rows_a, vocab = logits_a.shape
+    rows_b, vocab_b = logits_b.shape
+    assert vocab_b == vocab and logits_a.dtype == logits_b.dtype and logits_a.stride(1) == 1 and logits_b.stride(1) == 1
+    return [_ptr(logits_a), rows_a, logits_a.stride(0), _ptr(n_valid_a), rows_per_group_a, _ptr(workspace_a), _nbytes(workspace_a),
+            _ptr(logits_b), rows_b, logits_b.stride(0), k_b, _ptr(workspace_b), _nbytes(workspace_b), _dtype_code(logits_a),
+            vocab, _stream(stream)]
+
+
 def _args_build_tree_from_slices(slices, vocab, params: TreeParams, entropy, topk_idx, topk_prob, topk_renorm, topk_entropy,
                                  alpha, n_nodes, parent, depth, rank, anc_mask, cum_prob=None, node_token=None, stream=None,
                                  d_max_seq=None):
@@ -269,6 +280,7 @@ _MARSHAL = {"sage_close_step": _args_close_step,
             "sage_tree_attention_with_plan": _args_tree_attention_with_plan,
             "sage_verify_accept_close_from_slices": _args_verify_accept_close_from_slices,
             "sage_entropy_topk_slices": _args_entropy_topk_slices,
+            "sage_entropy_topk_slices_pair": _args_entropy_topk_slices_pair,
             "sage_build_tree_from_slices": _args_build_tree_from_slices,
             "sage_verify_accept_from_slices": _args_verify_accept_from_slices,
             "sage_entropy_topk": _args_entropy_topk, "sage_build_tree": _args_build_tree,
@@ -333,6 +345,10 @@ def sage_lm_head_topk(*a, **kw):
 
 def sage_entropy_topk_slices(*a, **kw):
     _check("sage_entropy_topk_slices", lib().sage_entropy_topk_slices(*_args_entropy_topk_slices(*a, **kw)))
+
+
+def sage_entropy_topk_slices_pair(*a, **kw):
+    _check("sage_entropy_topk_slices_pair", lib().sage_entropy_topk_slices_pair(*_args_entropy_topk_slices_pair(*a, **kw)))
 
 
 def sage_build_tree_from_slices(*a, **kw):

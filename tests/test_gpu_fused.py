@@ -151,3 +151,34 @@ def test_attention_with_plan_equals_separate_calls_and_oracle(gu, name, dtype, B
             for b in range(B):
                 n = int(o2["n_nodes"][b])
                 np.testing.assert_array_equal(a2[key][b, :n], o2[key][b, :n], err_msg=f"{key}[{b}]")
+
+
+@pytest.mark.parametrize("dtype,vocab,B,k", [("bf16", 152064, 1, 16), ("bf16", 152064, 8, 10), ("bf16", 5000, 3, 40),
+                                             ("f32", 1024, 2, 8), ("bf16", 1032, 70, 2)])
+def test_slices_pair_equals_the_two_separate_passes(gu, dtype, vocab, B, k):
+    """sage_entropy_topk_slices_pair leaves both workspaces exactly as the two separate first passes do (same kernels'
+    code, one launch), whatever the mix of live rows."""
+    import torch
+    from paper_2602_00523_amd import sage
+    g = wl.rng(9100 + B)
+    target = wl.draft_logits(9200 + B, B * MAX_NODES, vocab, dtype, 2.0)
+    draft = wl.draft_logits(9300 + B, B, vocab, dtype, 3.0)
+    n_nodes = g.integers(0, MAX_NODES + 1, size=B).astype(np.int32)
+    n_nodes[0] = MAX_NODES
+    T, Dr, nv = gu.to_dev(target), gu.to_dev(draft), gu.to_dev(n_nodes)
+    size_a = sage.sage_entropy_topk_workspace_bytes(B * MAX_NODES, vocab, 1)
+    size_b = sage.sage_entropy_topk_workspace_bytes(B, vocab, k)
+    ws = [torch.zeros(n, device=gu.DEV, dtype=torch.uint8) for n in (size_a, size_b, size_a, size_b)]
+    sage.sage_entropy_topk_slices(T, 1, ws[0], nv, MAX_NODES)
+    sage.sage_entropy_topk_slices(Dr, k, ws[1])
+    sage.sage_entropy_topk_slices_pair(T, nv, MAX_NODES, ws[2], Dr, k, ws[3])
+    torch.cuda.synchronize()
+    assert torch.equal(ws[0], ws[2]) and torch.equal(ws[1], ws[3])
+    assert ws[0].any() and ws[1].any()
+    # no live target row at all
+    zero = gu.to_dev(np.zeros(B, np.int32))
+    for w in ws[2:]:
+        w.zero_()
+    sage.sage_entropy_topk_slices_pair(T, zero, MAX_NODES, ws[2], Dr, k, ws[3])
+    torch.cuda.synchronize()
+    assert not ws[2].any() and torch.equal(ws[1], ws[3])
