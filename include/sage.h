@@ -238,8 +238,9 @@ int sage_close_step(const void* Kt, const void* Vt, void* Kc, void* Vc, int dtyp
  *
  * hidden [rows, dim], weight [vocab, dim], row-major with row strides in elements, rows
  * 16-byte aligned.  This build: bf16, k = 1, dim a multiple of 128, row strides <= 2^24
- * elements, vocab <= 655360 (others: UNSUPPORTED).  The weight matrix is
- * read once per block of 64 rows.
+ * elements, vocab <= 655360 (others: UNSUPPORTED).  The weight matrix is fetched from HBM
+ * once per call; rows that n_valid marks dead cost nothing (live rows are packed into blocks
+ * of 128 before the pass).
  * workspace: sage_lm_head_topk_workspace_bytes(rows, vocab) bytes, 16-byte aligned.
  * Errors: INVALID_ARG (null pointers, sizes, strides, alignment), UNSUPPORTED,
  * WORKSPACE_TOO_SMALL.
