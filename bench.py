@@ -728,7 +728,7 @@ def lm_head_projection(dim=8192, vocab=152064, launches=12):
         H = torch.randn(rows, dim, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
         ent = torch.zeros(rows, device=dev)
         idx = torch.zeros(rows, 1, device=dev, dtype=torch.int32)
-        ws = torch.empty(sage.sage_lm_head_topk_workspace_bytes(rows, vocab), device=dev, dtype=torch.uint8)
+        ws = torch.empty(sage.sage_lm_head_topk_workspace_bytes(rows, vocab, 1), device=dev, dtype=torch.uint8)
         nv = None if n_valid is None else torch.tensor(n_valid, device=dev, dtype=torch.int32)
         call = sage.prepare("sage_lm_head_topk", H, W, 1, ent, idx, None, None, None, None, ws, nv, 64)
         for _ in range(3):
@@ -755,6 +755,35 @@ def lm_head_projection(dim=8192, vocab=152064, launches=12):
                         argmax_agrees_with_fp32_matmul=float((ref == idx[:, 0].long())[alive].float().mean().item())))
         del H
     del W, Wf
+    torch.cuda.empty_cache()
+    # The draft side (Sec. 3.1): a 7B-shape projection (hidden 3584) with candidate lists of k = 10, for the one row of a
+    # step's root and for the 16 rows of a wide tree level.
+    ddim, k = 3584, 10
+    Wd = (torch.randn(vocab, ddim, generator=g, device=dev, dtype=torch.float32) * (3.0 / math.sqrt(ddim))).to(torch.bfloat16)
+    for rows in (1, 16):
+        H = torch.randn(rows, ddim, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        f = lambda *sh: torch.zeros(*sh, device=dev)
+        ent, hk, al, pr, rn = f(rows), f(rows), f(rows), f(rows, k), f(rows, k)
+        idx = torch.zeros(rows, k, device=dev, dtype=torch.int32)
+        ws = torch.empty(sage.sage_lm_head_topk_workspace_bytes(rows, vocab, k), device=dev, dtype=torch.uint8)
+        call = sage.prepare("sage_lm_head_topk", H, Wd, k, ent, idx, pr, rn, hk, al, ws)
+        for _ in range(3):
+            call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(launches):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        avg_s = e0.elapsed_time(e1) * 1e-3 / launches
+        byts = 2.0 * vocab * ddim + 2.0 * rows * ddim
+        ref = torch.topk(H.float() @ Wd.float().T, k, dim=1).indices
+        out.append(dict(rows=rows, live_rows=rows, dim=ddim, vocab=vocab, k=k, avg_us=avg_s * 1e6, algorithmic_bytes=byts,
+                        hbm_GBps=byts / avg_s / 1e9, hbm_frac=byts / avg_s / 1e9 / HBM_PEAK_GBPS, bound="hbm",
+                        topk_agrees_with_fp32_matmul=float((ref == idx.long()).float().mean().item())))
+        del H
+    del Wd
     torch.cuda.empty_cache()
     return out
 

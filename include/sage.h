@@ -237,15 +237,16 @@ int sage_close_step(const void* Kt, const void* Vt, void* Kc, void* Vc, int dtyp
  * row groups and n_valid exactly as in sage_entropy_topk.
  *
  * hidden [rows, dim], weight [vocab, dim], row-major with row strides in elements, rows
- * 16-byte aligned.  This build: bf16, k = 1, dim a multiple of 128, row strides <= 2^24
- * elements, vocab <= 655360 (others: UNSUPPORTED).  The weight matrix is fetched from HBM
- * once per call; rows that n_valid marks dead cost nothing (live rows are packed into blocks
- * of 128 before the pass).
- * workspace: sage_lm_head_topk_workspace_bytes(rows, vocab) bytes, 16-byte aligned.
- * Errors: INVALID_ARG (null pointers, sizes, strides, alignment), UNSUPPORTED,
- * WORKSPACE_TOO_SMALL.
+ * 16-byte aligned.  This build: bf16, dim a multiple of 128, row strides <= 2^24 elements,
+ * vocab <= 655360; k = 1 for any number of rows (the target's node rows), 1 < k <= 16 for up
+ * to 64 rows (a draft model's rows, Sec. 3.1); others: UNSUPPORTED.  The weight matrix is
+ * fetched from HBM once per call; rows that n_valid marks dead cost nothing (live rows are
+ * packed into blocks of 128 before the pass).
+ * workspace: sage_lm_head_topk_workspace_bytes(rows, vocab, k) bytes, 16-byte aligned.
+ * Errors: INVALID_ARG (null pointers, sizes, strides, alignment, k outside [1, min(vocab,
+ * SAGE_MAX_TOPK)]), UNSUPPORTED, WORKSPACE_TOO_SMALL.
  */
-size_t sage_lm_head_topk_workspace_bytes(int rows, int vocab);
+size_t sage_lm_head_topk_workspace_bytes(int rows, int vocab, int k);
 int sage_lm_head_topk(const void* hidden, const void* weight, int dtype, int rows, int dim, int vocab,
                       long hidden_stride, long weight_stride, int k, const int* n_valid, int rows_per_group,
                       float* entropy, int* topk_idx, float* topk_prob, float* topk_renorm,

@@ -43,6 +43,7 @@ constexpr int TILE_R = 64;               // hidden rows per launch block
 constexpr int CHUNK = 128;               // hidden elements per stage
 constexpr int ROW_B = CHUNK * 2;         // bytes of one row of a stage
 constexpr int THREADS = 256;
+constexpr int MAX_K = 16;                // largest candidate list per row
 constexpr int CUS = 256;                 // compute units of the MI355X: workgroups of a launch that stay resident
 constexpr int MAX_STAGES = 8;          // weight ring: all but one stage in flight per workgroup
 // stage layout: row t at (t % 16) * GROUP + (t / 16) * ROW_B; a group is the 1 KB one wave-level LDS-direct load
@@ -87,8 +88,13 @@ __device__ __forceinline__ void stage_barrier() {
 // launches with more than 64 rows: when every CU reads its weight tiles through L2 at once the chip delivers about
 // 46 GB/s per CU, which at 64 rows per workgroup (64 flops per byte) caps the call near 700 TFLOP/s whatever the MFMAs
 // could do; two row blocks per workgroup halve the bytes per flop.  The second hidden stage costs one weight stage.
-template <int T, int R>
+// TOPK: k candidates per (row, unit) instead of one (the draft side of Sec. 3.1, whose rows are few): after the fold, k
+// rounds pick the best remaining logit of every row in the total order (value descending, index ascending).  A round
+// scans the lane's 16 T logits for the best one that comes after the previous winner, combines the four lanes of a row
+// (lane halves by a swap, vocabulary halves through LDS) and writes the winner as key j of the unit's sorted list.
+template <int T, int R, bool TOPK>
 __global__ __launch_bounds__(THREADS) void lm_head_kernel(const Params prm) {
+    static_assert(!TOPK || R == 1, "the candidate rounds are written for one row block");
     // The ring position of a step must be a compile-time constant (every stage is its own LDS object, so that loads
     // in flight into one stage are known not to alias reads of another): step t of chunk kc uses stage
     // (kc T + t) mod STAGES, which is static once the chunk loop is unrolled UNROLL times.
@@ -111,6 +117,7 @@ __global__ __launch_bounds__(THREADS) void lm_head_kernel(const Params prm) {
     __shared__ uint64_t s_key[ROWS][4];
     __shared__ int s_row[ROWS];                              // hidden row behind each of this block's slots, -1 = none
     __shared__ int s_cnt[THREADS];
+    __shared__ uint64_t s_sel[TOPK ? 2 : 1][TOPK ? TILE_R : 1][2];   // candidate rounds: a row's winner per vocabulary half
     unsigned char* const sH1 = sW7;                          // R = 2: the ring has seven stages, the eighth buffer holds the second row block's chunk
 #define SW(i) ((i) == 0 ? sW0 : (i) == 1 ? sW1 : (i) == 2 ? sW2 : (i) == 3 ? sW3 : (i) == 4 ? sW4 : (i) == 5 ? sW5 : (i) == 6 ? sW6 : sW7)
 
@@ -361,7 +368,48 @@ __global__ __launch_bounds__(THREADS) void lm_head_kernel(const Params prm) {
         }
         const long o = static_cast<long>(s_row[tid]) * prm.nunits + unit;
         prm.stats[o] = UnitStats{m, z, t, 0.f};
-        prm.keys[o] = key_pack(bk);
+        if (!TOPK) prm.keys[o] = key_pack(bk);
+    }
+    if constexpr (TOPK) {
+        const int hr = rt * 32 + r32;
+        const int row = s_row[hr];
+        // the statistics are done: the logits give way, in place, to their order-preserving codes (0 = not a candidate:
+        // past the unit's end, or -inf), so that a round costs one 64-bit compare pair per logit
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const int v0 = (tile_begin + t) * TILE_V + 32 * vt + 4 * half;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int v = v0 + 8 * (i >> 2) + (i & 3);
+                const float x = acc[0][t][i];
+                acc[0][t][i] = __uint_as_float((v < v_end && x > -INFINITY) ? sortable(x) : 0u);
+            }
+        }
+        uint64_t prev = ~0ull;                               // the previous winner: candidates come after it in the order
+        for (int j = 0; j < prm.k; ++j) {
+            uint64_t best = 0xFFFFFFFFull;                   // (code 0, lowest index word): below every candidate
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const uint32_t lo0 = 0xFFFFFFFFu - static_cast<uint32_t>((tile_begin + t) * TILE_V + 32 * vt + 4 * half);
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const uint64_t key = (static_cast<uint64_t>(__float_as_uint(acc[0][t][i])) << 32) | (lo0 - (8 * (i >> 2) + (i & 3)));
+                    best = (key < prev && key > best) ? key : best;
+                }
+            }
+            Key mine = (best >> 32) == 0 ? Key{0, 0} : key_unpack(best);
+            {                                                // the other lane half of this row
+                const auto hi = __builtin_amdgcn_permlane32_swap(mine.hi, mine.hi, false, false);
+                const auto lo = __builtin_amdgcn_permlane32_swap(mine.lo, mine.lo, false, false);
+                mine = key_max(Key{hi[0], lo[0]}, Key{hi[1], lo[1]});
+            }
+            if (half == 0) s_sel[j & 1][hr][vt] = key_pack(mine);
+            __syncthreads();                                 // (rounds alternate between two buffers: one barrier per round)
+            const Key w = key_max(key_unpack(s_sel[j & 1][hr][0]), key_unpack(s_sel[j & 1][hr][1]));
+            if (vt == 0 && half == 0 && row >= 0)
+                prm.keys[(static_cast<long>(row) * prm.nunits + unit) * prm.k + j] = key_pack(w);
+            prev = key_none(w) ? 0ull : key_pack(w);         // an exhausted unit: nothing comes after
+        }
     }
     __syncthreads();                                         // the next item rewrites s_row and s_part
     }   // work items
@@ -386,11 +434,11 @@ inline Shape launch_shape(int vocab, int rows) {
 
 }  // namespace
 
-extern "C" size_t sage_lm_head_topk_workspace_bytes(int rows, int vocab) {
-    if (rows < 0 || vocab < 1) return 0;
+extern "C" size_t sage_lm_head_topk_workspace_bytes(int rows, int vocab, int k) {
+    if (rows < 0 || vocab < 1 || k < 1) return 0;
     const Shape sh = launch_shape(vocab, rows);
     return align256(static_cast<size_t>(rows) * sh.nunits * sizeof(UnitStats)) +
-           static_cast<size_t>(rows) * sh.nunits * sizeof(uint64_t) + 256;
+           static_cast<size_t>(rows) * sh.nunits * k * sizeof(uint64_t) + 256;
 }
 
 extern "C" int sage_lm_head_topk(const void* hidden, const void* weight, int dtype, int rows, int dim, int vocab,
@@ -401,13 +449,15 @@ extern "C" int sage_lm_head_topk(const void* hidden, const void* weight, int dty
     if (rows < 0 || dim < 1 || vocab < 1 || k < 1 || hidden_stride < dim || weight_stride < dim) return SAGE_INVALID_ARG;
     if (dtype != SAGE_F32 && dtype != SAGE_BF16) return SAGE_INVALID_ARG;
     if (n_valid && rows_per_group < 1) return SAGE_INVALID_ARG;
-    if (dtype != SAGE_BF16 || k != 1 || dim % CHUNK != 0) return SAGE_UNSUPPORTED;
+    if (k > SAGE_MAX_TOPK || k > vocab) return SAGE_INVALID_ARG;
+    if (dtype != SAGE_BF16 || dim % CHUNK != 0) return SAGE_UNSUPPORTED;
+    if (k > MAX_K || (k > 1 && rows > TILE_R)) return SAGE_UNSUPPORTED;   // candidate lists: the draft side, few rows
     if ((hidden_stride % 8) != 0 || (weight_stride % 8) != 0 || !sage::aligned(hidden, 16) || !sage::aligned(weight, 16) ||
         !sage::aligned(workspace, 16))
         return SAGE_INVALID_ARG;
     if (weight_stride > (1L << 24) || hidden_stride > (1L << 24)) return SAGE_UNSUPPORTED;
     if (rows > (1 << 20)) return SAGE_UNSUPPORTED;                                            // grid size
-    if (workspace_bytes < sage_lm_head_topk_workspace_bytes(rows, vocab)) return SAGE_WORKSPACE_TOO_SMALL;
+    if (workspace_bytes < sage_lm_head_topk_workspace_bytes(rows, vocab, k)) return SAGE_WORKSPACE_TOO_SMALL;
     if (rows == 0) return SAGE_OK;
     const Shape sh = launch_shape(vocab, rows);
     if (sh.nunits > sage::topk_max_units()) return SAGE_UNSUPPORTED;
@@ -426,9 +476,11 @@ extern "C" int sage_lm_head_topk(const void* hidden, const void* weight, int dty
     hipStream_t s = sage::as_stream(stream);
     const int most = ((sh.nunits + 7) / 8) * 8 * p.row_blocks;   // work items if every row is live
     const dim3 grid(most < CUS ? most : CUS);                // a workgroup fills a CU's LDS: one resident workgroup per CU
-    if (sh.rows_per_wg > TILE_R) hipLaunchKernelGGL((lm_head_kernel<5, 2>), grid, dim3(THREADS), 0, s, p);
-    else if (sh.tiles_per_unit == 5) hipLaunchKernelGGL((lm_head_kernel<5, 1>), grid, dim3(THREADS), 0, s, p);
-    else hipLaunchKernelGGL((lm_head_kernel<10, 1>), grid, dim3(THREADS), 0, s, p);
+    if (sh.rows_per_wg > TILE_R) hipLaunchKernelGGL((lm_head_kernel<5, 2, false>), grid, dim3(THREADS), 0, s, p);
+    else if (k > 1 && sh.tiles_per_unit == 5) hipLaunchKernelGGL((lm_head_kernel<5, 1, true>), grid, dim3(THREADS), 0, s, p);
+    else if (k > 1) hipLaunchKernelGGL((lm_head_kernel<10, 1, true>), grid, dim3(THREADS), 0, s, p);
+    else if (sh.tiles_per_unit == 5) hipLaunchKernelGGL((lm_head_kernel<5, 1, false>), grid, dim3(THREADS), 0, s, p);
+    else hipLaunchKernelGGL((lm_head_kernel<10, 1, false>), grid, dim3(THREADS), 0, s, p);
     if (hipGetLastError() != hipSuccess) return SAGE_LAUNCH_FAILED;
     sage::topk_merge(rows, k, n_valid, rows_per_group, sh.nunits, p.stats, p.keys, entropy, topk_idx, topk_prob, topk_renorm,
                      topk_entropy, alpha, s);

@@ -83,7 +83,7 @@ def lib():
         L.sage_build_tree_from_slices.argtypes = [_vp, _ci, _ci, _ci, ctypes.POINTER(TreeParams)] + [_vp] * 15
         L.sage_verify_accept_from_slices.restype = _ci
         L.sage_verify_accept_from_slices.argtypes = [_vp, _ci, _vp, _vp, _vp, _vp, _vp, _ci, _ci] + [_vp] * 7
-        L.sage_lm_head_topk_workspace_bytes.argtypes = [_ci, _ci]
+        L.sage_lm_head_topk_workspace_bytes.argtypes = [_ci, _ci, _ci]
         L.sage_lm_head_topk.restype = _ci
         L.sage_lm_head_topk.argtypes = [_vp, _vp, _ci, _ci, _ci, _ci, _cl, _cl, _ci, _vp, _ci, _vp, _vp, _vp, _vp, _vp, _vp,
                                         _vp, _sz, _vp]
@@ -122,8 +122,8 @@ def sage_entropy_topk_workspace_bytes(rows: int, vocab: int, k: int) -> int:
     return int(lib().sage_entropy_topk_workspace_bytes(rows, vocab, k))
 
 
-def sage_lm_head_topk_workspace_bytes(rows: int, vocab: int) -> int:
-    return int(lib().sage_lm_head_topk_workspace_bytes(rows, vocab))
+def sage_lm_head_topk_workspace_bytes(rows: int, vocab: int, k: int = 1) -> int:
+    return int(lib().sage_lm_head_topk_workspace_bytes(rows, vocab, k))
 
 
 def sage_tree_attention_workspace_bytes(dtype_code: int, B: int, Hq: int, Hkv: int, d: int, max_kv_len: int) -> int:

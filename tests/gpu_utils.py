@@ -146,7 +146,7 @@ def gpu_lm_head_topk(hidden_np, weight_np, k, n_valid=None, rows_per_group=1):
     f = lambda *s: torch.full(s, float("nan"), device=DEV, dtype=torch.float32)
     out = dict(entropy=f(rows), topk_idx=torch.full((rows, k), -1, device=DEV, dtype=torch.int32), topk_prob=f(rows, k),
                topk_renorm=f(rows, k), topk_entropy=f(rows), alpha=f(rows))
-    ws = torch.empty(sage.sage_lm_head_topk_workspace_bytes(rows, vocab), device=DEV, dtype=torch.uint8)
+    ws = torch.empty(sage.sage_lm_head_topk_workspace_bytes(rows, vocab, k), device=DEV, dtype=torch.uint8)
     nv = None if n_valid is None else to_dev(np.asarray(n_valid, np.int32))
     sage.sage_lm_head_topk(h, w, k, out["entropy"], out["topk_idx"], out["topk_prob"], out["topk_renorm"],
                            out["topk_entropy"], out["alpha"], ws, nv, rows_per_group)

@@ -115,13 +115,15 @@ def test_invalid_arguments_are_rejected_on_the_host(lib):
     assert lib.sage_lm_head_topk(*lm(idx=None)) == INVALID
     assert lib.sage_lm_head_topk(*lm(hs=100)) == INVALID                   # row stride shorter than a row
     assert lib.sage_lm_head_topk(*lm(hs=8196)) == INVALID                  # rows must stay 16-byte aligned
-    assert lib.sage_lm_head_topk(*lm(k=2)) == 2                            # only the greedy token so far
+    assert lib.sage_lm_head_topk(*lm(k=17)) == 2                           # candidate lists of up to 16
+    assert lib.sage_lm_head_topk(*lm(k=2, rows=65)) == 2                   # ... and only for up to 64 rows
+    assert lib.sage_lm_head_topk(*lm(k=65)) == INVALID
     assert lib.sage_lm_head_topk(*lm(dtype=0)) == 2
     assert lib.sage_lm_head_topk(*lm(dim=8100)) == 2                          # hidden size must be whole 128-element chunks
     assert lib.sage_lm_head_topk(*lm(wsb=64)) == 3
     assert lib.sage_lm_head_topk(*lm(rows=0)) == 0
     lib.sage_lm_head_topk_workspace_bytes.restype = ctypes.c_size_t
-    assert 0 < lib.sage_lm_head_topk_workspace_bytes(64, 152064) < (1 << 22)
+    assert 0 < lib.sage_lm_head_topk_workspace_bytes(64, 152064, 1) < (1 << 22)
     lib.sage_advance_kv_len.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
     assert lib.sage_advance_kv_len(None, 256, 1, 10, None) == INVALID
     assert lib.sage_advance_kv_len(256, 256, 0, 10, None) == 0

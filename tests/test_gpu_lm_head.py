@@ -61,7 +61,7 @@ def test_row_groups_and_padded_strides(gu):
     rows, vocab = 128, 900
     out_idx = torch.full((rows, 1), -1, device="cuda:0", dtype=torch.int32)
     ent = torch.full((rows,), float("nan"), device="cuda:0")
-    ws = torch.empty(sage.sage_lm_head_topk_workspace_bytes(rows, vocab), device="cuda:0", dtype=torch.uint8)
+    ws = torch.empty(sage.sage_lm_head_topk_workspace_bytes(rows, vocab, 1), device="cuda:0", dtype=torch.uint8)
     nv = gu.to_dev(np.array([10, 64], np.int32))
     sage.sage_lm_head_topk(hd, wd, 1, ent, out_idx, None, None, None, None, ws, nv, 64)
     torch.cuda.synchronize()
@@ -127,7 +127,7 @@ def test_full_size_72b_projection_sampled_rows(gu, rows, n_valid, sampled):
     H = torch.randn(rows, dim, generator=g, device="cuda:0", dtype=torch.float32).to(torch.bfloat16)
     ent = torch.full((rows,), float("nan"), device="cuda:0")
     idx = torch.full((rows, 1), -1, device="cuda:0", dtype=torch.int32)
-    ws = torch.empty(sage.sage_lm_head_topk_workspace_bytes(rows, vocab), device="cuda:0", dtype=torch.uint8)
+    ws = torch.empty(sage.sage_lm_head_topk_workspace_bytes(rows, vocab, 1), device="cuda:0", dtype=torch.uint8)
     nv = torch.tensor(n_valid, device="cuda:0", dtype=torch.int32)     # only the first n_valid rows of each tree are live
     sage.sage_lm_head_topk(H, W, 1, ent, idx, None, None, None, None, ws, nv, 64)
     torch.cuda.synchronize()
@@ -143,3 +143,42 @@ def test_full_size_72b_projection_sampled_rows(gu, rows, n_valid, sampled):
         tol = 1e-5 * np.sqrt(dim) * max(1.0, float(np.abs(o["logits"]).max()))
         assert gi[r] == oi or o["logits"][0, gi[r]] >= o["logits"][0, oi] - tol, (r, gi[r], oi)
         assert abs(ge[r] - o["entropy"][0]) <= 1e-3 * max(1.0, o["entropy"][0])
+
+
+@pytest.mark.parametrize("rows,dim,vocab,k", [(5, 256, 1000, 10), (64, 512, 4096, 16), (1, 1024, 130, 8), (33, 128, 70, 16),
+                                              (3, 128, 152064, 10), (16, 3584, 152064, 10), (2, 384, 81900, 2)])
+def test_candidate_lists_of_a_draft_row(gu, rows, dim, vocab, k):
+    """1 < k <= 16 (the draft side of Sec. 3.1): the k best tokens per row and Eq. 7-9 on them.  The order of two logits
+    that differ by less than the fp32 accumulation error is not decidable, so position j must hold a token whose fp64
+    logit equals the oracle's j-th largest within that error; the probabilities follow to 1e-3."""
+    h = wl.gaussian(rows + k, (rows, dim), "bf16", 1.0)
+    w = wl.gaussian(vocab + k, (vocab, dim), "bf16", 3.0 / np.sqrt(dim))
+    g = gu.gpu_lm_head_topk(h, w, k)
+    o = oracle.lm_head_topk(h, w, k, return_logits=True)
+    exact = 0
+    for r in range(rows):
+        gi = g["topk_idx"][r]
+        assert len(set(gi.tolist())) == k and gi.min() >= 0 and gi.max() < vocab
+        tol = 1e-5 * np.sqrt(dim) * max(1.0, float(np.abs(o["logits"][r]).max()))
+        want = np.sort(o["logits"][r])[::-1][:k]
+        assert np.abs(o["logits"][r, gi] - want).max() <= tol, r
+        exact += int((gi == o["topk_idx"][r]).all())
+        for key in ("topk_prob", "topk_renorm"):
+            np.testing.assert_allclose(np.sort(g[key][r])[::-1], np.sort(o[key][r])[::-1], rtol=2e-3, atol=1e-6, err_msg=key)
+        for key in ("entropy", "topk_entropy", "alpha"):
+            assert abs(g[key][r] - o[key][r]) <= 2e-3 * max(1.0, abs(o[key][r])), (key, r)
+    assert exact >= rows - max(1, rows // 8)                    # near-ties among the k best are rare on Gaussian logits
+
+
+def test_candidate_lists_with_exact_ties(gu):
+    """Identical weight rows give identical logits (same products, same order of accumulation): the lower index comes
+    first, across tiles and units alike."""
+    dim, vocab, k = 256, 3000, 6
+    h = wl.gaussian(15, (3, dim), "bf16", 1.0)
+    w = wl.gaussian(16, (vocab, dim), "bf16", 0.02)
+    for v in (2900, 70, 1500, 71):                             # four copies of the hidden row 1 scaled up: the four best
+        w[v] = h[1]
+    g = gu.gpu_lm_head_topk(h, w, k)
+    assert g["topk_idx"][1, :4].tolist() == [70, 71, 1500, 2900]
+    o = oracle.lm_head_topk(h, w, k)
+    np.testing.assert_array_equal(g["topk_idx"][1, :4], o["topk_idx"][1, :4])
