@@ -32,7 +32,7 @@ MIN_TIMED_MS = 5.0              # the timed region is stretched to at least this
 # HBM bytes of one sage_tree_attention call (main kernel + split merge) per workload, from the rocprofv3 FETCH_SIZE /
 # WRITE_SIZE runs summarised in profiles/tree_attention_hbm_traffic_by_workload.md (scaled by the counters' readings
 # for a 64 MiB copy; the summary states the commands, the tree sizes and the split counts they were taken at).
-MEASURED_TRAFFIC_BYTES = {"c2": 26.84e6, "c3": 82.88e6, "c4": 265.10e6, "c5": 172.57e6}
+MEASURED_TRAFFIC_BYTES = {"c2": 26.88e6, "c3": 82.92e6, "c4": 265.17e6, "c5": 172.61e6}
 
 # Trees of the 80-layer configuration are asked to have 64 nodes every step.  With the paper's own parameters the
 # rule never grows a tree that large, so that workload plants a geometric top-64 distribution (ratio 1/2) in the
