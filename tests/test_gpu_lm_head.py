@@ -182,3 +182,25 @@ def test_candidate_lists_with_exact_ties(gu):
     assert g["topk_idx"][1, :4].tolist() == [70, 71, 1500, 2900]
     o = oracle.lm_head_topk(h, w, k)
     np.testing.assert_array_equal(g["topk_idx"][1, :4], o["topk_idx"][1, :4])
+
+
+def test_candidate_lists_with_row_groups(gu):
+    """k > 1 together with n_valid: the live rows are packed into the block, dead rows stay untouched, and a row's list
+    does not depend on which slot it lands in."""
+    rows, rpg, dim, vocab, k = 40, 8, 256, 5000, 4
+    n_valid = np.array([3, 0, 8, 1, 5], np.int32)
+    h = wl.gaussian(77, (rows, dim), "bf16", 1.0)
+    w = wl.gaussian(78, (vocab, dim), "bf16", 3.0 / np.sqrt(dim))
+    g = gu.gpu_lm_head_topk(h, w, k, n_valid, rpg)
+    alone = gu.gpu_lm_head_topk(h, w, k)
+    o = oracle.lm_head_topk(h, w, k, n_valid=n_valid, rows_per_group=rpg, return_logits=True)
+    for r in range(rows):
+        if (r % rpg) < n_valid[r // rpg]:
+            np.testing.assert_array_equal(g["topk_idx"][r], alone["topk_idx"][r])
+            np.testing.assert_array_equal(g["topk_renorm"][r], alone["topk_renorm"][r])
+            tol = 1e-5 * np.sqrt(dim) * max(1.0, float(np.abs(o["logits"][r]).max()))
+            want = np.sort(o["logits"][r])[::-1][:k]
+            assert np.abs(o["logits"][r, g["topk_idx"][r]] - want).max() <= tol
+            assert abs(g["alpha"][r] - o["alpha"][r]) <= 2e-3
+        else:
+            assert (g["topk_idx"][r] == -1).all() and np.isnan(g["entropy"][r])
