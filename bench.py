@@ -614,7 +614,7 @@ def closed_loop(name="c2", steps=512, carry=True):
     def prep(stream):
         V = w.cfg["vocab"]
         c = dict(a1=[sg.prepare("sage_entropy_topk_slices", w.draft[s], w.k, w.ws1, stream=stream if carry else plan_stream)
-                     for s in range(w.slots)], a2=[], a3=[], a1t=[], a4=[], commit=[], a3p=[])
+                     for s in range(w.slots)], a2=[], a3=[], a1t=[], a4=[], commit=[], a3p=[], pair=[])
         for cur in range(2):
             t, nxt = w.tree[cur], w.tree[cur ^ 1]
             if carry:
@@ -631,6 +631,9 @@ def closed_loop(name="c2", steps=512, carry=True):
                             for s in range(w.slots)])
             c["a1t"].append([sg.prepare("sage_entropy_topk_slices", w.target[s], 1, w.ws1t, t["n_nodes"], MAX_NODES,
                                         stream=stream) for s in range(w.slots)])
+            if carry:                                         # ... or with the next step's draft row in the same launch
+                c["pair"].append([sg.prepare("sage_entropy_topk_slices_pair", w.target[s], t["n_nodes"], MAX_NODES, w.ws1t,
+                                             w.draft[(s + 1) % w.slots], w.k, w.ws1, stream=stream) for s in range(w.slots)])
             # acceptance, commit, advance and history in one launch
             c["a4"].append([sg.prepare("sage_verify_accept_close_from_slices", w.ws1t, V, t["node_token"], t["parent"], t["depth"],
                                        t["anc_mask"], t["n_nodes"], w.path_cap, w.tH, w.tgt_idx, w.acc_len, w.best, w.path,
@@ -639,12 +642,20 @@ def closed_loop(name="c2", steps=512, carry=True):
                                        stream=stream) for s in range(w.slots)])
         return c
 
-    state = dict(cur=0, step=0)
+    state = dict(cur=0, step=0, slices_for=-1)
 
-    def step(c):
+    def step(c, last=True):
         s, cur = state["step"] % w.slots, state["cur"]
         if carry:                                             # one stream: the plan (depth limit of the previous step) rides
-            c["a1"][s](); c["a3p"][cur][s](); c["a1t"][cur][s](); c["a4"][cur][s]()        # in the attention launch
+            if state["slices_for"] != state["step"]:         # in the attention launch, and inside a run of steps the draft
+                c["a1"][s]()                                  # row's slice pass rides in the previous step's target-row launch
+            c["a3p"][cur][s]()
+            if last:
+                c["a1t"][cur][s]()
+            else:
+                c["pair"][cur][s]()
+                state["slices_for"] = state["step"] + 1
+            c["a4"][cur][s]()
             acc_sum.add_(w.acc_len)
             state["cur"] ^= 1
             state["step"] += 1
@@ -665,7 +676,7 @@ def closed_loop(name="c2", steps=512, carry=True):
         for t, t0 in zip(w.tree, tree0):
             for k in t:
                 t[k].copy_(t0[k])
-        state.update(cur=0, step=0)
+        state.update(cur=0, step=0, slices_for=-1)
 
     def snapshot_state():
         grown = int((kv_len - kv_len0).max().item())
@@ -684,8 +695,8 @@ def closed_loop(name="c2", steps=512, carry=True):
     graphed = prep(side)
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph, stream=side):
-        for _ in range(cycle):
-            step(graphed)
+        for i in range(cycle):
+            step(graphed, last=i == cycle - 1)
     reset()                                                    # capture does not execute, but keep the start exact
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -696,8 +707,9 @@ def closed_loop(name="c2", steps=512, carry=True):
     got = snapshot_state()
     verified = all(torch.equal(a, b) for a, b in zip(want, got))
     out = dict(workload=name, steps=steps, steps_per_s=steps / wall, ms_per_step=wall * 1e3 / steps,
-               calls_per_step=("entropy_topk_slices, tree_attention_with_plan (per-sequence depth), entropy_topk_slices (k=1), "
-                               "verify_accept_close_from_slices (acceptance, commit, advance, history); one stream") if carry else
+               calls_per_step=("tree_attention_with_plan (per-sequence depth), entropy_topk_slices_pair (target rows + the next "
+                               "step's draft row), verify_accept_close_from_slices (acceptance, commit, advance, history); one "
+                               "stream; the first step of a graph runs entropy_topk_slices on its draft row itself") if carry else
                               ("entropy_topk_slices, build_tree_from_slices (per-sequence depth), tree_attention, "
                                "entropy_topk_slices (k=1), verify_accept_close_from_slices (acceptance, commit, advance, "
                                "history); the first two on a second stream beside the rest"),
