@@ -33,6 +33,10 @@ MIN_TIMED_MS = 5.0              # the timed region is stretched to at least this
 # WRITE_SIZE runs summarised in profiles/tree_attention_hbm_traffic_by_workload.md (scaled by the counters' readings
 # for a 64 MiB copy; the summary states the commands, the tree sizes and the split counts they were taken at).
 MEASURED_TRAFFIC_BYTES = {"c2": 26.88e6, "c3": 82.92e6, "c4": 265.17e6, "c5": 172.61e6}
+TRAFFIC_SPLITS = {"c2": "22 KV splits per KV head (65 tiles in splits of 3)",
+                  "c3": "29 KV splits per KV head (257 tiles in splits of 9); 15 + 15 for trees of more than 32 nodes",
+                  "c4": "256 ranges over all sequences and KV heads (batched decomposition)",
+                  "c5": "16 KV splits per column group, two column groups (513 tiles in splits of 33)"}
 
 # Trees of the 80-layer configuration are asked to have 64 nodes every step.  With the paper's own parameters the
 # rule never grows a tree that large, so that workload plants a geometric top-64 distribution (ratio 1/2) in the
@@ -517,7 +521,10 @@ def attention_roofline(w: Workload, name: str, eager: bool = False):
            "achieved": tflops if mfma_bound else gbps, "peak": MFMA_BF16_PEAK_TFLOPS if mfma_bound else HBM_PEAK_GBPS,
            "unit": "TFLOP/s" if mfma_bound else "GB/s",
            "frac": (tflops / MFMA_BF16_PEAK_TFLOPS) if mfma_bound else gbps / HBM_PEAK_GBPS,
-           "traffic": MEASURED_TRAFFIC_BYTES.get(name), "avg_launch_us": us,
+           "traffic": MEASURED_TRAFFIC_BYTES.get(name),
+           "traffic_source": (f"rocprofv3 FETCH_SIZE + WRITE_SIZE per call, profiles/tree_attention_hbm_traffic_by_workload.md, "
+                              f"taken at {TRAFFIC_SPLITS[name]}") if name in TRAFFIC_SPLITS else None,
+           "avg_launch_us": us,
            "algorithmic_bytes_per_launch": per_bytes, "hbm_GBps": gbps, "hbm_frac": gbps / HBM_PEAK_GBPS,
            "mfma_TFLOPs": tflops, "mfma_frac": tflops / MFMA_BF16_PEAK_TFLOPS,
            "mean_tree_nodes": sum(nodes) / len(nodes), "tree_size_histogram": dict(sorted(hist.items(), key=lambda kv: int(kv[0].split("-")[0]))),
