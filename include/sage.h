@@ -326,7 +326,8 @@ int sage_verify_accept_close_from_slices(
  * stream the cache, which removes planning's launch from the step's chain of dependent
  * launches.  Results of both halves are bit-identical to the two separate calls.
  *
- * Arguments: those of sage_tree_attention (through workspace_bytes), then those of
+ * Arguments: those of sage_tree_attention without first_node (a verify pass computes every
+ * node's rows), through workspace_bytes, then those of
  * sage_build_tree_from_slices without its B (one draft row per sequence of the attention
  * batch: `slices` filled by sage_entropy_topk_slices with rows = B); the planned tree goes to
  * next_n_nodes / next_parent / next_depth / next_rank / next_anc_mask (/ next_cum_prob,
@@ -350,7 +351,8 @@ int sage_tree_attention_with_plan(
  * sage_tree_attention_static -- sage_tree_attention for callers that cannot allocate: code
  * under HIP graph capture, serving loops and harnesses that must not call hipMalloc (or any
  * allocating routine) and so cannot provide a workspace sized per call.  Arguments, results
- * (bit-identical) and errors are those of sage_tree_attention without its workspace pair: the
+ * (bit-identical) and errors are those of sage_tree_attention without its workspace pair and
+ * without first_node (every node's rows are computed): the
  * split partials live in a device array inside the library,
  * sage_tree_attention_static_scratch_bytes() = 40 MiB per GPU the library runs on, held until
  * the process ends.  The call allocates and frees nothing.
